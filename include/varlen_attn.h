@@ -1,0 +1,196 @@
+/*
+ * varlen_attn.h - C ABI of the packed variable-length attention library for
+ * AMD MI355X (gfx950).
+ *
+ * The operation is the one behind the paper's "Data Packing" + "Variable-Length
+ * Flash-Attention" recipe (section 2.2.1, paragraphs (1) and (2); measured in
+ * section 3.2): several samples are concatenated end to end into one token
+ * stream, and softmax attention is computed on the valid tokens only, each
+ * sample attending to itself alone.  Inside a sample the mask is causal
+ * (autoregressive decoder, section 2.2.1 (1)) or prefix-LM (the pi-0.5 case of
+ * section 2.2.2: a bidirectional prefix, and a suffix that attends the prefix
+ * and the whole suffix).
+ *
+ * Conventions that hold for every entry point
+ *   - Plain C types only.  "host" pointers are ordinary memory; "device"
+ *     pointers are HIP device memory owned by the caller, which must stay alive
+ *     until the stream has passed the call.
+ *   - The library never allocates or frees device memory and never
+ *     synchronises; device entry points only enqueue kernels on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Return value: VA_OK (0) or a negative VA_E* code; va_last_error() then
+ *     holds a message (thread-local, valid until the next failing call on the
+ *     same thread).  On error nothing has been enqueued and no output touched.
+ *   - Layouts (row-major, innermost last): Q, O, dO, dQ are [T, Hq, D];
+ *     K, V, dK, dV are [T, Hkv, D]; LSE is [Hq, T] float32.  T is the number of
+ *     packed tokens, cu_seqlens[num_seqs].  Rows >= T of any buffer are never
+ *     read or written.  Query head h uses KV head h / (Hq / Hkv).
+ *   - Sample s owns rows [cu_seqlens[s], cu_seqlens[s+1]).  Zero-length
+ *     samples are legal and produce nothing.
+ *   - Mask: local query row i of a sample of length L sees keys j < vis(i):
+ *       VA_MASK_CAUSAL                vis(i) = i + 1
+ *       VA_MASK_PREFIX_LM             vis(i) = P if i < P else L
+ *       VA_MASK_PREFIX_LM_CAUSAL      vis(i) = P if i < P else i + 1
+ *     with P = prefix_lens[s], 0 <= P <= L.
+ *   - LSE[h, r] = ln sum_j exp(scale * q_r . k_j) over the visible keys
+ *     (natural logarithm, scale included).
+ */
+#ifndef VARLEN_ATTN_H
+#define VARLEN_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VA_OK 0
+#define VA_EINVAL (-1)       /* null pointer, negative size, inconsistent arguments */
+#define VA_EUNSUPPORTED (-2) /* head_dim not in {64,128,256}, Hq % Hkv != 0, unknown mask/pass */
+#define VA_EALIGN (-3)       /* a tensor pointer is not 16-byte aligned */
+#define VA_ESIZE (-4)        /* output/workspace buffer too small, sample longer than budget or max_seqlen */
+#define VA_EHIP (-5)         /* the HIP runtime refused a launch */
+
+#define VA_MASK_CAUSAL 0
+#define VA_MASK_PREFIX_LM 1
+#define VA_MASK_PREFIX_LM_CAUSAL 2
+
+#define VA_PASS_FWD 0
+#define VA_PASS_BWD_DKDV 1
+#define VA_PASS_BWD_DQ 2
+
+/* Shapes shared by the device calls. */
+typedef struct {
+    int32_t total_tokens; /* T = cu_seqlens[num_seqs] */
+    int32_t num_seqs;     /* n */
+    int32_t num_q_heads;  /* Hq */
+    int32_t num_kv_heads; /* Hkv, Hq % Hkv == 0 */
+    int32_t head_dim;     /* D in {64, 128, 256} */
+    int32_t max_seqlen;   /* >= every sample length; validation only, never changes results */
+    int32_t mask_mode;    /* VA_MASK_* ; VA_MASK_CAUSAL ignores prefix_lens */
+} va_shape;
+
+/* Message of the last failing call on this thread (static storage). */
+const char* va_last_error(void);
+
+/* ------------------------------------------------------------------ host, integers only */
+
+/*
+ * Online first-fit packing (section 2.2.1 (2): samples are concatenated into
+ * sequences close to the maximum context length; the bin rule is this build's
+ * reading).  Samples are taken in index order; each goes to the lowest-numbered
+ * bin with at least lens[i] free tokens, a new bin being opened when none has.
+ *   lens[N]           host in   sample lengths, 0 <= lens[i] <= budget
+ *   bin_of_sample[N]  host out  bin index of each sample
+ *   pos_in_bin[N]     host out  placement order of the sample inside its bin
+ *   num_bins          host out
+ * VA_ESIZE if a sample is longer than the budget (outputs untouched).
+ */
+int va_pack_first_fit(const int32_t* lens, int32_t N, int32_t budget,
+                      int32_t* bin_of_sample, int32_t* pos_in_bin, int32_t* num_bins);
+
+/*
+ * Layout of one bin: exclusive prefix sums of its samples' lengths.
+ *   lens[n], prefix[n] (prefix may be NULL)  host in, in placement order
+ *   cu_seqlens[n+1]   host out, cu_seqlens[0] = 0
+ *   prefix_lens[n]    host out (may be NULL when prefix is NULL); VA_EINVAL unless 0 <= P <= L
+ *   max_seqlen        host out
+ */
+int va_bin_layout(const int32_t* lens, const int32_t* prefix, int32_t n,
+                  int32_t* cu_seqlens, int32_t* prefix_lens, int32_t* max_seqlen);
+
+/*
+ * Tile shape the kernels of `pass` use for these head counts: *rows is the
+ * number of token rows of a work item (query rows for VA_PASS_FWD and
+ * VA_PASS_BWD_DQ, key rows for VA_PASS_BWD_DKDV) and *cols the number of token
+ * rows of the tiles it loops over.
+ */
+int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t num_kv_heads,
+                  int32_t* rows, int32_t* cols);
+
+/*
+ * Work list of one pass over one packed stream: a header of 8 int32 words
+ * {magic, pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
+ * followed by num_items items of 8 int32 words, heaviest first (ties by sample,
+ * then tile).  Only tiles holding at least one visible (query, key) pair are
+ * listed and no tile spans two samples (the varlen rule of section 2.2.1 (1):
+ * compute on valid tokens only).
+ *   forward / dQ item: {q_row0, q_rows, seq_row0, kv_len, n_full, n_tiles, P or -1, L}
+ *   dK/dV item:        {kv_row0, kv_rows, seq_row0, qt_first, qt_count, 0, P or -1, L}
+ * va_worklist_bytes gives the buffer size; va_build_worklist fills a host
+ * buffer of at least that size.  The caller copies the buffer to the device
+ * unchanged and hands it to the device calls.
+ */
+int va_worklist_bytes(const int32_t* cu_seqlens, int32_t num_seqs, int32_t pass, int32_t head_dim,
+                      int32_t num_q_heads, int32_t num_kv_heads, size_t* bytes);
+int va_build_worklist(const int32_t* cu_seqlens, const int32_t* prefix_lens, int32_t num_seqs,
+                      int32_t mask_mode, int32_t pass, int32_t head_dim,
+                      int32_t num_q_heads, int32_t num_kv_heads,
+                      void* host_out, size_t bytes, int32_t* num_items);
+
+/*
+ * Per-head OCP E4M3 quantisation on the host (per-channel scaling of section
+ * 2.2.3 applied along the head axis): descale[h] = amax_h / 448 (1 when the
+ * head is all zero), code = round-to-nearest-even e4m3 of x / descale[h],
+ * saturating at +-448.  x is bfloat16 bits, host, [T, H, D].
+ */
+int va_quantize_e4m3_per_head(const uint16_t* x_bf16, int32_t T, int32_t H, int32_t D,
+                              uint8_t* codes, float* descale);
+
+/* ------------------------------------------------------------------ device */
+
+/* Bytes of device scratch varlen_attn_bwd needs for these shapes. */
+size_t varlen_attn_bwd_workspace_bytes(const va_shape* shape);
+
+/*
+ * Forward: O = softmax(scale * Q K^T + mask) V per sample, and LSE.
+ *   q, k, v        device in   bfloat16
+ *   cu_seqlens     host  in    [num_seqs + 1] (validated here: monotone, [0] = 0, last = T)
+ *   worklist       device in   copy of va_build_worklist(VA_PASS_FWD)
+ *   worklist_host  host  in    the same bytes (header and bounds are validated here)
+ *   out            device out  bfloat16 [T, Hq, D]
+ *   lse            device out  float32 [Hq, T]
+ */
+int varlen_attn_fwd(const void* q, const void* k, const void* v,
+                    const int32_t* cu_seqlens, const void* worklist, const void* worklist_host,
+                    const va_shape* shape, float scale,
+                    void* out, float* lse, void* stream);
+
+/*
+ * Backward: dQ, dK, dV from dO, recomputing the probabilities from the saved
+ * LSE.  Three kernels: delta = rowsum(dO * O); dK/dV per key tile; dQ per query
+ * tile.  No atomics; results do not depend on scheduling.
+ *   out, lse            device in   what varlen_attn_fwd wrote
+ *   dout                device in   bfloat16 [T, Hq, D]
+ *   worklist_dkdv/_dq   device in   va_build_worklist(VA_PASS_BWD_DKDV / VA_PASS_BWD_DQ)
+ *   *_host              host  in    the same bytes
+ *   dq, dk, dv          device out  bfloat16
+ *   workspace           device      at least varlen_attn_bwd_workspace_bytes(shape), 256-byte aligned
+ */
+int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                    const void* dout, const int32_t* cu_seqlens,
+                    const void* worklist_dkdv, const void* worklist_dkdv_host,
+                    const void* worklist_dq, const void* worklist_dq_host,
+                    const va_shape* shape, float scale,
+                    void* dq, void* dk, void* dv,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * FP8 forward: Q, K, V are OCP E4M3 bytes with one float32 descale per head
+ * (device arrays q_descale[Hq], k_descale[Hkv], v_descale[Hkv]).  Scores are
+ * (scale * q_descale[h] * k_descale[g]) * (Q8 . K8) in float32; the softmax and
+ * LSE are float32; the probabilities are requantised to E4M3 (times 256) for
+ * the second product; the row sum uses the unquantised probabilities.
+ * Output bfloat16 O and float32 LSE as in varlen_attn_fwd.
+ */
+int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
+                        const float* q_descale, const float* k_descale, const float* v_descale,
+                        const int32_t* cu_seqlens, const void* worklist, const void* worklist_host,
+                        const va_shape* shape, float scale,
+                        void* out, float* lse, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VARLEN_ATTN_H */

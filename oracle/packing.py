@@ -1,0 +1,233 @@
+"""Oracle for the host-side integer work: first-fit packing, the per-bin layout
+and the per-tile work lists.
+
+TEST INFRASTRUCTURE ONLY.  Plain Python loops, written from the rule, sharing
+nothing with the C++ packer of the library.
+
+Packing (paper section 2.2.1 (2), "Data Packing"): samples are concatenated end
+to end into sequences close to a token budget.  The paper does not name the
+bin-packing rule; the reading taken is online first-fit in arrival order: bins
+are opened in order, each sample goes to the lowest-numbered bin that still has
+room for it, nothing is sorted or reordered, and the order inside a bin is the
+placement order.
+
+Work lists: one item per tile of rows, listing only the key tiles that hold at
+least one allowed (query, key) pair, so fully masked tiles are never visited
+and no tile spans two samples.  Items are 8 int32 words:
+
+  forward / dQ pass (one item per query tile of ``bm`` token rows)
+    0 q_row0      absolute first row of the tile in the stream
+    1 q_rows      valid rows in the tile (<= bm)
+    2 seq_row0    first row of the sample (cu_seqlens[s])
+    3 kv_len      keys visible to at least one row of the tile
+    4 n_full      leading key tiles in which every (row, key) pair is allowed
+    5 n_tiles     key tiles visited = ceil(kv_len / bn)
+    6 prefix_len  P_s, or -1 when the stream is causal
+    7 seq_len     L_s
+
+  dK/dV pass (one item per key tile of ``bn`` token rows)
+    0 kv_row0     absolute first key row of the tile
+    1 kv_rows     valid key rows (<= bn)
+    2 seq_row0    cu_seqlens[s]
+    3 qt_first    index (within the sample) of the first query tile, of ``bm``
+                  rows, that holds a row seeing a key of this tile
+    4 qt_count    number of query tiles from qt_first to the end of the sample
+    5 reserved    0
+    6 prefix_len  P_s or -1
+    7 seq_len     L_s
+
+Order: descending amount of work (n_tiles, resp. qt_count), ties in ascending
+(sample, tile) order.
+"""
+import numpy as np
+
+PASS_FWD = 0
+PASS_BWD_DKDV = 1
+PASS_BWD_DQ = 2
+
+MASK_CAUSAL = 0
+MASK_PREFIX_BIDIR_SUFFIX = 1
+MASK_PREFIX_CAUSAL_SUFFIX = 2
+
+
+def first_fit(lens, budget):
+    """Online first-fit.  Returns (bin_of_sample, pos_in_bin, num_bins)."""
+    free = []
+    count = []
+    bin_of = []
+    pos_in = []
+    for L in lens:
+        L = int(L)
+        if L < 0 or L > budget:
+            raise ValueError("sample length outside [0, budget]")
+        placed = None
+        for b in range(len(free)):
+            if free[b] >= L:
+                placed = b
+                break
+        if placed is None:
+            free.append(budget)
+            count.append(0)
+            placed = len(free) - 1
+        free[placed] -= L
+        bin_of.append(placed)
+        pos_in.append(count[placed])
+        count[placed] += 1
+    return (np.array(bin_of, dtype=np.int32), np.array(pos_in, dtype=np.int32), len(free))
+
+
+def bin_members(bin_of, pos_in, b):
+    """Original sample indices of bin ``b`` in placement order."""
+    idx = [i for i in range(len(bin_of)) if bin_of[i] == b]
+    idx.sort(key=lambda i: pos_in[i])
+    return np.array(idx, dtype=np.int32)
+
+
+def bin_layout(lens, prefix=None):
+    """cu_seqlens (exclusive prefix sums), prefix_lens and max_seqlen of one bin."""
+    cu = [0]
+    for L in lens:
+        cu.append(cu[-1] + int(L))
+    mx = max([int(L) for L in lens], default=0)
+    pl = None if prefix is None else np.array([int(p) for p in prefix], dtype=np.int32)
+    return np.array(cu, dtype=np.int32), pl, mx
+
+
+def visible(i, L, P, mode):
+    """Number of keys local query row i may attend to."""
+    if mode == MASK_CAUSAL:
+        return i + 1
+    if i < P:
+        return P
+    if mode == MASK_PREFIX_BIDIR_SUFFIX:
+        return L
+    return i + 1
+
+
+def allowed(i, j, L, P, mode):
+    return 0 <= j < visible(i, L, P, mode)
+
+
+def _mode(prefix_lens, mask_mode):
+    if mask_mode is None:
+        return MASK_CAUSAL if prefix_lens is None else MASK_PREFIX_BIDIR_SUFFIX
+    return mask_mode
+
+
+def build_worklist(cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=None):
+    """Canonical work list as an [n_items, 8] int32 array, by brute force over
+    rows and keys (no closed forms: every count is obtained by looking at every
+    (row, key) pair of the tile)."""
+    mode = _mode(prefix_lens, mask_mode)
+    n = len(cu_seqlens) - 1
+    items = []
+    for s in range(n):
+        c = int(cu_seqlens[s])
+        L = int(cu_seqlens[s + 1]) - c
+        P = -1 if mode == MASK_CAUSAL else int(prefix_lens[s])
+        if pass_id in (PASS_FWD, PASS_BWD_DQ):
+            for t in range((L + bm - 1) // bm):
+                rows = range(t * bm, min(L, (t + 1) * bm))
+                kv_len = 0
+                for i in rows:
+                    for j in range(L):
+                        if allowed(i, j, L, P, mode):
+                            kv_len = max(kv_len, j + 1)
+                n_tiles = (kv_len + bn - 1) // bn
+                n_full = 0
+                for kt in range(n_tiles):
+                    if kt != n_full:
+                        break
+                    ok = (kt + 1) * bn <= L
+                    for i in rows:
+                        for j in range(kt * bn, min(L, (kt + 1) * bn)):
+                            ok = ok and allowed(i, j, L, P, mode)
+                    if ok:
+                        n_full += 1
+                items.append(((n_tiles, s, t), [c + t * bm, len(rows), c, kv_len, n_full, n_tiles, P, L]))
+        else:
+            for kt in range((L + bn - 1) // bn):
+                keys = range(kt * bn, min(L, (kt + 1) * bn))
+                first_row = None
+                for i in range(L):
+                    if any(allowed(i, j, L, P, mode) for j in keys):
+                        first_row = i
+                        break
+                assert first_row is not None  # every key is seen by its own row
+                qt_first = first_row // bm
+                qt_count = (L + bm - 1) // bm - qt_first
+                items.append(((qt_count, s, kt), [c + kt * bn, len(keys), c, qt_first, qt_count, 0, P, L]))
+    items.sort(key=lambda e: (-e[0][0], e[0][1], e[0][2]))
+    if not items:
+        return np.zeros((0, 8), dtype=np.int32)
+    return np.array([e[1] for e in items], dtype=np.int32)
+
+
+def check_coverage(items, cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=None):
+    """Brute-force proof that a work list visits every allowed (query, key) pair
+    exactly once, visits no fully masked tile, marks as 'full' only tiles with
+    no masked pair, and never lets a tile cross a sample boundary.  Raises
+    AssertionError with the reason otherwise."""
+    mode = _mode(prefix_lens, mask_mode)
+    n = len(cu_seqlens) - 1
+    T = int(cu_seqlens[n])
+    sample_of_row = np.full(T, -1, dtype=np.int64)
+    for s in range(n):
+        sample_of_row[int(cu_seqlens[s]):int(cu_seqlens[s + 1])] = s
+    seen = {}
+    for it in np.asarray(items).reshape(-1, 8):
+        a, rows, c, w3, w4, w5, P, L = [int(x) for x in it]
+        assert rows > 0, "empty tile listed"
+        s = int(sample_of_row[a])
+        assert s >= 0 and int(cu_seqlens[s]) == c and int(cu_seqlens[s + 1]) - c == L, "wrong sample fields"
+        assert a + rows <= c + L, "tile crosses the end of its sample"
+        assert P == (-1 if mode == MASK_CAUSAL else int(prefix_lens[s])), "wrong prefix"
+        if pass_id in (PASS_FWD, PASS_BWD_DQ):
+            assert (a - c) % bm == 0 and rows <= bm
+            kv_len, n_full, n_tiles = w3, w4, w5
+            assert n_tiles == (kv_len + bn - 1) // bn and n_full <= n_tiles and kv_len <= L
+            for kt in range(n_tiles):
+                pairs = 0
+                masked = 0
+                for i in range(a - c, a - c + rows):
+                    for j in range(kt * bn, (kt + 1) * bn):
+                        if j < L and allowed(i, j, L, P, mode):
+                            pairs += 1
+                            key = (s, i, j)
+                            seen[key] = seen.get(key, 0) + 1
+                        else:
+                            masked += 1
+                assert pairs > 0, "fully masked tile listed"
+                if kt < n_full:
+                    assert masked == 0, "tile marked full holds a masked pair"
+        else:
+            assert (a - c) % bn == 0 and rows <= bn
+            qt_first, qt_count = w3, w4
+            assert qt_first + qt_count == (L + bm - 1) // bm
+            pairs_first = 0
+            for qt in range(qt_first, qt_first + qt_count):
+                for i in range(qt * bm, min(L, (qt + 1) * bm)):
+                    for j in range(a - c, a - c + rows):
+                        if allowed(i, j, L, P, mode):
+                            key = (s, i, j)
+                            seen[key] = seen.get(key, 0) + 1
+                            if qt == qt_first:
+                                pairs_first += 1
+            assert pairs_first > 0, "first listed query tile sees nothing of this key tile"
+    total = 0
+    for s in range(n):
+        c = int(cu_seqlens[s])
+        L = int(cu_seqlens[s + 1]) - c
+        P = -1 if mode == MASK_CAUSAL else int(prefix_lens[s])
+        for i in range(L):
+            for j in range(L):
+                if allowed(i, j, L, P, mode):
+                    total += 1
+                    assert seen.get((s, i, j), 0) == 1, f"pair {(s, i, j)} visited {seen.get((s, i, j), 0)} times"
+    assert total == len(seen), "a pair outside the mask was visited"
+    return total
+
+
+def allowed_pairs(L, P, mode):
+    """Number of allowed (query, key) pairs of one sample, by counting."""
+    return sum(visible(i, L, P, mode) for i in range(L))

@@ -1,0 +1,285 @@
+"""Pins for the fp64 attention oracle (CPU only).
+
+The paper prints no formula and no worked example for attention, so the oracle
+is pinned to what the mathematics fixes: closed forms, invariants, reductions
+to library routines (numpy einsum, PyTorch CPU scaled_dot_product_attention in
+float64), brute-force finite differences, and the defining property of the
+method (paper section 2.2.1 (2) / 3.2: packing changes nothing in the result).
+Each test is chosen so that a plausible slip in the oracle (wrong mask edge,
+wrong head mapping, dropped scale, log base, transposed operand, missing term
+in a gradient) fails at least one of them.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attn as oa
+from paper_2603_11101_amd import workloads as wl
+
+MODES = [oa.MASK_CAUSAL, oa.MASK_PREFIX_BIDIR_SUFFIX, oa.MASK_PREFIX_CAUSAL_SUFFIX]
+
+
+def stream(seed, lens, Hq, Hkv, D, prefix="rand"):
+    cu, pl, q, k, v, do = wl.random_stream(seed, lens, Hq, Hkv, D, prefix_frac=-1.0)
+    return cu, pl, q, k, v, do
+
+
+def dense_mask(L, P, mode):
+    i = np.arange(L)[:, None]
+    j = np.arange(L)[None, :]
+    if mode == oa.MASK_CAUSAL:
+        return j <= i
+    if mode == oa.MASK_PREFIX_BIDIR_SUFFIX:
+        return np.where(i < P, j < P, np.ones_like(j, dtype=bool))
+    return np.where(i < P, j < P, j <= i)
+
+
+def test_single_token_samples():
+    # one-token samples: softmax over one key is 1, so O = V, LSE = scale q.k,
+    # dV = sum of dO over the group's query heads, dQ = dK = 0
+    Hq, Hkv, D = 4, 2, 8
+    cu, pl, q, k, v, do = stream(1, [1, 1, 1], Hq, Hkv, D)
+    for mode in MODES:
+        pl1 = None if mode == oa.MASK_CAUSAL else np.array([1, 0, 1], dtype=np.int32)
+        out, lse = oa.attn_fwd(q, k, v, cu, pl1, scale=0.37, mask_mode=mode)
+        dq, dk, dv = oa.attn_bwd(q, k, v, do, cu, pl1, scale=0.37, mask_mode=mode)
+        for t in range(3):
+            for h in range(Hq):
+                g = h // (Hq // Hkv)
+                assert np.array_equal(out[t, h], v[t, g].astype(np.float64))
+                assert lse[h, t] == pytest.approx(0.37 * float(np.dot(q[t, h].astype(np.float64), k[t, g].astype(np.float64))), rel=1e-14)
+            for g in range(Hkv):
+                want = do[t, g * 2:(g + 1) * 2].astype(np.float64).sum(axis=0)
+                assert np.allclose(dv[t, g], want, rtol=0, atol=1e-15)
+        assert np.abs(dq).max() < 1e-15 and np.abs(dk).max() < 1e-15
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_uniform_keys_closed_form(mode):
+    # every key of a sample equal: p_ij = 1 / #A(i), O_i = mean of V over A(i),
+    # LSE_i = scale q_i.k + ln #A(i).  Pins the mask geometry and the log base.
+    Hq, Hkv, D = 2, 1, 4
+    lens = [7, 12]
+    cu, _, q, k, v, do = stream(2, lens, Hq, Hkv, D)
+    pl = np.array([3, 12], dtype=np.int32)
+    for s in range(2):
+        k[cu[s]:cu[s + 1]] = k[cu[s]]
+    scale = 0.5
+    out, lse = oa.attn_fwd(q, k, v, cu, None if mode == oa.MASK_CAUSAL else pl, scale=scale, mask_mode=mode)
+    for s, L in enumerate(lens):
+        c = cu[s]
+        P = pl[s]
+        for i in range(L):
+            if mode == oa.MASK_CAUSAL:
+                cnt = i + 1
+            elif mode == oa.MASK_PREFIX_BIDIR_SUFFIX:
+                cnt = P if i < P else L
+            else:
+                cnt = P if i < P else i + 1
+            for h in range(Hq):
+                mean_v = v[c:c + cnt, 0].astype(np.float64).mean(axis=0)
+                assert np.allclose(out[c + i, h], mean_v, rtol=1e-13, atol=1e-14)
+                s_i = scale * float(np.dot(q[c + i, h].astype(np.float64), k[c, 0].astype(np.float64)))
+                assert lse[h, c + i] == pytest.approx(s_i + np.log(cnt), abs=1e-12)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_rows_of_p_sum_to_one_and_rows_of_ds_to_zero(mode):
+    Hq, Hkv, D = 4, 2, 8
+    cu, pl, q, k, v, do = stream(3, [9, 1, 14], Hq, Hkv, D)
+    plm = None if mode == oa.MASK_CAUSAL else pl
+    for s in range(3):
+        for h in range(Hq):
+            p, ds = oa.attn_probs(q, k, v, do, cu, plm, s, h, mask_mode=mode)
+            L = cu[s + 1] - cu[s]
+            P = 0 if plm is None else plm[s]
+            assert np.allclose(p.sum(axis=1), 1.0, atol=1e-14)
+            assert np.abs(ds.sum(axis=1)).max() < 1e-13
+            assert np.all((p > 0) == dense_mask(L, P, mode))
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_dense_library_reduction(mode):
+    # single-sample stream against numpy einsum and torch CPU SDPA (float64, boolean mask)
+    Hq, Hkv, D, L = 4, 2, 16, 33
+    cu, _, q, k, v, do = stream(4, [L], Hq, Hkv, D)
+    P = 20
+    pl = None if mode == oa.MASK_CAUSAL else np.array([P], dtype=np.int32)
+    scale = 1.0 / np.sqrt(D)
+    out, lse = oa.attn_fwd(q, k, v, cu, pl, scale=scale, mask_mode=mode)
+    mask = dense_mask(L, P, mode)
+    G = Hq // Hkv
+    kk = np.repeat(k.astype(np.float64), G, axis=1)
+    vv = np.repeat(v.astype(np.float64), G, axis=1)
+    s = np.einsum("ihd,jhd->hij", q.astype(np.float64), kk) * scale
+    s = np.where(mask[None], s, -np.inf)
+    m = s.max(axis=2, keepdims=True)
+    e = np.exp(s - m)
+    p = e / e.sum(axis=2, keepdims=True)
+    ref = np.einsum("hij,jhd->ihd", p, vv)
+    assert np.allclose(out, ref, rtol=1e-12, atol=1e-13)
+    assert np.allclose(lse, (m[..., 0] + np.log(e.sum(axis=2))), rtol=0, atol=1e-12)
+    tq = torch.from_numpy(q.astype(np.float64)).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(kk).permute(1, 0, 2)[None]
+    tv = torch.from_numpy(vv).permute(1, 0, 2)[None]
+    tref = torch.nn.functional.scaled_dot_product_attention(
+        tq, tk, tv, attn_mask=torch.from_numpy(mask)[None, None], scale=scale)
+    assert np.allclose(out, tref[0].permute(1, 0, 2).numpy(), rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_gradients_against_torch_autograd(mode):
+    # third opinion on the backward: autograd through the dense float64 definition
+    Hq, Hkv, D = 4, 2, 8
+    lens = [11, 6]
+    cu, pl, q, k, v, do = stream(5, lens, Hq, Hkv, D)
+    plm = None if mode == oa.MASK_CAUSAL else pl
+    scale = 0.3
+    dq, dk, dv = oa.attn_bwd(q, k, v, do, cu, plm, scale=scale, mask_mode=mode)
+    G = Hq // Hkv
+    for s, L in enumerate(lens):
+        c = cu[s]
+        P = 0 if plm is None else plm[s]
+        tq = torch.tensor(q[c:c + L].astype(np.float64), requires_grad=True)
+        tk = torch.tensor(k[c:c + L].astype(np.float64), requires_grad=True)
+        tv = torch.tensor(v[c:c + L].astype(np.float64), requires_grad=True)
+        mask = torch.from_numpy(dense_mask(L, P, mode))
+        sc = torch.einsum("ihd,jhd->hij", tq, tk.repeat_interleave(G, dim=1)) * scale
+        sc = sc.masked_fill(~mask[None], float("-inf"))
+        o = torch.einsum("hij,jhd->ihd", torch.softmax(sc, dim=-1), tv.repeat_interleave(G, dim=1))
+        (o * torch.tensor(do[c:c + L].astype(np.float64))).sum().backward()
+        assert np.allclose(dq[c:c + L], tq.grad.numpy(), rtol=1e-11, atol=1e-12)
+        assert np.allclose(dk[c:c + L], tk.grad.numpy(), rtol=1e-11, atol=1e-12)
+        assert np.allclose(dv[c:c + L], tv.grad.numpy(), rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_finite_differences(mode):
+    # central differences of loss = sum(O * dO) on tiny inputs, every input element
+    Hq, Hkv, D = 2, 1, 4
+    lens = [1, 3, 5]
+    cu, pl, q, k, v, do = stream(6, lens, Hq, Hkv, D)
+    plm = None if mode == oa.MASK_CAUSAL else pl
+    scale = 0.7
+    dq, dk, dv = oa.attn_bwd(q, k, v, do, cu, plm, scale=scale, mask_mode=mode)
+
+    # the oracle takes float32 inputs; perturb in float32-representable steps
+    h = np.float32(2.0 ** -10)
+
+    def loss(qq, kk, vv):
+        out, _ = oa.attn_fwd(qq, kk, vv, cu, plm, scale=scale, mask_mode=mode)
+        return float((out * do.astype(np.float64)).sum())
+
+    for name, x, g in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        for idx in np.ndindex(*x.shape):
+            xp = x.copy()
+            xm = x.copy()
+            xp[idx] += h
+            xm[idx] -= h
+            args_p = {"q": q, "k": k, "v": v}
+            args_m = dict(args_p)
+            args_p[name] = xp
+            args_m[name] = xm
+            step = float(xp[idx].astype(np.float64) - xm[idx].astype(np.float64))
+            fd = (loss(args_p["q"], args_p["k"], args_p["v"]) - loss(args_m["q"], args_m["k"], args_m["v"])) / step
+            assert fd == pytest.approx(g[idx], rel=2e-5, abs=2e-6), (name, idx)
+
+
+def test_key_shift_and_value_scaling():
+    # adding u to every key of a sample leaves O unchanged and moves LSE_i by scale q_i.u;
+    # scaling V scales O
+    Hq, Hkv, D = 2, 2, 8
+    cu, pl, q, k, v, do = stream(7, [10, 5], Hq, Hkv, D)
+    u = wl.round_to_bf16(np.random.default_rng(0).standard_normal(D).astype(np.float32) * 0.25)
+    out0, lse0 = oa.attn_fwd(q, k, v, cu, None, scale=0.4)
+    # keep the shifted keys exactly representable: K and u are bf16 numbers, their float32 sum is exact here
+    k2 = k.copy()
+    k2[cu[1]:cu[2]] += u
+    assert np.array_equal(k2[cu[1]:cu[2]].astype(np.float64), k[cu[1]:cu[2]].astype(np.float64) + u.astype(np.float64))
+    out1, lse1 = oa.attn_fwd(q, k2, v, cu, None, scale=0.4)
+    assert np.allclose(out1, out0, rtol=1e-12, atol=1e-13)
+    shift = 0.4 * np.einsum("ihd,d->hi", q[cu[1]:cu[2]].astype(np.float64), u.astype(np.float64))
+    assert np.allclose(lse1[:, cu[1]:cu[2]] - lse0[:, cu[1]:cu[2]], shift, atol=1e-12)
+    assert np.array_equal(lse1[:, :cu[1]], lse0[:, :cu[1]])
+    out2, _ = oa.attn_fwd(q, k, v * np.float32(2.0), cu, None, scale=0.4)
+    assert np.allclose(out2, 2.0 * out0, rtol=1e-14)
+
+
+def test_gqa_equals_mha_with_repeated_heads():
+    Hq, Hkv, D = 6, 2, 8
+    cu, pl, q, k, v, do = stream(8, [13, 4], Hq, Hkv, D)
+    G = Hq // Hkv
+    out, lse = oa.attn_fwd(q, k, v, cu, pl)
+    dq, dk, dv = oa.attn_bwd(q, k, v, do, cu, pl)
+    kr = np.repeat(k, G, axis=1)
+    vr = np.repeat(v, G, axis=1)
+    out2, lse2 = oa.attn_fwd(q, kr, vr, cu, pl)
+    dq2, dk2, dv2 = oa.attn_bwd(q, kr, vr, do, cu, pl)
+    assert np.array_equal(out, out2) and np.array_equal(lse, lse2) and np.array_equal(dq, dq2)
+    assert np.allclose(dk, dk2.reshape(-1, Hkv, G, D).sum(axis=2), rtol=1e-13, atol=1e-14)
+    assert np.allclose(dv, dv2.reshape(-1, Hkv, G, D).sum(axis=2), rtol=1e-13, atol=1e-14)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_packing_invariance_permutation_and_no_leak(mode):
+    Hq, Hkv, D = 4, 2, 8
+    lens = [5, 17, 1, 9]
+    cu, pl, q, k, v, do = stream(9, lens, Hq, Hkv, D)
+    plm = None if mode == oa.MASK_CAUSAL else pl
+    out, lse = oa.attn_fwd(q, k, v, cu, plm, mask_mode=mode)
+    dq, dk, dv = oa.attn_bwd(q, k, v, do, cu, plm, mask_mode=mode)
+    # each sample alone gives bit-identical rows
+    for s, L in enumerate(lens):
+        c = cu[s]
+        sl = slice(c, c + L)
+        cu1 = np.array([0, L], dtype=np.int32)
+        pl1 = None if plm is None else plm[s:s + 1]
+        o1, l1 = oa.attn_fwd(q[sl], k[sl], v[sl], cu1, pl1, mask_mode=mode)
+        g1 = oa.attn_bwd(q[sl], k[sl], v[sl], do[sl], cu1, pl1, mask_mode=mode)
+        assert np.array_equal(out[sl], o1) and np.array_equal(lse[:, sl], l1)
+        assert np.array_equal(dq[sl], g1[0]) and np.array_equal(dk[sl], g1[1]) and np.array_equal(dv[sl], g1[2])
+    # reversing the sample order permutes the results
+    order = [3, 2, 1, 0]
+    rows = np.concatenate([np.arange(cu[s], cu[s + 1]) for s in order])
+    cu_r = np.zeros(5, dtype=np.int32)
+    cu_r[1:] = np.cumsum([lens[s] for s in order])
+    pl_r = None if plm is None else plm[order]
+    out_r, lse_r = oa.attn_fwd(q[rows], k[rows], v[rows], cu_r, pl_r, mask_mode=mode)
+    assert np.array_equal(out_r, out[rows]) and np.array_equal(lse_r, lse[:, rows])
+    # NaN/Inf in another sample never reaches this one
+    q2, k2, v2, do2 = q.copy(), k.copy(), v.copy(), do.copy()
+    bad = slice(cu[1], cu[2])
+    q2[bad] = np.nan
+    k2[bad] = np.inf
+    v2[bad] = np.nan
+    do2[bad] = np.nan
+    out_n, lse_n = oa.attn_fwd(q2, k2, v2, cu, plm, mask_mode=mode)
+    g_n = oa.attn_bwd(q2, k2, v2, do2, cu, plm, mask_mode=mode)
+    keep = np.r_[0:cu[1], cu[2]:cu[4]]
+    assert np.array_equal(out_n[keep], out[keep]) and np.array_equal(lse_n[:, keep], lse[:, keep])
+    assert np.array_equal(g_n[0][keep], dq[keep]) and np.array_equal(g_n[1][keep], dk[keep]) and np.array_equal(g_n[2][keep], dv[keep])
+
+
+def test_prefix_degenerate_cases_reduce_to_bidirectional_and_causal():
+    Hq, Hkv, D = 2, 1, 8
+    lens = [6, 9]
+    cu, _, q, k, v, do = stream(10, lens, Hq, Hkv, D)
+    full = np.array(lens, dtype=np.int32)
+    zero = np.zeros(2, dtype=np.int32)
+    a, la = oa.attn_fwd(q, k, v, cu, full, mask_mode=oa.MASK_PREFIX_BIDIR_SUFFIX)
+    b, lb = oa.attn_fwd(q, k, v, cu, zero, mask_mode=oa.MASK_PREFIX_BIDIR_SUFFIX)
+    assert np.array_equal(a, b) and np.array_equal(la, lb)       # P = L and P = 0: fully bidirectional
+    c, lc = oa.attn_fwd(q, k, v, cu, zero, mask_mode=oa.MASK_PREFIX_CAUSAL_SUFFIX)
+    d, ld = oa.attn_fwd(q, k, v, cu, None, mask_mode=oa.MASK_CAUSAL)
+    assert np.array_equal(c, d) and np.array_equal(lc, ld)       # causal suffix with empty prefix = causal
+
+
+def test_sel_restricts_to_chosen_samples_and_zero_length_samples_are_legal():
+    Hq, Hkv, D = 2, 2, 4
+    lens = [4, 0, 6, 3]
+    cu, pl, q, k, v, do = stream(11, lens, Hq, Hkv, D)
+    out, lse = oa.attn_fwd(q, k, v, cu, None)
+    out_s, lse_s = oa.attn_fwd(q, k, v, cu, None, sel=[2])
+    sl = slice(cu[2], cu[3])
+    assert np.array_equal(out_s[sl], out[sl]) and np.isnan(out_s[:cu[2]]).all() and np.isnan(out_s[cu[3]:]).all()
+    assert not np.isnan(out).any() and not np.isnan(lse).any()
