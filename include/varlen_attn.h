@@ -147,13 +147,17 @@ size_t varlen_attn_bwd_workspace_bytes(const va_shape* shape);
  * Forward: O = softmax(scale * Q K^T + mask) V per sample, and LSE.
  *   q, k, v        device in   bfloat16
  *   cu_seqlens     host  in    [num_seqs + 1] (validated here: monotone, [0] = 0, last = T)
+ *   prefix_lens    host  in    [num_seqs], NULL allowed for VA_MASK_CAUSAL (validated: 0 <= P <= L);
+ *                              the kernels take each sample's P from the work list built from it
+ *   scale          positive and finite
  *   worklist       device in   copy of va_build_worklist(VA_PASS_FWD)
  *   worklist_host  host  in    the same bytes (header and bounds are validated here)
  *   out            device out  bfloat16 [T, Hq, D]
  *   lse            device out  float32 [Hq, T]
  */
 int varlen_attn_fwd(const void* q, const void* k, const void* v,
-                    const int32_t* cu_seqlens, const void* worklist, const void* worklist_host,
+                    const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                    const void* worklist, const void* worklist_host,
                     const va_shape* shape, float scale,
                     void* out, float* lse, void* stream);
 
@@ -169,7 +173,7 @@ int varlen_attn_fwd(const void* q, const void* k, const void* v,
  *   workspace           device      at least varlen_attn_bwd_workspace_bytes(shape), 256-byte aligned
  */
 int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                    const void* dout, const int32_t* cu_seqlens,
+                    const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
                     const void* worklist_dkdv, const void* worklist_dkdv_host,
                     const void* worklist_dq, const void* worklist_dq_host,
                     const va_shape* shape, float scale,
@@ -186,7 +190,8 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
  */
 int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
                         const float* q_descale, const float* k_descale, const float* v_descale,
-                        const int32_t* cu_seqlens, const void* worklist, const void* worklist_host,
+                        const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                    const void* worklist, const void* worklist_host,
                         const va_shape* shape, float scale,
                         void* out, float* lse, void* stream);
 

@@ -1,0 +1,225 @@
+"""ctypes binding of ``libvarlen_attn.so`` with the same names as the C ABI
+(``include/varlen_attn.h``).  Argument marshalling only: every step of the
+path runs in the library.  PyTorch is used for device memory and streams.
+
+The library must have been built (``python -m paper_2603_11101_amd.build``);
+there is no fallback of any kind: a missing library raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+# torch first: the library then binds to the HIP runtime torch has already loaded, so both
+# share one runtime (and one view of the device) inside the process
+import torch  # noqa: F401
+
+VA_OK = 0
+VA_EINVAL, VA_EUNSUPPORTED, VA_EALIGN, VA_ESIZE, VA_EHIP = -1, -2, -3, -4, -5
+VA_MASK_CAUSAL, VA_MASK_PREFIX_LM, VA_MASK_PREFIX_LM_CAUSAL = 0, 1, 2
+VA_PASS_FWD, VA_PASS_BWD_DKDV, VA_PASS_BWD_DQ = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvarlen_attn.so")
+
+
+class VarlenAttnError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"[{code}] {message}")
+        self.code = code
+
+
+class va_shape(ctypes.Structure):
+    _fields_ = [("total_tokens", ctypes.c_int32), ("num_seqs", ctypes.c_int32),
+                ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("max_seqlen", ctypes.c_int32),
+                ("mask_mode", ctypes.c_int32)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_11101_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    lib.va_last_error.restype = ctypes.c_char_p
+    lib.varlen_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.varlen_attn_bwd_workspace_bytes.argtypes = [ctypes.POINTER(va_shape)]
+    return lib
+
+
+_lib = _load()
+
+EXPORTS = ["va_last_error", "va_pack_first_fit", "va_bin_layout", "va_tile_shape", "va_worklist_bytes",
+           "va_build_worklist", "va_quantize_e4m3_per_head", "varlen_attn_bwd_workspace_bytes",
+           "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_fwd_fp8"]
+
+
+def _check(rc):
+    if rc != VA_OK:
+        raise VarlenAttnError(rc, _lib.va_last_error().decode())
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a):
+    """Pointer of a numpy array, a torch tensor, or None."""
+    if a is None:
+        return ctypes.c_void_p(0)
+    if isinstance(a, np.ndarray):
+        return a.ctypes.data_as(ctypes.c_void_p)
+    return ctypes.c_void_p(a.data_ptr())
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def va_last_error() -> str:
+    return _lib.va_last_error().decode()
+
+
+def va_pack_first_fit(lens, budget):
+    lens = _i32(lens)
+    n = len(lens)
+    bin_of = np.zeros(n, dtype=np.int32)
+    pos = np.zeros(n, dtype=np.int32)
+    nb = ctypes.c_int32(0)
+    _check(_lib.va_pack_first_fit(_ptr(lens), ctypes.c_int32(n), ctypes.c_int32(budget),
+                                  _ptr(bin_of), _ptr(pos), ctypes.byref(nb)))
+    return bin_of, pos, nb.value
+
+
+def va_bin_layout(lens, prefix=None):
+    lens = _i32(lens)
+    n = len(lens)
+    pre = None if prefix is None else _i32(prefix)
+    cu = np.zeros(n + 1, dtype=np.int32)
+    pl = None if prefix is None else np.zeros(n, dtype=np.int32)
+    mx = ctypes.c_int32(0)
+    _check(_lib.va_bin_layout(_ptr(lens), _ptr(pre), ctypes.c_int32(n), _ptr(cu), _ptr(pl), ctypes.byref(mx)))
+    return cu, pl, mx.value
+
+
+def va_tile_shape(pass_id, head_dim, num_q_heads, num_kv_heads):
+    rows, cols = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(_lib.va_tile_shape(ctypes.c_int32(pass_id), ctypes.c_int32(head_dim), ctypes.c_int32(num_q_heads),
+                              ctypes.c_int32(num_kv_heads), ctypes.byref(rows), ctypes.byref(cols)))
+    return rows.value, cols.value
+
+
+def va_worklist_bytes(cu_seqlens, pass_id, head_dim, num_q_heads, num_kv_heads):
+    cu = _i32(cu_seqlens)
+    nbytes = ctypes.c_size_t(0)
+    _check(_lib.va_worklist_bytes(_ptr(cu), ctypes.c_int32(len(cu) - 1), ctypes.c_int32(pass_id),
+                                  ctypes.c_int32(head_dim), ctypes.c_int32(num_q_heads),
+                                  ctypes.c_int32(num_kv_heads), ctypes.byref(nbytes)))
+    return nbytes.value
+
+
+def va_build_worklist(cu_seqlens, prefix_lens, mask_mode, pass_id, head_dim, num_q_heads, num_kv_heads):
+    """Returns the work list as an int32 array [1 + num_items, 8] (row 0 = header)."""
+    cu = _i32(cu_seqlens)
+    pl = None if prefix_lens is None else _i32(prefix_lens)
+    nbytes = va_worklist_bytes(cu, pass_id, head_dim, num_q_heads, num_kv_heads)
+    buf = np.zeros((nbytes // 32, 8), dtype=np.int32)
+    n_items = ctypes.c_int32(0)
+    _check(_lib.va_build_worklist(_ptr(cu), _ptr(pl), ctypes.c_int32(len(cu) - 1), ctypes.c_int32(mask_mode),
+                                  ctypes.c_int32(pass_id), ctypes.c_int32(head_dim), ctypes.c_int32(num_q_heads),
+                                  ctypes.c_int32(num_kv_heads), _ptr(buf), ctypes.c_size_t(nbytes),
+                                  ctypes.byref(n_items)))
+    return buf[:1 + n_items.value]
+
+
+def va_quantize_e4m3_per_head(x_bf16_bits):
+    """x: uint16 array [T, H, D] of bfloat16 bit patterns -> (uint8 codes, float32 descale[H])."""
+    x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
+    T, H, D = x.shape
+    codes = np.zeros((T, H, D), dtype=np.uint8)
+    descale = np.zeros(H, dtype=np.float32)
+    _check(_lib.va_quantize_e4m3_per_head(_ptr(x), ctypes.c_int32(T), ctypes.c_int32(H), ctypes.c_int32(D),
+                                          _ptr(codes), _ptr(descale)))
+    return codes, descale
+
+
+def make_shape(total_tokens, num_seqs, num_q_heads, num_kv_heads, head_dim, max_seqlen, mask_mode):
+    return va_shape(int(total_tokens), int(num_seqs), int(num_q_heads), int(num_kv_heads), int(head_dim),
+                    int(max_seqlen), int(mask_mode))
+
+
+def varlen_attn_bwd_workspace_bytes(shape):
+    return int(_lib.varlen_attn_bwd_workspace_bytes(ctypes.byref(shape)))
+
+
+def varlen_attn_fwd(q, k, v, cu_seqlens, prefix_lens, worklist, worklist_host, shape, scale, out, lse, stream=None):
+    cu = _i32(cu_seqlens)
+    pl = None if prefix_lens is None else _i32(prefix_lens)
+    _check(_lib.varlen_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(cu), _ptr(pl), _ptr(worklist), _ptr(worklist_host),
+                                ctypes.byref(shape), ctypes.c_float(scale), _ptr(out), _ptr(lse), _stream_ptr(stream)))
+
+
+def varlen_attn_bwd(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
+                    worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes, stream=None):
+    cu = _i32(cu_seqlens)
+    pl = None if prefix_lens is None else _i32(prefix_lens)
+    _check(_lib.varlen_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(cu), _ptr(pl),
+                                _ptr(worklist_dkdv), _ptr(worklist_dkdv_host), _ptr(worklist_dq), _ptr(worklist_dq_host),
+                                ctypes.byref(shape), ctypes.c_float(scale), _ptr(dq), _ptr(dk), _ptr(dv),
+                                _ptr(workspace), ctypes.c_size_t(workspace_bytes), _stream_ptr(stream)))
+
+
+def varlen_attn_fwd_fp8(q8, k8, v8, q_descale, k_descale, v_descale, cu_seqlens, prefix_lens, worklist, worklist_host,
+                        shape, scale, out, lse, stream=None):
+    cu = _i32(cu_seqlens)
+    pl = None if prefix_lens is None else _i32(prefix_lens)
+    _check(_lib.varlen_attn_fwd_fp8(_ptr(q8), _ptr(k8), _ptr(v8), _ptr(q_descale), _ptr(k_descale), _ptr(v_descale),
+                                    _ptr(cu), _ptr(pl), _ptr(worklist), _ptr(worklist_host), ctypes.byref(shape),
+                                    ctypes.c_float(scale), _ptr(out), _ptr(lse), _stream_ptr(stream)))
+
+
+class PackedStream:
+    """Everything the device calls need for one packed stream, kept together:
+    the host index arrays, the three work lists (host copies and device copies)
+    and the shape record.  Plumbing only."""
+
+    def __init__(self, cu_seqlens, prefix_lens, mask_mode, num_q_heads, num_kv_heads, head_dim,
+                 max_seqlen=None, device="cuda:0", passes=(VA_PASS_FWD, VA_PASS_BWD_DKDV, VA_PASS_BWD_DQ)):
+        self.cu_seqlens = _i32(cu_seqlens)
+        self.prefix_lens = None if prefix_lens is None else _i32(prefix_lens)
+        self.mask_mode = int(mask_mode)
+        n = len(self.cu_seqlens) - 1
+        lens = np.diff(self.cu_seqlens)
+        if max_seqlen is None:
+            max_seqlen = int(lens.max()) if n else 0
+        self.shape = make_shape(self.cu_seqlens[-1], n, num_q_heads, num_kv_heads, head_dim, max_seqlen, mask_mode)
+        self.worklist_host = {}
+        self.worklist = {}
+        for pid in passes:
+            wl = va_build_worklist(self.cu_seqlens, self.prefix_lens, mask_mode, pid, head_dim, num_q_heads, num_kv_heads)
+            self.worklist_host[pid] = wl
+            self.worklist[pid] = torch.from_numpy(wl).to(device)
+        self.device = device
+        self._workspace = None
+
+    def workspace(self):
+        if self._workspace is None:
+            nbytes = max(256, varlen_attn_bwd_workspace_bytes(self.shape))
+            self._workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        return self._workspace
+
+    def fwd(self, q, k, v, scale, out, lse, stream=None):
+        varlen_attn_fwd(q, k, v, self.cu_seqlens, self.prefix_lens, self.worklist[VA_PASS_FWD],
+                        self.worklist_host[VA_PASS_FWD], self.shape, scale, out, lse, stream)
+
+    def bwd(self, q, k, v, out, lse, dout, scale, dq, dk, dv, stream=None):
+        ws = self.workspace()
+        varlen_attn_bwd(q, k, v, out, lse, dout, self.cu_seqlens, self.prefix_lens,
+                        self.worklist[VA_PASS_BWD_DKDV], self.worklist_host[VA_PASS_BWD_DKDV],
+                        self.worklist[VA_PASS_BWD_DQ], self.worklist_host[VA_PASS_BWD_DQ],
+                        self.shape, scale, dq, dk, dv, ws, ws.numel(), stream)
+
+    def fwd_fp8(self, q8, k8, v8, q_descale, k_descale, v_descale, scale, out, lse, stream=None):
+        varlen_attn_fwd_fp8(q8, k8, v8, q_descale, k_descale, v_descale, self.cu_seqlens, self.prefix_lens,
+                            self.worklist[VA_PASS_FWD], self.worklist_host[VA_PASS_FWD], self.shape, scale,
+                            out, lse, stream)

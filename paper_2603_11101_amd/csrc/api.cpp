@@ -1,0 +1,225 @@
+// C-ABI device entry points: argument validation on the host, then kernel
+// launches on the caller's stream.  No allocation, no synchronisation.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "kernels.h"
+
+using namespace va;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens, const char* who) {
+    if (!s || !cu) return fail(VA_EINVAL, "%s: null shape or cu_seqlens", who);
+    if (s->mask_mode != VA_MASK_CAUSAL && !prefix_lens)
+        return fail(VA_EINVAL, "%s: a prefix mask needs prefix_lens", who);
+    if (s->head_dim != 64 && s->head_dim != 128 && s->head_dim != 256)
+        return fail(VA_EUNSUPPORTED, "%s: head_dim %d not in {64,128,256}", who, s->head_dim);
+    if (s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->num_q_heads % s->num_kv_heads != 0)
+        return fail(VA_EUNSUPPORTED, "%s: num_q_heads %d is not a positive multiple of num_kv_heads %d", who,
+                    s->num_q_heads, s->num_kv_heads);
+    if (s->mask_mode < VA_MASK_CAUSAL || s->mask_mode > VA_MASK_PREFIX_LM_CAUSAL)
+        return fail(VA_EUNSUPPORTED, "%s: unknown mask mode %d", who, s->mask_mode);
+    if (s->num_seqs < 0 || s->total_tokens < 0) return fail(VA_EINVAL, "%s: negative sizes", who);
+    if (cu[0] != 0) return fail(VA_EINVAL, "%s: cu_seqlens[0] = %d, expected 0", who, cu[0]);
+    for (int32_t i = 0; i < s->num_seqs; ++i) {
+        const int32_t L = cu[i + 1] - cu[i];
+        if (L < 0) return fail(VA_EINVAL, "%s: cu_seqlens decreases at sample %d", who, i);
+        if (L > s->max_seqlen)
+            return fail(VA_ESIZE, "%s: sample %d has %d tokens, max_seqlen is %d", who, i, L, s->max_seqlen);
+        if (s->mask_mode != VA_MASK_CAUSAL && (prefix_lens[i] < 0 || prefix_lens[i] > L))
+            return fail(VA_EINVAL, "%s: prefix_lens[%d] = %d outside [0, %d]", who, i, prefix_lens[i], L);
+    }
+    if (cu[s->num_seqs] != s->total_tokens)
+        return fail(VA_EINVAL, "%s: cu_seqlens ends at %d, total_tokens is %d", who, cu[s->num_seqs], s->total_tokens);
+    // element offsets are computed in size_t on the device; the row index itself is int32
+    return VA_OK;
+}
+
+// The host copy of a work list is checked against the stream it claims to
+// describe: header fields, and every item must lie inside one sample.
+int check_worklist(const void* dev, const void* host, const va_shape* s, const int32_t* cu, int32_t pass,
+                   const char* who, int32_t* num_items) {
+    if (!dev || !host) return fail(VA_EINVAL, "%s: null work list", who);
+    const WorkItem* w = static_cast<const WorkItem*>(host);
+    int32_t rows, cols;
+    int rc = tile_shape(pass, s->head_dim, s->num_q_heads, s->num_kv_heads, &rows, &cols);
+    if (rc) return rc;
+    const int32_t* h = w[0].w;
+    if (h[0] != kWorklistMagic || h[1] != pass || h[2] != rows || h[3] != cols || h[4] != s->head_dim ||
+        h[5] != s->mask_mode || h[6] < 0 || h[7] != s->total_tokens)
+        return fail(VA_EINVAL, "%s: work list header does not match this call (pass %d, tile %dx%d, head_dim %d, mask %d, T %d)",
+                    who, pass, rows, cols, s->head_dim, s->mask_mode, s->total_tokens);
+    const int32_t n = h[6];
+    int64_t expect = 0;
+    for (int32_t i = 0; i < s->num_seqs; ++i) expect += (cu[i + 1] - cu[i] + rows - 1) / rows;
+    if (n != expect) return fail(VA_EINVAL, "%s: work list holds %d items, this stream needs %lld", who, n, (long long)expect);
+    for (int32_t i = 1; i <= n; ++i) {
+        const int32_t* it = w[i].w;
+        const int32_t row0 = it[0], nrows = it[1], seq0 = it[2], L = it[7];
+        const bool ok = nrows > 0 && nrows <= rows && seq0 >= 0 && L > 0 && row0 >= seq0 && row0 + nrows <= seq0 + L &&
+                        seq0 + L <= s->total_tokens && it[6] <= L && (row0 - seq0) % rows == 0;
+        if (!ok) return fail(VA_EINVAL, "%s: work item %d is out of bounds", who, i - 1);
+        // (seq0, L) must be one of the samples of cu_seqlens
+        const int32_t* lo = std::lower_bound(cu, cu + s->num_seqs, seq0);
+        while (lo < cu + s->num_seqs && lo[0] == seq0 && lo[1] == seq0) ++lo;  // skip empty samples at this row
+        if (lo >= cu + s->num_seqs || lo[0] != seq0 || lo[1] - lo[0] != L)
+            return fail(VA_EINVAL, "%s: work item %d does not match a sample of cu_seqlens", who, i - 1);
+        if (pass == VA_PASS_BWD_DKDV) {
+            if (it[3] < 0 || it[4] <= 0 || it[3] + it[4] != (L + cols - 1) / cols)
+                return fail(VA_EINVAL, "%s: work item %d has a bad query-tile range", who, i - 1);
+        } else {
+            if (it[3] <= 0 || it[3] > L || it[5] != (it[3] + cols - 1) / cols || it[4] < 0 || it[4] > it[5])
+                return fail(VA_EINVAL, "%s: work item %d has a bad key range", who, i - 1);
+        }
+    }
+    *num_items = n;
+    return VA_OK;
+}
+
+int check_scale(float scale, const char* who) {
+    if (!(scale > 0.0f) || !std::isfinite(scale)) return fail(VA_EINVAL, "%s: scale must be positive and finite", who);
+    return VA_OK;
+}
+
+AttnParams base_params(const va_shape* s, float scale) {
+    AttnParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.T = s->total_tokens;
+    p.Hq = s->num_q_heads;
+    p.Hkv = s->num_kv_heads;
+    p.D = s->head_dim;
+    p.mask_mode = s->mask_mode;
+    p.scale = scale;
+    return p;
+}
+
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+size_t varlen_attn_bwd_workspace_bytes(const va_shape* s) {
+    if (!s || s->total_tokens < 0 || s->num_q_heads <= 0) return 0;
+    // delta = rowsum(dO * O), float32 [Hq, T]
+    return round_up((size_t)s->total_tokens * (size_t)s->num_q_heads * sizeof(float), 256);
+}
+
+int varlen_attn_fwd(const void* q, const void* k, const void* v,
+                    const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                    const void* worklist, const void* worklist_host,
+                    const va_shape* shape, float scale,
+                    void* out, float* lse, void* stream) {
+    const char* who = "varlen_attn_fwd";
+    int rc = check_shape(shape, cu_seqlens, prefix_lens, who);
+    if (rc) return rc;
+    if ((rc = check_scale(scale, who))) return rc;
+    if (shape->total_tokens == 0) return VA_OK;
+    if (!q || !k || !v || !out || !lse) return fail(VA_EINVAL, "%s: null tensor pointer", who);
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
+        return fail(VA_EALIGN, "%s: tensor pointers must be 16-byte aligned", who);
+    int32_t n_items = 0;
+    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, VA_PASS_FWD, who, &n_items))) return rc;
+    AttnParams p = base_params(shape, scale);
+    p.q = q;
+    p.k = k;
+    p.v = v;
+    p.out = out;
+    p.lse = lse;
+    p.items = static_cast<const WorkItem*>(worklist) + 1;
+    p.num_items = n_items;
+    hipError_t e = launch_fwd_bf16(p, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    return VA_OK;
+}
+
+int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                    const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                    const void* worklist_dkdv, const void* worklist_dkdv_host,
+                    const void* worklist_dq, const void* worklist_dq_host,
+                    const va_shape* shape, float scale,
+                    void* dq, void* dk, void* dv,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+    const char* who = "varlen_attn_bwd";
+    int rc = check_shape(shape, cu_seqlens, prefix_lens, who);
+    if (rc) return rc;
+    if ((rc = check_scale(scale, who))) return rc;
+    if (shape->total_tokens == 0) return VA_OK;
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace)
+        return fail(VA_EINVAL, "%s: null tensor pointer", who);
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse) || !aligned16(dout) ||
+        !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+        return fail(VA_EALIGN, "%s: tensor pointers must be 16-byte aligned", who);
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return fail(VA_EALIGN, "%s: workspace must be 256-byte aligned", who);
+    if (workspace_bytes < varlen_attn_bwd_workspace_bytes(shape))
+        return fail(VA_ESIZE, "%s: workspace of %zu bytes, need %zu", who, workspace_bytes,
+                    varlen_attn_bwd_workspace_bytes(shape));
+    int32_t n_dkdv = 0, n_dq = 0;
+    if ((rc = check_worklist(worklist_dkdv, worklist_dkdv_host, shape, cu_seqlens, VA_PASS_BWD_DKDV, who, &n_dkdv))) return rc;
+    if ((rc = check_worklist(worklist_dq, worklist_dq_host, shape, cu_seqlens, VA_PASS_BWD_DQ, who, &n_dq))) return rc;
+    AttnParams p = base_params(shape, scale);
+    p.q = q;
+    p.k = k;
+    p.v = v;
+    p.out = const_cast<void*>(out);
+    p.lse = const_cast<float*>(lse);
+    p.dout = dout;
+    p.dq = dq;
+    p.dk = dk;
+    p.dv = dv;
+    p.delta = static_cast<float*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_bwd_delta(p, st);
+    if (e == hipSuccess) {
+        p.items = static_cast<const WorkItem*>(worklist_dkdv) + 1;
+        p.num_items = n_dkdv;
+        e = launch_bwd_dkdv(p, st);
+    }
+    if (e == hipSuccess) {
+        p.items = static_cast<const WorkItem*>(worklist_dq) + 1;
+        p.num_items = n_dq;
+        e = launch_bwd_dq(p, st);
+    }
+    if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    return VA_OK;
+}
+
+int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
+                        const float* q_descale, const float* k_descale, const float* v_descale,
+                        const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                    const void* worklist, const void* worklist_host,
+                        const va_shape* shape, float scale,
+                        void* out, float* lse, void* stream) {
+    const char* who = "varlen_attn_fwd_fp8";
+    int rc = check_shape(shape, cu_seqlens, prefix_lens, who);
+    if (rc) return rc;
+    if ((rc = check_scale(scale, who))) return rc;
+    if (shape->total_tokens == 0) return VA_OK;
+    if (!q8 || !k8 || !v8 || !q_descale || !k_descale || !v_descale || !out || !lse)
+        return fail(VA_EINVAL, "%s: null tensor pointer", who);
+    if (!aligned16(q8) || !aligned16(k8) || !aligned16(v8) || !aligned16(out) || !aligned16(lse))
+        return fail(VA_EALIGN, "%s: tensor pointers must be 16-byte aligned", who);
+    int32_t n_items = 0;
+    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, VA_PASS_FWD, who, &n_items))) return rc;
+    AttnParams p = base_params(shape, scale);
+    p.q = q8;
+    p.k = k8;
+    p.v = v8;
+    p.q_descale = q_descale;
+    p.k_descale = k_descale;
+    p.v_descale = v_descale;
+    p.out = out;
+    p.lse = lse;
+    p.items = static_cast<const WorkItem*>(worklist) + 1;
+    p.num_items = n_items;
+    hipError_t e = launch_fwd_fp8(p, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    return VA_OK;
+}
+
+}  // extern "C"

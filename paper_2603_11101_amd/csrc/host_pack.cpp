@@ -1,0 +1,261 @@
+// Host-side integer work of the packed variable-length attention library:
+// first-fit packing, per-bin layout, tile shapes, per-tile work lists and the
+// per-head E4M3 quantiser.  Pure host code; nothing here touches the GPU.
+//
+// Paper: section 2.2.1 (2) "Data Packing" (samples are concatenated into
+// sequences close to the maximum context length, no padding tokens) and
+// section 2.2.1 (1) (compute on valid tokens only).  The paper names no bin
+// rule; online first-fit in arrival order is this library's reading.
+#include "common.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+namespace va {
+
+thread_local char g_error[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// Number of keys local query row i of a sample (length L, prefix P) may see.
+static inline int32_t visible(int32_t i, int32_t L, int32_t P, int32_t mode) {
+    if (mode == VA_MASK_CAUSAL) return i + 1;
+    if (i < P) return P;
+    return mode == VA_MASK_PREFIX_LM ? L : i + 1;
+}
+
+// Heads of one KV group that a forward / dQ workgroup stacks on its 128 rows.
+int heads_per_block(int32_t Hq, int32_t Hkv) {
+    const int G = Hq / Hkv;
+    int hpb = 1;
+    while (hpb * 2 <= 8 && G % (hpb * 2) == 0) hpb *= 2;
+    return hpb;
+}
+
+int tile_shape(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t* rows, int32_t* cols) {
+    if (D != 64 && D != 128 && D != 256) return fail(VA_EUNSUPPORTED, "head_dim %d not in {64,128,256}", D);
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0)
+        return fail(VA_EUNSUPPORTED, "num_q_heads %d is not a positive multiple of num_kv_heads %d", Hq, Hkv);
+    switch (pass) {
+        case VA_PASS_FWD:
+            *rows = kFwdBlockRows / heads_per_block(Hq, Hkv);
+            *cols = kFwdKvTile;
+            return VA_OK;
+        case VA_PASS_BWD_DQ:
+            *rows = kDqBlockRows / heads_per_block(Hq, Hkv);
+            *cols = kDqKvTile;
+            return VA_OK;
+        case VA_PASS_BWD_DKDV:
+            *rows = kDkdvKvRows;
+            *cols = kDkdvQTile;
+            return VA_OK;
+        default:
+            return fail(VA_EUNSUPPORTED, "unknown pass %d", pass);
+    }
+}
+
+}  // namespace va
+
+using namespace va;
+
+extern "C" {
+
+const char* va_last_error(void) { return g_error; }
+
+int va_pack_first_fit(const int32_t* lens, int32_t N, int32_t budget,
+                      int32_t* bin_of_sample, int32_t* pos_in_bin, int32_t* num_bins) {
+    if (N < 0 || budget < 0 || !num_bins || (N > 0 && (!lens || !bin_of_sample || !pos_in_bin)))
+        return fail(VA_EINVAL, "va_pack_first_fit: null pointer or negative size");
+    for (int32_t i = 0; i < N; ++i) {
+        if (lens[i] < 0) return fail(VA_EINVAL, "va_pack_first_fit: lens[%d] = %d is negative", i, lens[i]);
+        if (lens[i] > budget)
+            return fail(VA_ESIZE, "va_pack_first_fit: lens[%d] = %d exceeds the budget %d", i, lens[i], budget);
+    }
+    std::vector<int32_t> free_tokens, count;
+    for (int32_t i = 0; i < N; ++i) {
+        size_t b = 0;
+        while (b < free_tokens.size() && free_tokens[b] < lens[i]) ++b;
+        if (b == free_tokens.size()) {
+            free_tokens.push_back(budget);
+            count.push_back(0);
+        }
+        free_tokens[b] -= lens[i];
+        bin_of_sample[i] = (int32_t)b;
+        pos_in_bin[i] = count[b]++;
+    }
+    *num_bins = (int32_t)free_tokens.size();
+    return VA_OK;
+}
+
+int va_bin_layout(const int32_t* lens, const int32_t* prefix, int32_t n,
+                  int32_t* cu_seqlens, int32_t* prefix_lens, int32_t* max_seqlen) {
+    if (n < 0 || !cu_seqlens || !max_seqlen || (n > 0 && !lens) || (prefix && !prefix_lens))
+        return fail(VA_EINVAL, "va_bin_layout: null pointer or negative size");
+    int64_t sum = 0;
+    int32_t mx = 0;
+    for (int32_t s = 0; s < n; ++s) {
+        if (lens[s] < 0) return fail(VA_EINVAL, "va_bin_layout: lens[%d] is negative", s);
+        if (prefix && (prefix[s] < 0 || prefix[s] > lens[s]))
+            return fail(VA_EINVAL, "va_bin_layout: prefix[%d] = %d outside [0, %d]", s, prefix[s], lens[s]);
+        sum += lens[s];
+        if (sum > INT32_MAX) return fail(VA_ESIZE, "va_bin_layout: more than 2^31-1 tokens");
+        mx = std::max(mx, lens[s]);
+    }
+    cu_seqlens[0] = 0;
+    for (int32_t s = 0; s < n; ++s) {
+        cu_seqlens[s + 1] = cu_seqlens[s] + lens[s];
+        if (prefix) prefix_lens[s] = prefix[s];
+    }
+    *max_seqlen = mx;
+    return VA_OK;
+}
+
+int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t num_kv_heads,
+                  int32_t* rows, int32_t* cols) {
+    if (!rows || !cols) return fail(VA_EINVAL, "va_tile_shape: null pointer");
+    return tile_shape(pass, head_dim, num_q_heads, num_kv_heads, rows, cols);
+}
+
+static int check_cu(const int32_t* cu, int32_t n, const char* who) {
+    if (n < 0 || !cu) return fail(VA_EINVAL, "%s: null cu_seqlens or negative num_seqs", who);
+    if (cu[0] != 0) return fail(VA_EINVAL, "%s: cu_seqlens[0] = %d, expected 0", who, cu[0]);
+    for (int32_t s = 0; s < n; ++s)
+        if (cu[s + 1] < cu[s]) return fail(VA_EINVAL, "%s: cu_seqlens decreases at %d", who, s);
+    return VA_OK;
+}
+
+int va_worklist_bytes(const int32_t* cu, int32_t n, int32_t pass, int32_t D,
+                      int32_t Hq, int32_t Hkv, size_t* bytes) {
+    if (!bytes) return fail(VA_EINVAL, "va_worklist_bytes: null pointer");
+    int rc = check_cu(cu, n, "va_worklist_bytes");
+    if (rc) return rc;
+    int32_t rows, cols;
+    rc = tile_shape(pass, D, Hq, Hkv, &rows, &cols);
+    if (rc) return rc;
+    size_t items = 0;
+    for (int32_t s = 0; s < n; ++s) items += (size_t)((cu[s + 1] - cu[s] + rows - 1) / rows);
+    *bytes = (items + 1) * sizeof(WorkItem);
+    return VA_OK;
+}
+
+int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
+                      int32_t mask_mode, int32_t pass, int32_t D, int32_t Hq, int32_t Hkv,
+                      void* host_out, size_t bytes, int32_t* num_items) {
+    if (!host_out || !num_items) return fail(VA_EINVAL, "va_build_worklist: null pointer");
+    if (mask_mode < VA_MASK_CAUSAL || mask_mode > VA_MASK_PREFIX_LM_CAUSAL)
+        return fail(VA_EUNSUPPORTED, "va_build_worklist: unknown mask mode %d", mask_mode);
+    if (mask_mode != VA_MASK_CAUSAL && !prefix_lens)
+        return fail(VA_EINVAL, "va_build_worklist: prefix mask needs prefix_lens");
+    size_t need;
+    int rc = va_worklist_bytes(cu, n, pass, D, Hq, Hkv, &need);
+    if (rc) return rc;
+    if (bytes < need) return fail(VA_ESIZE, "va_build_worklist: buffer of %zu bytes, need %zu", bytes, need);
+    int32_t bm, bn;  // rows of an item, rows of the tiles it loops over
+    tile_shape(pass, D, Hq, Hkv, &bm, &bn);
+
+    struct Keyed {
+        int32_t work;
+        WorkItem it;
+    };
+    std::vector<Keyed> items;
+    for (int32_t s = 0; s < n; ++s) {
+        const int32_t c = cu[s], L = cu[s + 1] - c;
+        int32_t P = -1;
+        if (mask_mode != VA_MASK_CAUSAL) {
+            P = prefix_lens[s];
+            if (P < 0 || P > L)
+                return fail(VA_EINVAL, "va_build_worklist: prefix_lens[%d] = %d outside [0, %d]", s, P, L);
+        }
+        const int32_t Pm = P < 0 ? 0 : P;
+        if (pass == VA_PASS_BWD_DKDV) {
+            // item rows are key rows (bm), inner tiles are query tiles (bn)
+            const int32_t q_tiles = (L + bn - 1) / bn;
+            for (int32_t j0 = 0; j0 < L; j0 += bm) {
+                int32_t first_row;  // first query row that sees key j0
+                if (mask_mode == VA_MASK_CAUSAL) first_row = j0;
+                else if (j0 < Pm) first_row = 0;
+                else first_row = mask_mode == VA_MASK_PREFIX_LM ? Pm : j0;
+                const int32_t qt_first = first_row / bn;
+                WorkItem it = {{c + j0, std::min(bm, L - j0), c, qt_first, q_tiles - qt_first, 0, P, L}};
+                items.push_back({it.w[4], it});
+            }
+        } else {
+            for (int32_t r0 = 0; r0 < L; r0 += bm) {
+                const int32_t rows = std::min(bm, L - r0);
+                const int32_t kv_len = visible(r0 + rows - 1, L, Pm, mask_mode);
+                const int32_t n_tiles = (kv_len + bn - 1) / bn;
+                const int32_t n_full = visible(r0, L, Pm, mask_mode) / bn;
+                WorkItem it = {{c + r0, rows, c, kv_len, n_full, n_tiles, P, L}};
+                items.push_back({n_tiles, it});
+            }
+        }
+    }
+    std::stable_sort(items.begin(), items.end(), [](const Keyed& a, const Keyed& b) { return a.work > b.work; });
+    WorkItem* out = static_cast<WorkItem*>(host_out);
+    out[0] = {{kWorklistMagic, pass, bm, bn, D, mask_mode, (int32_t)items.size(), cu[n]}};
+    for (size_t i = 0; i < items.size(); ++i) out[i + 1] = items[i].it;
+    *num_items = (int32_t)items.size();
+    return VA_OK;
+}
+
+// bfloat16 bits -> float
+static inline float bf16_to_float(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+// Round-to-nearest-even E4M3 (OCP, "fn": no infinities, NaN = 0x7F), saturating.
+static inline uint8_t encode_e4m3(float x) {
+    if (std::isnan(x)) return 0x7F;
+    const uint8_t sign = std::signbit(x) ? 0x80 : 0x00;
+    const float a = std::fabs(x);
+    if (a >= 448.0f) return sign | 0x7E;
+    if (a < 0.015625f) {  // below 2^-6: subnormal spacing 2^-9; a result of 8 is the first normal
+        return sign | (uint8_t)std::nearbyintf(a * 512.0f);
+    }
+    int e;
+    const float frac = std::frexp(a, &e);  // a = frac * 2^e, frac in [0.5, 1)
+    int m = (int)std::nearbyintf((frac * 2.0f - 1.0f) * 8.0f);
+    e -= 1;
+    if (m == 8) {
+        m = 0;
+        e += 1;
+    }
+    return sign | (uint8_t)(((e + 7) << 3) | m);
+}
+
+int va_quantize_e4m3_per_head(const uint16_t* x, int32_t T, int32_t H, int32_t D,
+                              uint8_t* codes, float* descale) {
+    if (T < 0 || H <= 0 || D <= 0 || !descale || (T > 0 && (!x || !codes)))
+        return fail(VA_EINVAL, "va_quantize_e4m3_per_head: null pointer or bad size");
+    std::vector<float> amax((size_t)H, 0.0f);
+    for (int64_t t = 0; t < T; ++t)
+        for (int32_t h = 0; h < H; ++h) {
+            const uint16_t* row = x + ((size_t)t * H + h) * D;
+            float m = amax[h];
+            for (int32_t d = 0; d < D; ++d) m = std::max(m, std::fabs(bf16_to_float(row[d])));
+            amax[h] = m;
+        }
+    for (int32_t h = 0; h < H; ++h) {
+        const float s = amax[h] / 448.0f;
+        descale[h] = s > 0.0f ? s : 1.0f;
+    }
+    for (int64_t t = 0; t < T; ++t)
+        for (int32_t h = 0; h < H; ++h) {
+            const size_t base = ((size_t)t * H + h) * D;
+            for (int32_t d = 0; d < D; ++d) codes[base + d] = encode_e4m3(bf16_to_float(x[base + d]) / descale[h]);
+        }
+    return VA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,38 @@
+// Launch interfaces between the C-ABI layer (api.cpp) and the kernel
+// translation units.  Every launcher only enqueues on `stream`.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+
+namespace va {
+
+struct AttnParams {
+    const void* q;        // [T, Hq, D]
+    const void* k;        // [T, Hkv, D]
+    const void* v;        // [T, Hkv, D]
+    void* out;            // [T, Hq, D]
+    float* lse;           // [Hq, T]
+    const void* dout;     // [T, Hq, D]
+    void* dq;             // [T, Hq, D]
+    void* dk;             // [T, Hkv, D]
+    void* dv;             // [T, Hkv, D]
+    float* delta;         // [Hq, T]  rowsum(dO * O)
+    const float* q_descale;  // fp8 only
+    const float* k_descale;
+    const float* v_descale;
+    const WorkItem* items;   // device, header skipped
+    int32_t num_items;
+    int32_t T, Hq, Hkv, D;
+    int32_t mask_mode;
+    float scale;
+};
+
+hipError_t launch_fwd_bf16(const AttnParams& p, hipStream_t stream);
+hipError_t launch_fwd_fp8(const AttnParams& p, hipStream_t stream);
+hipError_t launch_bwd_delta(const AttnParams& p, hipStream_t stream);
+hipError_t launch_bwd_dkdv(const AttnParams& p, hipStream_t stream);
+hipError_t launch_bwd_dq(const AttnParams& p, hipStream_t stream);
+
+}  // namespace va

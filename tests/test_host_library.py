@@ -1,0 +1,178 @@
+"""CPU-only tests of the built library: it loads, exports every symbol the
+header declares, and its host-side integer work (first-fit packing, layout,
+work lists, E4M3 quantiser) equals the oracle's bit for bit.  Device entry
+points are only driven into their host-side validation errors here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import e4m3 as oe
+from oracle import packing as op
+from paper_2603_11101_amd import binding as va
+from paper_2603_11101_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "varlen_attn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(va_\w+|varlen_attn_\w+)\s*\(", header))
+    assert declared == set(va.EXPORTS)
+    lib = ctypes.CDLL(va.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_first_fit_and_layout_equal_oracle_on_every_workload():
+    for name, w in wl.WORKLOADS.items():
+        lens, prefix = wl.sample_lengths(name)
+        b, p, n = va.va_pack_first_fit(lens, w.budget)
+        ob, opos, on = op.first_fit(lens, w.budget)
+        assert n == on and np.array_equal(b, ob) and np.array_equal(p, opos)
+        for bin_id in (0, n - 1):
+            idx = op.bin_members(ob, opos, bin_id)
+            cu, pl, mx = va.va_bin_layout(lens[idx], None if prefix is None else prefix[idx])
+            ocu, opl, omx = op.bin_layout(lens[idx], None if prefix is None else prefix[idx])
+            assert np.array_equal(cu, ocu) and mx == omx and cu.dtype == np.int32
+            assert (pl is None and opl is None) or np.array_equal(pl, opl)
+
+
+def test_first_fit_random_and_edge_cases():
+    r = np.random.default_rng(5)
+    for trial in range(20):
+        budget = int(r.integers(1, 500))
+        lens = r.integers(0, budget + 1, size=int(r.integers(0, 200)))
+        b, p, n = va.va_pack_first_fit(lens, budget)
+        ob, opos, on = op.first_fit(lens, budget)
+        assert n == on and np.array_equal(b, ob) and np.array_equal(p, opos)
+    with pytest.raises(va.VarlenAttnError) as e:
+        va.va_pack_first_fit([5, 11], 10)
+    assert e.value.code == va.VA_ESIZE and "exceeds the budget" in str(e.value)
+    with pytest.raises(va.VarlenAttnError) as e:
+        va.va_pack_first_fit([5, -1], 10)
+    assert e.value.code == va.VA_EINVAL
+    with pytest.raises(va.VarlenAttnError) as e:
+        va.va_bin_layout([5, 3], [2, 4])
+    assert e.value.code == va.VA_EINVAL
+
+
+HEADS = [(2, 2, 64), (16, 8, 128), (8, 1, 256), (4, 1, 64), (6, 2, 128)]
+
+
+@pytest.mark.parametrize("mode", [va.VA_MASK_CAUSAL, va.VA_MASK_PREFIX_LM, va.VA_MASK_PREFIX_LM_CAUSAL])
+@pytest.mark.parametrize("Hq,Hkv,D", HEADS)
+def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
+    r = np.random.default_rng(Hq * 1000 + D + mode)
+    lens = np.concatenate([[1, 0, 300, 129, 64, 17], r.integers(1, 260, size=5)]).astype(np.int32)
+    cu, _, _ = va.va_bin_layout(lens)
+    prefix = None if mode == va.VA_MASK_CAUSAL else np.array([int(r.integers(0, L + 1)) for L in lens], dtype=np.int32)
+    if prefix is not None:
+        prefix[2], prefix[3] = 300, 0    # degenerate: whole sample is prefix / no prefix at all
+    for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DKDV, va.VA_PASS_BWD_DQ):
+        rows, cols = va.va_tile_shape(pass_id, D, Hq, Hkv)
+        got = va.va_build_worklist(cu, prefix, mode, pass_id, D, Hq, Hkv)
+        header, items = got[0], got[1:]
+        assert header[1] == pass_id and header[2] == rows and header[3] == cols and header[4] == D
+        assert header[5] == mode and header[6] == len(items) and header[7] == cu[-1]
+        # the oracle names tile sizes by role: bm = query rows, bn = key rows
+        bm, bn = (cols, rows) if pass_id == va.VA_PASS_BWD_DKDV else (rows, cols)
+        want = op.build_worklist(cu, prefix, pass_id, bm, bn, mode)
+        assert np.array_equal(items, want)
+    # brute-force coverage of the library's own lists on a smaller stream (quadratic check)
+    small = np.array([1, 70, 33, 130], dtype=np.int32)
+    cu_s, _, _ = va.va_bin_layout(small)
+    pre_s = None if mode == va.VA_MASK_CAUSAL else np.array([1, 40, 0, 97], dtype=np.int32)
+    for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DKDV, va.VA_PASS_BWD_DQ):
+        rows, cols = va.va_tile_shape(pass_id, D, Hq, Hkv)
+        bm, bn = (cols, rows) if pass_id == va.VA_PASS_BWD_DKDV else (rows, cols)
+        items = va.va_build_worklist(cu_s, pre_s, mode, pass_id, D, Hq, Hkv)[1:]
+        op.check_coverage(items, cu_s, pre_s, pass_id, bm, bn, mode)
+
+
+def test_worklist_counts_on_the_workloads():
+    # closed-form item and key-tile counts for the first bin of each workload
+    for name in ("vlm", "pi05", "longtail"):
+        w = wl.WORKLOADS[name]
+        lens, prefix = wl.sample_lengths(name)
+        b, p, n = va.va_pack_first_fit(lens, w.budget)
+        idx = op.bin_members(b, p, 0)
+        cu, pl, mx = va.va_bin_layout(lens[idx], None if prefix is None else prefix[idx])
+        mode = va.VA_MASK_PREFIX_LM if w.prefix_lm else va.VA_MASK_CAUSAL
+        rows, cols = va.va_tile_shape(va.VA_PASS_FWD, w.head_dim, w.num_q_heads, w.num_kv_heads)
+        items = va.va_build_worklist(cu, pl, mode, va.VA_PASS_FWD, w.head_dim, w.num_q_heads, w.num_kv_heads)[1:]
+        assert len(items) == sum(-(-int(L) // rows) for L in lens[idx])
+        if not w.prefix_lm:
+            want_tiles = sum(-(-min(int(L), (t + 1) * rows) // cols) for L in lens[idx] for t in range(-(-int(L) // rows)))
+            assert int(items[:, 5].sum()) == want_tiles
+        assert np.all(np.diff(items[:, 5]) <= 0)
+
+
+def test_tile_shape_errors():
+    for bad in ((va.VA_PASS_FWD, 96, 4, 2), (va.VA_PASS_FWD, 128, 5, 2), (7, 128, 4, 2)):
+        with pytest.raises(va.VarlenAttnError) as e:
+            va.va_tile_shape(*bad)
+        assert e.value.code == va.VA_EUNSUPPORTED
+
+
+def test_e4m3_quantiser_equals_oracle_bit_for_bit():
+    r = np.random.default_rng(9)
+    x = wl.round_to_bf16((r.standard_normal((300, 5, 64)) * np.array([1e-3, 0.1, 1.0, 30.0, 0.0])[None, :, None]).astype(np.float32))
+    codes, descale = va.va_quantize_e4m3_per_head(wl.bf16_bits(x))
+    ocodes, odescale = oe.quantize_per_head(x)
+    assert np.array_equal(descale, odescale) and np.array_equal(codes, ocodes)
+    # every representable magnitude and every midpoint, scaled so that descale = 1
+    vals = [oe.decode_scalar(c) for c in range(0x7F)]
+    mids = [(vals[i] + vals[i + 1]) / 2 for i in range(0x7E)]
+    probe = np.array(vals + mids + [448.0], dtype=np.float32)
+    probe = probe[wl.round_to_bf16(probe) == probe]           # keep those bf16 can hold exactly
+    probe = np.concatenate([probe, -probe]).reshape(-1, 1, 1)
+    probe = np.concatenate([probe, np.full((1, 1, 1), 448.0, dtype=np.float32)])
+    codes, descale = va.va_quantize_e4m3_per_head(wl.bf16_bits(probe))
+    assert descale[0] == 1.0 and np.array_equal(codes, oe.encode(probe))
+
+
+def _fake(n=1 << 12):
+    return np.zeros(n, dtype=np.uint8)
+
+
+def test_device_entry_points_reject_bad_arguments_on_the_host():
+    Hq, Hkv, D = 4, 2, 64
+    cu = np.array([0, 40, 100], dtype=np.int32)
+    wl_h = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_FWD, D, Hq, Hkv)
+    buf = _fake()
+    lse = np.zeros(1024, dtype=np.float32)
+
+    def call(shape, cu_=cu, wl_=wl_h, q=buf, scale=0.125, prefix=None):
+        # stream pointer 0 is never reached: validation fails first
+        rc = va._lib.varlen_attn_fwd(va._ptr(q), va._ptr(buf), va._ptr(buf), va._ptr(cu_), va._ptr(prefix), va._ptr(wl_),
+                                     va._ptr(wl_), ctypes.byref(shape), ctypes.c_float(scale), va._ptr(buf),
+                                     va._ptr(lse), ctypes.c_void_p(0))
+        return rc, va.va_last_error()
+
+    ok = dict(total_tokens=100, num_seqs=2, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, max_seqlen=60,
+              mask_mode=va.VA_MASK_CAUSAL)
+    assert call(va.make_shape(**{**ok, "head_dim": 96}))[0] == va.VA_EUNSUPPORTED
+    assert call(va.make_shape(**{**ok, "num_q_heads": 3}))[0] == va.VA_EUNSUPPORTED
+    assert call(va.make_shape(**{**ok, "max_seqlen": 59}))[0] == va.VA_ESIZE
+    assert call(va.make_shape(**{**ok, "total_tokens": 101}))[0] == va.VA_EINVAL
+    assert call(va.make_shape(**ok), cu_=np.array([0, 60, 40], dtype=np.int32))[0] == va.VA_EINVAL
+    assert call(va.make_shape(**ok), cu_=np.array([1, 40, 100], dtype=np.int32))[0] == va.VA_EINVAL
+    assert call(va.make_shape(**ok), scale=0.0)[0] == va.VA_EINVAL
+    assert call(va.make_shape(**ok), scale=float("nan"))[0] == va.VA_EINVAL
+    assert call(va.make_shape(**{**ok, "mask_mode": va.VA_MASK_PREFIX_LM}))[0] == va.VA_EINVAL      # no prefix_lens
+    assert call(va.make_shape(**{**ok, "mask_mode": va.VA_MASK_PREFIX_LM}),
+                prefix=np.array([41, 0], dtype=np.int32))[0] == va.VA_EINVAL
+    rc, msg = call(va.make_shape(**ok), q=buf[1:])
+    assert rc == va.VA_EALIGN and "aligned" in msg
+    # a work list built for another stream, pass or head_dim is refused
+    other = va.va_build_worklist(np.array([0, 50, 100], dtype=np.int32), None, va.VA_MASK_CAUSAL, va.VA_PASS_FWD, D, Hq, Hkv)
+    tampered = wl_h.copy()
+    tampered[1, 1] = 1000
+    wrong_pass = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_BWD_DKDV, D, Hq, Hkv)
+    for bad in (other, tampered, wrong_pass):
+        assert call(va.make_shape(**ok), wl_=np.ascontiguousarray(bad))[0] == va.VA_EINVAL
+    assert va.varlen_attn_bwd_workspace_bytes(va.make_shape(**ok)) >= 100 * Hq * 4
