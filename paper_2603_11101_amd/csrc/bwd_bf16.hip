@@ -1,0 +1,383 @@
+// Backward kernels, bf16.  The probabilities are recomputed from the saved LSE
+// instead of being stored by the forward (paper section 2.2.1 (1) relies on the
+// FlashAttention scheme for this; the schedule below is this library's own):
+//
+//   1. delta[h, r] = sum_d dO[r,h,d] * O[r,h,d]                (memory bound)
+//   2. dK/dV: one workgroup per (key tile of 128 rows, KV head).  The K and V
+//      fragments of the tile stay in registers; the workgroup walks over the
+//      query tiles that see the key tile, for every query head of the group,
+//      and accumulates dV^T += dO^T P and dK^T += Q^T dS in registers.
+//   3. dQ: one workgroup per (query tile, head group), the mirror image of the
+//      forward: walks over the visible key tiles and accumulates
+//      dQ^T += K^T dS^T.
+// No atomics anywhere: every output element is written by exactly one lane, so
+// results do not depend on scheduling.
+//
+// With p = exp(scale * s - LSE):  dP = dO V^T,  dS = p * (dP - delta),
+// dQ = scale * dS K,  dK = scale * dS^T Q,  dV = p^T dO.
+#include "kernels.h"
+#include "mfma_util.h"
+
+namespace va {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+VA_DEV int visible_keys(int i, int L, int P, int mode) {
+    if (mode == VA_MASK_CAUSAL) return i + 1;
+    if (i < P) return P;
+    return mode == VA_MASK_PREFIX_LM ? L : i + 1;
+}
+
+// ------------------------------------------------------------------ delta
+
+// One group of D/8 lanes per (token, head) row; each lane multiplies 8 pairs.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ dout,
+                                                        float* __restrict__ delta, int T, int Hq) {
+    constexpr int LPR = D / 8;  // lanes per row
+    constexpr int RPB = 256 / LPR;
+    const size_t row = (size_t)blockIdx.x * RPB + threadIdx.x / LPR;
+    const int c = threadIdx.x % LPR;
+    const size_t rows = (size_t)T * Hq;
+    float acc = 0.0f;
+    if (row < rows) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + row * D + c * 8);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(dout + row * D + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
+    }
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if (row < rows && c == 0) {
+        const size_t t = row / Hq, h = row % Hq;
+        delta[h * T + t] = acc;
+    }
+}
+
+// ------------------------------------------------------------------ dK / dV
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
+    constexpr int BMQ = dkdv_q_tile(D);  // query rows staged per step
+    constexpr int QB = BMQ / 32;     // 32-row query blocks per step
+    constexpr int KSTEPS = D / 16;
+    constexpr int DT = D / 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* q_tile = smem;
+    char* do_tile = smem + BMQ * D * 2;
+    float* lse_s = reinterpret_cast<float*>(smem + 2 * BMQ * D * 2);  // LSE * log2(e), +inf on rows past the sample
+    float* delta_s = lse_s + BMQ;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hf = lane >> 5, l32 = lane & 31;
+    const int g = blockIdx.x % p.Hkv;
+    const WorkItem it = p.items[blockIdx.x / p.Hkv];
+    const int kv_row0 = it.w[0], kv_rows = it.w[1], seq_row0 = it.w[2];
+    const int qt_first = it.w[3], qt_count = it.w[4], P = it.w[6], L = it.w[7];
+    const int G = p.Hq / p.Hkv;
+    const float c = p.scale * kLog2e;
+
+    // this wave's 32 key rows; the lane owns key row jw + l32 (local index in the sample)
+    const int jw = kv_row0 - seq_row0 + 32 * wave;
+    const int kv_local = jw + l32;
+    const bool kv_valid = 32 * wave + l32 < kv_rows;
+
+    // K and V fragments of the lane's key row: k-slots d = 16 t + 8 hf + 0..7
+    bf16x8 kf[KSTEPS], vf[KSTEPS];
+    {
+        const size_t off = ((size_t)(kv_row0 + 32 * wave + l32) * p.Hkv + g) * D;
+        const __bf16* krow = static_cast<const __bf16*>(p.k) + off;
+        const __bf16* vrow = static_cast<const __bf16*>(p.v) + off;
+#pragma unroll
+        for (int t = 0; t < KSTEPS; ++t) {
+            u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
+            if (kv_valid) {
+                a = *reinterpret_cast<const u32x4*>(krow + 16 * t + 8 * hf);
+                b = *reinterpret_cast<const u32x4*>(vrow + 16 * t + 8 * hf);
+            }
+            kf[t] = __builtin_bit_cast(bf16x8, a);
+            vf[t] = __builtin_bit_cast(bf16x8, b);
+        }
+    }
+
+    f32x16 dk[DT], dv[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            dk[dt][r] = 0.0f;
+            dv[dt][r] = 0.0f;
+        }
+
+    const size_t q_stride = (size_t)p.Hq * D;
+    for (int hg = 0; hg < G; ++hg) {
+        const int head = g * G + hg;
+        const __bf16* q_base = static_cast<const __bf16*>(p.q) + ((size_t)seq_row0 * p.Hq + head) * D;
+        const __bf16* do_base = static_cast<const __bf16*>(p.dout) + ((size_t)seq_row0 * p.Hq + head) * D;
+        const float* lse_base = p.lse + (size_t)head * p.T + seq_row0;
+        const float* delta_base = p.delta + (size_t)head * p.T + seq_row0;
+        for (int qt = qt_first; qt < qt_first + qt_count; ++qt) {
+            const int q0 = qt * BMQ;
+            __syncthreads();
+            load_tile<D, BMQ, 256>(q_tile, q_base + (size_t)q0 * q_stride, q_stride, L - q0, tid);
+            load_tile<D, BMQ, 256>(do_tile, do_base + (size_t)q0 * q_stride, q_stride, L - q0, tid);
+            if (tid < BMQ) {
+                const bool ok = q0 + tid < L;
+                lse_s[tid] = ok ? lse_base[q0 + tid] * kLog2e : INFINITY;
+                delta_s[tid] = ok ? delta_base[q0 + tid] : 0.0f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const int i0 = q0 + 32 * qb;  // first query row of the block (local index in the sample)
+                if (i0 >= L) break;
+                const int i1 = min(i0 + 31, L - 1);
+                if (visible_keys(i1, L, P, p.mask_mode) <= jw) continue;  // nothing of this key block is visible
+                const bool need_mask = visible_keys(i0, L, P, p.mask_mode) < jw + 32;
+
+                // S = Q K^T : rows = query rows (registers), columns = key rows (lanes)
+                f32x16 s, dp;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    s[r] = 0.0f;
+                    dp[r] = 0.0f;
+                }
+#pragma unroll
+                for (int t = 0; t < KSTEPS; ++t) s = mfma32(frag_rowmajor<D>(q_tile, 32 * qb + l32, t, hf), kf[t], s);
+#pragma unroll
+                for (int t = 0; t < KSTEPS; ++t) dp = mfma32(frag_rowmajor<D>(do_tile, 32 * qb + l32, t, hf), vf[t], dp);
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int rb = 32 * qb + 8 * r4 + 4 * hf;  // tile row of registers 4 r4 .. 4 r4 + 3
+                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + rb);
+                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_s + rb);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int r = 4 * r4 + e;
+                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
+                        if (need_mask && kv_local >= visible_keys(q0 + rb + e, L, P, p.mask_mode)) pv = 0.0f;
+                        s[r] = pv;
+                        dp[r] = pv * (dp[r] - d4[e]);
+                    }
+                }
+                bf16x8 pb[2], dsb[2];
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    pb[x] = to_bf16x8(s[8 * x], s[8 * x + 1], s[8 * x + 2], s[8 * x + 3], s[8 * x + 4], s[8 * x + 5],
+                                      s[8 * x + 6], s[8 * x + 7]);
+                    dsb[x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
+                                       dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
+                }
+                // dV^T += dO^T P ; dK^T += Q^T dS  (rows = d, columns = key rows)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int x = 0; x < 2; ++x) {
+                        dv[dt] = mfma32(frag_transposed<D>(do_tile, 32 * qb + 16 * x, 32 * dt, lane), pb[x], dv[dt]);
+                        dk[dt] = mfma32(frag_transposed<D>(q_tile, 32 * qb + 16 * x, 32 * dt, lane), dsb[x], dk[dt]);
+                    }
+            }
+        }
+    }
+
+    if (kv_valid) {
+        const size_t off = ((size_t)(kv_row0 + 32 * wave + l32) * p.Hkv + g) * D;
+        __bf16* dk_row = static_cast<__bf16*>(p.dk) + off;
+        __bf16* dv_row = static_cast<__bf16*>(p.dv) + off;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                f32x4 a = {dk[dt][4 * r4] * p.scale, dk[dt][4 * r4 + 1] * p.scale, dk[dt][4 * r4 + 2] * p.scale,
+                           dk[dt][4 * r4 + 3] * p.scale};
+                f32x4 b = {dv[dt][4 * r4], dv[dt][4 * r4 + 1], dv[dt][4 * r4 + 2], dv[dt][4 * r4 + 3]};
+                *reinterpret_cast<bf16x4*>(dk_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(a, bf16x4);
+                *reinterpret_cast<bf16x4*>(dv_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(b, bf16x4);
+            }
+    }
+}
+
+// ------------------------------------------------------------------ dQ
+
+template <int D, int HPB>
+__global__ __launch_bounds__(256) void bwd_dq_kernel(AttnParams p) {
+    constexpr int BMT = kDqBlockRows / HPB;
+    constexpr int BN = kDqKvTile;
+    constexpr int KSTEPS = D / 16;
+    constexpr int DT = D / 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* k_tile = smem;
+    char* v_tile = smem + BN * D * 2;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hf = lane >> 5, l32 = lane & 31;
+    const int G = p.Hq / p.Hkv;
+    const int chunks_per_group = G / HPB;
+    const int nhc = p.Hkv * chunks_per_group;
+    const int hc = blockIdx.x % nhc;
+    const WorkItem it = p.items[blockIdx.x / nhc];
+    const int q_row0 = it.w[0], q_rows = it.w[1], seq_row0 = it.w[2];
+    const int n_full = it.w[4], n_tiles = it.w[5], P = it.w[6], L = it.w[7];
+    const int g = hc / chunks_per_group;
+    const int h0 = g * G + (hc % chunks_per_group) * HPB;
+
+    const int row = wave * 32 + l32;
+    const int head = h0 + row / BMT;
+    const int tok = row % BMT;
+    const bool row_valid = tok < q_rows;
+    const int vis = visible_keys(q_row0 - seq_row0 + tok, L, P, p.mask_mode);
+    const float c = p.scale * kLog2e;
+
+    bf16x8 qf[KSTEPS], dof[KSTEPS];
+    float lse2 = INFINITY, delta = 0.0f;  // rows past the sample: p = exp2(-inf) = 0
+    {
+        const size_t off = ((size_t)(q_row0 + tok) * p.Hq + head) * D;
+        const __bf16* qrow = static_cast<const __bf16*>(p.q) + off;
+        const __bf16* dorow = static_cast<const __bf16*>(p.dout) + off;
+#pragma unroll
+        for (int t = 0; t < KSTEPS; ++t) {
+            u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
+            if (row_valid) {
+                a = *reinterpret_cast<const u32x4*>(qrow + 16 * t + 8 * hf);
+                b = *reinterpret_cast<const u32x4*>(dorow + 16 * t + 8 * hf);
+            }
+            qf[t] = __builtin_bit_cast(bf16x8, a);
+            dof[t] = __builtin_bit_cast(bf16x8, b);
+        }
+        if (row_valid) {
+            lse2 = p.lse[(size_t)head * p.T + q_row0 + tok] * kLog2e;
+            delta = p.delta[(size_t)head * p.T + q_row0 + tok];
+        }
+    }
+
+    f32x16 dq[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dq[dt][r] = 0.0f;
+
+    const size_t kv_stride = (size_t)p.Hkv * D;
+    const __bf16* k_base = static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D;
+    const __bf16* v_base = static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
+
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        const int j0 = kt * BN;
+        __syncthreads();
+        load_tile<D, BN, 256>(k_tile, k_base + (size_t)j0 * kv_stride, kv_stride, L - j0, tid);
+        load_tile<D, BN, 256>(v_tile, v_base + (size_t)j0 * kv_stride, kv_stride, L - j0, tid);
+        __syncthreads();
+        bf16x8 dsb[4];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            // S^T and dP^T blocks: rows = key rows (registers), columns = query rows (lanes)
+            f32x16 s, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                s[r] = 0.0f;
+                dp[r] = 0.0f;
+            }
+#pragma unroll
+            for (int t = 0; t < KSTEPS; ++t) s = mfma32(frag_rowmajor<D>(k_tile, 32 * b + l32, t, hf), qf[t], s);
+#pragma unroll
+            for (int t = 0; t < KSTEPS; ++t) dp = mfma32(frag_rowmajor<D>(v_tile, 32 * b + l32, t, hf), dof[t], dp);
+            const bool need_mask = kt >= n_full;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse2));
+                if (need_mask && j0 + 32 * b + acc_row(r, hf) >= vis) pv = 0.0f;
+                dp[r] = pv * (dp[r] - delta);
+            }
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+                dsb[2 * b + x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
+                                           dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
+        }
+        // dQ^T += K^T dS^T
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                dq[dt] = mfma32(frag_transposed<D>(k_tile, 16 * x, 32 * dt, lane), dsb[x], dq[dt]);
+    }
+
+    if (row_valid) {
+        __bf16* dq_row = static_cast<__bf16*>(p.dq) + ((size_t)(q_row0 + tok) * p.Hq + head) * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                f32x4 f = {dq[dt][4 * r4] * p.scale, dq[dt][4 * r4 + 1] * p.scale, dq[dt][4 * r4 + 2] * p.scale,
+                           dq[dt][4 * r4 + 3] * p.scale};
+                *reinterpret_cast<bf16x4*>(dq_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(f, bf16x4);
+            }
+    }
+}
+
+template <int D>
+hipError_t launch_dq_d(const AttnParams& p, hipStream_t stream) {
+    const int G = p.Hq / p.Hkv;
+    const int hpb = heads_per_block(p.Hq, p.Hkv);
+    const unsigned grid = (unsigned)p.num_items * (unsigned)(p.Hkv * (G / hpb));
+    const size_t smem = 2 * kDqKvTile * D * 2;
+    if (grid == 0) return hipSuccess;
+    switch (hpb) {
+        case 1: hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3(grid), dim3(256), smem, stream, p); break;
+        case 2: hipLaunchKernelGGL((bwd_dq_kernel<D, 2>), dim3(grid), dim3(256), smem, stream, p); break;
+        case 4: hipLaunchKernelGGL((bwd_dq_kernel<D, 4>), dim3(grid), dim3(256), smem, stream, p); break;
+        default: hipLaunchKernelGGL((bwd_dq_kernel<D, 8>), dim3(grid), dim3(256), smem, stream, p); break;
+    }
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
+    const unsigned grid = (unsigned)p.num_items * (unsigned)p.Hkv;
+    const size_t smem = 2 * dkdv_q_tile(D) * D * 2 + 2 * dkdv_q_tile(D) * sizeof(float);
+    if (grid == 0) return hipSuccess;
+    hipLaunchKernelGGL((bwd_dkdv_kernel<D>), dim3(grid), dim3(256), smem, stream, p);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_delta_d(const AttnParams& p, hipStream_t stream) {
+    const size_t rows = (size_t)p.T * p.Hq;
+    constexpr int RPB = 256 / (D / 8);
+    const unsigned grid = (unsigned)((rows + RPB - 1) / RPB);
+    if (grid == 0) return hipSuccess;
+    hipLaunchKernelGGL((bwd_delta_kernel<D>), dim3(grid), dim3(256), 0, stream, static_cast<const __bf16*>(p.out),
+                       static_cast<const __bf16*>(p.dout), p.delta, p.T, p.Hq);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_bwd_delta(const AttnParams& p, hipStream_t stream) {
+    switch (p.D) {
+        case 64: return launch_delta_d<64>(p, stream);
+        case 128: return launch_delta_d<128>(p, stream);
+        case 256: return launch_delta_d<256>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_bwd_dkdv(const AttnParams& p, hipStream_t stream) {
+    switch (p.D) {
+        case 64: return launch_dkdv_d<64>(p, stream);
+        case 128: return launch_dkdv_d<128>(p, stream);
+        case 256: return launch_dkdv_d<256>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_bwd_dq(const AttnParams& p, hipStream_t stream) {
+    switch (p.D) {
+        case 64: return launch_dq_d<64>(p, stream);
+        case 128: return launch_dq_d<128>(p, stream);
+        case 256: return launch_dq_d<256>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace va

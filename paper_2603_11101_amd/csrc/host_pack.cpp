@@ -55,7 +55,7 @@ int tile_shape(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t* rows, 
             return VA_OK;
         case VA_PASS_BWD_DKDV:
             *rows = kDkdvKvRows;
-            *cols = kDkdvQTile;
+            *cols = dkdv_q_tile(D);
             return VA_OK;
         default:
             return fail(VA_EUNSUPPORTED, "unknown pass %d", pass);
