@@ -181,6 +181,22 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Measurement aid: runs exactly what varlen_attn_bwd runs, `iters` times, with
+ * HIP events recorded on `stream` around each of the three kernels, then waits
+ * for the stream (the only entry point that synchronises) and writes the
+ * average milliseconds per launch to the host array ms[3] = {delta, dK/dV, dQ}.
+ * Same arguments and errors as varlen_attn_bwd; iters >= 1.
+ */
+int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                            const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                            const void* worklist_dkdv, const void* worklist_dkdv_host,
+                            const void* worklist_dq, const void* worklist_dq_host,
+                            const va_shape* shape, float scale,
+                            void* dq, void* dk, void* dv,
+                            void* workspace, size_t workspace_bytes, void* stream,
+                            int32_t iters, float* ms);
+
+/*
  * FP8 forward: Q, K, V are OCP E4M3 bytes with one float32 descale per head
  * (device arrays q_descale[Hq], k_descale[Hkv], v_descale[Hkv]).  Scores are
  * (scale * q_descale[h] * k_descale[g]) * (Q8 . K8) in float32; the softmax and

@@ -49,7 +49,7 @@ _lib = _load()
 
 EXPORTS = ["va_last_error", "va_pack_first_fit", "va_bin_layout", "va_tile_shape", "va_worklist_bytes",
            "va_build_worklist", "va_quantize_e4m3_per_head", "varlen_attn_bwd_workspace_bytes",
-           "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_fwd_fp8"]
+           "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_profile", "varlen_attn_fwd_fp8"]
 
 
 def _check(rc):
@@ -169,6 +169,21 @@ def varlen_attn_bwd(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_d
                                 _ptr(workspace), ctypes.c_size_t(workspace_bytes), _stream_ptr(stream)))
 
 
+def varlen_attn_bwd_profile(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
+                            worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
+                            stream=None, iters=1):
+    """Returns average milliseconds per launch of (delta, dK/dV, dQ); waits for the stream."""
+    cu = _i32(cu_seqlens)
+    pl = None if prefix_lens is None else _i32(prefix_lens)
+    ms = (ctypes.c_float * 3)()
+    _check(_lib.varlen_attn_bwd_profile(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(cu), _ptr(pl),
+                                        _ptr(worklist_dkdv), _ptr(worklist_dkdv_host), _ptr(worklist_dq),
+                                        _ptr(worklist_dq_host), ctypes.byref(shape), ctypes.c_float(scale),
+                                        _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), ctypes.c_size_t(workspace_bytes),
+                                        _stream_ptr(stream), ctypes.c_int32(iters), ms))
+    return float(ms[0]), float(ms[1]), float(ms[2])
+
+
 def varlen_attn_fwd_fp8(q8, k8, v8, q_descale, k_descale, v_descale, cu_seqlens, prefix_lens, worklist, worklist_host,
                         shape, scale, out, lse, stream=None):
     cu = _i32(cu_seqlens)
@@ -218,6 +233,13 @@ class PackedStream:
                         self.worklist[VA_PASS_BWD_DKDV], self.worklist_host[VA_PASS_BWD_DKDV],
                         self.worklist[VA_PASS_BWD_DQ], self.worklist_host[VA_PASS_BWD_DQ],
                         self.shape, scale, dq, dk, dv, ws, ws.numel(), stream)
+
+    def bwd_profile(self, q, k, v, out, lse, dout, scale, dq, dk, dv, stream=None, iters=1):
+        ws = self.workspace()
+        return varlen_attn_bwd_profile(q, k, v, out, lse, dout, self.cu_seqlens, self.prefix_lens,
+                                       self.worklist[VA_PASS_BWD_DKDV], self.worklist_host[VA_PASS_BWD_DKDV],
+                                       self.worklist[VA_PASS_BWD_DQ], self.worklist_host[VA_PASS_BWD_DQ],
+                                       self.shape, scale, dq, dk, dv, ws, ws.numel(), stream, iters)
 
     def fwd_fp8(self, q8, k8, v8, q_descale, k_descale, v_descale, scale, out, lse, stream=None):
         varlen_attn_fwd_fp8(q8, k8, v8, q_descale, k_descale, v_descale, self.cu_seqlens, self.prefix_lens,

@@ -137,18 +137,19 @@ int varlen_attn_fwd(const void* q, const void* k, const void* v,
     return VA_OK;
 }
 
-int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                    const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
-                    const void* worklist_dkdv, const void* worklist_dkdv_host,
-                    const void* worklist_dq, const void* worklist_dq_host,
-                    const va_shape* shape, float scale,
-                    void* dq, void* dk, void* dv,
-                    void* workspace, size_t workspace_bytes, void* stream) {
-    const char* who = "varlen_attn_bwd";
+// Validation shared by varlen_attn_bwd and varlen_attn_bwd_profile; fills the kernel parameters.
+static int prepare_bwd(const char* who, const void* q, const void* k, const void* v, const void* out, const float* lse,
+                       const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                       const void* worklist_dkdv, const void* worklist_dkdv_host,
+                       const void* worklist_dq, const void* worklist_dq_host,
+                       const va_shape* shape, float scale, void* dq, void* dk, void* dv,
+                       void* workspace, size_t workspace_bytes,
+                       AttnParams* p, int32_t* n_dkdv, int32_t* n_dq, bool* empty) {
     int rc = check_shape(shape, cu_seqlens, prefix_lens, who);
     if (rc) return rc;
     if ((rc = check_scale(scale, who))) return rc;
-    if (shape->total_tokens == 0) return VA_OK;
+    *empty = shape->total_tokens == 0;
+    if (*empty) return VA_OK;
     if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv || !workspace)
         return fail(VA_EINVAL, "%s: null tensor pointer", who);
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse) || !aligned16(dout) ||
@@ -159,20 +160,37 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
     if (workspace_bytes < varlen_attn_bwd_workspace_bytes(shape))
         return fail(VA_ESIZE, "%s: workspace of %zu bytes, need %zu", who, workspace_bytes,
                     varlen_attn_bwd_workspace_bytes(shape));
+    if ((rc = check_worklist(worklist_dkdv, worklist_dkdv_host, shape, cu_seqlens, VA_PASS_BWD_DKDV, who, n_dkdv))) return rc;
+    if ((rc = check_worklist(worklist_dq, worklist_dq_host, shape, cu_seqlens, VA_PASS_BWD_DQ, who, n_dq))) return rc;
+    *p = base_params(shape, scale);
+    p->q = q;
+    p->k = k;
+    p->v = v;
+    p->out = const_cast<void*>(out);
+    p->lse = const_cast<float*>(lse);
+    p->dout = dout;
+    p->dq = dq;
+    p->dk = dk;
+    p->dv = dv;
+    p->delta = static_cast<float*>(workspace);
+    return VA_OK;
+}
+
+int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                    const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                    const void* worklist_dkdv, const void* worklist_dkdv_host,
+                    const void* worklist_dq, const void* worklist_dq_host,
+                    const va_shape* shape, float scale,
+                    void* dq, void* dk, void* dv,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+    const char* who = "varlen_attn_bwd";
+    AttnParams p;
     int32_t n_dkdv = 0, n_dq = 0;
-    if ((rc = check_worklist(worklist_dkdv, worklist_dkdv_host, shape, cu_seqlens, VA_PASS_BWD_DKDV, who, &n_dkdv))) return rc;
-    if ((rc = check_worklist(worklist_dq, worklist_dq_host, shape, cu_seqlens, VA_PASS_BWD_DQ, who, &n_dq))) return rc;
-    AttnParams p = base_params(shape, scale);
-    p.q = q;
-    p.k = k;
-    p.v = v;
-    p.out = const_cast<void*>(out);
-    p.lse = const_cast<float*>(lse);
-    p.dout = dout;
-    p.dq = dq;
-    p.dk = dk;
-    p.dv = dv;
-    p.delta = static_cast<float*>(workspace);
+    bool empty = false;
+    int rc = prepare_bwd(who, q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
+                         worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
+                         &p, &n_dkdv, &n_dq, &empty);
+    if (rc || empty) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = launch_bwd_delta(p, st);
     if (e == hipSuccess) {
@@ -186,6 +204,59 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
         e = launch_bwd_dq(p, st);
     }
     if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    return VA_OK;
+}
+
+int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                            const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                            const void* worklist_dkdv, const void* worklist_dkdv_host,
+                            const void* worklist_dq, const void* worklist_dq_host,
+                            const va_shape* shape, float scale,
+                            void* dq, void* dk, void* dv,
+                            void* workspace, size_t workspace_bytes, void* stream,
+                            int32_t iters, float* ms) {
+    const char* who = "varlen_attn_bwd_profile";
+    if (iters < 1 || !ms) return fail(VA_EINVAL, "%s: iters must be >= 1 and ms non-null", who);
+    AttnParams p;
+    int32_t n_dkdv = 0, n_dq = 0;
+    bool empty = false;
+    int rc = prepare_bwd(who, q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
+                         worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
+                         &p, &n_dkdv, &n_dq, &empty);
+    ms[0] = ms[1] = ms[2] = 0.0f;
+    if (rc || empty) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipEvent_t ev[4];
+    for (auto& e : ev)
+        if (hipEventCreate(&e) != hipSuccess) return fail(VA_EHIP, "%s: hipEventCreate failed", who);
+    hipError_t e = hipSuccess;
+    double sum[3] = {0.0, 0.0, 0.0};
+    for (int32_t i = 0; i < iters && e == hipSuccess; ++i) {
+        hipEventRecord(ev[0], st);
+        e = launch_bwd_delta(p, st);
+        hipEventRecord(ev[1], st);
+        if (e == hipSuccess) {
+            p.items = static_cast<const WorkItem*>(worklist_dkdv) + 1;
+            p.num_items = n_dkdv;
+            e = launch_bwd_dkdv(p, st);
+        }
+        hipEventRecord(ev[2], st);
+        if (e == hipSuccess) {
+            p.items = static_cast<const WorkItem*>(worklist_dq) + 1;
+            p.num_items = n_dq;
+            e = launch_bwd_dq(p, st);
+        }
+        hipEventRecord(ev[3], st);
+        if (e == hipSuccess) e = hipEventSynchronize(ev[3]);
+        for (int s = 0; s < 3 && e == hipSuccess; ++s) {
+            float t = 0.0f;
+            e = hipEventElapsedTime(&t, ev[s], ev[s + 1]);
+            sum[s] += t;
+        }
+    }
+    for (auto& x : ev) hipEventDestroy(x);
+    if (e != hipSuccess) return fail(VA_EHIP, "%s: %s", who, hipGetErrorString(e));
+    for (int s = 0; s < 3; ++s) ms[s] = (float)(sum[s] / iters);
     return VA_OK;
 }
 
