@@ -1,0 +1,79 @@
+"""GPU parity of the FP8 (E4M3) forward against the fp64 oracle run on the
+dequantised inputs.  Quantised codes and descales must equal the oracle
+quantiser's bit for bit; the attention output must be within rel-L2 5e-2
+(the requantisation of the probabilities is not modelled by the oracle)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attn as oa
+from oracle import e4m3 as oe
+from paper_2603_11101_amd import binding as va
+from paper_2603_11101_amd import workloads as wl
+
+from gpu_util import DEV, TOL_FP8_REL, TOL_LSE_ABS, from_dev_bf16, max_abs, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def run_fp8(cu, prefix, mode, q, k, v, scale):
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    q8, qd = va.va_quantize_e4m3_per_head(wl.bf16_bits(q))
+    k8, kd = va.va_quantize_e4m3_per_head(wl.bf16_bits(k))
+    v8, vd = va.va_quantize_e4m3_per_head(wl.bf16_bits(v))
+    for x, codes, ds in ((q, q8, qd), (k, k8, kd), (v, v8, vd)):
+        oc, od = oe.quantize_per_head(x)
+        assert np.array_equal(codes, oc) and np.array_equal(ds, od)      # bit-exact quantiser
+    ps = va.PackedStream(cu, prefix, mode, Hq, Hkv, D, device=DEV, passes=(va.VA_PASS_FWD,))
+    out = torch.full((T + 2, Hq, D), 768.0, dtype=torch.bfloat16, device=DEV)
+    lse = torch.empty((Hq, T), dtype=torch.float32, device=DEV)
+    pad = np.full((2,) + q8.shape[1:], 0x7F, dtype=np.uint8)            # NaN codes beyond T
+    padk = np.full((2,) + k8.shape[1:], 0x7F, dtype=np.uint8)
+    tq = torch.from_numpy(np.concatenate([q8, pad])).to(DEV)
+    tk = torch.from_numpy(np.concatenate([k8, padk])).to(DEV)
+    tv = torch.from_numpy(np.concatenate([v8, padk])).to(DEV)
+    ps.fwd_fp8(tq, tk, tv, torch.from_numpy(qd).to(DEV), torch.from_numpy(kd).to(DEV), torch.from_numpy(vd).to(DEV),
+               scale, out, lse)
+    torch.cuda.synchronize()
+    got = from_dev_bf16(out)
+    assert np.all(got[T:] == 768.0)
+    deq = [oe.dequantize_per_head(c, d).astype(np.float32) for c, d in ((q8, qd), (k8, kd), (v8, vd))]
+    return got[:T], lse.cpu().numpy().astype(np.float64), deq
+
+
+@pytest.mark.parametrize("mode,Hq,Hkv", [(va.VA_MASK_CAUSAL, 4, 2), (va.VA_MASK_PREFIX_LM, 8, 1), (va.VA_MASK_CAUSAL, 2, 2),
+                                         (va.VA_MASK_PREFIX_LM_CAUSAL, 4, 1)])
+def test_fp8_forward_parity(mode, Hq, Hkv):
+    D = 128
+    lens = [17, 64, 95, 200, 1, 130, 0, 257]
+    cu, prefix, q, k, v, _ = wl.random_stream(50 + Hq + mode, lens, Hq, Hkv, D, prefix_frac=-1.0)
+    if mode == va.VA_MASK_CAUSAL:
+        prefix = None
+    scale = 1.0 / np.sqrt(D)
+    print(f"fp8 forward mode={mode} Hq={Hq} Hkv={Hkv}", flush=True)
+    out, lse, (qd, kd, vd) = run_fp8(cu, prefix, mode, q, k, v, scale)
+    omode = {va.VA_MASK_CAUSAL: oa.MASK_CAUSAL, va.VA_MASK_PREFIX_LM: oa.MASK_PREFIX_BIDIR_SUFFIX,
+             va.VA_MASK_PREFIX_LM_CAUSAL: oa.MASK_PREFIX_CAUSAL_SUFFIX}[mode]
+    ref_out, ref_lse = oa.attn_fwd(qd, kd, vd, cu, prefix, scale=scale, mask_mode=omode)
+    print(f"  out rel-L2 {rel_l2(out, ref_out):.2e} max-abs {max_abs(out, ref_out):.2e} lse max-abs {max_abs(lse, ref_lse):.2e}",
+          flush=True)
+    assert rel_l2(out, ref_out) <= TOL_FP8_REL
+    assert max_abs(lse, ref_lse) <= TOL_LSE_ABS
+    for s in range(len(lens)):
+        if lens[s]:
+            sl = slice(cu[s], cu[s + 1])
+            assert rel_l2(out[sl], ref_out[sl]) <= TOL_FP8_REL, f"sample {s}"
+
+
+def test_fp8_uniform_keys_is_exact_for_power_of_two_counts():
+    # every key equal: p = 1 / (i + 1); for rows where i + 1 is a power of two, p * 2^8 is exactly
+    # representable in E4M3, so O is the exact mean of the (quantised) values up to bf16 rounding
+    Hq, Hkv, D, L = 2, 1, 128, 64
+    cu, _, q, k, v, _ = wl.random_stream(60, [L], Hq, Hkv, D)
+    k[:] = k[0]
+    out, lse, (qd, kd, vd) = run_fp8(cu, None, va.VA_MASK_CAUSAL, q, k, v, 0.05)
+    for i in (0, 1, 3, 7, 15, 31, 63):
+        want = vd[:i + 1, 0].astype(np.float64).mean(axis=0)
+        for h in range(Hq):
+            assert np.allclose(out[i, h], want, rtol=2.0 ** -7, atol=1e-6), (i, h)
