@@ -1,0 +1,96 @@
+"""Parity at the full workload sizes, in the launch configuration bench.py
+times: the first first-fit bin of each workload runs on the GPU as a whole; the
+oracle computes a selection of its samples (all heads, all rows, all gradients
+of those samples) and the two are compared element by element.  Work lists and
+packing at these sizes are compared bit for bit in the host-library tests."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attn as oa
+from oracle import e4m3 as oe
+from oracle import packing as op
+from paper_2603_11101_amd import binding as va
+from paper_2603_11101_amd import workloads as wl
+
+from gpu_util import (DEV, GpuRun, TOL_FP8_REL, TOL_FWD_ABS, TOL_FWD_REL, TOL_GRAD_REL, TOL_LSE_ABS, from_dev_bf16,
+                      max_abs, rel_l2)
+
+pytestmark = pytest.mark.gpu
+
+
+def bin0(name):
+    w = wl.WORKLOADS[name]
+    lens, prefix = wl.sample_lengths(name)
+    b, p, _ = va.va_pack_first_fit(lens, w.budget)
+    idx = op.bin_members(b, p, 0)
+    cu, pl, mx = va.va_bin_layout(lens[idx], None if prefix is None else prefix[idx])
+    return w, lens[idx], cu, pl, mx
+
+
+def pick(lens, count):
+    """longest, shortest, first, last, then evenly spaced others"""
+    order = [int(np.argmax(lens)), int(np.argmin(lens)), 0, len(lens) - 1]
+    order += [int(i) for i in np.linspace(0, len(lens) - 1, count)]
+    sel = []
+    for s in order:
+        if s not in sel:
+            sel.append(s)
+    return sel[:count]
+
+
+@pytest.mark.parametrize("name,count", [("vlm", 30), ("pi05", 6), ("longtail", 7)])
+def test_full_size_forward_backward(name, count):
+    w, lens, cu, pl, mx = bin0(name)
+    T, Hq, Hkv, D = int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim
+    mode = va.VA_MASK_PREFIX_LM if w.prefix_lm else va.VA_MASK_CAUSAL
+    omode = oa.MASK_PREFIX_BIDIR_SUFFIX if w.prefix_lm else oa.MASK_CAUSAL
+    scale = 1.0 / np.sqrt(D)
+    q, k, v, do = wl.tensor_values(w.seed, T, Hq, Hkv, D)
+    sel = pick(lens, min(count, len(lens)))
+    print(f"full size {name}: T={T} samples={len(lens)} checking samples {sel} (lengths {[int(lens[s]) for s in sel]})", flush=True)
+    run = GpuRun(cu, pl, mode, q, k, v, do, scale, max_seqlen=mx)
+    print("  gpu done, oracle forward", flush=True)
+    ref_out, ref_lse = oa.attn_fwd(q, k, v, cu, pl, scale=scale, sel=sel, mask_mode=omode)
+    print("  oracle backward", flush=True)
+    ref_dq, ref_dk, ref_dv = oa.attn_bwd(q, k, v, do, cu, pl, scale=scale, sel=sel, mask_mode=omode)
+    for s in sel:
+        sl = slice(cu[s], cu[s + 1])
+        e = {"out": rel_l2(run.out[sl], ref_out[sl]), "out_abs": max_abs(run.out[sl], ref_out[sl]),
+             "lse": max_abs(run.lse[:, sl], ref_lse[:, sl]), "dq": rel_l2(run.dq[sl], ref_dq[sl]),
+             "dk": rel_l2(run.dk[sl], ref_dk[sl]), "dv": rel_l2(run.dv[sl], ref_dv[sl])}
+        print(f"  sample {s} L={int(lens[s])}: " + " ".join(f"{n} {x:.2e}" for n, x in e.items()), flush=True)
+        assert e["out"] <= TOL_FWD_REL and e["out_abs"] <= TOL_FWD_ABS and e["lse"] <= TOL_LSE_ABS
+        assert max(e["dq"], e["dk"], e["dv"]) <= TOL_GRAD_REL
+    assert run.tail_untouched("out", "dq", "dk", "dv")
+    # properties that hold for every row at any size: finite outputs, LSE above the largest possible
+    # single score is impossible to check cheaply, but LSE must be finite and rows of O bounded by max |V|
+    assert np.isfinite(run.out).all() and np.isfinite(run.lse).all()
+    assert np.isfinite(run.dq).all() and np.isfinite(run.dk).all() and np.isfinite(run.dv).all()
+    assert np.abs(run.out).max() <= np.abs(v).max() * (1 + 2.0 ** -7)       # O is a convex combination of V rows
+
+
+def test_full_size_fp8_forward():
+    w, lens, cu, pl, mx = bin0("vlm_fp8")
+    T, Hq, Hkv, D = int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim
+    scale = 1.0 / np.sqrt(D)
+    q, k, v, _ = wl.tensor_values(w.seed, T, Hq, Hkv, D, with_dout=False)
+    quant = [va.va_quantize_e4m3_per_head(wl.bf16_bits(x)) for x in (q, k, v)]
+    for x, (codes, ds) in zip((q, k, v), quant):
+        oc, od = oe.quantize_per_head(x)
+        assert np.array_equal(codes, oc) and np.array_equal(ds, od)
+    ps = va.PackedStream(cu, None, va.VA_MASK_CAUSAL, Hq, Hkv, D, max_seqlen=mx, device=DEV, passes=(va.VA_PASS_FWD,))
+    out = torch.empty((T, Hq, D), dtype=torch.bfloat16, device=DEV)
+    lse = torch.empty((Hq, T), dtype=torch.float32, device=DEV)
+    dev = [(torch.from_numpy(c).to(DEV), torch.from_numpy(d).to(DEV)) for c, d in quant]
+    print(f"full size fp8: T={T}", flush=True)
+    ps.fwd_fp8(dev[0][0], dev[1][0], dev[2][0], dev[0][1], dev[1][1], dev[2][1], scale, out, lse)
+    torch.cuda.synchronize()
+    got, got_lse = from_dev_bf16(out), lse.cpu().numpy().astype(np.float64)
+    deq = [oe.dequantize_per_head(c, d).astype(np.float32) for c, d in quant]
+    ref_out, ref_lse = oa.attn_fwd(deq[0], deq[1], deq[2], cu, None, scale=scale)
+    print(f"  out rel-L2 {rel_l2(got, ref_out):.2e} lse max-abs {max_abs(got_lse, ref_lse):.2e}", flush=True)
+    assert rel_l2(got, ref_out) <= TOL_FP8_REL and max_abs(got_lse, ref_lse) <= TOL_LSE_ABS
+    for s in range(len(lens)):
+        sl = slice(cu[s], cu[s + 1])
+        assert rel_l2(got[sl], ref_out[sl]) <= TOL_FP8_REL, f"sample {s}"
