@@ -27,6 +27,7 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kMaxLag = 8.0f;  // the softmax reference may trail a row's true maximum by this many powers of two
 
 VA_DEV int visible_keys(int i, int L, int P, int mode) {
     if (mode == VA_MASK_CAUSAL) return i + 1;
@@ -35,14 +36,14 @@ VA_DEV int visible_keys(int i, int L, int P, int mode) {
 }
 
 template <int D, int HPB>
-__global__ __launch_bounds__(256) void fwd_bf16_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnParams p) {
     constexpr int BMT = kFwdBlockRows / HPB;  // token rows of the work item
     constexpr int BN = kFwdKvTile;
     constexpr int KSTEPS = D / 16;  // MFMA steps over the head dimension
     constexpr int DT = D / 32;      // 32-row blocks of O^T
+    constexpr int TILE_BYTES = BN * D * 2;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* k_tile = smem;
-    char* v_tile = smem + BN * D * 2;
+    // two stages, each a K tile followed by a V tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
@@ -55,6 +56,14 @@ __global__ __launch_bounds__(256) void fwd_bf16_kernel(AttnParams p) {
     const int n_full = it.w[4], n_tiles = it.w[5], P = it.w[6], L = it.w[7];
     const int g = hc / chunks_per_group;
     const int h0 = g * G + (hc % chunks_per_group) * HPB;
+
+    const size_t kv_stride = (size_t)p.Hkv * D;
+    const __bf16* k_base = static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D;
+    const __bf16* v_base = static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
+
+    // first K/V tile on its way before anything else
+    async_load_tile<D, BN, 4>(smem, k_base, kv_stride, L, wave, lane);
+    async_load_tile<D, BN, 4>(smem + TILE_BYTES, v_base, kv_stride, L, wave, lane);
 
     // the stacked row this lane owns
     const int row = wave * 32 + l32;
@@ -80,20 +89,26 @@ __global__ __launch_bounds__(256) void fwd_bf16_kernel(AttnParams p) {
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
-    float m = -INFINITY;  // running maximum of scale * log2(e) * s
-    float lsum = 0.0f;    // this lane's share of the running sum (other share in lane + 32)
+    // Reference point of the exponentials, in units of scale * log2(e) * s.  It only moves when some
+    // row of the wave would otherwise exceed 2^kMaxLag, so most tiles skip the rescaling of O;
+    // the probabilities are then at most 2^kMaxLag instead of 1, which float32 sums and bf16 P absorb.
+    float m = -INFINITY;
+    float lsum = 0.0f;  // this lane's share of the running sum (other share in lane + 32)
     const float c = p.scale * kLog2e;
 
-    const size_t kv_stride = (size_t)p.Hkv * D;
-    const __bf16* k_base = static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D;
-    const __bf16* v_base = static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
+    wait_async_loads();
+    __syncthreads();
 
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int j0 = kt * BN;
-        __syncthreads();
-        load_tile<D, BN, 256>(k_tile, k_base + (size_t)j0 * kv_stride, kv_stride, L - j0, tid);
-        load_tile<D, BN, 256>(v_tile, v_base + (size_t)j0 * kv_stride, kv_stride, L - j0, tid);
-        __syncthreads();
+        const char* k_tile = smem + (kt & 1) * 2 * TILE_BYTES;
+        const char* v_tile = k_tile + TILE_BYTES;
+        if (kt + 1 < n_tiles) {
+            char* nk = smem + ((kt + 1) & 1) * 2 * TILE_BYTES;
+            const int j1 = j0 + BN;
+            async_load_tile<D, BN, 4>(nk, k_base + (size_t)j1 * kv_stride, kv_stride, L - j1, wave, lane);
+            async_load_tile<D, BN, 4>(nk + TILE_BYTES, v_base + (size_t)j1 * kv_stride, kv_stride, L - j1, wave, lane);
+        }
 
         // S^T: two blocks of 32 keys x 32 query rows
         f32x16 s[2];
@@ -117,25 +132,27 @@ __global__ __launch_bounds__(256) void fwd_bf16_kernel(AttnParams p) {
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
-        mx = pair_max(mx);
-        const float m_new = fmaxf(m, mx * c);
-        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-        m = m_new;
+        mx = pair_max(mx) * c;
+        if (__builtin_amdgcn_ballot_w64(mx > m + kMaxLag) != 0) {  // wave-uniform: some row needs a new reference
+            const float m_new = fmaxf(m, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);  // m = -inf on the first tile: alpha = 0, O = 0
+            m = m_new;
+            lsum *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        }
         float psum = 0.0f;
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, -m_use));
+                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, -m));
                 s[b][r] = pv;
                 psum += pv;
             }
-        lsum = lsum * alpha + psum;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        lsum += psum;
 
         // P^T as second operand: registers 8 x .. 8 x + 7 of a block are the k-slots of step x
         bf16x8 pf[4];
@@ -150,6 +167,10 @@ __global__ __launch_bounds__(256) void fwd_bf16_kernel(AttnParams p) {
 #pragma unroll
             for (int x = 0; x < 4; ++x)
                 o[dt] = mfma32(frag_transposed<D>(v_tile, 16 * x, 32 * dt, lane), pf[x], o[dt]);
+
+        // the next tile has landed and every wave is done reading this one
+        wait_async_loads();
+        __syncthreads();
     }
 
     lsum = pair_sum(lsum);
@@ -168,20 +189,27 @@ __global__ __launch_bounds__(256) void fwd_bf16_kernel(AttnParams p) {
     }
 }
 
+template <int D, int HPB>
+hipError_t launch_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
+    constexpr size_t smem = 2 * 2 * kFwdKvTile * D * 2;  // two stages of (K tile, V tile)
+    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&fwd_bf16_kernel<D, HPB>), smem);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, HPB>), dim3(grid), dim3(256), smem, stream, p);
+    return hipGetLastError();
+}
+
 template <int D>
 hipError_t launch_d(const AttnParams& p, hipStream_t stream) {
     const int G = p.Hq / p.Hkv;
     const int hpb = heads_per_block(p.Hq, p.Hkv);
     const unsigned grid = (unsigned)p.num_items * (unsigned)(p.Hkv * (G / hpb));
-    const size_t smem = 2 * kFwdKvTile * D * 2;
     if (grid == 0) return hipSuccess;
     switch (hpb) {
-        case 1: hipLaunchKernelGGL((fwd_bf16_kernel<D, 1>), dim3(grid), dim3(256), smem, stream, p); break;
-        case 2: hipLaunchKernelGGL((fwd_bf16_kernel<D, 2>), dim3(grid), dim3(256), smem, stream, p); break;
-        case 4: hipLaunchKernelGGL((fwd_bf16_kernel<D, 4>), dim3(grid), dim3(256), smem, stream, p); break;
-        default: hipLaunchKernelGGL((fwd_bf16_kernel<D, 8>), dim3(grid), dim3(256), smem, stream, p); break;
+        case 1: return launch_dh<D, 1>(p, stream, grid);
+        case 2: return launch_dh<D, 2>(p, stream, grid);
+        case 4: return launch_dh<D, 4>(p, stream, grid);
+        default: return launch_dh<D, 8>(p, stream, grid);
     }
-    return hipGetLastError();
 }
 
 }  // namespace

@@ -29,6 +29,12 @@ struct AttnParams {
     float scale;
 };
 
+// Kernels that need more than the default 64 KiB of dynamic LDS must say so once.
+inline hipError_t allow_dynamic_lds(const void* kernel, size_t bytes) {
+    if (bytes <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
 hipError_t launch_fwd_bf16(const AttnParams& p, hipStream_t stream);
 hipError_t launch_fwd_fp8(const AttnParams& p, hipStream_t stream);
 hipError_t launch_bwd_delta(const AttnParams& p, hipStream_t stream);

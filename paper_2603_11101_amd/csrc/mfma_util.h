@@ -130,6 +130,37 @@ VA_DEV void load_tile(char* tile, const __bf16* g, size_t gstride, int valid_row
     }
 }
 
+// Asynchronous copy of ROWS x D bf16 values from global memory straight into a
+// swizzled LDS tile (global_load_lds_dwordx4: every lane fetches 16 bytes and
+// the hardware writes them to LDS at base + 16 * lane, no registers involved).
+// One wave instruction fills 1 KiB of the tile; the NWAVES waves of the
+// workgroup share the tile's instructions.  The swizzle is applied on the
+// global side: the lane that fills chunk position pc of row r fetches chunk
+// pc ^ swizzle(r) of that row.  Rows >= valid_rows (>= 1) are filled with a copy
+// of the last valid row instead of being read: callers make sure such rows meet
+// a zero probability, so a finite stand-in is as good as zero.
+// The caller must wait (wait_async_loads) and then barrier before reading.
+template <int D, int ROWS, int NWAVES>
+VA_DEV void async_load_tile(char* tile, const __bf16* g, size_t gstride, int valid_rows, int wave, int lane) {
+    constexpr int CPR = D / 8;
+    constexpr int RPI = 64 / CPR;  // rows per wave instruction
+    constexpr int INSTR = ROWS / RPI;
+    static_assert(INSTR % NWAVES == 0, "tile must divide among the waves");
+    typedef __attribute__((address_space(3))) void lds_void;
+    typedef __attribute__((address_space(1))) const void glb_void;
+    const int pc = lane % CPR;
+#pragma unroll
+    for (int j = 0; j < INSTR / NWAVES; ++j) {
+        const int inst = wave * (INSTR / NWAVES) + j;
+        const int r = inst * RPI + lane / CPR;
+        const int rc = min(r, valid_rows - 1);
+        const __bf16* src = g + (size_t)rc * gstride + ((pc ^ swizzle<D>(r)) << 3);
+        __builtin_amdgcn_global_load_lds((glb_void*)src, (lds_void*)(tile + inst * 1024), 16, 0, 0);
+    }
+}
+
+VA_DEV void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // float pairs -> packed bf16 (round to nearest even)
 VA_DEV bf16x8 to_bf16x8(float a0, float a1, float a2, float a3, float a4, float a5, float a6, float a7) {
     f32x8 f = {a0, a1, a2, a3, a4, a5, a6, a7};
