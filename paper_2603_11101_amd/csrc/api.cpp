@@ -105,8 +105,8 @@ extern "C" {
 
 size_t varlen_attn_bwd_workspace_bytes(const va_shape* s) {
     if (!s || s->total_tokens < 0 || s->num_q_heads <= 0) return 0;
-    // delta = rowsum(dO * O), float32 [Hq, T]
-    return round_up((size_t)s->total_tokens * (size_t)s->num_q_heads * sizeof(float), 256);
+    // delta = rowsum(dO * O) and LSE * log2(e), float32 [Hq, T] each
+    return 2 * round_up((size_t)s->total_tokens * (size_t)s->num_q_heads * sizeof(float), 256);
 }
 
 int varlen_attn_fwd(const void* q, const void* k, const void* v,
@@ -173,6 +173,7 @@ static int prepare_bwd(const char* who, const void* q, const void* k, const void
     p->dk = dk;
     p->dv = dv;
     p->delta = static_cast<float*>(workspace);
+    p->lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + varlen_attn_bwd_workspace_bytes(shape) / 2);
     return VA_OK;
 }
 

@@ -35,7 +35,8 @@ VA_DEV int visible_keys(int i, int L, int P, int mode) {
 // One group of D/8 lanes per (token, head) row; each lane multiplies 8 pairs.
 template <int D>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ dout,
-                                                        float* __restrict__ delta, int T, int Hq) {
+                                                        const float* __restrict__ lse, float* __restrict__ delta,
+                                                        float* __restrict__ lse2, int T, int Hq) {
     constexpr int LPR = D / 8;  // lanes per row
     constexpr int RPB = 256 / LPR;
     const size_t row = (size_t)blockIdx.x * RPB + threadIdx.x / LPR;
@@ -53,6 +54,7 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
     if (row < rows && c == 0) {
         const size_t t = row / Hq, h = row % Hq;
         delta[h * T + t] = acc;
+        lse2[h * T + t] = lse[h * T + t] * kLog2e;  // the other kernels work with base-2 exponentials
     }
 }
 
@@ -61,14 +63,12 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
 template <int D>
 __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
     constexpr int BMQ = dkdv_q_tile(D);  // query rows staged per step
-    constexpr int QB = BMQ / 32;     // 32-row query blocks per step
+    constexpr int QB = BMQ / 32;         // 32-row query blocks per step
     constexpr int KSTEPS = D / 16;
     constexpr int DT = D / 32;
+    constexpr int TILE_BYTES = BMQ * D * 2;
+    constexpr int STAGE_BYTES = 2 * TILE_BYTES + 2 * 64 * (int)sizeof(float);  // Q, dO, LSE2[64], delta[64]
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* q_tile = smem;
-    char* do_tile = smem + BMQ * D * 2;
-    float* lse_s = reinterpret_cast<float*>(smem + 2 * BMQ * D * 2);  // LSE * log2(e), +inf on rows past the sample
-    float* delta_s = lse_s + BMQ;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
@@ -78,6 +78,25 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
     const int qt_first = it.w[3], qt_count = it.w[4], P = it.w[6], L = it.w[7];
     const int G = p.Hq / p.Hkv;
     const float c = p.scale * kLog2e;
+    const size_t q_stride = (size_t)p.Hq * D;
+
+    // Stage n holds query tile qt_first + n % qt_count of head g * G + n / qt_count.
+    const int n_steps = G * qt_count;
+    auto issue = [&](int n) {
+        char* st = smem + (n & 1) * STAGE_BYTES;
+        const int head = g * G + n / qt_count;
+        const int q0 = (qt_first + n % qt_count) * BMQ;
+        const size_t off = ((size_t)(seq_row0 + q0) * p.Hq + head) * D;
+        async_load_tile<D, BMQ, 4>(st, static_cast<const __bf16*>(p.q) + off, q_stride, L - q0, wave, lane);
+        async_load_tile<D, BMQ, 4>(st + TILE_BYTES, static_cast<const __bf16*>(p.dout) + off, q_stride, L - q0, wave, lane);
+        if (wave < 2) {  // 64 floats each: lane i fetches row q0 + i (clamped to the sample)
+            typedef __attribute__((address_space(3))) void lds_void;
+            typedef __attribute__((address_space(1))) const void glb_void;
+            const float* src = (wave == 0 ? p.lse2 : p.delta) + (size_t)head * p.T + seq_row0 + min(q0 + lane, L - 1);
+            __builtin_amdgcn_global_load_lds((glb_void*)src, (lds_void*)(st + 2 * TILE_BYTES + wave * 256), 4, 0, 0);
+        }
+    };
+    issue(0);
 
     // this wave's 32 key rows; the lane owns key row jw + l32 (local index in the sample)
     const int jw = kv_row0 - seq_row0 + 32 * wave;
@@ -111,75 +130,72 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
             dv[dt][r] = 0.0f;
         }
 
-    const size_t q_stride = (size_t)p.Hq * D;
-    for (int hg = 0; hg < G; ++hg) {
-        const int head = g * G + hg;
-        const __bf16* q_base = static_cast<const __bf16*>(p.q) + ((size_t)seq_row0 * p.Hq + head) * D;
-        const __bf16* do_base = static_cast<const __bf16*>(p.dout) + ((size_t)seq_row0 * p.Hq + head) * D;
-        const float* lse_base = p.lse + (size_t)head * p.T + seq_row0;
-        const float* delta_base = p.delta + (size_t)head * p.T + seq_row0;
-        for (int qt = qt_first; qt < qt_first + qt_count; ++qt) {
-            const int q0 = qt * BMQ;
-            __syncthreads();
-            load_tile<D, BMQ, 256>(q_tile, q_base + (size_t)q0 * q_stride, q_stride, L - q0, tid);
-            load_tile<D, BMQ, 256>(do_tile, do_base + (size_t)q0 * q_stride, q_stride, L - q0, tid);
-            if (tid < BMQ) {
-                const bool ok = q0 + tid < L;
-                lse_s[tid] = ok ? lse_base[q0 + tid] * kLog2e : INFINITY;
-                delta_s[tid] = ok ? delta_base[q0 + tid] : 0.0f;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                const int i0 = q0 + 32 * qb;  // first query row of the block (local index in the sample)
-                if (i0 >= L) break;
-                const int i1 = min(i0 + 31, L - 1);
-                if (visible_keys(i1, L, P, p.mask_mode) <= jw) continue;  // nothing of this key block is visible
-                const bool need_mask = visible_keys(i0, L, P, p.mask_mode) < jw + 32;
+    wait_async_loads();
+    __syncthreads();
 
-                // S = Q K^T : rows = query rows (registers), columns = key rows (lanes)
-                f32x16 s, dp;
+    for (int n = 0; n < n_steps; ++n) {
+        if (n + 1 < n_steps) issue(n + 1);
+        const char* q_tile = smem + (n & 1) * STAGE_BYTES;
+        const char* do_tile = q_tile + TILE_BYTES;
+        const float* lse_s = reinterpret_cast<const float*>(q_tile + 2 * TILE_BYTES);
+        const float* delta_s = lse_s + 64;
+        const int q0 = (qt_first + n % qt_count) * BMQ;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    s[r] = 0.0f;
-                    dp[r] = 0.0f;
-                }
+        for (int qb = 0; qb < QB; ++qb) {
+            const int i0 = q0 + 32 * qb;  // first query row of the block (local index in the sample)
+            if (i0 >= L) break;
+            const int i1 = min(i0 + 31, L - 1);
+            if (visible_keys(i1, L, P, p.mask_mode) <= jw) continue;  // nothing of this key block is visible
+            // rows past the sample hold stand-in data and must get p = 0: they count as seeing no key
+            const bool need_mask = visible_keys(i0, L, P, p.mask_mode) < jw + 32 || i0 + 32 > L;
+
+            // S = Q K^T : rows = query rows (registers), columns = key rows (lanes)
+            f32x16 s, dp;
 #pragma unroll
-                for (int t = 0; t < KSTEPS; ++t) s = mfma32(frag_rowmajor<D>(q_tile, 32 * qb + l32, t, hf), kf[t], s);
+            for (int r = 0; r < 16; ++r) {
+                s[r] = 0.0f;
+                dp[r] = 0.0f;
+            }
 #pragma unroll
-                for (int t = 0; t < KSTEPS; ++t) dp = mfma32(frag_rowmajor<D>(do_tile, 32 * qb + l32, t, hf), vf[t], dp);
+            for (int t = 0; t < KSTEPS; ++t) s = mfma32(frag_rowmajor<D>(q_tile, 32 * qb + l32, t, hf), kf[t], s);
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int rb = 32 * qb + 8 * r4 + 4 * hf;  // tile row of registers 4 r4 .. 4 r4 + 3
-                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + rb);
-                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_s + rb);
+            for (int t = 0; t < KSTEPS; ++t) dp = mfma32(frag_rowmajor<D>(do_tile, 32 * qb + l32, t, hf), vf[t], dp);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int r = 4 * r4 + e;
-                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
-                        if (need_mask && kv_local >= visible_keys(q0 + rb + e, L, P, p.mask_mode)) pv = 0.0f;
-                        s[r] = pv;
-                        dp[r] = pv * (dp[r] - d4[e]);
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int rb = 32 * qb + 8 * r4 + 4 * hf;  // tile row of registers 4 r4 .. 4 r4 + 3
+                const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + rb);
+                const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_s + rb);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = 4 * r4 + e;
+                    float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
+                    if (need_mask) {
+                        const int i = q0 + rb + e;
+                        if (i >= L || kv_local >= visible_keys(i, L, P, p.mask_mode)) pv = 0.0f;
                     }
+                    s[r] = pv;
+                    dp[r] = pv * (dp[r] - d4[e]);
                 }
-                bf16x8 pb[2], dsb[2];
+            }
+            bf16x8 pb[2], dsb[2];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                pb[x] = to_bf16x8(s[8 * x], s[8 * x + 1], s[8 * x + 2], s[8 * x + 3], s[8 * x + 4], s[8 * x + 5],
+                                  s[8 * x + 6], s[8 * x + 7]);
+                dsb[x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
+                                   dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
+            }
+            // dV^T += dO^T P ; dK^T += Q^T dS  (rows = d, columns = key rows)
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int x = 0; x < 2; ++x) {
-                    pb[x] = to_bf16x8(s[8 * x], s[8 * x + 1], s[8 * x + 2], s[8 * x + 3], s[8 * x + 4], s[8 * x + 5],
-                                      s[8 * x + 6], s[8 * x + 7]);
-                    dsb[x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
-                                       dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
+                    dv[dt] = mfma32(frag_transposed<D>(do_tile, 32 * qb + 16 * x, 32 * dt, lane), pb[x], dv[dt]);
+                    dk[dt] = mfma32(frag_transposed<D>(q_tile, 32 * qb + 16 * x, 32 * dt, lane), dsb[x], dk[dt]);
                 }
-                // dV^T += dO^T P ; dK^T += Q^T dS  (rows = d, columns = key rows)
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int x = 0; x < 2; ++x) {
-                        dv[dt] = mfma32(frag_transposed<D>(do_tile, 32 * qb + 16 * x, 32 * dt, lane), pb[x], dv[dt]);
-                        dk[dt] = mfma32(frag_transposed<D>(q_tile, 32 * qb + 16 * x, 32 * dt, lane), dsb[x], dk[dt]);
-                    }
-            }
         }
+        wait_async_loads();
+        __syncthreads();
     }
 
     if (kv_valid) {
@@ -202,14 +218,13 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
 // ------------------------------------------------------------------ dQ
 
 template <int D, int HPB>
-__global__ __launch_bounds__(256) void bwd_dq_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParams p) {
     constexpr int BMT = kDqBlockRows / HPB;
     constexpr int BN = kDqKvTile;
     constexpr int KSTEPS = D / 16;
     constexpr int DT = D / 32;
+    constexpr int TILE_BYTES = BN * D * 2;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* k_tile = smem;
-    char* v_tile = smem + BN * D * 2;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
@@ -222,6 +237,12 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(AttnParams p) {
     const int n_full = it.w[4], n_tiles = it.w[5], P = it.w[6], L = it.w[7];
     const int g = hc / chunks_per_group;
     const int h0 = g * G + (hc % chunks_per_group) * HPB;
+
+    const size_t kv_stride = (size_t)p.Hkv * D;
+    const __bf16* k_base = static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D;
+    const __bf16* v_base = static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
+    async_load_tile<D, BN, 4>(smem, k_base, kv_stride, L, wave, lane);
+    async_load_tile<D, BN, 4>(smem + TILE_BYTES, v_base, kv_stride, L, wave, lane);
 
     const int row = wave * 32 + l32;
     const int head = h0 + row / BMT;
@@ -247,7 +268,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(AttnParams p) {
             dof[t] = __builtin_bit_cast(bf16x8, b);
         }
         if (row_valid) {
-            lse2 = p.lse[(size_t)head * p.T + q_row0 + tok] * kLog2e;
+            lse2 = p.lse2[(size_t)head * p.T + q_row0 + tok];
             delta = p.delta[(size_t)head * p.T + q_row0 + tok];
         }
     }
@@ -258,16 +279,19 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(AttnParams p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[dt][r] = 0.0f;
 
-    const size_t kv_stride = (size_t)p.Hkv * D;
-    const __bf16* k_base = static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D;
-    const __bf16* v_base = static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
+    wait_async_loads();
+    __syncthreads();
 
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int j0 = kt * BN;
-        __syncthreads();
-        load_tile<D, BN, 256>(k_tile, k_base + (size_t)j0 * kv_stride, kv_stride, L - j0, tid);
-        load_tile<D, BN, 256>(v_tile, v_base + (size_t)j0 * kv_stride, kv_stride, L - j0, tid);
-        __syncthreads();
+        const char* k_tile = smem + (kt & 1) * 2 * TILE_BYTES;
+        const char* v_tile = k_tile + TILE_BYTES;
+        if (kt + 1 < n_tiles) {
+            char* nk = smem + ((kt + 1) & 1) * 2 * TILE_BYTES;
+            const int j1 = j0 + BN;
+            async_load_tile<D, BN, 4>(nk, k_base + (size_t)j1 * kv_stride, kv_stride, L - j1, wave, lane);
+            async_load_tile<D, BN, 4>(nk + TILE_BYTES, v_base + (size_t)j1 * kv_stride, kv_stride, L - j1, wave, lane);
+        }
         bf16x8 dsb[4];
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
@@ -300,6 +324,8 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(AttnParams p) {
 #pragma unroll
             for (int x = 0; x < 4; ++x)
                 dq[dt] = mfma32(frag_transposed<D>(k_tile, 16 * x, 32 * dt, lane), dsb[x], dq[dt]);
+        wait_async_loads();
+        __syncthreads();
     }
 
     if (row_valid) {
@@ -315,27 +341,36 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(AttnParams p) {
     }
 }
 
+template <int D, int HPB>
+hipError_t launch_dq_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
+    constexpr size_t smem = 2 * 2 * kDqKvTile * D * 2;  // two stages of (K tile, V tile)
+    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dq_kernel<D, HPB>), smem);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((bwd_dq_kernel<D, HPB>), dim3(grid), dim3(256), smem, stream, p);
+    return hipGetLastError();
+}
+
 template <int D>
 hipError_t launch_dq_d(const AttnParams& p, hipStream_t stream) {
     const int G = p.Hq / p.Hkv;
     const int hpb = heads_per_block(p.Hq, p.Hkv);
     const unsigned grid = (unsigned)p.num_items * (unsigned)(p.Hkv * (G / hpb));
-    const size_t smem = 2 * kDqKvTile * D * 2;
     if (grid == 0) return hipSuccess;
     switch (hpb) {
-        case 1: hipLaunchKernelGGL((bwd_dq_kernel<D, 1>), dim3(grid), dim3(256), smem, stream, p); break;
-        case 2: hipLaunchKernelGGL((bwd_dq_kernel<D, 2>), dim3(grid), dim3(256), smem, stream, p); break;
-        case 4: hipLaunchKernelGGL((bwd_dq_kernel<D, 4>), dim3(grid), dim3(256), smem, stream, p); break;
-        default: hipLaunchKernelGGL((bwd_dq_kernel<D, 8>), dim3(grid), dim3(256), smem, stream, p); break;
+        case 1: return launch_dq_dh<D, 1>(p, stream, grid);
+        case 2: return launch_dq_dh<D, 2>(p, stream, grid);
+        case 4: return launch_dq_dh<D, 4>(p, stream, grid);
+        default: return launch_dq_dh<D, 8>(p, stream, grid);
     }
-    return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     const unsigned grid = (unsigned)p.num_items * (unsigned)p.Hkv;
-    const size_t smem = 2 * dkdv_q_tile(D) * D * 2 + 2 * dkdv_q_tile(D) * sizeof(float);
+    constexpr size_t smem = 2 * (2 * dkdv_q_tile(D) * D * 2 + 2 * 64 * sizeof(float));
     if (grid == 0) return hipSuccess;
+    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D>), smem);
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((bwd_dkdv_kernel<D>), dim3(grid), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
@@ -347,7 +382,7 @@ hipError_t launch_delta_d(const AttnParams& p, hipStream_t stream) {
     const unsigned grid = (unsigned)((rows + RPB - 1) / RPB);
     if (grid == 0) return hipSuccess;
     hipLaunchKernelGGL((bwd_delta_kernel<D>), dim3(grid), dim3(256), 0, stream, static_cast<const __bf16*>(p.out),
-                       static_cast<const __bf16*>(p.dout), p.delta, p.T, p.Hq);
+                       static_cast<const __bf16*>(p.dout), p.lse, p.delta, p.lse2, p.T, p.Hq);
     return hipGetLastError();
 }
 

@@ -19,6 +19,7 @@ struct AttnParams {
     void* dk;             // [T, Hkv, D]
     void* dv;             // [T, Hkv, D]
     float* delta;         // [Hq, T]  rowsum(dO * O)
+    float* lse2;          // [Hq, T]  LSE * log2(e), written by the delta kernel
     const float* q_descale;  // fp8 only
     const float* k_descale;
     const float* v_descale;
