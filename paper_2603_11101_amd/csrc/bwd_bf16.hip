@@ -24,12 +24,6 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-VA_DEV int visible_keys(int i, int L, int P, int mode) {
-    if (mode == VA_MASK_CAUSAL) return i + 1;
-    if (i < P) return P;
-    return mode == VA_MASK_PREFIX_LM ? L : i + 1;
-}
-
 // ------------------------------------------------------------------ delta
 
 // One group of D/8 lanes per (token, head) row; each lane multiplies 8 pairs.
@@ -60,15 +54,23 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
 
 // ------------------------------------------------------------------ dK / dV
 
-template <int D>
-__global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
+// V_LDS: the V rows of the key tile live in LDS (read as second operand of dP = dO V^T) instead of in
+// registers, which buys the register room for two workgroups per CU at D = 128 and avoids spilling at
+// D = 256.
+// PART: 0 = dK and dV in one pass; 1 = dV only; 2 = dK only.  At D = 256 the two accumulators together
+// (256 registers per lane) leave no room for anything else, so the kernel is launched once per part
+// there, at the price of recomputing the scores (5 products instead of 4).
+template <int D, bool V_LDS, int PART>
+__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnParams p) {
+    constexpr bool DO_DV = PART != 2, DO_DK = PART != 1;
     constexpr int BMQ = dkdv_q_tile(D);  // query rows staged per step
     constexpr int QB = BMQ / 32;         // 32-row query blocks per step
     constexpr int KSTEPS = D / 16;
     constexpr int DT = D / 32;
     constexpr int TILE_BYTES = BMQ * D * 2;
     constexpr int STAGE_BYTES = 2 * TILE_BYTES + 2 * 64 * (int)sizeof(float);  // Q, dO, LSE2[64], delta[64]
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // two stages, then the V tile if V_LDS
+    const char* v_tile = smem + 2 * STAGE_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
@@ -78,25 +80,37 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
     const int qt_first = it.w[3], qt_count = it.w[4], P = it.w[6], L = it.w[7];
     const int G = p.Hq / p.Hkv;
     const float c = p.scale * kLog2e;
-    const size_t q_stride = (size_t)p.Hq * D;
+    const RowMask mask(P, L, p.mask_mode);
 
-    // Stage n holds query tile qt_first + n % qt_count of head g * G + n / qt_count.
+    // Stage n holds query tile qt_first + n % qt_count of head g * G + n / qt_count.  Q and dO rows of
+    // (sample, head) and the LSE / delta rows are raw buffers: anything past the sample reads as zero.
     const int n_steps = G * qt_count;
+    const int q_row_bytes = p.Hq * D * 2;
+    const unsigned q_bytes = (unsigned)(L - 1) * q_row_bytes + D * 2;
+    AsyncTile<D, BMQ, 4> loader;
+    loader.init(wave, lane, q_row_bytes);
+    const unsigned smem_lds = lds_addr(smem);
     auto issue = [&](int n) {
-        char* st = smem + (n & 1) * STAGE_BYTES;
+        const unsigned st = smem_lds + (n & 1) * STAGE_BYTES;
         const int head = g * G + n / qt_count;
         const int q0 = (qt_first + n % qt_count) * BMQ;
-        const size_t off = ((size_t)(seq_row0 + q0) * p.Hq + head) * D;
-        async_load_tile<D, BMQ, 4>(st, static_cast<const __bf16*>(p.q) + off, q_stride, L - q0, wave, lane);
-        async_load_tile<D, BMQ, 4>(st + TILE_BYTES, static_cast<const __bf16*>(p.dout) + off, q_stride, L - q0, wave, lane);
-        if (wave < 2) {  // 64 floats each: lane i fetches row q0 + i (clamped to the sample)
-            typedef __attribute__((address_space(3))) void lds_void;
-            typedef __attribute__((address_space(1))) const void glb_void;
-            const float* src = (wave == 0 ? p.lse2 : p.delta) + (size_t)head * p.T + seq_row0 + min(q0 + lane, L - 1);
-            __builtin_amdgcn_global_load_lds((glb_void*)src, (lds_void*)(st + 2 * TILE_BYTES + wave * 256), 4, 0, 0);
+        const size_t off = ((size_t)seq_row0 * p.Hq + head) * D;
+        loader.issue(make_rsrc(static_cast<const __bf16*>(p.q) + off, q_bytes), st, q0 * q_row_bytes);
+        loader.issue(make_rsrc(static_cast<const __bf16*>(p.dout) + off, q_bytes), st + TILE_BYTES, q0 * q_row_bytes);
+        if (wave < 2) {  // 64 floats each: lane i fetches row q0 + i
+            const float* src = (wave == 0 ? p.lse2 : p.delta) + (size_t)head * p.T + seq_row0;
+            buffer_load_lds_4(st + 2 * TILE_BYTES + wave * 256, lane * 4, make_rsrc(src, (unsigned)L * 4), q0 * 4);
         }
     };
     issue(0);
+    if (V_LDS && DO_DK) {
+        const int kv_row_bytes = p.Hkv * D * 2;
+        AsyncTile<D, kDkdvKvRows, 4> v_loader;
+        v_loader.init(wave, lane, kv_row_bytes);
+        const __bf16* v_seq = static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
+        v_loader.issue(make_rsrc(v_seq, (unsigned)(L - 1) * kv_row_bytes + D * 2), smem_lds + 2 * STAGE_BYTES,
+                       (kv_row0 - seq_row0) * kv_row_bytes);
+    }
 
     // this wave's 32 key rows; the lane owns key row jw + l32 (local index in the sample)
     const int jw = kv_row0 - seq_row0 + 32 * wave;
@@ -104,7 +118,8 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
     const bool kv_valid = 32 * wave + l32 < kv_rows;
 
     // K and V fragments of the lane's key row: k-slots d = 16 t + 8 hf + 0..7
-    bf16x8 kf[KSTEPS], vf[KSTEPS];
+    constexpr bool V_REGS = !V_LDS && DO_DK;
+    bf16x8 kf[KSTEPS], vf[V_REGS ? KSTEPS : 1];
     {
         const size_t off = ((size_t)(kv_row0 + 32 * wave + l32) * p.Hkv + g) * D;
         const __bf16* krow = static_cast<const __bf16*>(p.k) + off;
@@ -114,22 +129,27 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
             u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
             if (kv_valid) {
                 a = *reinterpret_cast<const u32x4*>(krow + 16 * t + 8 * hf);
-                b = *reinterpret_cast<const u32x4*>(vrow + 16 * t + 8 * hf);
+                if (V_REGS) b = *reinterpret_cast<const u32x4*>(vrow + 16 * t + 8 * hf);
             }
             kf[t] = __builtin_bit_cast(bf16x8, a);
-            vf[t] = __builtin_bit_cast(bf16x8, b);
+            if (V_REGS) vf[t] = __builtin_bit_cast(bf16x8, b);
         }
     }
 
-    f32x16 dk[DT], dv[DT];
+    f32x16 dk[DO_DK ? DT : 1], dv[DO_DV ? DT : 1];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            dk[dt][r] = 0.0f;
-            dv[dt][r] = 0.0f;
+            if (DO_DK) dk[dt][r] = 0.0f;
+            if (DO_DV) dv[dt][r] = 0.0f;
         }
 
+#pragma unroll
+    for (int t = 0; t < KSTEPS; ++t) {
+        settle(kf[t]);
+        if (V_REGS) settle(vf[t]);
+    }
     wait_async_loads();
     __syncthreads();
 
@@ -145,9 +165,9 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
             const int i0 = q0 + 32 * qb;  // first query row of the block (local index in the sample)
             if (i0 >= L) break;
             const int i1 = min(i0 + 31, L - 1);
-            if (visible_keys(i1, L, P, p.mask_mode) <= jw) continue;  // nothing of this key block is visible
-            // rows past the sample hold stand-in data and must get p = 0: they count as seeing no key
-            const bool need_mask = visible_keys(i0, L, P, p.mask_mode) < jw + 32 || i0 + 32 > L;
+            if (mask.vis(i1) <= jw) continue;  // nothing of this key block is visible
+            // rows past the sample read as zeros and must get p = 0: they count as seeing no key
+            const bool need_mask = mask.vis(i0) < jw + 32 || i0 + 32 > L;
 
             // S = Q K^T : rows = query rows (registers), columns = key rows (lanes)
             f32x16 s, dp;
@@ -158,8 +178,14 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
             }
 #pragma unroll
             for (int t = 0; t < KSTEPS; ++t) s = mfma32(frag_rowmajor<D>(q_tile, 32 * qb + l32, t, hf), kf[t], s);
+            __builtin_amdgcn_sched_barrier(0);  // keep the fragment reads of one product from piling up ahead of another
+            if (DO_DK) {
 #pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) dp = mfma32(frag_rowmajor<D>(do_tile, 32 * qb + l32, t, hf), vf[t], dp);
+                for (int t = 0; t < KSTEPS; ++t)
+                    dp = mfma32(frag_rowmajor<D>(do_tile, 32 * qb + l32, t, hf),
+                                V_LDS ? frag_rowmajor<D>(v_tile, 32 * wave + l32, t, hf) : vf[V_REGS ? t : 0], dp);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
                 const int rb = 32 * qb + 8 * r4 + 4 * hf;  // tile row of registers 4 r4 .. 4 r4 + 3
@@ -169,12 +195,9 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
                 for (int e = 0; e < 4; ++e) {
                     const int r = 4 * r4 + e;
                     float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
-                    if (need_mask) {
-                        const int i = q0 + rb + e;
-                        if (i >= L || kv_local >= visible_keys(i, L, P, p.mask_mode)) pv = 0.0f;
-                    }
+                    if (need_mask && kv_local >= mask.vis_in_sample(q0 + rb + e)) pv = 0.0f;
                     s[r] = pv;
-                    dp[r] = pv * (dp[r] - d4[e]);
+                    if (DO_DK) dp[r] = pv * (dp[r] - d4[e]);
                 }
             }
             bf16x8 pb[2], dsb[2];
@@ -185,14 +208,17 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
                 dsb[x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
                                    dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
             }
+            __builtin_amdgcn_sched_barrier(0);
             // dV^T += dO^T P ; dK^T += Q^T dS  (rows = d, columns = key rows)
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+            for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
                 for (int x = 0; x < 2; ++x) {
-                    dv[dt] = mfma32(frag_transposed<D>(do_tile, 32 * qb + 16 * x, 32 * dt, lane), pb[x], dv[dt]);
-                    dk[dt] = mfma32(frag_transposed<D>(q_tile, 32 * qb + 16 * x, 32 * dt, lane), dsb[x], dk[dt]);
+                    if (DO_DV) dv[dt] = mfma32(frag_transposed<D>(do_tile, 32 * qb + 16 * x, 32 * dt, lane), pb[x], dv[dt]);
+                    if (DO_DK) dk[dt] = mfma32(frag_transposed<D>(q_tile, 32 * qb + 16 * x, 32 * dt, lane), dsb[x], dk[dt]);
                 }
+                if (D == 256 && (dt & 1)) __builtin_amdgcn_sched_barrier(0);
+            }
         }
         wait_async_loads();
         __syncthreads();
@@ -206,11 +232,15 @@ __global__ __launch_bounds__(256) void bwd_dkdv_kernel(AttnParams p) {
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
-                f32x4 a = {dk[dt][4 * r4] * p.scale, dk[dt][4 * r4 + 1] * p.scale, dk[dt][4 * r4 + 2] * p.scale,
-                           dk[dt][4 * r4 + 3] * p.scale};
-                f32x4 b = {dv[dt][4 * r4], dv[dt][4 * r4 + 1], dv[dt][4 * r4 + 2], dv[dt][4 * r4 + 3]};
-                *reinterpret_cast<bf16x4*>(dk_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(a, bf16x4);
-                *reinterpret_cast<bf16x4*>(dv_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(b, bf16x4);
+                if (DO_DK) {
+                    f32x4 a = {dk[dt][4 * r4] * p.scale, dk[dt][4 * r4 + 1] * p.scale, dk[dt][4 * r4 + 2] * p.scale,
+                               dk[dt][4 * r4 + 3] * p.scale};
+                    *reinterpret_cast<bf16x4*>(dk_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(a, bf16x4);
+                }
+                if (DO_DV) {
+                    f32x4 b = {dv[dt][4 * r4], dv[dt][4 * r4 + 1], dv[dt][4 * r4 + 2], dv[dt][4 * r4 + 3]};
+                    *reinterpret_cast<bf16x4*>(dv_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(b, bf16x4);
+                }
             }
     }
 }
@@ -238,17 +268,22 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     const int g = hc / chunks_per_group;
     const int h0 = g * G + (hc % chunks_per_group) * HPB;
 
-    const size_t kv_stride = (size_t)p.Hkv * D;
-    const __bf16* k_base = static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D;
-    const __bf16* v_base = static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
-    async_load_tile<D, BN, 4>(smem, k_base, kv_stride, L, wave, lane);
-    async_load_tile<D, BN, 4>(smem + TILE_BYTES, v_base, kv_stride, L, wave, lane);
+    const int kv_row_bytes = p.Hkv * D * 2;
+    const unsigned kv_bytes = (unsigned)(L - 1) * kv_row_bytes + D * 2;
+    const i32x4 k_rsrc = make_rsrc(static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D, kv_bytes);
+    const i32x4 v_rsrc = make_rsrc(static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D, kv_bytes);
+    AsyncTile<D, BN, 4> loader;
+    loader.init(wave, lane, kv_row_bytes);
+    const unsigned smem_lds = lds_addr(smem);
+    const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
+    loader.issue(k_rsrc, smem_lds, 0);
+    loader.issue(v_rsrc, smem_lds + TILE_BYTES, 0);
 
     const int row = wave * 32 + l32;
     const int head = h0 + row / BMT;
     const int tok = row % BMT;
     const bool row_valid = tok < q_rows;
-    const int vis = visible_keys(q_row0 - seq_row0 + tok, L, P, p.mask_mode);
+    const int vis = RowMask(P, L, p.mask_mode).vis(q_row0 - seq_row0 + tok);
     const float c = p.scale * kLog2e;
 
     bf16x8 qf[KSTEPS], dof[KSTEPS];
@@ -279,6 +314,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[dt][r] = 0.0f;
 
+#pragma unroll
+    for (int t = 0; t < KSTEPS; ++t) {
+        settle(qf[t]);
+        settle(dof[t]);
+    }
+    asm volatile("" ::"v"(lse2), "v"(delta));
     wait_async_loads();
     __syncthreads();
 
@@ -287,10 +328,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         const char* k_tile = smem + (kt & 1) * 2 * TILE_BYTES;
         const char* v_tile = k_tile + TILE_BYTES;
         if (kt + 1 < n_tiles) {
-            char* nk = smem + ((kt + 1) & 1) * 2 * TILE_BYTES;
-            const int j1 = j0 + BN;
-            async_load_tile<D, BN, 4>(nk, k_base + (size_t)j1 * kv_stride, kv_stride, L - j1, wave, lane);
-            async_load_tile<D, BN, 4>(nk + TILE_BYTES, v_base + (size_t)j1 * kv_stride, kv_stride, L - j1, wave, lane);
+            const unsigned nk = smem_lds + ((kt + 1) & 1) * 2 * TILE_BYTES;
+            loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
+            loader.issue(v_rsrc, nk + TILE_BYTES, (kt + 1) * tile_step);
         }
         bf16x8 dsb[4];
 #pragma unroll
@@ -364,15 +404,26 @@ hipError_t launch_dq_d(const AttnParams& p, hipStream_t stream) {
     }
 }
 
+template <int D, int PART>
+hipError_t launch_dkdv_part(const AttnParams& p, hipStream_t stream, unsigned grid) {
+    constexpr bool V_LDS = D >= 128;
+    constexpr size_t smem = 2 * (2 * dkdv_q_tile(D) * D * 2 + 2 * 64 * sizeof(float)) + (V_LDS ? kDkdvKvRows * D * 2 : 0);
+    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, PART>), smem);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, PART>), dim3(grid), dim3(256), smem, stream, p);
+    return hipGetLastError();
+}
+
 template <int D>
 hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     const unsigned grid = (unsigned)p.num_items * (unsigned)p.Hkv;
-    constexpr size_t smem = 2 * (2 * dkdv_q_tile(D) * D * 2 + 2 * 64 * sizeof(float));
     if (grid == 0) return hipSuccess;
-    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D>), smem);
-    if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((bwd_dkdv_kernel<D>), dim3(grid), dim3(256), smem, stream, p);
-    return hipGetLastError();
+    if constexpr (D <= 128) {
+        return launch_dkdv_part<D, 0>(p, stream, grid);
+    } else {
+        const hipError_t e = launch_dkdv_part<D, 1>(p, stream, grid);
+        return e != hipSuccess ? e : launch_dkdv_part<D, 2>(p, stream, grid);
+    }
 }
 
 template <int D>

@@ -28,7 +28,7 @@ constexpr int32_t kDqKvTile = 64;
 // A dK/dV workgroup owns kDkdvKvRows key rows of one KV head and visits the
 // query rows that see them kDkdvQTile rows at a time, for every head of the group.
 constexpr int32_t kDkdvKvRows = 128;
-constexpr int32_t dkdv_q_tile(int32_t D) { return D == 256 ? 32 : 64; }
+constexpr int32_t dkdv_q_tile(int32_t D) { return D >= 128 ? 32 : 64; }
 
 extern thread_local char g_error[512];
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));

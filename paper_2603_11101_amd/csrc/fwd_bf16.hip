@@ -27,13 +27,8 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kPrefetch = 4;       // LDS fragment reads in flight ahead of the MFMA that uses them
 constexpr float kMaxLag = 8.0f;  // the softmax reference may trail a row's true maximum by this many powers of two
-
-VA_DEV int visible_keys(int i, int L, int P, int mode) {
-    if (mode == VA_MASK_CAUSAL) return i + 1;
-    if (i < P) return P;
-    return mode == VA_MASK_PREFIX_LM ? L : i + 1;
-}
 
 template <int D, int HPB>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnParams p) {
@@ -57,20 +52,26 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     const int g = hc / chunks_per_group;
     const int h0 = g * G + (hc % chunks_per_group) * HPB;
 
-    const size_t kv_stride = (size_t)p.Hkv * D;
-    const __bf16* k_base = static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D;
-    const __bf16* v_base = static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
+    // K and V rows of this sample and KV head as raw buffers: rows >= L read as zero
+    const int kv_row_bytes = p.Hkv * D * 2;
+    const unsigned kv_bytes = (unsigned)(L - 1) * kv_row_bytes + D * 2;
+    const i32x4 k_rsrc = make_rsrc(static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D, kv_bytes);
+    const i32x4 v_rsrc = make_rsrc(static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D, kv_bytes);
+    AsyncTile<D, BN, 4> loader;
+    loader.init(wave, lane, kv_row_bytes);
+    const unsigned smem_lds = lds_addr(smem);
+    const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
 
     // first K/V tile on its way before anything else
-    async_load_tile<D, BN, 4>(smem, k_base, kv_stride, L, wave, lane);
-    async_load_tile<D, BN, 4>(smem + TILE_BYTES, v_base, kv_stride, L, wave, lane);
+    loader.issue(k_rsrc, smem_lds, 0);
+    loader.issue(v_rsrc, smem_lds + TILE_BYTES, 0);
 
     // the stacked row this lane owns
     const int row = wave * 32 + l32;
     const int head = h0 + row / BMT;
     const int tok = row % BMT;
     const bool row_valid = tok < q_rows;
-    const int vis = visible_keys(q_row0 - seq_row0 + tok, L, P, p.mask_mode);
+    const int vis = RowMask(P, L, p.mask_mode).vis(q_row0 - seq_row0 + tok);
 
     // Q fragments stay in registers for the whole item: k-slots d = 16 t + 8 hf + 0..7
     bf16x8 qf[KSTEPS];
@@ -96,6 +97,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     float lsum = 0.0f;  // this lane's share of the running sum (other share in lane + 32)
     const float c = p.scale * kLog2e;
 
+#pragma unroll
+    for (int t = 0; t < KSTEPS; ++t) settle(qf[t]);
     wait_async_loads();
     __syncthreads();
 
@@ -104,21 +107,38 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         const char* k_tile = smem + (kt & 1) * 2 * TILE_BYTES;
         const char* v_tile = k_tile + TILE_BYTES;
         if (kt + 1 < n_tiles) {
-            char* nk = smem + ((kt + 1) & 1) * 2 * TILE_BYTES;
-            const int j1 = j0 + BN;
-            async_load_tile<D, BN, 4>(nk, k_base + (size_t)j1 * kv_stride, kv_stride, L - j1, wave, lane);
-            async_load_tile<D, BN, 4>(nk + TILE_BYTES, v_base + (size_t)j1 * kv_stride, kv_stride, L - j1, wave, lane);
+            const unsigned nk = smem_lds + ((kt + 1) & 1) * 2 * TILE_BYTES;
+            loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
+            loader.issue(v_rsrc, nk + TILE_BYTES, (kt + 1) * tile_step);
         }
 
-        // S^T: two blocks of 32 keys x 32 query rows
+        // S^T: two blocks of 32 keys x 32 query rows.  The K fragments are fetched from LDS kPrefetch
+        // steps ahead of the MFMA that consumes them so the matrix pipe never waits on an LDS read.
         f32x16 s[2];
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[b][r] = 0.0f;
+        {
+            constexpr int NS = 2 * KSTEPS;
+            bf16x8 ring[kPrefetch];
 #pragma unroll
-            for (int t = 0; t < KSTEPS; ++t)
-                s[b] = mfma32(frag_rowmajor<D>(k_tile, 32 * b + l32, t, hf), qf[t], s[b]);
+            for (int i = 0; i < kPrefetch; ++i) ring[i] = frag_rowmajor<D>(k_tile, 32 * (i / KSTEPS) + l32, i % KSTEPS, hf);
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                const bf16x8 a = ring[i % kPrefetch];
+                if (i + kPrefetch < NS)
+                    ring[i % kPrefetch] = frag_rowmajor<D>(k_tile, 32 * ((i + kPrefetch) / KSTEPS) + l32, (i + kPrefetch) % KSTEPS, hf);
+                s[i / KSTEPS] = mfma32(a, qf[i % KSTEPS], s[i / KSTEPS]);
+            }
+            // pin the issue order: kPrefetch reads up front, then one read per MFMA
+#pragma unroll
+            for (int i = 0; i < kPrefetch; ++i) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (i + kPrefetch < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
         }
         if (kt >= n_full) {
 #pragma unroll
@@ -127,6 +147,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
                 for (int r = 0; r < 16; ++r)
                     if (j0 + 32 * b + acc_row(r, hf) >= vis) s[b][r] = -INFINITY;
         }
+        // first V^T fragments on their way while the softmax runs
+        bf16x8 vring[kPrefetch];
+#pragma unroll
+        for (int i = 0; i < kPrefetch; ++i) vring[i] = frag_transposed<D>(v_tile, 16 * (i % 4), 32 * (i / 4), lane);
         float mx = s[0][0];
 #pragma unroll
         for (int b = 0; b < 2; ++b)
@@ -162,11 +186,21 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
             for (int x = 0; x < 2; ++x)
                 pf[2 * b + x] = to_bf16x8(s[b][8 * x + 0], s[b][8 * x + 1], s[b][8 * x + 2], s[b][8 * x + 3],
                                           s[b][8 * x + 4], s[b][8 * x + 5], s[b][8 * x + 6], s[b][8 * x + 7]);
+        {
+            constexpr int NS = 4 * DT;  // step i: O^T block i / 4, keys 16 (i % 4) .. + 15
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+            for (int i = 0; i < NS; ++i) {
+                const bf16x8 a = vring[i % kPrefetch];
+                if (i + kPrefetch < NS)
+                    vring[i % kPrefetch] = frag_transposed<D>(v_tile, 16 * ((i + kPrefetch) % 4), 32 * ((i + kPrefetch) / 4), lane);
+                o[i / 4] = mfma32(a, pf[i % 4], o[i / 4]);
+            }
 #pragma unroll
-            for (int x = 0; x < 4; ++x)
-                o[dt] = mfma32(frag_transposed<D>(v_tile, 16 * x, 32 * dt, lane), pf[x], o[dt]);
+            for (int i = 0; i < NS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                if (i + kPrefetch < NS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+            }
+        }
 
         // the next tile has landed and every wave is done reading this one
         wait_async_loads();

@@ -33,12 +33,6 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-VA_DEV int visible_keys(int i, int L, int P, int mode) {
-    if (mode == VA_MASK_CAUSAL) return i + 1;
-    if (i < P) return P;
-    return mode == VA_MASK_PREFIX_LM ? L : i + 1;
-}
-
 VA_DEV f32x16 mfma_f8(i32x8 a, i32x8 b, f32x16 c) {
     // formats 0 = E4M3 for both operands; block scales 127 = 2^0
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 127, 0, 127);
@@ -77,7 +71,7 @@ __global__ __launch_bounds__(256) void fwd_fp8_kernel(AttnParams p) {
     const int head = h0 + row / BMT;
     const int tok = row % BMT;
     const bool row_valid = tok < q_rows;
-    const int vis = visible_keys(q_row0 - seq_row0 + tok, L, P, p.mask_mode);
+    const int vis = RowMask(P, L, p.mask_mode).vis(q_row0 - seq_row0 + tok);
 
     // Q fragments: contraction slots d = 64 t + 32 hf + 0..31
     i32x8 qf[KSTEPS];

@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "../../include/varlen_attn.h"
+
 namespace va {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -49,6 +51,21 @@ VA_DEV float pair_sum(float x) {
     u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+
+// ---------------------------------------------------------------- masks
+//
+// Every mask of the library has the form "local query row i sees keys j < vis(i)" with vis
+// non-decreasing: causal i + 1; prefix-LM P for i < P, else L; prefix-LM with causal suffix P for
+// i < P, else i + 1.  Branch-free so that it can sit in per-element code.
+struct RowMask {
+    int P;   // prefix length (0 when causal)
+    int SF;  // L when suffix rows see the whole sample, else 0
+    int L;
+    VA_DEV RowMask(int item_P, int item_L, int mode)
+        : P(item_P < 0 ? 0 : item_P), SF(mode == VA_MASK_PREFIX_LM ? item_L : 0), L(item_L) {}
+    VA_DEV int vis(int i) const { return i < P ? P : max(i + 1, SF); }  // any i >= 0
+    VA_DEV int vis_in_sample(int i) const { return i < L ? vis(i) : 0; }  // rows past the sample see nothing
+};
 
 // ---------------------------------------------------------------- LDS tiles
 //
@@ -130,36 +147,90 @@ VA_DEV void load_tile(char* tile, const __bf16* g, size_t gstride, int valid_row
     }
 }
 
-// Asynchronous copy of ROWS x D bf16 values from global memory straight into a
-// swizzled LDS tile (global_load_lds_dwordx4: every lane fetches 16 bytes and
-// the hardware writes them to LDS at base + 16 * lane, no registers involved).
-// One wave instruction fills 1 KiB of the tile; the NWAVES waves of the
-// workgroup share the tile's instructions.  The swizzle is applied on the
-// global side: the lane that fills chunk position pc of row r fetches chunk
-// pc ^ swizzle(r) of that row.  Rows >= valid_rows (>= 1) are filled with a copy
-// of the last valid row instead of being read: callers make sure such rows meet
-// a zero probability, so a finite stand-in is as good as zero.
-// The caller must wait (wait_async_loads) and then barrier before reading.
-template <int D, int ROWS, int NWAVES>
-VA_DEV void async_load_tile(char* tile, const __bf16* g, size_t gstride, int valid_rows, int wave, int lane) {
-    constexpr int CPR = D / 8;
-    constexpr int RPI = 64 / CPR;  // rows per wave instruction
-    constexpr int INSTR = ROWS / RPI;
-    static_assert(INSTR % NWAVES == 0, "tile must divide among the waves");
-    typedef __attribute__((address_space(3))) void lds_void;
-    typedef __attribute__((address_space(1))) const void glb_void;
-    const int pc = lane % CPR;
-#pragma unroll
-    for (int j = 0; j < INSTR / NWAVES; ++j) {
-        const int inst = wave * (INSTR / NWAVES) + j;
-        const int r = inst * RPI + lane / CPR;
-        const int rc = min(r, valid_rows - 1);
-        const __bf16* src = g + (size_t)rc * gstride + ((pc ^ swizzle<D>(r)) << 3);
-        __builtin_amdgcn_global_load_lds((glb_void*)src, (lds_void*)(tile + inst * 1024), 16, 0, 0);
-    }
+// ---------------------------------------------------------------- asynchronous tile loads
+//
+// Tiles travel from global memory straight into LDS (buffer_load_dwordx4 ... lds:
+// every lane fetches 16 bytes and the hardware writes them to LDS at
+// M0 + 16 * lane, no registers involved).  The loads are issued from inline
+// assembly so that the compiler does not see them as LDS writes: it would
+// otherwise wait for them before the next LDS read that might alias, which
+// defeats prefetching into the other stage.  The kernels order them by hand:
+// wait_async_loads() and a barrier before the first read of a stage.
+//
+// The global side is a raw buffer resource covering exactly the rows of one
+// sample for one head, so rows past the sample read as zero and are never
+// touched in memory.
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// Buffer resource for `bytes` bytes starting at `base` (wave-uniform).
+VA_DEV i32x4 make_rsrc(const void* base, unsigned bytes) {
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(a & 0xffffffffu));
+    r[1] = __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu));  // stride 0: raw buffer
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
 }
 
+// LDS byte address of a pointer into shared memory (wave-uniform).
+VA_DEV unsigned lds_addr(const void* p) {
+    return __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lds_char*)p);
+}
+
+// lds_dst, rsrc and soffset must be wave-uniform; readfirstlane makes that explicit to the compiler
+VA_DEV void buffer_load_lds_16(unsigned lds_dst, int voffset, i32x4 rsrc, int soffset) {
+    lds_dst = __builtin_amdgcn_readfirstlane(lds_dst);
+    soffset = __builtin_amdgcn_readfirstlane(soffset);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds_dst), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+}
+VA_DEV void buffer_load_lds_4(unsigned lds_dst, int voffset, i32x4 rsrc, int soffset) {
+    lds_dst = __builtin_amdgcn_readfirstlane(lds_dst);
+    soffset = __builtin_amdgcn_readfirstlane(soffset);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(lds_dst), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+}
+
+// A fragment that was loaded from global memory by ordinary loads before a loop that also issues
+// asynchronous tile loads: touching it here makes the compiler place its own wait for those ordinary
+// loads now, instead of a conservative wait-for-everything at the first use inside the loop (which
+// would also wait for the freshly issued tile loads it knows nothing about).
+VA_DEV void settle(const bf16x8& f) { asm volatile("" ::"v"(f)); }
+
 VA_DEV void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Copy plan of one swizzled ROWS x D bf16 tile shared by NWAVES waves.  One
+// wave instruction fills 1 KiB of the tile (64 / (D/8) rows); the lane that
+// fills chunk position pc of row r fetches chunk pc ^ swizzle(r) of that row, so
+// the swizzle costs nothing.  The per-lane offsets do not depend on which tile
+// of the sample is fetched: that goes into the scalar offset of the load.
+template <int D, int ROWS, int NWAVES>
+struct AsyncTile {
+    static constexpr int CPR = D / 8;
+    static constexpr int RPI = 64 / CPR;
+    static constexpr int INSTR = ROWS / RPI;
+    static constexpr int PER_WAVE = INSTR / NWAVES;
+    static_assert(INSTR % NWAVES == 0, "tile must divide among the waves");
+    int voff[PER_WAVE];
+    int first;  // first instruction of this wave
+
+    VA_DEV void init(int wave, int lane, int row_bytes) {
+        first = __builtin_amdgcn_readfirstlane(wave * PER_WAVE);
+        const int pc = lane % CPR;
+#pragma unroll
+        for (int j = 0; j < PER_WAVE; ++j) {
+            const int r = (wave * PER_WAVE + j) * RPI + lane / CPR;
+            voff[j] = r * row_bytes + ((pc ^ swizzle<D>(r)) << 4);
+        }
+    }
+    // tile_lds: LDS address of the tile; soffset: byte offset of the tile's first row in the buffer
+    VA_DEV void issue(i32x4 rsrc, unsigned tile_lds, int soffset) const {
+#pragma unroll
+        for (int j = 0; j < PER_WAVE; ++j) buffer_load_lds_16(tile_lds + (first + j) * 1024, voff[j], rsrc, soffset);
+    }
+};
 
 // float pairs -> packed bf16 (round to nearest even)
 VA_DEV bf16x8 to_bf16x8(float a0, float a1, float a2, float a3, float a4, float a5, float a6, float a7) {
