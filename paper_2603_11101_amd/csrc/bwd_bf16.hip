@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     constexpr int TILE_BYTES = BMQ * D * 2;
     constexpr int STAGE_BYTES = 2 * TILE_BYTES + 2 * 64 * (int)sizeof(float);  // Q, dO, LSE2[64], delta[64]
     extern __shared__ __attribute__((aligned(16))) char smem[];  // two stages, then the V tile if V_LDS
-    const char* v_tile = smem + 2 * STAGE_BYTES;
+    constexpr int v_tile = 2 * STAGE_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
@@ -153,11 +153,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     wait_async_loads();
     __syncthreads();
 
+    const FragAddr<D> fa(lane);
     for (int n = 0; n < n_steps; ++n) {
         if (n + 1 < n_steps) issue(n + 1);
-        const char* q_tile = smem + (n & 1) * STAGE_BYTES;
-        const char* do_tile = q_tile + TILE_BYTES;
-        const float* lse_s = reinterpret_cast<const float*>(q_tile + 2 * TILE_BYTES);
+        const int q_tile = (n & 1) * STAGE_BYTES;  // byte offsets of this stage's tiles
+        const int do_tile = q_tile + TILE_BYTES;
+        const float* lse_s = reinterpret_cast<const float*>(smem + q_tile + 2 * TILE_BYTES);
         const float* delta_s = lse_s + 64;
         const int q0 = (qt_first + n % qt_count) * BMQ;
 #pragma unroll
@@ -177,13 +178,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                 dp[r] = 0.0f;
             }
 #pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) s = mfma32(frag_rowmajor<D>(q_tile, 32 * qb + l32, t, hf), kf[t], s);
+            for (int t = 0; t < KSTEPS; ++t) s = mfma32(fa.rowmajor(smem, q_tile, qb, t), kf[t], s);
             __builtin_amdgcn_sched_barrier(0);  // keep the fragment reads of one product from piling up ahead of another
             if (DO_DK) {
 #pragma unroll
                 for (int t = 0; t < KSTEPS; ++t)
-                    dp = mfma32(frag_rowmajor<D>(do_tile, 32 * qb + l32, t, hf),
-                                V_LDS ? frag_rowmajor<D>(v_tile, 32 * wave + l32, t, hf) : vf[V_REGS ? t : 0], dp);
+                    dp = mfma32(fa.rowmajor(smem, do_tile, qb, t),
+                                V_LDS ? fa.rowmajor(smem, v_tile, wave, t) : vf[V_REGS ? t : 0], dp);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -214,8 +215,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
             for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
                 for (int x = 0; x < 2; ++x) {
-                    if (DO_DV) dv[dt] = mfma32(frag_transposed<D>(do_tile, 32 * qb + 16 * x, 32 * dt, lane), pb[x], dv[dt]);
-                    if (DO_DK) dk[dt] = mfma32(frag_transposed<D>(q_tile, 32 * qb + 16 * x, 32 * dt, lane), dsb[x], dk[dt]);
+                    if (DO_DV) dv[dt] = mfma32(fa.transposed(smem, do_tile, 2 * qb + x, dt), pb[x], dv[dt]);
+                    if (DO_DK) dk[dt] = mfma32(fa.transposed(smem, q_tile, 2 * qb + x, dt), dsb[x], dk[dt]);
                 }
                 if (D == 256 && (dt & 1)) __builtin_amdgcn_sched_barrier(0);
             }
@@ -323,10 +324,11 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     wait_async_loads();
     __syncthreads();
 
+    const FragAddr<D> fa(lane);
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int j0 = kt * BN;
-        const char* k_tile = smem + (kt & 1) * 2 * TILE_BYTES;
-        const char* v_tile = k_tile + TILE_BYTES;
+        const int k_tile = (kt & 1) * 2 * TILE_BYTES;  // byte offsets of this stage's tiles
+        const int v_tile = k_tile + TILE_BYTES;
         if (kt + 1 < n_tiles) {
             const unsigned nk = smem_lds + ((kt + 1) & 1) * 2 * TILE_BYTES;
             loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
@@ -343,9 +345,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
                 dp[r] = 0.0f;
             }
 #pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) s = mfma32(frag_rowmajor<D>(k_tile, 32 * b + l32, t, hf), qf[t], s);
+            for (int t = 0; t < KSTEPS; ++t) s = mfma32(fa.rowmajor(smem, k_tile, b, t), qf[t], s);
 #pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) dp = mfma32(frag_rowmajor<D>(v_tile, 32 * b + l32, t, hf), dof[t], dp);
+            for (int t = 0; t < KSTEPS; ++t) dp = mfma32(fa.rowmajor(smem, v_tile, b, t), dof[t], dp);
             const bool need_mask = kt >= n_full;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -363,7 +365,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int x = 0; x < 4; ++x)
-                dq[dt] = mfma32(frag_transposed<D>(k_tile, 16 * x, 32 * dt, lane), dsb[x], dq[dt]);
+                dq[dt] = mfma32(fa.transposed(smem, k_tile, x, dt), dsb[x], dq[dt]);
         wait_async_loads();
         __syncthreads();
     }

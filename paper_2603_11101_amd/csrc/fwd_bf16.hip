@@ -102,15 +102,18 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     wait_async_loads();
     __syncthreads();
 
+    const FragAddr<D> fa(lane);
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int j0 = kt * BN;
-        const char* k_tile = smem + (kt & 1) * 2 * TILE_BYTES;
-        const char* v_tile = k_tile + TILE_BYTES;
+        const int k_tile = (kt & 1) * 2 * TILE_BYTES;  // byte offsets of this stage's tiles
+        const int v_tile = k_tile + TILE_BYTES;
+#ifndef VA_EXP_NO_PREFETCH
         if (kt + 1 < n_tiles) {
             const unsigned nk = smem_lds + ((kt + 1) & 1) * 2 * TILE_BYTES;
             loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
             loader.issue(v_rsrc, nk + TILE_BYTES, (kt + 1) * tile_step);
         }
+#endif
 
         // S^T: two blocks of 32 keys x 32 query rows.  The K fragments are fetched from LDS kPrefetch
         // steps ahead of the MFMA that consumes them so the matrix pipe never waits on an LDS read.
@@ -123,12 +126,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
             constexpr int NS = 2 * KSTEPS;
             bf16x8 ring[kPrefetch];
 #pragma unroll
-            for (int i = 0; i < kPrefetch; ++i) ring[i] = frag_rowmajor<D>(k_tile, 32 * (i / KSTEPS) + l32, i % KSTEPS, hf);
+            for (int i = 0; i < kPrefetch; ++i) ring[i] = fa.rowmajor(smem, k_tile, i / KSTEPS, i % KSTEPS);
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
                 const bf16x8 a = ring[i % kPrefetch];
                 if (i + kPrefetch < NS)
-                    ring[i % kPrefetch] = frag_rowmajor<D>(k_tile, 32 * ((i + kPrefetch) / KSTEPS) + l32, (i + kPrefetch) % KSTEPS, hf);
+                    ring[i % kPrefetch] = fa.rowmajor(smem, k_tile, (i + kPrefetch) / KSTEPS, (i + kPrefetch) % KSTEPS);
                 s[i / KSTEPS] = mfma32(a, qf[i % KSTEPS], s[i / KSTEPS]);
             }
             // pin the issue order: kPrefetch reads up front, then one read per MFMA
@@ -150,7 +153,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         // first V^T fragments on their way while the softmax runs
         bf16x8 vring[kPrefetch];
 #pragma unroll
-        for (int i = 0; i < kPrefetch; ++i) vring[i] = frag_transposed<D>(v_tile, 16 * (i % 4), 32 * (i / 4), lane);
+        for (int i = 0; i < kPrefetch; ++i) 
+#if defined(VA_EXP_V_ROWMAJOR)
+            vring[i] = fa.rowmajor(smem, v_tile, i % 2, i / 4);
+#else
+            vring[i] = fa.transposed(smem, v_tile, i % 4, i / 4);
+#endif
+
         float mx = s[0][0];
 #pragma unroll
         for (int b = 0; b < 2; ++b)
@@ -172,7 +181,11 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
+#ifdef VA_EXP_NO_EXP
+                const float pv = s[b][r];
+#else
                 const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, -m));
+#endif
                 s[b][r] = pv;
                 psum += pv;
             }
@@ -192,7 +205,15 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
             for (int i = 0; i < NS; ++i) {
                 const bf16x8 a = vring[i % kPrefetch];
                 if (i + kPrefetch < NS)
-                    vring[i % kPrefetch] = frag_transposed<D>(v_tile, 16 * ((i + kPrefetch) % 4), 32 * ((i + kPrefetch) / 4), lane);
+                    {
+#if defined(VA_EXP_V_ROWMAJOR)
+                    vring[i % kPrefetch] = fa.rowmajor(smem, v_tile, (i + kPrefetch) % 2, (i + kPrefetch) / 4);
+#elif defined(VA_EXP_V_NOREAD)
+                    vring[i % kPrefetch] = a;
+#else
+                    vring[i % kPrefetch] = fa.transposed(smem, v_tile, (i + kPrefetch) % 4, (i + kPrefetch) / 4);
+#endif
+                }
                 o[i / 4] = mfma32(a, pf[i % 4], o[i / 4]);
             }
 #pragma unroll
@@ -204,7 +225,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
 
         // the next tile has landed and every wave is done reading this one
         wait_async_loads();
+#ifndef VA_EXP_NO_BARRIER
         __syncthreads();
+#endif
     }
 
     lsum = pair_sum(lsum);

@@ -77,57 +77,91 @@ struct RowMask {
 // (2) 32 lanes reading 4 consecutive rows by 4 consecutive chunks with the
 // transposing read.
 template <int D>
-VA_DEV int swizzle(int r) {
-    if (D == 64) return (((r >> 1) & 1) << 2) | ((r >> 2) & 3);
-    return ((r & 3) << 2) | ((r >> 2) & 3);
+__host__ __device__ constexpr int swizzle(int r) {
+    return D == 64 ? ((((r >> 1) & 1) << 2) | ((r >> 2) & 3)) : (((r & 3) << 2) | ((r >> 2) & 3));
 }
 
 // Byte offset inside a tile of the 16-byte chunk c of row r.
 template <int D>
-VA_DEV int tile_off(int r, int c) {
+__host__ __device__ constexpr int tile_off(int r, int c) {
     return r * (D * 2) + ((c ^ swizzle<D>(r)) << 4);
 }
 
 typedef __attribute__((address_space(3))) char lds_char;
 
-VA_DEV bf16x8 lds_read_chunk(const char* tile, int off) {
-    return *reinterpret_cast<const bf16x8*>(tile + off);
-}
-
-// Operand fragment "rows x k" for a row-major tile whose contraction index is
-// the column (the D axis): lane holds row `row`, k-slots d = 16*t + 8*hf + 0..7.
-template <int D>
-VA_DEV bf16x8 frag_rowmajor(const char* tile, int row, int t, int hf) {
-    return lds_read_chunk(tile, tile_off<D>(row, 2 * t + hf));
-}
-
-// Operand fragment for a row-major tile whose contraction index is the ROW
-// (token) axis: the lane wants column `col` (a D index) and the 8 token rows
-// row0 + {4*hf + 0..3, 8 + 4*hf + 0..3}, which is exactly the order in which a
-// 32x32 accumulator holds its rows (see acc_row), so a product whose other
-// operand comes straight out of an accumulator lines up.
+// Per-lane constants of the two fragment patterns, so that the address of a fragment is one XOR
+// (plus an immediate) away from a value computed once per kernel.
 //
-// ds_read_b64_tr_b16 works on groups of 16 lanes: lane i of a group receives,
-// as element e, the 16-bit word (i % 4) of the 8 bytes addressed by lane
-// 4 * e + i / 4 of the group (measured).  Pointing lane s of a group at row
-// (s / 4), columns 4 * (s % 4) .. + 3 of a 4 x 16 block therefore hands lane i
-// the column i of that block, rows 0..3.
+// Row-major fragment (contraction over D): the lane reads row 32 b + lane % 32, k-slots
+// d = 16 t + 8 hf + 0..7, i.e. chunk 2 t + hf.  The swizzle of that row only depends on lane % 32 and
+// only touches chunk bits, so   offset(b, t) = (rm ^ (t << 5)) + b * 32 rows.
+//
+// Transposed fragment (contraction over token rows): the lane wants column 32 dt + lane % 32 and the
+// 8 token rows 16 x + {4 hf + 0..3, 8 + 4 hf + 0..3}, the order in which a 32x32 accumulator holds
+// its rows (acc_row), so a product whose other operand comes straight out of an accumulator lines up.
+// ds_read_b64_tr_b16 works on groups of 16 lanes: lane i of a group receives, as element e, the
+// 16-bit word (i % 4) of the 8 bytes addressed by lane 4 e + i / 4 of the group (measured).  Lane s of
+// a group therefore points at row s / 4, columns 4 (s % 4) .. + 3 of a 4 x 16 block, and lane i gets
+// column i of the block, rows 0..3.  Two reads (rows + 0 and + 8) make one fragment:
+//   offset(j, x, dt) = (tr[j] ^ (dt << 6)) + x * 16 rows.
 template <int D>
-VA_DEV bf16x8 frag_transposed(const char* tile, int row0, int col_base32, int lane) {
-    const int hf = lane >> 5;
-    const int s = lane & 15;
-    const int col = col_base32 + ((lane >> 4) & 1) * 16 + (s & 3) * 4;  // first of the 4 columns this lane addresses
-    const int r0 = row0 + 4 * hf + (s >> 2);
-    const int r1 = r0 + 8;
-    const int chunk = col >> 3;
-    const int half = (col & 4) << 1;  // 0 or 8 bytes
-    typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(lds_char*)(tile + tile_off<D>(r0, chunk) + half));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(lds_char*)(tile + tile_off<D>(r1, chunk) + half));
-    typedef short s16x8 __attribute__((ext_vector_type(8)));
-    s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, both);
-}
+struct FragAddr {
+    int rm;
+    int tr[2];
+
+    static __host__ __device__ constexpr int rm_base(int lane) {
+        const int l32 = lane & 31, hf = lane >> 5, sw = swizzle<D>(l32);
+        return l32 * (D * 2) + ((hf ^ (sw & 1)) << 4) + ((sw >> 1) << 5);
+    }
+    static __host__ __device__ constexpr int tr_base(int lane, int j) {
+        const int hf = lane >> 5, s = lane & 15;
+        const int r = 4 * hf + (s >> 2) + 8 * j;
+        const int sw = swizzle<D>(r);
+        const int cl = 2 * ((lane >> 4) & 1) + ((s & 3) >> 1);  // chunk of the lane's 4 columns inside a 32-column block
+        const int half = (s & 1) << 3;                          // which 8 bytes of the chunk
+        return r * (D * 2) + half + ((cl ^ (sw & 3)) << 4) + ((sw >> 2) << 6);
+    }
+    static __host__ __device__ constexpr int rm_off(int lane, int b, int t) {
+        return (rm_base(lane) ^ (t << 5)) + b * 32 * (D * 2);
+    }
+    static __host__ __device__ constexpr int tr_off(int lane, int j, int x, int dt) {
+        return (tr_base(lane, j) ^ (dt << 6)) + x * 16 * (D * 2);
+    }
+    // the closed forms against the plain definition, every lane and step
+    static constexpr bool self_check() {
+        for (int lane = 0; lane < 64; ++lane) {
+            const int l32 = lane & 31, hf = lane >> 5, s = lane & 15;
+            for (int b = 0; b < 4; ++b)
+                for (int t = 0; t < D / 16; ++t)
+                    if (rm_off(lane, b, t) != tile_off<D>(32 * b + l32, 2 * t + hf)) return false;
+            for (int j = 0; j < 2; ++j)
+                for (int x = 0; x < 8; ++x)
+                    for (int dt = 0; dt < D / 32; ++dt) {
+                        const int row = 16 * x + 4 * hf + (s >> 2) + 8 * j;
+                        const int col = 32 * dt + ((lane >> 4) & 1) * 16 + (s & 3) * 4;
+                        if (tr_off(lane, j, x, dt) != tile_off<D>(row, col >> 3) + ((col & 4) << 1)) return false;
+                    }
+        }
+        return true;
+    }
+    static_assert(self_check(), "fragment address closed forms disagree with the tile layout");
+
+    VA_DEV explicit FragAddr(int lane) : rm(rm_base(lane)), tr{tr_base(lane, 0), tr_base(lane, 1)} {}
+
+    // `lds` is the base of dynamic shared memory, `tile` the byte offset of the tile inside it
+    VA_DEV bf16x8 rowmajor(const char* lds, int tile, int b, int t) const {
+        return *reinterpret_cast<const bf16x8*>(lds + (((rm + tile) ^ (t << 5)) + b * 32 * (D * 2)));
+    }
+    VA_DEV bf16x8 transposed(const char* lds, int tile, int x, int dt) const {
+        typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4)(lds_char*)(lds + (((tr[0] + tile) ^ (dt << 6)) + x * 16 * (D * 2))));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4)(lds_char*)(lds + (((tr[1] + tile) ^ (dt << 6)) + x * 16 * (D * 2))));
+        return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+};
 
 // Copy ROWS x D bf16 values from global memory (row stride `gstride` elements)
 // into a swizzled LDS tile with 16-byte accesses; rows >= valid_rows are filled
