@@ -119,7 +119,8 @@ def va_worklist_bytes(cu_seqlens, pass_id, head_dim, num_q_heads, num_kv_heads):
 
 
 def va_build_worklist(cu_seqlens, prefix_lens, mask_mode, pass_id, head_dim, num_q_heads, num_kv_heads):
-    """Returns the work list as an int32 array [1 + num_items, 8] (row 0 = header)."""
+    """Returns the whole work list as an int32 array of 8-word records (see ``worklist_items`` and
+    ``worklist_schedule`` for its parts)."""
     cu = _i32(cu_seqlens)
     pl = None if prefix_lens is None else _i32(prefix_lens)
     nbytes = va_worklist_bytes(cu, pass_id, head_dim, num_q_heads, num_kv_heads)
@@ -129,7 +130,22 @@ def va_build_worklist(cu_seqlens, prefix_lens, mask_mode, pass_id, head_dim, num
                                   ctypes.c_int32(pass_id), ctypes.c_int32(head_dim), ctypes.c_int32(num_q_heads),
                                   ctypes.c_int32(num_kv_heads), _ptr(buf), ctypes.c_size_t(nbytes),
                                   ctypes.byref(n_items)))
-    return buf[:1 + n_items.value]
+    assert n_items.value == buf[0, 6]
+    return buf
+
+
+def worklist_items(wl):
+    """Item records [num_items, 8] of a work list."""
+    return wl[wl[1, 3]:wl[1, 3] + wl[0, 6]]
+
+
+def worklist_schedule(wl):
+    """(table [num_workgroups, 2] of (first work, count), work ids [num_works]) of a work list."""
+    flat = wl.reshape(-1)
+    P, W = int(wl[1, 0]), int(wl[1, 1])
+    table = flat[8 * wl[1, 4]:8 * wl[1, 4] + 2 * P].reshape(P, 2)
+    ids = flat[8 * wl[1, 5]:8 * wl[1, 5] + W]
+    return table, ids
 
 
 def va_quantize_e4m3_per_head(x_bf16_bits):

@@ -40,9 +40,10 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
 }
 
 // The host copy of a work list is checked against the stream it claims to
-// describe: header fields, and every item must lie inside one sample.
+// describe: headers, every item must lie inside one sample of cu_seqlens, and
+// the workgroup table must partition the works.
 int check_worklist(const void* dev, const void* host, const va_shape* s, const int32_t* cu, int32_t pass,
-                   const char* who, int32_t* num_items) {
+                   const char* who, WorklistLayout* layout) {
     if (!dev || !host) return fail(VA_EINVAL, "%s: null work list", who);
     const WorkItem* w = static_cast<const WorkItem*>(host);
     int32_t rows, cols;
@@ -57,27 +58,53 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
     int64_t expect = 0;
     for (int32_t i = 0; i < s->num_seqs; ++i) expect += (cu[i + 1] - cu[i] + rows - 1) / rows;
     if (n != expect) return fail(VA_EINVAL, "%s: work list holds %d items, this stream needs %lld", who, n, (long long)expect);
-    for (int32_t i = 1; i <= n; ++i) {
-        const int32_t* it = w[i].w;
+    const WorklistLayout lay = worklist_layout(pass, s->head_dim, s->num_q_heads, s->num_kv_heads, n);
+    const int32_t* h1 = w[1].w;
+    if (h1[0] != lay.num_workgroups || h1[1] != lay.num_works || h1[2] != lay.works_per_item || h1[3] != lay.item_rec ||
+        h1[4] != lay.table_rec || h1[5] != lay.id_rec || h1[6] != lay.total_recs)
+        return fail(VA_EINVAL, "%s: work list schedule header does not match this call", who);
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t* it = w[lay.item_rec + i].w;
         const int32_t row0 = it[0], nrows = it[1], seq0 = it[2], L = it[7];
         const bool ok = nrows > 0 && nrows <= rows && seq0 >= 0 && L > 0 && row0 >= seq0 && row0 + nrows <= seq0 + L &&
                         seq0 + L <= s->total_tokens && it[6] <= L && (row0 - seq0) % rows == 0;
-        if (!ok) return fail(VA_EINVAL, "%s: work item %d is out of bounds", who, i - 1);
+        if (!ok) return fail(VA_EINVAL, "%s: work item %d is out of bounds", who, i);
         // (seq0, L) must be one of the samples of cu_seqlens
         const int32_t* lo = std::lower_bound(cu, cu + s->num_seqs, seq0);
         while (lo < cu + s->num_seqs && lo[0] == seq0 && lo[1] == seq0) ++lo;  // skip empty samples at this row
         if (lo >= cu + s->num_seqs || lo[0] != seq0 || lo[1] - lo[0] != L)
-            return fail(VA_EINVAL, "%s: work item %d does not match a sample of cu_seqlens", who, i - 1);
+            return fail(VA_EINVAL, "%s: work item %d does not match a sample of cu_seqlens", who, i);
         if (pass == VA_PASS_BWD_DKDV) {
             if (it[3] < 0 || it[4] <= 0 || it[3] + it[4] != (L + cols - 1) / cols)
-                return fail(VA_EINVAL, "%s: work item %d has a bad query-tile range", who, i - 1);
+                return fail(VA_EINVAL, "%s: work item %d has a bad query-tile range", who, i);
         } else {
             if (it[3] <= 0 || it[3] > L || it[5] != (it[3] + cols - 1) / cols || it[4] < 0 || it[4] > it[5])
-                return fail(VA_EINVAL, "%s: work item %d has a bad key range", who, i - 1);
+                return fail(VA_EINVAL, "%s: work item %d has a bad key range", who, i);
         }
     }
-    *num_items = n;
+    const int32_t* table = w[lay.table_rec].w;
+    const int32_t* ids = w[lay.id_rec].w;
+    int32_t at = 0;
+    for (int32_t g = 0; g < lay.num_workgroups; ++g) {
+        if (table[2 * g] != at || table[2 * g + 1] < 0 || table[2 * g + 1] > lay.num_works - at)
+            return fail(VA_EINVAL, "%s: workgroup table does not partition the works", who);
+        at += table[2 * g + 1];
+    }
+    if (at != lay.num_works) return fail(VA_EINVAL, "%s: workgroup table does not partition the works", who);
+    for (int32_t i = 0; i < lay.num_works; ++i)
+        if (ids[i] < 0 || ids[i] >= lay.num_works) return fail(VA_EINVAL, "%s: work id %d out of range", who, i);
+    *layout = lay;
     return VA_OK;
+}
+
+void set_worklist(AttnParams* p, const void* dev, const WorklistLayout& lay) {
+    const WorkItem* recs = static_cast<const WorkItem*>(dev);
+    p->items = recs + lay.item_rec;
+    p->wg_table = recs[lay.table_rec].w;
+    p->work_ids = recs[lay.id_rec].w;
+    p->num_items = lay.num_items;
+    p->num_workgroups = lay.num_workgroups;
+    p->works_per_item = lay.works_per_item;
 }
 
 int check_scale(float scale, const char* who) {
@@ -122,16 +149,15 @@ int varlen_attn_fwd(const void* q, const void* k, const void* v,
     if (!q || !k || !v || !out || !lse) return fail(VA_EINVAL, "%s: null tensor pointer", who);
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
         return fail(VA_EALIGN, "%s: tensor pointers must be 16-byte aligned", who);
-    int32_t n_items = 0;
-    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, VA_PASS_FWD, who, &n_items))) return rc;
+    WorklistLayout lay;
+    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, VA_PASS_FWD, who, &lay))) return rc;
     AttnParams p = base_params(shape, scale);
     p.q = q;
     p.k = k;
     p.v = v;
     p.out = out;
     p.lse = lse;
-    p.items = static_cast<const WorkItem*>(worklist) + 1;
-    p.num_items = n_items;
+    set_worklist(&p, worklist, lay);
     hipError_t e = launch_fwd_bf16(p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
     return VA_OK;
@@ -144,7 +170,7 @@ static int prepare_bwd(const char* who, const void* q, const void* k, const void
                        const void* worklist_dq, const void* worklist_dq_host,
                        const va_shape* shape, float scale, void* dq, void* dk, void* dv,
                        void* workspace, size_t workspace_bytes,
-                       AttnParams* p, int32_t* n_dkdv, int32_t* n_dq, bool* empty) {
+                       AttnParams* p, WorklistLayout* lay_dkdv, WorklistLayout* lay_dq, bool* empty) {
     int rc = check_shape(shape, cu_seqlens, prefix_lens, who);
     if (rc) return rc;
     if ((rc = check_scale(scale, who))) return rc;
@@ -160,8 +186,8 @@ static int prepare_bwd(const char* who, const void* q, const void* k, const void
     if (workspace_bytes < varlen_attn_bwd_workspace_bytes(shape))
         return fail(VA_ESIZE, "%s: workspace of %zu bytes, need %zu", who, workspace_bytes,
                     varlen_attn_bwd_workspace_bytes(shape));
-    if ((rc = check_worklist(worklist_dkdv, worklist_dkdv_host, shape, cu_seqlens, VA_PASS_BWD_DKDV, who, n_dkdv))) return rc;
-    if ((rc = check_worklist(worklist_dq, worklist_dq_host, shape, cu_seqlens, VA_PASS_BWD_DQ, who, n_dq))) return rc;
+    if ((rc = check_worklist(worklist_dkdv, worklist_dkdv_host, shape, cu_seqlens, VA_PASS_BWD_DKDV, who, lay_dkdv))) return rc;
+    if ((rc = check_worklist(worklist_dq, worklist_dq_host, shape, cu_seqlens, VA_PASS_BWD_DQ, who, lay_dq))) return rc;
     *p = base_params(shape, scale);
     p->q = q;
     p->k = k;
@@ -186,22 +212,20 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
                     void* workspace, size_t workspace_bytes, void* stream) {
     const char* who = "varlen_attn_bwd";
     AttnParams p;
-    int32_t n_dkdv = 0, n_dq = 0;
+    WorklistLayout lay_dkdv, lay_dq;
     bool empty = false;
     int rc = prepare_bwd(who, q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
                          worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
-                         &p, &n_dkdv, &n_dq, &empty);
+                         &p, &lay_dkdv, &lay_dq, &empty);
     if (rc || empty) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = launch_bwd_delta(p, st);
     if (e == hipSuccess) {
-        p.items = static_cast<const WorkItem*>(worklist_dkdv) + 1;
-        p.num_items = n_dkdv;
+        set_worklist(&p, worklist_dkdv, lay_dkdv);
         e = launch_bwd_dkdv(p, st);
     }
     if (e == hipSuccess) {
-        p.items = static_cast<const WorkItem*>(worklist_dq) + 1;
-        p.num_items = n_dq;
+        set_worklist(&p, worklist_dq, lay_dq);
         e = launch_bwd_dq(p, st);
     }
     if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
@@ -219,11 +243,11 @@ int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const v
     const char* who = "varlen_attn_bwd_profile";
     if (iters < 1 || !ms) return fail(VA_EINVAL, "%s: iters must be >= 1 and ms non-null", who);
     AttnParams p;
-    int32_t n_dkdv = 0, n_dq = 0;
+    WorklistLayout lay_dkdv, lay_dq;
     bool empty = false;
     int rc = prepare_bwd(who, q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
                          worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
-                         &p, &n_dkdv, &n_dq, &empty);
+                         &p, &lay_dkdv, &lay_dq, &empty);
     ms[0] = ms[1] = ms[2] = 0.0f;
     if (rc || empty) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -237,14 +261,12 @@ int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const v
         e = launch_bwd_delta(p, st);
         hipEventRecord(ev[1], st);
         if (e == hipSuccess) {
-            p.items = static_cast<const WorkItem*>(worklist_dkdv) + 1;
-            p.num_items = n_dkdv;
+            set_worklist(&p, worklist_dkdv, lay_dkdv);
             e = launch_bwd_dkdv(p, st);
         }
         hipEventRecord(ev[2], st);
         if (e == hipSuccess) {
-            p.items = static_cast<const WorkItem*>(worklist_dq) + 1;
-            p.num_items = n_dq;
+            set_worklist(&p, worklist_dq, lay_dq);
             e = launch_bwd_dq(p, st);
         }
         hipEventRecord(ev[3], st);
@@ -276,8 +298,8 @@ int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
         return fail(VA_EINVAL, "%s: null tensor pointer", who);
     if (!aligned16(q8) || !aligned16(k8) || !aligned16(v8) || !aligned16(out) || !aligned16(lse))
         return fail(VA_EALIGN, "%s: tensor pointers must be 16-byte aligned", who);
-    int32_t n_items = 0;
-    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, VA_PASS_FWD, who, &n_items))) return rc;
+    WorklistLayout lay;
+    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, VA_PASS_FWD, who, &lay))) return rc;
     AttnParams p = base_params(shape, scale);
     p.q = q8;
     p.k = k8;
@@ -287,8 +309,7 @@ int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
     p.v_descale = v_descale;
     p.out = out;
     p.lse = lse;
-    p.items = static_cast<const WorkItem*>(worklist) + 1;
-    p.num_items = n_items;
+    set_worklist(&p, worklist, lay);
     hipError_t e = launch_fwd_fp8(p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
     return VA_OK;

@@ -15,7 +15,22 @@ struct WorkItem {
 };
 static_assert(sizeof(WorkItem) == 32, "work items are 32 bytes");
 
-constexpr int32_t kWorklistMagic = 0x56415731;  // "VAW1"
+constexpr int32_t kWorklistMagic = 0x56415732;  // "VAW2"
+
+// Work-list layout, in 32-byte records:
+//   record 0   {magic, pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
+//   record 1   {num_workgroups, num_works, works_per_item, first item record (2), first table record,
+//               first work-id record, total records, 0}
+//   items      num_items records, heaviest first
+//   table      one (first work, count) pair per persistent workgroup, 4 pairs per record
+//   work ids   num_works words, 8 per record: item * works_per_item + head chunk, grouped by workgroup
+// A work is one item for one head chunk (forward, dQ: the query heads a workgroup stacks; dK/dV: one
+// KV head).  The kernels are launched with num_workgroups persistent workgroups; the table is a
+// longest-processing-time-first assignment of the works to them, computed on the host.
+struct WorklistLayout {
+    int32_t num_workgroups, num_works, works_per_item, num_items;
+    int32_t item_rec, table_rec, id_rec, total_recs;
+};
 
 // Tile geometry.  A forward / dQ workgroup owns kFwdBlockRows rows of the
 // (head, token) product: the query heads of one KV group are stacked on the
@@ -30,7 +45,14 @@ constexpr int32_t kDqKvTile = 64;
 constexpr int32_t kDkdvKvRows = 128;
 constexpr int32_t dkdv_q_tile(int32_t D) { return D >= 128 ? 32 : 64; }
 
+// Persistent workgroups launched for a pass: CUs of an MI355X times the workgroups a CU holds.
+constexpr int32_t persistent_workgroups(int32_t /*pass*/, int32_t D) { return D <= 128 ? 512 : 256; }
+// Cost of a work in units of inner-loop steps: its steps plus a fixed part for the item switch.
+constexpr int32_t kWorkFixedCost = 2;
+
 extern thread_local char g_error[512];
+int works_per_item(int32_t pass, int32_t Hq, int32_t Hkv);
+WorklistLayout worklist_layout(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t num_items);
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int heads_per_block(int32_t Hq, int32_t Hkv);
 int tile_shape(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t* rows, int32_t* cols);

@@ -18,6 +18,8 @@
 // own registers plus one exchange with lane + 32, and O^T = V^T P^T takes P^T
 // straight from those registers as its second operand.  V^T fragments come
 // from the row-major LDS tile through the transposing LDS read.
+#include <type_traits>
+
 #include "kernels.h"
 #include "mfma_util.h"
 
@@ -30,6 +32,35 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kPrefetch = 4;       // LDS fragment reads in flight ahead of the MFMA that uses them
 constexpr float kMaxLag = 8.0f;  // the softmax reference may trail a row's true maximum by this many powers of two
 
+// What one workgroup needs to know about a work (all wave-uniform).
+struct FwdWork {
+    int q_row0, q_rows, seq_row0, n_full, n_tiles, P, L, g, h0;
+};
+
+template <int HPB>
+VA_DEV FwdWork fetch_fwd_work(const AttnParams& p, int work_index) {
+    const int id = p.work_ids[work_index];
+    const WorkItem it = p.items[id / p.works_per_item];
+    const int hc = id % p.works_per_item;
+    const int G = p.Hq / p.Hkv;
+    const int chunks_per_group = G / HPB;
+    FwdWork w;
+    w.q_row0 = it.w[0];
+    w.q_rows = it.w[1];
+    w.seq_row0 = it.w[2];
+    w.n_full = it.w[4];
+    w.n_tiles = it.w[5];
+    w.P = it.w[6];
+    w.L = it.w[7];
+    w.g = hc / chunks_per_group;
+    w.h0 = w.g * G + (hc % chunks_per_group) * HPB;
+    return w;
+}
+
+// Persistent kernel: workgroup b runs the works the host assigned to it, one after the other.  While the
+// last key tile of a work is being processed, the first K/V tile of the next work is already on its way
+// into the free LDS stage and the next Q fragments are being loaded, so a work switch costs no memory
+// round trip.
 template <int D, int HPB>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnParams p) {
     constexpr int BMT = kFwdBlockRows / HPB;  // token rows of the work item
@@ -37,212 +68,221 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     constexpr int KSTEPS = D / 16;  // MFMA steps over the head dimension
     constexpr int DT = D / 32;      // 32-row blocks of O^T
     constexpr int TILE_BYTES = BN * D * 2;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    // two stages, each a K tile followed by a V tile
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // two stages, each a K tile then a V tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int G = p.Hq / p.Hkv;
-    const int chunks_per_group = G / HPB;
-    const int nhc = p.Hkv * chunks_per_group;
-    const int hc = blockIdx.x % nhc;
-    const WorkItem it = p.items[blockIdx.x / nhc];
-    const int q_row0 = it.w[0], q_rows = it.w[1], seq_row0 = it.w[2];
-    const int n_full = it.w[4], n_tiles = it.w[5], P = it.w[6], L = it.w[7];
-    const int g = hc / chunks_per_group;
-    const int h0 = g * G + (hc % chunks_per_group) * HPB;
+    int work = p.wg_table[2 * blockIdx.x];
+    const int work_end = work + p.wg_table[2 * blockIdx.x + 1];
+    if (work >= work_end) return;
 
-    // K and V rows of this sample and KV head as raw buffers: rows >= L read as zero
     const int kv_row_bytes = p.Hkv * D * 2;
-    const unsigned kv_bytes = (unsigned)(L - 1) * kv_row_bytes + D * 2;
-    const i32x4 k_rsrc = make_rsrc(static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D, kv_bytes);
-    const i32x4 v_rsrc = make_rsrc(static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D, kv_bytes);
+    const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
+    const unsigned smem_lds = lds_addr(smem);
     AsyncTile<D, BN, 4> loader;
     loader.init(wave, lane, kv_row_bytes);
-    const unsigned smem_lds = lds_addr(smem);
-    const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
+    const FragAddr<D> fa(lane);
+    const float c = p.scale * kLog2e;
 
-    // first K/V tile on its way before anything else
-    loader.issue(k_rsrc, smem_lds, 0);
-    loader.issue(v_rsrc, smem_lds + TILE_BYTES, 0);
-
-    // the stacked row this lane owns
+    // K and V rows of one sample and KV head as raw buffers: rows >= L read as zero
+    auto kv_rsrc = [&](const void* base, const FwdWork& w) {
+        return make_rsrc(static_cast<const __bf16*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D,
+                         (unsigned)(w.L - 1) * kv_row_bytes + D * 2);
+    };
+    // the stacked row this lane owns: Q fragments with k-slots d = 16 t + 8 hf + 0..7
     const int row = wave * 32 + l32;
-    const int head = h0 + row / BMT;
-    const int tok = row % BMT;
-    const bool row_valid = tok < q_rows;
-    const int vis = RowMask(P, L, p.mask_mode).vis(q_row0 - seq_row0 + tok);
-
-    // Q fragments stay in registers for the whole item: k-slots d = 16 t + 8 hf + 0..7
-    bf16x8 qf[KSTEPS];
-    {
-        const __bf16* qrow = static_cast<const __bf16*>(p.q) + ((size_t)(q_row0 + tok) * p.Hq + head) * D;
+    auto load_q = [&](bf16x8 (&qf)[KSTEPS], const FwdWork& w) {
+        const int tok = row % BMT;
+        const __bf16* qrow = static_cast<const __bf16*>(p.q) + ((size_t)(w.q_row0 + tok) * p.Hq + w.h0 + row / BMT) * D;
 #pragma unroll
         for (int t = 0; t < KSTEPS; ++t) {
             u32x4 raw = {0u, 0u, 0u, 0u};
-            if (row_valid) raw = *reinterpret_cast<const u32x4*>(qrow + 16 * t + 8 * hf);
+#ifndef VA_EXP_NO_QLOAD
+            if (tok < w.q_rows) raw = *reinterpret_cast<const u32x4*>(qrow + 16 * t + 8 * hf);
+#endif
             qf[t] = __builtin_bit_cast(bf16x8, raw);
         }
-    }
+    };
 
-    f32x16 o[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
-    // Reference point of the exponentials, in units of scale * log2(e) * s.  It only moves when some
-    // row of the wave would otherwise exceed 2^kMaxLag, so most tiles skip the rescaling of O;
-    // the probabilities are then at most 2^kMaxLag instead of 1, which float32 sums and bf16 P absorb.
-    float m = -INFINITY;
-    float lsum = 0.0f;  // this lane's share of the running sum (other share in lane + 32)
-    const float c = p.scale * kLog2e;
+    FwdWork cur = fetch_fwd_work<HPB>(p, work);
+    int stage = 0;  // LDS stage that holds (or will hold) the tile about to be processed
+    loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
+    loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
+    bf16x8 qf[KSTEPS];
+    load_q(qf, cur);
 
-#pragma unroll
-    for (int t = 0; t < KSTEPS; ++t) settle(qf[t]);
-    wait_async_loads();
-    __syncthreads();
+    for (;;) {
+        const bool has_next = work + 1 < work_end;
+        FwdWork nxt = cur;
+        if (has_next) nxt = fetch_fwd_work<HPB>(p, work + 1);
+        const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
+        const int tok = row % BMT;
+        const int head = cur.h0 + row / BMT;
+        const bool row_valid = tok < cur.q_rows;
+        const int vis = RowMask(cur.P, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
 
-    const FragAddr<D> fa(lane);
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        const int j0 = kt * BN;
-        const int k_tile = (kt & 1) * 2 * TILE_BYTES;  // byte offsets of this stage's tiles
-        const int v_tile = k_tile + TILE_BYTES;
-#ifndef VA_EXP_NO_PREFETCH
-        if (kt + 1 < n_tiles) {
-            const unsigned nk = smem_lds + ((kt + 1) & 1) * 2 * TILE_BYTES;
-            loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
-            loader.issue(v_rsrc, nk + TILE_BYTES, (kt + 1) * tile_step);
-        }
-#endif
-
-        // S^T: two blocks of 32 keys x 32 query rows.  The K fragments are fetched from LDS kPrefetch
-        // steps ahead of the MFMA that consumes them so the matrix pipe never waits on an LDS read.
-        f32x16 s[2];
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[b][r] = 0.0f;
-        {
-            constexpr int NS = 2 * KSTEPS;
-            bf16x8 ring[kPrefetch];
-#pragma unroll
-            for (int i = 0; i < kPrefetch; ++i) ring[i] = fa.rowmajor(smem, k_tile, i / KSTEPS, i % KSTEPS);
-#pragma unroll
-            for (int i = 0; i < NS; ++i) {
-                const bf16x8 a = ring[i % kPrefetch];
-                if (i + kPrefetch < NS)
-                    ring[i % kPrefetch] = fa.rowmajor(smem, k_tile, (i + kPrefetch) / KSTEPS, (i + kPrefetch) % KSTEPS);
-                s[i / KSTEPS] = mfma32(a, qf[i % KSTEPS], s[i / KSTEPS]);
-            }
-            // pin the issue order: kPrefetch reads up front, then one read per MFMA
-#pragma unroll
-            for (int i = 0; i < kPrefetch; ++i) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-#pragma unroll
-            for (int i = 0; i < NS; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (i + kPrefetch < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-        }
-        if (kt >= n_full) {
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (j0 + 32 * b + acc_row(r, hf) >= vis) s[b][r] = -INFINITY;
-        }
-        // first V^T fragments on their way while the softmax runs
-        bf16x8 vring[kPrefetch];
-#pragma unroll
-        for (int i = 0; i < kPrefetch; ++i) 
-#if defined(VA_EXP_V_ROWMAJOR)
-            vring[i] = fa.rowmajor(smem, v_tile, i % 2, i / 4);
-#else
-            vring[i] = fa.transposed(smem, v_tile, i % 4, i / 4);
-#endif
-
-        float mx = s[0][0];
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
-        mx = pair_max(mx) * c;
-        if (__builtin_amdgcn_ballot_w64(mx > m + kMaxLag) != 0) {  // wave-uniform: some row needs a new reference
-            const float m_new = fmaxf(m, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m - m_new);  // m = -inf on the first tile: alpha = 0, O = 0
-            m = m_new;
-            lsum *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-        }
-        float psum = 0.0f;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-#ifdef VA_EXP_NO_EXP
-                const float pv = s[b][r];
-#else
-                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, -m));
-#endif
-                s[b][r] = pv;
-                psum += pv;
-            }
-        lsum += psum;
-
-        // P^T as second operand: registers 8 x .. 8 x + 7 of a block are the k-slots of step x
-        bf16x8 pf[4];
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int x = 0; x < 2; ++x)
-                pf[2 * b + x] = to_bf16x8(s[b][8 * x + 0], s[b][8 * x + 1], s[b][8 * x + 2], s[b][8 * x + 3],
-                                          s[b][8 * x + 4], s[b][8 * x + 5], s[b][8 * x + 6], s[b][8 * x + 7]);
-        {
-            constexpr int NS = 4 * DT;  // step i: O^T block i / 4, keys 16 (i % 4) .. + 15
-#pragma unroll
-            for (int i = 0; i < NS; ++i) {
-                const bf16x8 a = vring[i % kPrefetch];
-                if (i + kPrefetch < NS)
-                    {
-#if defined(VA_EXP_V_ROWMAJOR)
-                    vring[i % kPrefetch] = fa.rowmajor(smem, v_tile, (i + kPrefetch) % 2, (i + kPrefetch) / 4);
-#elif defined(VA_EXP_V_NOREAD)
-                    vring[i % kPrefetch] = a;
-#else
-                    vring[i % kPrefetch] = fa.transposed(smem, v_tile, (i + kPrefetch) % 4, (i + kPrefetch) / 4);
-#endif
-                }
-                o[i / 4] = mfma32(a, pf[i % 4], o[i / 4]);
-            }
-#pragma unroll
-            for (int i = 0; i < NS; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-                if (i + kPrefetch < NS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
-            }
-        }
-
-        // the next tile has landed and every wave is done reading this one
-        wait_async_loads();
-#ifndef VA_EXP_NO_BARRIER
-        __syncthreads();
-#endif
-    }
-
-    lsum = pair_sum(lsum);
-    if (row_valid) {
-        const float inv = 1.0f / lsum;
-        __bf16* orow = static_cast<__bf16*>(p.out) + ((size_t)(q_row0 + tok) * p.Hq + head) * D;
+        f32x16 o[DT];
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                f32x4 f = {o[dt][4 * r4] * inv, o[dt][4 * r4 + 1] * inv, o[dt][4 * r4 + 2] * inv, o[dt][4 * r4 + 3] * inv};
-                bf16x4 h = __builtin_convertvector(f, bf16x4);
-                *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * r4 + 4 * hf) = h;
+            for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
+        // Reference point of the exponentials, in units of scale * log2(e) * s.  It only moves when some
+        // row of the wave would otherwise exceed 2^kMaxLag, so most tiles skip the rescaling of O;
+        // the probabilities are then at most 2^kMaxLag instead of 1, which float32 sums and bf16 P absorb.
+        float m = -INFINITY;
+        float lsum = 0.0f;  // this lane's share of the running sum (other share in lane + 32)
+
+#pragma unroll
+        for (int t = 0; t < KSTEPS; ++t) settle(qf[t]);
+        wait_async_loads();
+        __syncthreads();
+
+        // One key tile.  The last tile of a work is a separate instantiation: it alone prefetches for the
+        // next work, so the loop over the other tiles contains no ordinary global load and the compiler
+        // has no reason to wait for memory inside it.
+        auto tile = [&](const int kt, auto last_tag) {
+            constexpr bool last = decltype(last_tag)::value;
+            const int j0 = kt * BN;
+            const int k_tile = stage * 2 * TILE_BYTES;  // byte offsets of this stage's tiles
+            const int v_tile = k_tile + TILE_BYTES;
+            {
+                // next tile of this work, or the first tile of the next work, into the other stage
+                const unsigned nk = smem_lds + (stage ^ 1) * 2 * TILE_BYTES;
+                if constexpr (!last) {
+                    loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
+                    loader.issue(v_rsrc, nk + TILE_BYTES, (kt + 1) * tile_step);
+                } else if (has_next) {
+                    loader.issue(kv_rsrc(p.k, nxt), nk, 0);
+                    loader.issue(kv_rsrc(p.v, nxt), nk + TILE_BYTES, 0);
+                }
             }
-        if (hf == 0) p.lse[(size_t)head * p.T + q_row0 + tok] = (m + __builtin_amdgcn_logf(lsum)) * kLn2;
+
+            // S^T: two blocks of 32 keys x 32 query rows.  The K fragments are fetched from LDS kPrefetch
+            // steps ahead of the MFMA that consumes them; consecutive MFMAs alternate between the two
+            // blocks so that none waits for the result of the one just issued.
+            f32x16 s[2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[b][r] = 0.0f;
+            {
+                constexpr int NS = 2 * KSTEPS;  // step i: block i % 2, k-step i / 2
+                bf16x8 ring[kPrefetch];
+#pragma unroll
+                for (int i = 0; i < kPrefetch; ++i) ring[i] = fa.rowmajor(smem, k_tile, i % 2, i / 2);
+#pragma unroll
+                for (int i = 0; i < NS; ++i) {
+                    const bf16x8 a = ring[i % kPrefetch];
+                    if (i + kPrefetch < NS) ring[i % kPrefetch] = fa.rowmajor(smem, k_tile, (i + kPrefetch) % 2, (i + kPrefetch) / 2);
+                    s[i % 2] = mfma32(a, qf[i / 2], s[i % 2]);
+                }
+                // pin the issue order: kPrefetch reads up front, then one read per MFMA
+#pragma unroll
+                for (int i = 0; i < kPrefetch; ++i) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+                for (int i = 0; i < NS; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (i + kPrefetch < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+            }
+            // the Q fragments are free now: those of the next work can start loading
+            if constexpr (last) {
+                if (has_next) load_q(qf, nxt);
+            }
+
+            if (kt >= cur.n_full) {
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (j0 + 32 * b + acc_row(r, hf) >= vis) s[b][r] = -INFINITY;
+            }
+            // first V^T fragments on their way while the softmax runs.  Step i: keys 16 (i / DT) .. + 15,
+            // O^T block i % DT, so consecutive MFMAs go to different accumulators.
+            bf16x8 vring[kPrefetch];
+#pragma unroll
+            for (int i = 0; i < kPrefetch; ++i) vring[i] = fa.transposed(smem, v_tile, i / DT, i % DT);
+            float mx = s[0][0];
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
+            mx = pair_max(mx) * c;
+            if (__builtin_amdgcn_ballot_w64(mx > m + kMaxLag) != 0) {  // wave-uniform: some row needs a new reference
+                const float m_new = fmaxf(m, mx);
+                const float alpha = __builtin_amdgcn_exp2f(m - m_new);  // m = -inf on the first tile: alpha = 0, O = 0
+                m = m_new;
+                lsum *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+            }
+            float psum = 0.0f;
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, -m));
+                    s[b][r] = pv;
+                    psum += pv;
+                }
+            lsum += psum;
+
+            // P^T as second operand: registers 8 x .. 8 x + 7 of a block are the k-slots of step x
+            bf16x8 pf[4];
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int x = 0; x < 2; ++x)
+                    pf[2 * b + x] = to_bf16x8(s[b][8 * x + 0], s[b][8 * x + 1], s[b][8 * x + 2], s[b][8 * x + 3],
+                                              s[b][8 * x + 4], s[b][8 * x + 5], s[b][8 * x + 6], s[b][8 * x + 7]);
+            {
+                constexpr int NS = 4 * DT;
+#pragma unroll
+                for (int i = 0; i < NS; ++i) {
+                    const bf16x8 a = vring[i % kPrefetch];
+                    if (i + kPrefetch < NS)
+                        vring[i % kPrefetch] = fa.transposed(smem, v_tile, (i + kPrefetch) / DT, (i + kPrefetch) % DT);
+                    o[i % DT] = mfma32(a, pf[i / DT], o[i % DT]);
+                }
+#pragma unroll
+                for (int i = 0; i < NS; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                    if (i + kPrefetch < NS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+                }
+            }
+
+            stage ^= 1;
+            if constexpr (!last) {
+                // the next tile has landed and every wave is done reading this one
+                wait_async_loads();
+                __syncthreads();
+            }
+        };
+        for (int kt = 0; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{});
+        tile(cur.n_tiles - 1, std::true_type{});
+
+        lsum = pair_sum(lsum);
+        // O leaves through the LDS stage that was just processed (the other one may already be receiving
+        // the first tile of the next work); every wave must be done reading it first
+        __syncthreads();
+        {
+            char* out_stage = smem + (stage ^ 1) * 2 * TILE_BYTES + wave * (32 * D * 2);
+            store_block_rows<D>(out_stage, o, 1.0f / lsum, lane, [&](int r) -> __bf16* {
+                const int rr = wave * 32 + r, t = rr % BMT;
+#ifdef VA_EXP_NO_STORE
+                if (lsum != 12345.0f) return nullptr;
+#endif
+                if (t >= cur.q_rows) return nullptr;
+                return static_cast<__bf16*>(p.out) + ((size_t)(cur.q_row0 + t) * p.Hq + cur.h0 + rr / BMT) * D;
+            });
+        }
+        if (row_valid && hf == 0)
+            p.lse[(size_t)head * p.T + cur.q_row0 + tok] = (m + __builtin_amdgcn_logf(lsum)) * kLn2;
+        if (!has_next) break;
+        ++work;
+        cur = nxt;
     }
 }
 
@@ -257,10 +297,9 @@ hipError_t launch_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
 
 template <int D>
 hipError_t launch_d(const AttnParams& p, hipStream_t stream) {
-    const int G = p.Hq / p.Hkv;
     const int hpb = heads_per_block(p.Hq, p.Hkv);
-    const unsigned grid = (unsigned)p.num_items * (unsigned)(p.Hkv * (G / hpb));
-    if (grid == 0) return hipSuccess;
+    const unsigned grid = (unsigned)p.num_workgroups;
+    if (p.num_items == 0) return hipSuccess;
     switch (hpb) {
         case 1: return launch_dh<D, 1>(p, stream, grid);
         case 2: return launch_dh<D, 2>(p, stream, grid);

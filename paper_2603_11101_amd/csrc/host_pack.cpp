@@ -62,6 +62,24 @@ int tile_shape(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t* rows, 
     }
 }
 
+int works_per_item(int32_t pass, int32_t Hq, int32_t Hkv) {
+    if (pass == VA_PASS_BWD_DKDV) return Hkv;
+    return Hkv * ((Hq / Hkv) / heads_per_block(Hq, Hkv));
+}
+
+WorklistLayout worklist_layout(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t num_items) {
+    WorklistLayout l;
+    l.num_workgroups = persistent_workgroups(pass, D);
+    l.works_per_item = works_per_item(pass, Hq, Hkv);
+    l.num_works = num_items * l.works_per_item;
+    l.num_items = num_items;
+    l.item_rec = 2;
+    l.table_rec = l.item_rec + num_items;
+    l.id_rec = l.table_rec + (2 * l.num_workgroups + 7) / 8;
+    l.total_recs = l.id_rec + (l.num_works + 7) / 8;
+    return l;
+}
+
 }  // namespace va
 
 using namespace va;
@@ -140,9 +158,10 @@ int va_worklist_bytes(const int32_t* cu, int32_t n, int32_t pass, int32_t D,
     int32_t rows, cols;
     rc = tile_shape(pass, D, Hq, Hkv, &rows, &cols);
     if (rc) return rc;
-    size_t items = 0;
-    for (int32_t s = 0; s < n; ++s) items += (size_t)((cu[s + 1] - cu[s] + rows - 1) / rows);
-    *bytes = (items + 1) * sizeof(WorkItem);
+    int64_t items = 0;
+    for (int32_t s = 0; s < n; ++s) items += (cu[s + 1] - cu[s] + rows - 1) / rows;
+    if (items * works_per_item(pass, Hq, Hkv) > INT32_MAX / 2) return fail(VA_ESIZE, "va_worklist_bytes: too many works");
+    *bytes = (size_t)worklist_layout(pass, D, Hq, Hkv, (int32_t)items).total_recs * sizeof(WorkItem);
     return VA_OK;
 }
 
@@ -199,10 +218,41 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
         }
     }
     std::stable_sort(items.begin(), items.end(), [](const Keyed& a, const Keyed& b) { return a.work > b.work; });
+    const WorklistLayout lay = worklist_layout(pass, D, Hq, Hkv, (int32_t)items.size());
     WorkItem* out = static_cast<WorkItem*>(host_out);
-    out[0] = {{kWorklistMagic, pass, bm, bn, D, mask_mode, (int32_t)items.size(), cu[n]}};
-    for (size_t i = 0; i < items.size(); ++i) out[i + 1] = items[i].it;
-    *num_items = (int32_t)items.size();
+    std::memset(out, 0, (size_t)lay.total_recs * sizeof(WorkItem));
+    out[0] = {{kWorklistMagic, pass, bm, bn, D, mask_mode, lay.num_items, cu[n]}};
+    out[1] = {{lay.num_workgroups, lay.num_works, lay.works_per_item, lay.item_rec, lay.table_rec, lay.id_rec,
+               lay.total_recs, 0}};
+    for (size_t i = 0; i < items.size(); ++i) out[lay.item_rec + i] = items[i].it;
+
+    // Longest-processing-time-first assignment of the works to the persistent workgroups: works in
+    // descending cost order (ties: ascending id), each to the least-loaded workgroup (ties: lowest index).
+    // Items are already sorted by cost and every work of an item costs the same, so id order is cost order.
+    const int32_t G = Hq / Hkv;
+    const int32_t P = lay.num_workgroups;
+    std::vector<int64_t> load((size_t)P, 0);
+    std::vector<std::vector<int32_t>> mine((size_t)P);
+    auto heavier = [&](int32_t a, int32_t b) { return load[a] != load[b] ? load[a] > load[b] : a > b; };
+    std::vector<int32_t> heap((size_t)P);
+    for (int32_t w = 0; w < P; ++w) heap[w] = w;  // min-heap on (load, index); all loads 0: already a heap
+    for (int32_t id = 0; id < lay.num_works; ++id) {
+        const int32_t steps = items[id / lay.works_per_item].work * (pass == VA_PASS_BWD_DKDV ? G : 1);
+        std::pop_heap(heap.begin(), heap.end(), heavier);
+        const int32_t w = heap.back();
+        load[w] += steps + kWorkFixedCost;
+        mine[w].push_back(id);
+        std::push_heap(heap.begin(), heap.end(), heavier);
+    }
+    int32_t* table = out[lay.table_rec].w;
+    int32_t* ids = out[lay.id_rec].w;
+    int32_t at = 0;
+    for (int32_t w = 0; w < P; ++w) {
+        table[2 * w] = at;
+        table[2 * w + 1] = (int32_t)mine[w].size();
+        for (int32_t id : mine[w]) ids[at++] = id;
+    }
+    *num_items = lay.num_items;
     return VA_OK;
 }
 

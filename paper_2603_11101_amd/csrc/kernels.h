@@ -23,8 +23,12 @@ struct AttnParams {
     const float* q_descale;  // fp8 only
     const float* k_descale;
     const float* v_descale;
-    const WorkItem* items;   // device, header skipped
+    const WorkItem* items;     // device: item records of the work list
+    const int32_t* wg_table;   // device: (first work, count) per persistent workgroup
+    const int32_t* work_ids;   // device: item * works_per_item + head chunk
     int32_t num_items;
+    int32_t num_workgroups;
+    int32_t works_per_item;
     int32_t T, Hq, Hkv, D;
     int32_t mask_mode;
     float scale;

@@ -266,6 +266,45 @@ struct AsyncTile {
     }
 };
 
+// ---------------------------------------------------------------- coalesced output rows
+//
+// A wave holds a 32 x D result transposed in its accumulators: lane % 32 is the row, and registers
+// 4 q .. 4 q + 3 of block dt hold columns 32 dt + 8 q + 4 (lane / 32) + 0..3.  Stored directly, every
+// lane would write 8-byte pieces 2 D bytes apart.  Instead the block goes through 32 * D * 2 bytes of
+// LDS that belong to the wave and leaves as whole rows, 16 bytes per lane, 16-byte chunks of one row in
+// consecutive lanes.  The 8-byte units of a row are XOR-permuted with a function of the row so that both
+// the column-wise writes and the row-wise reads are free of bank conflicts.
+template <int D>
+__host__ __device__ constexpr int out_stage_perm(int row) { return D == 64 ? ((row >> 1) & 15) : (row & 31); }
+
+// row_ptr(r): global address of row r (0..31) of the block, or nullptr if the row must not be written.
+template <int D, typename RowPtr>
+VA_DEV void store_block_rows(char* stage, const f32x16 (&acc)[D / 32], float factor, int lane, RowPtr row_ptr) {
+    constexpr int RB = D * 2, CPR = D / 8;
+    const int row = lane & 31, hf = lane >> 5;
+    const int perm = out_stage_perm<D>(row);
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            f32x4 f = {acc[dt][4 * q] * factor, acc[dt][4 * q + 1] * factor, acc[dt][4 * q + 2] * factor,
+                       acc[dt][4 * q + 3] * factor};
+            const int unit = 8 * dt + 2 * q + hf;  // 8-byte unit of the row
+            *reinterpret_cast<bf16x4*>(stage + row * RB + ((unit ^ perm) << 3)) = __builtin_convertvector(f, bf16x4);
+        }
+    // the wave reads back only what it wrote itself
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int it = 0; it < 32 * CPR / 64; ++it) {
+        const int r = it * (64 / CPR) + lane / CPR, c = lane % CPR;
+        const int pr = out_stage_perm<D>(r);
+        u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * RB + ((c ^ (pr >> 1)) << 4));
+        if (pr & 1) v = u32x4{v[2], v[3], v[0], v[1]};
+        __bf16* dst = row_ptr(r);
+        if (dst) *reinterpret_cast<u32x4*>(dst + c * 8) = v;
+    }
+}
+
 // float pairs -> packed bf16 (round to nearest even)
 VA_DEV bf16x8 to_bf16x8(float a0, float a1, float a2, float a3, float a4, float a5, float a6, float a7) {
     f32x8 f = {a0, a1, a2, a3, a4, a5, a6, a7};

@@ -75,9 +75,19 @@ def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
     for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DKDV, va.VA_PASS_BWD_DQ):
         rows, cols = va.va_tile_shape(pass_id, D, Hq, Hkv)
         got = va.va_build_worklist(cu, prefix, mode, pass_id, D, Hq, Hkv)
-        header, items = got[0], got[1:]
+        header, items = got[0], va.worklist_items(got)
         assert header[1] == pass_id and header[2] == rows and header[3] == cols and header[4] == D
         assert header[5] == mode and header[6] == len(items) and header[7] == cu[-1]
+        # the schedule assigns every work (item x head chunk) to exactly one persistent workgroup
+        table, ids = va.worklist_schedule(got)
+        per_item = Hkv if pass_id == va.VA_PASS_BWD_DKDV else got[1, 2]
+        assert got[1, 1] == len(items) * per_item and sorted(ids.tolist()) == list(range(len(ids)))
+        assert table[0, 0] == 0 and np.array_equal(table[1:, 0], np.cumsum(table[:-1, 1])) and table[:, 1].sum() == len(ids)
+        # longest-processing-time-first: no workgroup exceeds the mean load by more than the heaviest work
+        steps = items[:, 4] * (Hq // Hkv) if pass_id == va.VA_PASS_BWD_DKDV else items[:, 5]
+        cost = np.repeat(steps, per_item) + 2
+        loads = np.array([cost[ids[a:a + n]].sum() for a, n in table])
+        assert loads.max() <= cost.sum() / len(table) + cost.max()
         # the oracle names tile sizes by role: bm = query rows, bn = key rows
         bm, bn = (cols, rows) if pass_id == va.VA_PASS_BWD_DKDV else (rows, cols)
         want = op.build_worklist(cu, prefix, pass_id, bm, bn, mode)
@@ -89,7 +99,7 @@ def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
     for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DKDV, va.VA_PASS_BWD_DQ):
         rows, cols = va.va_tile_shape(pass_id, D, Hq, Hkv)
         bm, bn = (cols, rows) if pass_id == va.VA_PASS_BWD_DKDV else (rows, cols)
-        items = va.va_build_worklist(cu_s, pre_s, mode, pass_id, D, Hq, Hkv)[1:]
+        items = va.worklist_items(va.va_build_worklist(cu_s, pre_s, mode, pass_id, D, Hq, Hkv))
         op.check_coverage(items, cu_s, pre_s, pass_id, bm, bn, mode)
 
 
@@ -103,7 +113,7 @@ def test_worklist_counts_on_the_workloads():
         cu, pl, mx = va.va_bin_layout(lens[idx], None if prefix is None else prefix[idx])
         mode = va.VA_MASK_PREFIX_LM if w.prefix_lm else va.VA_MASK_CAUSAL
         rows, cols = va.va_tile_shape(va.VA_PASS_FWD, w.head_dim, w.num_q_heads, w.num_kv_heads)
-        items = va.va_build_worklist(cu, pl, mode, va.VA_PASS_FWD, w.head_dim, w.num_q_heads, w.num_kv_heads)[1:]
+        items = va.worklist_items(va.va_build_worklist(cu, pl, mode, va.VA_PASS_FWD, w.head_dim, w.num_q_heads, w.num_kv_heads))
         assert len(items) == sum(-(-int(L) // rows) for L in lens[idx])
         if not w.prefix_lm:
             want_tiles = sum(-(-min(int(L), (t + 1) * rows) // cols) for L in lens[idx] for t in range(-(-int(L) // rows)))
@@ -171,8 +181,12 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     # a work list built for another stream, pass or head_dim is refused
     other = va.va_build_worklist(np.array([0, 50, 100], dtype=np.int32), None, va.VA_MASK_CAUSAL, va.VA_PASS_FWD, D, Hq, Hkv)
     tampered = wl_h.copy()
-    tampered[1, 1] = 1000
+    tampered[2, 1] = 1000
     wrong_pass = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_BWD_DKDV, D, Hq, Hkv)
-    for bad in (other, tampered, wrong_pass):
+    bad_table = wl_h.copy()
+    bad_table[wl_h[1, 4], 1] += 1                      # first workgroup claims one work too many
+    bad_id = wl_h.copy()
+    bad_id[wl_h[1, 5], 0] = wl_h[1, 1]                 # a work id past the end
+    for bad in (other, tampered, wrong_pass, bad_table, bad_id):
         assert call(va.make_shape(**ok), wl_=np.ascontiguousarray(bad))[0] == va.VA_EINVAL
     assert va.varlen_attn_bwd_workspace_bytes(va.make_shape(**ok)) >= 100 * Hq * 4
