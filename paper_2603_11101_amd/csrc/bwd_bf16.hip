@@ -15,6 +15,8 @@
 //
 // With p = exp(scale * s - LSE):  dP = dO V^T,  dS = p * (dP - delta),
 // dQ = scale * dS K,  dK = scale * dS^T Q,  dV = p^T dO.
+#include <type_traits>
+
 #include "kernels.h"
 #include "mfma_util.h"
 
@@ -23,6 +25,7 @@ namespace va {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kPrefetch = 4;  // LDS fragment reads in flight ahead of the MFMA that uses them
 
 // ------------------------------------------------------------------ delta
 
@@ -248,6 +251,33 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 
 // ------------------------------------------------------------------ dQ
 
+// What one workgroup needs to know about a dQ work (all wave-uniform).
+struct DqWork {
+    int q_row0, q_rows, seq_row0, n_full, n_tiles, P, L, g, h0;
+};
+
+template <int HPB>
+VA_DEV DqWork fetch_dq_work(const AttnParams& p, int work_index) {
+    const int id = p.work_ids[work_index];
+    const WorkItem it = p.items[id / p.works_per_item];
+    const int hc = id % p.works_per_item;
+    const int G = p.Hq / p.Hkv;
+    const int chunks_per_group = G / HPB;
+    DqWork w;
+    w.q_row0 = it.w[0];
+    w.q_rows = it.w[1];
+    w.seq_row0 = it.w[2];
+    w.n_full = it.w[4];
+    w.n_tiles = it.w[5];
+    w.P = it.w[6];
+    w.L = it.w[7];
+    w.g = hc / chunks_per_group;
+    w.h0 = w.g * G + (hc % chunks_per_group) * HPB;
+    return w;
+}
+
+// Persistent, like the forward: workgroup b runs the works the host assigned to it; the first K/V tile and
+// the Q / dO fragments of the next work are fetched while the last key tile of the current one is processed.
 template <int D, int HPB>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParams p) {
     constexpr int BMT = kDqBlockRows / HPB;
@@ -255,131 +285,195 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     constexpr int KSTEPS = D / 16;
     constexpr int DT = D / 32;
     constexpr int TILE_BYTES = BN * D * 2;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int PF = D == 128 ? 2 : kPrefetch;  // fragment reads in flight; D = 128 has no registers to spare
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // two stages, each a K tile then a V tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int G = p.Hq / p.Hkv;
-    const int chunks_per_group = G / HPB;
-    const int nhc = p.Hkv * chunks_per_group;
-    const int hc = blockIdx.x % nhc;
-    const WorkItem it = p.items[blockIdx.x / nhc];
-    const int q_row0 = it.w[0], q_rows = it.w[1], seq_row0 = it.w[2];
-    const int n_full = it.w[4], n_tiles = it.w[5], P = it.w[6], L = it.w[7];
-    const int g = hc / chunks_per_group;
-    const int h0 = g * G + (hc % chunks_per_group) * HPB;
+    int work = p.wg_table[2 * blockIdx.x];
+    const int work_end = work + p.wg_table[2 * blockIdx.x + 1];
+    if (work >= work_end) return;
 
     const int kv_row_bytes = p.Hkv * D * 2;
-    const unsigned kv_bytes = (unsigned)(L - 1) * kv_row_bytes + D * 2;
-    const i32x4 k_rsrc = make_rsrc(static_cast<const __bf16*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D, kv_bytes);
-    const i32x4 v_rsrc = make_rsrc(static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D, kv_bytes);
+    const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
+    const unsigned smem_lds = lds_addr(smem);
     AsyncTile<D, BN, 4> loader;
     loader.init(wave, lane, kv_row_bytes);
-    const unsigned smem_lds = lds_addr(smem);
-    const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
-    loader.issue(k_rsrc, smem_lds, 0);
-    loader.issue(v_rsrc, smem_lds + TILE_BYTES, 0);
-
-    const int row = wave * 32 + l32;
-    const int head = h0 + row / BMT;
-    const int tok = row % BMT;
-    const bool row_valid = tok < q_rows;
-    const int vis = RowMask(P, L, p.mask_mode).vis(q_row0 - seq_row0 + tok);
+    const FragAddr<D> fa(lane);
     const float c = p.scale * kLog2e;
 
+    auto kv_rsrc = [&](const void* base, const DqWork& w) {
+        return make_rsrc(static_cast<const __bf16*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D,
+                         (unsigned)(w.L - 1) * kv_row_bytes + D * 2);
+    };
+    // the stacked row this lane owns: Q and dO fragments (k-slots d = 16 t + 8 hf + 0..7), LSE and delta
+    const int row = wave * 32 + l32;
     bf16x8 qf[KSTEPS], dof[KSTEPS];
-    float lse2 = INFINITY, delta = 0.0f;  // rows past the sample: p = exp2(-inf) = 0
-    {
-        const size_t off = ((size_t)(q_row0 + tok) * p.Hq + head) * D;
+    float lse2, delta;
+    auto load_rows = [&](const DqWork& w) {
+        const int tok = row % BMT;
+        const int head = w.h0 + row / BMT;
+        const bool valid = tok < w.q_rows;
+        const size_t off = ((size_t)(w.q_row0 + tok) * p.Hq + head) * D;
         const __bf16* qrow = static_cast<const __bf16*>(p.q) + off;
         const __bf16* dorow = static_cast<const __bf16*>(p.dout) + off;
 #pragma unroll
         for (int t = 0; t < KSTEPS; ++t) {
             u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
-            if (row_valid) {
+            if (valid) {
                 a = *reinterpret_cast<const u32x4*>(qrow + 16 * t + 8 * hf);
                 b = *reinterpret_cast<const u32x4*>(dorow + 16 * t + 8 * hf);
             }
             qf[t] = __builtin_bit_cast(bf16x8, a);
             dof[t] = __builtin_bit_cast(bf16x8, b);
         }
-        if (row_valid) {
-            lse2 = p.lse2[(size_t)head * p.T + q_row0 + tok];
-            delta = p.delta[(size_t)head * p.T + q_row0 + tok];
+        lse2 = INFINITY;  // rows past the item: p = exp2(-inf) = 0
+        delta = 0.0f;
+        if (valid) {
+            lse2 = p.lse2[(size_t)head * p.T + w.q_row0 + tok];
+            delta = p.delta[(size_t)head * p.T + w.q_row0 + tok];
         }
-    }
+    };
 
-    f32x16 dq[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dq[dt][r] = 0.0f;
+    DqWork cur = fetch_dq_work<HPB>(p, work);
+    int stage = 0;
+    loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
+    loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
+    load_rows(cur);
 
-#pragma unroll
-    for (int t = 0; t < KSTEPS; ++t) {
-        settle(qf[t]);
-        settle(dof[t]);
-    }
-    asm volatile("" ::"v"(lse2), "v"(delta));
-    wait_async_loads();
-    __syncthreads();
+    for (;;) {
+        const bool has_next = work + 1 < work_end;
+        DqWork nxt = cur;
+        if (has_next) nxt = fetch_dq_work<HPB>(p, work + 1);
+        const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
+        const int tok = row % BMT;
+        const int vis = RowMask(cur.P, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
 
-    const FragAddr<D> fa(lane);
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        const int j0 = kt * BN;
-        const int k_tile = (kt & 1) * 2 * TILE_BYTES;  // byte offsets of this stage's tiles
-        const int v_tile = k_tile + TILE_BYTES;
-        if (kt + 1 < n_tiles) {
-            const unsigned nk = smem_lds + ((kt + 1) & 1) * 2 * TILE_BYTES;
-            loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
-            loader.issue(v_rsrc, nk + TILE_BYTES, (kt + 1) * tile_step);
-        }
-        bf16x8 dsb[4];
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            // S^T and dP^T blocks: rows = key rows (registers), columns = query rows (lanes)
-            f32x16 s, dp;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                s[r] = 0.0f;
-                dp[r] = 0.0f;
-            }
-#pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) s = mfma32(fa.rowmajor(smem, k_tile, b, t), qf[t], s);
-#pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) dp = mfma32(fa.rowmajor(smem, v_tile, b, t), dof[t], dp);
-            const bool need_mask = kt >= n_full;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse2));
-                if (need_mask && j0 + 32 * b + acc_row(r, hf) >= vis) pv = 0.0f;
-                dp[r] = pv * (dp[r] - delta);
-            }
-#pragma unroll
-            for (int x = 0; x < 2; ++x)
-                dsb[2 * b + x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
-                                           dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
-        }
-        // dQ^T += K^T dS^T
+        f32x16 dq[DT];
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int x = 0; x < 4; ++x)
-                dq[dt] = mfma32(fa.transposed(smem, k_tile, x, dt), dsb[x], dq[dt]);
+            for (int r = 0; r < 16; ++r) dq[dt][r] = 0.0f;
+
+#pragma unroll
+        for (int t = 0; t < KSTEPS; ++t) {
+            settle(qf[t]);
+            settle(dof[t]);
+        }
+        asm volatile("" ::"v"(lse2), "v"(delta));
+        const float my_lse2 = lse2, my_delta = delta;
         wait_async_loads();
         __syncthreads();
-    }
 
-    if (row_valid) {
-        __bf16* dq_row = static_cast<__bf16*>(p.dq) + ((size_t)(q_row0 + tok) * p.Hq + head) * D;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                f32x4 f = {dq[dt][4 * r4] * p.scale, dq[dt][4 * r4 + 1] * p.scale, dq[dt][4 * r4 + 2] * p.scale,
-                           dq[dt][4 * r4 + 3] * p.scale};
-                *reinterpret_cast<bf16x4*>(dq_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(f, bf16x4);
+        // One key tile; the last tile of a work is a separate instantiation that alone prefetches for the
+        // next work, so the loop over the other tiles holds no ordinary global load.
+        auto tile = [&](const int kt, auto last_tag) {
+            constexpr bool last = decltype(last_tag)::value;
+            const int j0 = kt * BN;
+            const int k_tile = stage * 2 * TILE_BYTES;
+            const int v_tile = k_tile + TILE_BYTES;
+            {
+                const unsigned nk = smem_lds + (stage ^ 1) * 2 * TILE_BYTES;
+                if constexpr (!last) {
+                    loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
+                    loader.issue(v_rsrc, nk + TILE_BYTES, (kt + 1) * tile_step);
+                } else if (has_next) {
+                    loader.issue(kv_rsrc(p.k, nxt), nk, 0);
+                    loader.issue(kv_rsrc(p.v, nxt), nk + TILE_BYTES, 0);
+                }
             }
+            // One 32-key block at a time: S^T and dP^T (rows = key rows in registers, columns = query rows in
+            // lanes), the elementwise part, then dQ^T += K^T dS^T for these 32 keys.  MFMAs alternate between
+            // independent accumulators so that none waits on the one just issued.
+            const bool need_mask = kt >= cur.n_full;
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                f32x16 s, dp;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    s[r] = 0.0f;
+                    dp[r] = 0.0f;
+                }
+                {
+                    constexpr int NS = 2 * KSTEPS;  // step i: product i % 2 (0: S from K, 1: dP from V), k-step i / 2
+                    auto frag = [&](int i) { return fa.rowmajor(smem, (i % 2) ? v_tile : k_tile, b, i / 2); };
+                    bf16x8 ring[PF];
+#pragma unroll
+                    for (int i = 0; i < PF; ++i) ring[i] = frag(i);
+#pragma unroll
+                    for (int i = 0; i < NS; ++i) {
+                        const bf16x8 a = ring[i % PF];
+                        if (i + PF < NS) ring[i % PF] = frag(i + PF);
+                        if (i % 2) dp = mfma32(a, dof[i / 2], dp);
+                        else s = mfma32(a, qf[i / 2], s);
+                    }
+#pragma unroll
+                    for (int i = 0; i < PF; ++i) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+                    for (int i = 0; i < NS; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (i + PF < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                }
+                if (b == 1) {
+                    // the row fragments are free now: those of the next work can start loading
+                    if constexpr (last) {
+                        if (has_next) load_rows(nxt);
+                    }
+                }
+                // first K^T fragments on their way while the elementwise part runs.
+                // Step i of the last product: keys 32 b + 16 (i / DT) .. + 15, dQ^T block i % DT.
+                bf16x8 kring[PF];
+#pragma unroll
+                for (int i = 0; i < PF; ++i) kring[i] = fa.transposed(smem, k_tile, 2 * b + i / DT, i % DT);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -my_lse2));
+                    if (need_mask && j0 + 32 * b + acc_row(r, hf) >= vis) pv = 0.0f;
+                    dp[r] = pv * (dp[r] - my_delta);
+                }
+                bf16x8 dsb[2];
+#pragma unroll
+                for (int x = 0; x < 2; ++x)
+                    dsb[x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3],
+                                       dp[8 * x + 4], dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
+                {
+                    constexpr int NS = 2 * DT;
+#pragma unroll
+                    for (int i = 0; i < NS; ++i) {
+                        const bf16x8 a = kring[i % PF];
+                        if (i + PF < NS) kring[i % PF] = fa.transposed(smem, k_tile, 2 * b + (i + PF) / DT, (i + PF) % DT);
+                        dq[i % DT] = mfma32(a, dsb[i / DT], dq[i % DT]);
+                    }
+#pragma unroll
+                    for (int i = 0; i < NS; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                        if (i + PF < NS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+                    }
+                }
+            }
+            stage ^= 1;
+            if constexpr (!last) {
+                wait_async_loads();
+                __syncthreads();
+            }
+        };
+        for (int kt = 0; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{});
+        tile(cur.n_tiles - 1, std::true_type{});
+
+        // dQ leaves through the LDS stage that was just processed; every wave must be done reading it first
+        __syncthreads();
+        {
+            char* out_stage = smem + (stage ^ 1) * 2 * TILE_BYTES + wave * (32 * D * 2);
+            store_block_rows<D>(out_stage, dq, p.scale, lane, [&](int r) -> __bf16* {
+                const int rr = wave * 32 + r, t = rr % BMT;
+                if (t >= cur.q_rows) return nullptr;
+                return static_cast<__bf16*>(p.dq) + ((size_t)(cur.q_row0 + t) * p.Hq + cur.h0 + rr / BMT) * D;
+            });
+        }
+        if (!has_next) break;
+        ++work;
+        cur = nxt;
     }
 }
 
@@ -394,10 +488,9 @@ hipError_t launch_dq_dh(const AttnParams& p, hipStream_t stream, unsigned grid) 
 
 template <int D>
 hipError_t launch_dq_d(const AttnParams& p, hipStream_t stream) {
-    const int G = p.Hq / p.Hkv;
     const int hpb = heads_per_block(p.Hq, p.Hkv);
-    const unsigned grid = (unsigned)p.num_items * (unsigned)(p.Hkv * (G / hpb));
-    if (grid == 0) return hipSuccess;
+    const unsigned grid = (unsigned)p.num_workgroups;
+    if (p.num_items == 0) return hipSuccess;
     switch (hpb) {
         case 1: return launch_dq_dh<D, 1>(p, stream, grid);
         case 2: return launch_dq_dh<D, 2>(p, stream, grid);
