@@ -57,195 +57,322 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
 
 // ------------------------------------------------------------------ dK / dV
 
-// V_LDS: the V rows of the key tile live in LDS (read as second operand of dP = dO V^T) instead of in
-// registers, which buys the register room for two workgroups per CU at D = 128 and avoids spilling at
-// D = 256.
-// PART: 0 = dK and dV in one pass; 1 = dV only; 2 = dK only.  At D = 256 the two accumulators together
-// (256 registers per lane) leave no room for anything else, so the kernel is launched once per part
-// there, at the price of recomputing the scores (5 products instead of 4).
-template <int D, bool V_LDS, int PART>
+// What one workgroup needs to know about a dK/dV work (all wave-uniform).
+struct DkdvWork {
+    int kv_row0, kv_rows, seq_row0, qt_first, qt_count, P, L, g;
+};
+
+template <bool PERSIST>
+VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int work_index) {
+    const int id = PERSIST ? p.work_ids[work_index] : work_index;  // one work per workgroup: heaviest first
+    const WorkItem it = p.items[id / p.works_per_item];
+    DkdvWork w;
+    w.kv_row0 = it.w[0];
+    w.kv_rows = it.w[1];
+    w.seq_row0 = it.w[2];
+    w.qt_first = it.w[3];
+    w.qt_count = it.w[4];
+    w.P = it.w[6];
+    w.L = it.w[7];
+    w.g = id % p.works_per_item;
+    return w;
+}
+
+// Persistent dK/dV kernel.  A work is one key tile of 128 rows of one KV head; each wave owns 32 key rows
+// and keeps their K fragments in registers.  The workgroup walks over the query tiles that see the key
+// tile, for every query head of the group, staging Q, dO, LSE and delta in two LDS stages that are filled
+// asynchronously one step ahead (across works too).
+//   V_LDS  the V rows of the key tile live in LDS (second operand of dP = dO V^T) instead of registers:
+//          that buys the register room for two workgroups per CU at D = 128
+//   PART   0 = dK and dV in one pass; 1 = dV only; 2 = dK only.  At D = 256 the two accumulators together
+//          (256 registers per lane) leave no room for anything else, so the kernel is launched once per
+//          part there, at the price of recomputing the scores (5 products instead of 4).
+//   PERSIST  true: the workgroup runs the list of works the host assigned to it, prefetching across works;
+//          false: one work per workgroup, launched heaviest first (fewer live registers)
+template <int D, bool V_LDS, int PART, bool PERSIST>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnParams p) {
     constexpr bool DO_DV = PART != 2, DO_DK = PART != 1;
+    constexpr bool V_IN_LDS = V_LDS && DO_DK, V_REGS = !V_LDS && DO_DK;
     constexpr int BMQ = dkdv_q_tile(D);  // query rows staged per step
     constexpr int QB = BMQ / 32;         // 32-row query blocks per step
     constexpr int KSTEPS = D / 16;
     constexpr int DT = D / 32;
+    constexpr int PF = (D == 128 && PART == 0) ? 2 : kPrefetch;  // D = 128 in one pass has no registers to spare
     constexpr int TILE_BYTES = BMQ * D * 2;
     constexpr int STAGE_BYTES = 2 * TILE_BYTES + 2 * 64 * (int)sizeof(float);  // Q, dO, LSE2[64], delta[64]
-    extern __shared__ __attribute__((aligned(16))) char smem[];  // two stages, then the V tile if V_LDS
-    constexpr int v_tile = 2 * STAGE_BYTES;
+    constexpr int AUX = 2 * STAGE_BYTES;  // V tile of the work; output staging at the end of the work
+    extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int g = blockIdx.x % p.Hkv;
-    const WorkItem it = p.items[blockIdx.x / p.Hkv];
-    const int kv_row0 = it.w[0], kv_rows = it.w[1], seq_row0 = it.w[2];
-    const int qt_first = it.w[3], qt_count = it.w[4], P = it.w[6], L = it.w[7];
+    int work = PERSIST ? p.wg_table[2 * blockIdx.x] : (int)blockIdx.x;
+    const int work_end = PERSIST ? work + p.wg_table[2 * blockIdx.x + 1] : work + 1;
+    if (work >= work_end) return;
+
     const int G = p.Hq / p.Hkv;
     const float c = p.scale * kLog2e;
-    const RowMask mask(P, L, p.mask_mode);
-
-    // Stage n holds query tile qt_first + n % qt_count of head g * G + n / qt_count.  Q and dO rows of
-    // (sample, head) and the LSE / delta rows are raw buffers: anything past the sample reads as zero.
-    const int n_steps = G * qt_count;
     const int q_row_bytes = p.Hq * D * 2;
-    const unsigned q_bytes = (unsigned)(L - 1) * q_row_bytes + D * 2;
+    const int kv_row_bytes = p.Hkv * D * 2;
+    const unsigned smem_lds = lds_addr(smem);
     AsyncTile<D, BMQ, 4> loader;
     loader.init(wave, lane, q_row_bytes);
-    const unsigned smem_lds = lds_addr(smem);
-    auto issue = [&](int n) {
-        const unsigned st = smem_lds + (n & 1) * STAGE_BYTES;
-        const int head = g * G + n / qt_count;
-        const int q0 = (qt_first + n % qt_count) * BMQ;
-        const size_t off = ((size_t)seq_row0 * p.Hq + head) * D;
+    const FragAddr<D> fa(lane);
+
+    // Step n of a work is query tile qt_first + n % qt_count of head g * G + n / qt_count.  Q and dO rows
+    // of (sample, head) and the LSE / delta rows are raw buffers: anything past the sample reads as zero.
+    auto issue_stage = [&](const DkdvWork& w, int n, int st_index) {
+        const unsigned st = smem_lds + st_index * STAGE_BYTES;
+        const int head = w.g * G + n / w.qt_count;
+        const int q0 = (w.qt_first + n % w.qt_count) * BMQ;
+        const size_t off = ((size_t)w.seq_row0 * p.Hq + head) * D;
+        const unsigned q_bytes = (unsigned)(w.L - 1) * q_row_bytes + D * 2;
         loader.issue(make_rsrc(static_cast<const __bf16*>(p.q) + off, q_bytes), st, q0 * q_row_bytes);
         loader.issue(make_rsrc(static_cast<const __bf16*>(p.dout) + off, q_bytes), st + TILE_BYTES, q0 * q_row_bytes);
         if (wave < 2) {  // 64 floats each: lane i fetches row q0 + i
-            const float* src = (wave == 0 ? p.lse2 : p.delta) + (size_t)head * p.T + seq_row0;
-            buffer_load_lds_4(st + 2 * TILE_BYTES + wave * 256, lane * 4, make_rsrc(src, (unsigned)L * 4), q0 * 4);
+            const float* src = (wave == 0 ? p.lse2 : p.delta) + (size_t)head * p.T + w.seq_row0;
+            buffer_load_lds_4(st + 2 * TILE_BYTES + wave * 256, lane * 4, make_rsrc(src, (unsigned)w.L * 4), q0 * 4);
         }
     };
-    issue(0);
-    if (V_LDS && DO_DK) {
-        const int kv_row_bytes = p.Hkv * D * 2;
-        AsyncTile<D, kDkdvKvRows, 4> v_loader;
-        v_loader.init(wave, lane, kv_row_bytes);
-        const __bf16* v_seq = static_cast<const __bf16*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
-        v_loader.issue(make_rsrc(v_seq, (unsigned)(L - 1) * kv_row_bytes + D * 2), smem_lds + 2 * STAGE_BYTES,
-                       (kv_row0 - seq_row0) * kv_row_bytes);
-    }
-
-    // this wave's 32 key rows; the lane owns key row jw + l32 (local index in the sample)
-    const int jw = kv_row0 - seq_row0 + 32 * wave;
-    const int kv_local = jw + l32;
-    const bool kv_valid = 32 * wave + l32 < kv_rows;
-
-    // K and V fragments of the lane's key row: k-slots d = 16 t + 8 hf + 0..7
-    constexpr bool V_REGS = !V_LDS && DO_DK;
+    auto issue_v = [&](const DkdvWork& w) {
+        if (V_IN_LDS) {
+            AsyncTile<D, kDkdvKvRows, 4> v_loader;  // rebuilt per work: not worth registers across the step loop
+            v_loader.init(wave, lane, kv_row_bytes);
+            const __bf16* v_seq = static_cast<const __bf16*>(p.v) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D;
+            v_loader.issue(make_rsrc(v_seq, (unsigned)(w.L - 1) * kv_row_bytes + D * 2), smem_lds + AUX,
+                           (w.kv_row0 - w.seq_row0) * kv_row_bytes);
+        }
+    };
+    // K (and V) fragments of the lane's key row: k-slots d = 16 t + 8 hf + 0..7
     bf16x8 kf[KSTEPS], vf[V_REGS ? KSTEPS : 1];
-    {
-        const size_t off = ((size_t)(kv_row0 + 32 * wave + l32) * p.Hkv + g) * D;
+    auto load_k = [&](const DkdvWork& w) {
+        const bool valid = 32 * wave + l32 < w.kv_rows;
+        const size_t off = ((size_t)(w.kv_row0 + 32 * wave + l32) * p.Hkv + w.g) * D;
         const __bf16* krow = static_cast<const __bf16*>(p.k) + off;
         const __bf16* vrow = static_cast<const __bf16*>(p.v) + off;
 #pragma unroll
         for (int t = 0; t < KSTEPS; ++t) {
             u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
-            if (kv_valid) {
+            if (valid) {
                 a = *reinterpret_cast<const u32x4*>(krow + 16 * t + 8 * hf);
                 if (V_REGS) b = *reinterpret_cast<const u32x4*>(vrow + 16 * t + 8 * hf);
             }
             kf[t] = __builtin_bit_cast(bf16x8, a);
             if (V_REGS) vf[t] = __builtin_bit_cast(bf16x8, b);
         }
-    }
+    };
 
-    f32x16 dk[DO_DK ? DT : 1], dv[DO_DV ? DT : 1];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            if (DO_DK) dk[dt][r] = 0.0f;
-            if (DO_DV) dv[dt][r] = 0.0f;
-        }
+    DkdvWork cur = fetch_dkdv_work<PERSIST>(p, work);
+    int stage = 0;
+    issue_stage(cur, 0, 0);
+    issue_v(cur);
+    load_k(cur);
 
-#pragma unroll
-    for (int t = 0; t < KSTEPS; ++t) {
-        settle(kf[t]);
-        if (V_REGS) settle(vf[t]);
-    }
-    wait_async_loads();
-    __syncthreads();
+    for (;;) {
+        const bool has_next = PERSIST && work + 1 < work_end;
+        DkdvWork nxt = cur;
+        if (has_next) nxt = fetch_dkdv_work<PERSIST>(p, work + 1);
+        const int n_steps = G * cur.qt_count;
+        const RowMask mask(cur.P, cur.L, p.mask_mode);
+        const int L = cur.L;
+        // this wave's 32 key rows; the lane owns key row jw + l32 (local index in the sample)
+        const int jw = cur.kv_row0 - cur.seq_row0 + 32 * wave;
+        const int kv_local = jw + l32;
 
-    const FragAddr<D> fa(lane);
-    for (int n = 0; n < n_steps; ++n) {
-        if (n + 1 < n_steps) issue(n + 1);
-        const int q_tile = (n & 1) * STAGE_BYTES;  // byte offsets of this stage's tiles
-        const int do_tile = q_tile + TILE_BYTES;
-        const float* lse_s = reinterpret_cast<const float*>(smem + q_tile + 2 * TILE_BYTES);
-        const float* delta_s = lse_s + 64;
-        const int q0 = (qt_first + n % qt_count) * BMQ;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            const int i0 = q0 + 32 * qb;  // first query row of the block (local index in the sample)
-            if (i0 >= L) break;
-            const int i1 = min(i0 + 31, L - 1);
-            if (mask.vis(i1) <= jw) continue;  // nothing of this key block is visible
-            // rows past the sample read as zeros and must get p = 0: they count as seeing no key
-            const bool need_mask = mask.vis(i0) < jw + 32 || i0 + 32 > L;
-
-            // S = Q K^T : rows = query rows (registers), columns = key rows (lanes)
-            f32x16 s, dp;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                s[r] = 0.0f;
-                dp[r] = 0.0f;
-            }
-#pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) s = mfma32(fa.rowmajor(smem, q_tile, qb, t), kf[t], s);
-            __builtin_amdgcn_sched_barrier(0);  // keep the fragment reads of one product from piling up ahead of another
-            if (DO_DK) {
-#pragma unroll
-                for (int t = 0; t < KSTEPS; ++t)
-                    dp = mfma32(fa.rowmajor(smem, do_tile, qb, t),
-                                V_LDS ? fa.rowmajor(smem, v_tile, wave, t) : vf[V_REGS ? t : 0], dp);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                const int rb = 32 * qb + 8 * r4 + 4 * hf;  // tile row of registers 4 r4 .. 4 r4 + 3
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + rb);
-                const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_s + rb);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int r = 4 * r4 + e;
-                    float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
-                    if (need_mask && kv_local >= mask.vis_in_sample(q0 + rb + e)) pv = 0.0f;
-                    s[r] = pv;
-                    if (DO_DK) dp[r] = pv * (dp[r] - d4[e]);
-                }
-            }
-            bf16x8 pb[2], dsb[2];
-#pragma unroll
-            for (int x = 0; x < 2; ++x) {
-                pb[x] = to_bf16x8(s[8 * x], s[8 * x + 1], s[8 * x + 2], s[8 * x + 3], s[8 * x + 4], s[8 * x + 5],
-                                  s[8 * x + 6], s[8 * x + 7]);
-                dsb[x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
-                                   dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            // dV^T += dO^T P ; dK^T += Q^T dS  (rows = d, columns = key rows)
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-#pragma unroll
-                for (int x = 0; x < 2; ++x) {
-                    if (DO_DV) dv[dt] = mfma32(fa.transposed(smem, do_tile, 2 * qb + x, dt), pb[x], dv[dt]);
-                    if (DO_DK) dk[dt] = mfma32(fa.transposed(smem, q_tile, 2 * qb + x, dt), dsb[x], dk[dt]);
-                }
-                if (D == 256 && (dt & 1)) __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        wait_async_loads();
-        __syncthreads();
-    }
-
-    if (kv_valid) {
-        const size_t off = ((size_t)(kv_row0 + 32 * wave + l32) * p.Hkv + g) * D;
-        __bf16* dk_row = static_cast<__bf16*>(p.dk) + off;
-        __bf16* dv_row = static_cast<__bf16*>(p.dv) + off;
+        f32x16 dk[DO_DK ? DT : 1], dv[DO_DV ? DT : 1];
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                if (DO_DK) {
-                    f32x4 a = {dk[dt][4 * r4] * p.scale, dk[dt][4 * r4 + 1] * p.scale, dk[dt][4 * r4 + 2] * p.scale,
-                               dk[dt][4 * r4 + 3] * p.scale};
-                    *reinterpret_cast<bf16x4*>(dk_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(a, bf16x4);
+            for (int r = 0; r < 16; ++r) {
+                if (DO_DK) dk[dt][r] = 0.0f;
+                if (DO_DV) dv[dt][r] = 0.0f;
+            }
+#pragma unroll
+        for (int t = 0; t < KSTEPS; ++t) {
+            settle(kf[t]);
+            if (V_REGS) settle(vf[t]);
+        }
+        wait_async_loads();
+        __syncthreads();
+
+        // One step; the last step of a work is a separate instantiation that alone prefetches for the next
+        // work, so the loop over the other steps holds no ordinary global load.
+        auto step = [&](const int n, auto last_tag) {
+            constexpr bool last = decltype(last_tag)::value;
+            if constexpr (!last) {
+                issue_stage(cur, n + 1, stage ^ 1);
+            } else if (has_next) {
+                issue_stage(nxt, 0, stage ^ 1);
+            }
+            const int q_tile = stage * STAGE_BYTES;  // byte offsets of this stage's tiles
+            const int do_tile = q_tile + TILE_BYTES;
+            const float* lse_s = reinterpret_cast<const float*>(smem + q_tile + 2 * TILE_BYTES);
+            const float* delta_s = lse_s + 64;
+            const int q0 = (cur.qt_first + n % cur.qt_count) * BMQ;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const int i0 = q0 + 32 * qb;  // first query row of the block (local index in the sample)
+                if (i0 >= L) break;
+                const int i1 = min(i0 + 31, L - 1);
+                if (mask.vis(i1) <= jw) continue;  // nothing of this key block is visible
+                // rows past the sample read as zeros and must get p = 0: they count as seeing no key
+                const bool need_mask = mask.vis(i0) < jw + 32 || i0 + 32 > L;
+
+                // S = Q K^T and dP = dO V^T: rows = query rows (registers), columns = key rows (lanes).
+                // MFMAs alternate between the two accumulators so that none waits on the one just issued.
+                f32x16 s, dp;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    s[r] = 0.0f;
+                    dp[r] = 0.0f;
                 }
-                if (DO_DV) {
-                    f32x4 b = {dv[dt][4 * r4], dv[dt][4 * r4 + 1], dv[dt][4 * r4 + 2], dv[dt][4 * r4 + 3]};
-                    *reinterpret_cast<bf16x4*>(dv_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(b, bf16x4);
+                {
+                    constexpr int NS = DO_DK ? 2 * KSTEPS : KSTEPS;  // step i: product i % 2 (0: S, 1: dP) if both
+                    auto prod = [&](int i) { return DO_DK ? i % 2 : 0; };
+                    auto kstep = [&](int i) { return DO_DK ? i / 2 : i; };
+                    bf16x8 ring[PF], vring[V_IN_LDS ? PF : 1];
+                    auto fetch = [&](int i) {
+                        ring[i % PF] = fa.rowmajor(smem, prod(i) ? do_tile : q_tile, qb, kstep(i));
+                        if (V_IN_LDS && prod(i)) vring[i % PF] = fa.rowmajor(smem, AUX, wave, kstep(i));
+                    };
+#pragma unroll
+                    for (int i = 0; i < PF; ++i) fetch(i);
+#pragma unroll
+                    for (int i = 0; i < NS; ++i) {
+                        const bf16x8 a = ring[i % PF];
+                        const bf16x8 bv = V_IN_LDS ? vring[i % PF] : vf[V_REGS ? kstep(i) : 0];
+                        if (i + PF < NS) fetch(i + PF);
+                        if (prod(i)) dp = mfma32(a, bv, dp);
+                        else s = mfma32(a, kf[kstep(i)], s);
+                    }
+#pragma unroll
+                    for (int i = 0; i < PF; ++i) {
+                        if (V_IN_LDS && (i % 2)) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                        else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+#pragma unroll
+                    for (int i = 0; i < NS; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        if (i + PF < NS) {
+                            if (V_IN_LDS && ((i + PF) % 2)) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                            else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        }
+                    }
+                }
+                // first transposed fragments on their way while the elementwise part runs.
+                // Step i of the last products: which = i % NW (dV from dO^T, dK from Q^T), block (i / NW) % DT,
+                // query rows 16 (i / (NW DT)) .. + 15 of the block.
+                constexpr int NW = (DO_DV ? 1 : 0) + (DO_DK ? 1 : 0);
+                constexpr int NT = 2 * DT * NW;
+                auto tfrag = [&](int i) {
+                    const bool is_dk = DO_DK && (!DO_DV || (i % NW) == 1);
+                    return fa.transposed(smem, is_dk ? q_tile : do_tile, 2 * qb + i / (NW * DT), (i / NW) % DT);
+                };
+                bf16x8 tring[PF];
+#pragma unroll
+                for (int i = 0; i < PF; ++i) tring[i] = tfrag(i);
+
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int rb = 32 * qb + 8 * r4 + 4 * hf;  // tile row of registers 4 r4 .. 4 r4 + 3
+                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + rb);
+                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_s + rb);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int r = 4 * r4 + e;
+                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
+                        if (need_mask && kv_local >= mask.vis_in_sample(q0 + rb + e)) pv = 0.0f;
+                        s[r] = pv;
+                        if (DO_DK) dp[r] = pv * (dp[r] - d4[e]);
+                    }
+                }
+                bf16x8 pb[2], dsb[2];
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    if (DO_DV)
+                        pb[x] = to_bf16x8(s[8 * x], s[8 * x + 1], s[8 * x + 2], s[8 * x + 3], s[8 * x + 4], s[8 * x + 5],
+                                          s[8 * x + 6], s[8 * x + 7]);
+                    if (DO_DK)
+                        dsb[x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
+                                           dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
+                }
+                // dV^T += dO^T P ; dK^T += Q^T dS  (rows = d, columns = key rows): consecutive MFMAs go to
+                // different accumulators
+#pragma unroll
+                for (int i = 0; i < NT; ++i) {
+                    const bf16x8 a = tring[i % PF];
+                    if (i + PF < NT) tring[i % PF] = tfrag(i + PF);
+                    const bool is_dk = DO_DK && (!DO_DV || (i % NW) == 1);
+                    const int dt = (i / NW) % DT, x = i / (NW * DT);
+                    if (is_dk) dk[DO_DK ? dt : 0] = mfma32(a, dsb[x], dk[DO_DK ? dt : 0]);
+                    else dv[DO_DV ? dt : 0] = mfma32(a, pb[x], dv[DO_DV ? dt : 0]);
+                }
+#pragma unroll
+                for (int i = 0; i < NT; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                    if (i + PF < NT) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
                 }
             }
+            stage ^= 1;
+            if constexpr (!last) {
+                wait_async_loads();
+                __syncthreads();
+            }
+        };
+        for (int n = 0; n + 1 < n_steps; ++n) step(n, std::false_type{});
+        step(n_steps - 1, std::true_type{});
+
+        // dK and dV leave as whole rows through the V-tile region; every wave must be done with it first
+        __syncthreads();
+        {
+            char* out_stage = smem + AUX + wave * (32 * D * 2);
+#ifdef VA_X_NOSTORE
+            const int rows_here = cur.kv_rows > 100000 ? 1 : 0;
+#else
+            const int rows_here = cur.kv_rows - 32 * wave;
+#endif
+            const size_t off = ((size_t)(cur.kv_row0 + 32 * wave) * p.Hkv + cur.g) * D;
+            const size_t row_stride = (size_t)p.Hkv * D;
+#ifdef VA_X_NOEPI
+            if (32 * wave + l32 < cur.kv_rows) {
+                __bf16* dk_row = static_cast<__bf16*>(p.dk) + off + l32 * row_stride;
+                __bf16* dv_row = static_cast<__bf16*>(p.dv) + off + l32 * row_stride;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        if constexpr (DO_DK) {
+                            f32x4 a = {dk[dt][4 * r4] * p.scale, dk[dt][4 * r4 + 1] * p.scale, dk[dt][4 * r4 + 2] * p.scale, dk[dt][4 * r4 + 3] * p.scale};
+                            *reinterpret_cast<bf16x4*>(dk_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(a, bf16x4);
+                        }
+                        if constexpr (DO_DV) {
+                            f32x4 b = {dv[dt][4 * r4], dv[dt][4 * r4 + 1], dv[dt][4 * r4 + 2], dv[dt][4 * r4 + 3]};
+                            *reinterpret_cast<bf16x4*>(dv_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(b, bf16x4);
+                        }
+                    }
+            }
+#else
+            if constexpr (DO_DK)
+                store_block_rows<D>(out_stage, dk, p.scale, lane, [&](int r) -> __bf16* {
+                    return r < rows_here ? static_cast<__bf16*>(p.dk) + off + r * row_stride : nullptr;
+                });
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (DO_DV)
+                store_block_rows<D>(out_stage, dv, 1.0f, lane, [&](int r) -> __bf16* {
+                    return r < rows_here ? static_cast<__bf16*>(p.dv) + off + r * row_stride : nullptr;
+                });
+            __builtin_amdgcn_sched_barrier(0);
+#endif
+        }
+        if (!has_next) break;
+        load_k(nxt);  // after the accumulators are gone: the epilogue has no registers to spare
+#ifndef VA_X_NOVRELOAD
+        if (V_IN_LDS) {
+            __syncthreads();  // the staging reads are done: the next V tile may land
+            issue_v(nxt);
+        }
+#endif
+        ++work;
+        cur = nxt;
     }
 }
 
@@ -499,25 +626,29 @@ hipError_t launch_dq_d(const AttnParams& p, hipStream_t stream) {
     }
 }
 
-template <int D, int PART>
-hipError_t launch_dkdv_part(const AttnParams& p, hipStream_t stream, unsigned grid) {
+template <int D, int PART, bool PERSIST>
+hipError_t launch_dkdv_part(const AttnParams& p, hipStream_t stream) {
     constexpr bool V_LDS = D >= 128;
-    constexpr size_t smem = 2 * (2 * dkdv_q_tile(D) * D * 2 + 2 * 64 * sizeof(float)) + (V_LDS ? kDkdvKvRows * D * 2 : 0);
-    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, PART>), smem);
+    // two stages of (Q tile, dO tile, LSE, delta), then the V tile / output staging region
+    constexpr size_t smem = 2 * (2 * dkdv_q_tile(D) * D * 2 + 2 * 64 * sizeof(float)) + kDkdvKvRows * D * 2;
+    const unsigned grid = PERSIST ? (unsigned)p.num_workgroups : (unsigned)(p.num_items * p.works_per_item);
+    static const hipError_t attr =
+        allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, PART, PERSIST>), smem);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, PART>), dim3(grid), dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, PART, PERSIST>), dim3(grid), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 
+// D <= 128: one pass, one work per workgroup (the persistent form needs more registers than two
+// workgroups per CU leave).  D = 256: dV pass then dK pass, persistent.
 template <int D>
 hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
-    const unsigned grid = (unsigned)p.num_items * (unsigned)p.Hkv;
-    if (grid == 0) return hipSuccess;
+    if (p.num_items == 0) return hipSuccess;
     if constexpr (D <= 128) {
-        return launch_dkdv_part<D, 0>(p, stream, grid);
+        return launch_dkdv_part<D, 0, false>(p, stream);
     } else {
-        const hipError_t e = launch_dkdv_part<D, 1>(p, stream, grid);
-        return e != hipSuccess ? e : launch_dkdv_part<D, 2>(p, stream, grid);
+        const hipError_t e = launch_dkdv_part<D, 1, true>(p, stream);
+        return e != hipSuccess ? e : launch_dkdv_part<D, 2, true>(p, stream);
     }
 }
 

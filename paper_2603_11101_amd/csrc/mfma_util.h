@@ -291,10 +291,12 @@ VA_DEV void store_block_rows(char* stage, const f32x16 (&acc)[D / 32], float fac
                        acc[dt][4 * q + 3] * factor};
             const int unit = 8 * dt + 2 * q + hf;  // 8-byte unit of the row
             *reinterpret_cast<bf16x4*>(stage + row * RB + ((unit ^ perm) << 3)) = __builtin_convertvector(f, bf16x4);
+            if (q == 3) __builtin_amdgcn_sched_barrier(0);  // bounded live ranges: this code runs with few registers free
         }
     // the wave reads back only what it wrote itself
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
+    // a real loop on purpose: this code runs with few registers free
+#pragma unroll 1
     for (int it = 0; it < 32 * CPR / 64; ++it) {
         const int r = it * (64 / CPR) + lane / CPR, c = lane % CPR;
         const int pr = out_stage_perm<D>(r);
