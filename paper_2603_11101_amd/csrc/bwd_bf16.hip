@@ -29,29 +29,40 @@ constexpr int kPrefetch = 4;  // LDS fragment reads in flight ahead of the MFMA 
 
 // ------------------------------------------------------------------ delta
 
-// One group of D/8 lanes per (token, head) row; each lane multiplies 8 pairs.
+// One group of D/8 lanes per (token, head) row; each lane multiplies 8 pairs per row and handles
+// kDeltaRowsPerGroup rows, all of whose loads are issued before the first is used.
+constexpr int kDeltaRowsPerGroup = 4;
+
 template <int D>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ dout,
                                                         const float* __restrict__ lse, float* __restrict__ delta,
                                                         float* __restrict__ lse2, int T, int Hq) {
     constexpr int LPR = D / 8;  // lanes per row
-    constexpr int RPB = 256 / LPR;
-    const size_t row = (size_t)blockIdx.x * RPB + threadIdx.x / LPR;
-    const int c = threadIdx.x % LPR;
+    constexpr int GROUPS = 256 / LPR;
+    constexpr int R = kDeltaRowsPerGroup;
     const size_t rows = (size_t)T * Hq;
-    float acc = 0.0f;
-    if (row < rows) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + row * D + c * 8);
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(dout + row * D + c * 8);
+    const size_t row0 = ((size_t)blockIdx.x * GROUPS + threadIdx.x / LPR) * R;
+    const int c = threadIdx.x % LPR;
+    bf16x8 a[R], b[R];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
+    for (int i = 0; i < R; ++i) {
+        const size_t row = row0 + i < rows ? row0 + i : rows - 1;
+        a[i] = *reinterpret_cast<const bf16x8*>(o + row * D + c * 8);
+        b[i] = *reinterpret_cast<const bf16x8*>(dout + row * D + c * 8);
     }
 #pragma unroll
-    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-    if (row < rows && c == 0) {
-        const size_t t = row / Hq, h = row % Hq;
-        delta[h * T + t] = acc;
-        lse2[h * T + t] = lse[h * T + t] * kLog2e;  // the other kernels work with base-2 exponentials
+    for (int i = 0; i < R; ++i) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc += (float)a[i][e] * (float)b[i][e];
+#pragma unroll
+        for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+        const size_t row = row0 + i;
+        if (row < rows && c == 0) {
+            const size_t t = row / Hq, h = row % Hq;
+            delta[h * T + t] = acc;
+            lse2[h * T + t] = lse[h * T + t] * kLog2e;  // the other kernels work with base-2 exponentials
+        }
     }
 }
 
@@ -655,7 +666,7 @@ hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
 template <int D>
 hipError_t launch_delta_d(const AttnParams& p, hipStream_t stream) {
     const size_t rows = (size_t)p.T * p.Hq;
-    constexpr int RPB = 256 / (D / 8);
+    constexpr int RPB = 256 / (D / 8) * kDeltaRowsPerGroup;
     const unsigned grid = (unsigned)((rows + RPB - 1) / RPB);
     if (grid == 0) return hipSuccess;
     hipLaunchKernelGGL((bwd_delta_kernel<D>), dim3(grid), dim3(256), 0, stream, static_cast<const __bf16*>(p.out),
