@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 WORKLOAD = "vlm"
 NUM_BUFFER_SETS = 4
+COPY_CALIBRATION_BYTES = 256 << 20
 
 
 def allowed_pairs(lens, prefix):
@@ -84,6 +85,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=WORKLOAD, choices=["vlm", "pi05", "longtail", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a device-to-device copy of 256 MiB three times, the reference that scales the "
+                         "HBM byte counters of a counter-collection run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -126,6 +130,14 @@ def main():
         ps.fwd(s["q"], s["k"], s["v"], scale, s["out"], s["lse"])
         ps.bwd(s["q"], s["k"], s["v"], s["out"], s["lse"], s["do"], scale, s["dq"], s["dk"], s["dv"])
 
+    if args.copy_calibration:
+        src = torch.ones(COPY_CALIBRATION_BYTES // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(sets[i % NUM_BUFFER_SETS])
     torch.cuda.synchronize()
@@ -136,24 +148,24 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
-    # per-kernel durations with HIP events on the launch stream, over the same rotation
+    # per-kernel durations with HIP events on the launch stream, over the same rotation; every launch of a
+    # pass is enqueued before the first wait, so the events sit on kernel boundaries of a busy stream
     iters = max(8, min(args.steps, 40))
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    fwd_ms = 0.0
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
     for i in range(iters):
         s = sets[i % NUM_BUFFER_SETS]
-        ev0.record()
+        evs[i].record()
         ps.fwd(s["q"], s["k"], s["v"], scale, s["out"], s["lse"])
-        ev1.record()
-        ev1.synchronize()
-        fwd_ms += ev0.elapsed_time(ev1)
-    fwd_ms /= iters
+    evs[iters].record()
+    evs[iters].synchronize()
+    fwd_ms = float(np.mean([evs[i].elapsed_time(evs[i + 1]) for i in range(iters)]))
     kms = np.zeros(3)
-    for i in range(iters):
-        s = sets[i % NUM_BUFFER_SETS]
+    per_set = max(2, iters // NUM_BUFFER_SETS)
+    for i in range(NUM_BUFFER_SETS):
+        s = sets[i]
         kms += np.array(ps.bwd_profile(s["q"], s["k"], s["v"], s["out"], s["lse"], s["do"], scale,
-                                       s["dq"], s["dk"], s["dv"], iters=1))
-    kms /= iters
+                                       s["dq"], s["dk"], s["dv"], iters=per_set))
+    kms /= NUM_BUFFER_SETS
     # algorithmic work per launch: forward 2 products; dK/dV kernel 4 (scores, dP, dV, dK); dQ kernel 1 (dQ;
     # its recomputation of the scores and dP is overhead and is not counted)
     kernels = {

@@ -110,17 +110,31 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
                   int32_t* rows, int32_t* cols);
 
 /*
- * Work list of one pass over one packed stream: a header of 8 int32 words
- * {magic, pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
- * followed by num_items items of 8 int32 words, heaviest first (ties by sample,
- * then tile).  Only tiles holding at least one visible (query, key) pair are
- * listed and no tile spans two samples (the varlen rule of section 2.2.1 (1):
- * compute on valid tokens only).
+ * Work list of one pass over one packed stream, in records of 8 int32 words:
+ *   record 0   {magic "VAW2", pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
+ *   record 1   {num_workgroups, num_works, works_per_item, first item record (2),
+ *               first table record, first work-id record, total records, 0}
+ *   items      num_items records, heaviest first (ties by sample, then tile)
+ *   table      one (first work, count) pair per persistent workgroup, 4 pairs per record
+ *   work ids   num_works words, 8 per record: item * works_per_item + head chunk,
+ *              grouped by workgroup in the order the workgroup runs them
+ * Only tiles holding at least one visible (query, key) pair are listed and no
+ * tile spans two samples (the varlen rule of section 2.2.1 (1): compute on
+ * valid tokens only).
  *   forward / dQ item: {q_row0, q_rows, seq_row0, kv_len, n_full, n_tiles, P or -1, L}
  *   dK/dV item:        {kv_row0, kv_rows, seq_row0, qt_first, qt_count, 0, P or -1, L}
+ * A work is one item for one head chunk: the query heads one workgroup stacks
+ * (forward, dQ) or one KV head (dK/dV), so works_per_item depends on the head
+ * counts the list was built for.  The kernels run num_workgroups persistent
+ * workgroups; the table assigns the works to them longest-processing-time
+ * first, with a work's cost taken as its inner-loop steps plus a fixed part.
+ * Kernels that run one work per workgroup ignore the table and take work ids
+ * 0 .. num_works-1 in item order.
  * va_worklist_bytes gives the buffer size; va_build_worklist fills a host
  * buffer of at least that size.  The caller copies the buffer to the device
- * unchanged and hands it to the device calls.
+ * unchanged and hands both copies to the device calls, which validate the host
+ * copy (records, bounds, that every item lies inside one sample of cu_seqlens,
+ * that the table partitions the works) and return VA_EINVAL on a mismatch.
  */
 int va_worklist_bytes(const int32_t* cu_seqlens, int32_t num_seqs, int32_t pass, int32_t head_dim,
                       int32_t num_q_heads, int32_t num_kv_heads, size_t* bytes);

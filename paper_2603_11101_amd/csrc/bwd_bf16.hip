@@ -336,32 +336,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         __syncthreads();
         {
             char* out_stage = smem + AUX + wave * (32 * D * 2);
-#ifdef VA_X_NOSTORE
-            const int rows_here = cur.kv_rows > 100000 ? 1 : 0;
-#else
             const int rows_here = cur.kv_rows - 32 * wave;
-#endif
             const size_t off = ((size_t)(cur.kv_row0 + 32 * wave) * p.Hkv + cur.g) * D;
             const size_t row_stride = (size_t)p.Hkv * D;
-#ifdef VA_X_NOEPI
-            if (32 * wave + l32 < cur.kv_rows) {
-                __bf16* dk_row = static_cast<__bf16*>(p.dk) + off + l32 * row_stride;
-                __bf16* dv_row = static_cast<__bf16*>(p.dv) + off + l32 * row_stride;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        if constexpr (DO_DK) {
-                            f32x4 a = {dk[dt][4 * r4] * p.scale, dk[dt][4 * r4 + 1] * p.scale, dk[dt][4 * r4 + 2] * p.scale, dk[dt][4 * r4 + 3] * p.scale};
-                            *reinterpret_cast<bf16x4*>(dk_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(a, bf16x4);
-                        }
-                        if constexpr (DO_DV) {
-                            f32x4 b = {dv[dt][4 * r4], dv[dt][4 * r4 + 1], dv[dt][4 * r4 + 2], dv[dt][4 * r4 + 3]};
-                            *reinterpret_cast<bf16x4*>(dv_row + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(b, bf16x4);
-                        }
-                    }
-            }
-#else
             if constexpr (DO_DK)
                 store_block_rows<D>(out_stage, dk, p.scale, lane, [&](int r) -> __bf16* {
                     return r < rows_here ? static_cast<__bf16*>(p.dk) + off + r * row_stride : nullptr;
@@ -372,16 +349,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                     return r < rows_here ? static_cast<__bf16*>(p.dv) + off + r * row_stride : nullptr;
                 });
             __builtin_amdgcn_sched_barrier(0);
-#endif
         }
         if (!has_next) break;
         load_k(nxt);  // after the accumulators are gone: the epilogue has no registers to spare
-#ifndef VA_X_NOVRELOAD
         if (V_IN_LDS) {
             __syncthreads();  // the staging reads are done: the next V tile may land
             issue_v(nxt);
         }
-#endif
         ++work;
         cur = nxt;
     }

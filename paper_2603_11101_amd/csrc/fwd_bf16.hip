@@ -97,9 +97,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
 #pragma unroll
         for (int t = 0; t < KSTEPS; ++t) {
             u32x4 raw = {0u, 0u, 0u, 0u};
-#ifndef VA_EXP_NO_QLOAD
             if (tok < w.q_rows) raw = *reinterpret_cast<const u32x4*>(qrow + 16 * t + 8 * hf);
-#endif
             qf[t] = __builtin_bit_cast(bf16x8, raw);
         }
     };
@@ -271,9 +269,6 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
             char* out_stage = smem + (stage ^ 1) * 2 * TILE_BYTES + wave * (32 * D * 2);
             store_block_rows<D>(out_stage, o, 1.0f / lsum, lane, [&](int r) -> __bf16* {
                 const int rr = wave * 32 + r, t = rr % BMT;
-#ifdef VA_EXP_NO_STORE
-                if (lsum != 12345.0f) return nullptr;
-#endif
                 if (t >= cur.q_rows) return nullptr;
                 return static_cast<__bf16*>(p.out) + ((size_t)(cur.q_row0 + t) * p.Hq + cur.h0 + rr / BMT) * D;
             });
