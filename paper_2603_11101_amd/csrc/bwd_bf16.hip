@@ -336,18 +336,20 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         __syncthreads();
         {
             char* out_stage = smem + AUX + wave * (32 * D * 2);
-            const int rows_here = cur.kv_rows - 32 * wave;
+            // this wave's 32 key rows of KV head g, as far as the sample goes
+            const int rows_here = min(max(cur.kv_rows - 32 * wave, 0), 32);
             const size_t off = ((size_t)(cur.kv_row0 + 32 * wave) * p.Hkv + cur.g) * D;
-            const size_t row_stride = (size_t)p.Hkv * D;
+            const int row_bytes = p.Hkv * D * 2;
+            const unsigned bytes = rows_here > 0 ? (unsigned)(rows_here - 1) * row_bytes + D * 2 : 0u;
+            const int lane_off = RowBlock<D>::lane_offset(lane, row_bytes);
+            auto soff = [&](int j) { return j * RowBlock<D>::RPI * row_bytes; };
             if constexpr (DO_DK)
-                store_block_rows<D>(out_stage, dk, p.scale, lane, [&](int r) -> __bf16* {
-                    return r < rows_here ? static_cast<__bf16*>(p.dk) + off + r * row_stride : nullptr;
-                });
+                store_block_rows<D>(out_stage, dk, p.scale, lane,
+                                    RowBlock<D>::rows(static_cast<__bf16*>(p.dk) + off, bytes), lane_off, soff);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (DO_DV)
-                store_block_rows<D>(out_stage, dv, 1.0f, lane, [&](int r) -> __bf16* {
-                    return r < rows_here ? static_cast<__bf16*>(p.dv) + off + r * row_stride : nullptr;
-                });
+                store_block_rows<D>(out_stage, dv, 1.0f, lane,
+                                    RowBlock<D>::rows(static_cast<__bf16*>(p.dv) + off, bytes), lane_off, soff);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (!has_next) break;
@@ -418,40 +420,47 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         return make_rsrc(static_cast<const __bf16*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D,
                          (unsigned)(w.L - 1) * kv_row_bytes + D * 2);
     };
-    // the stacked row this lane owns: Q and dO fragments (k-slots d = 16 t + 8 hf + 0..7), LSE and delta
+    // Q and dO rows of the wave's 32 stacked rows, whole rows per group of lanes (to_fragments() turns them
+    // into the fragments of the row this lane owns, k-slots d = 16 t + 8 hf + 0..7), and its LSE and delta
     const int row = wave * 32 + l32;
     bf16x8 qf[KSTEPS], dof[KSTEPS];
     float lse2, delta;
+    // Stacked row rr = wave * 32 + r is token rr % BMT of head h0 + rr / BMT; seen from the first row of
+    // the work's first head, tokens past q_rows lie beyond the end of the buffer and read as zero.
+    const int q_tok_bytes = p.Hq * D * 2;
+    auto block_rows = [&](const void* tensor, const DqWork& w) {
+        return RowBlock<D>::rows(static_cast<const __bf16*>(tensor) + ((size_t)w.q_row0 * p.Hq + w.h0) * D,
+                                 (unsigned)(w.q_rows - 1) * q_tok_bytes + HPB * D * 2);
+    };
+    auto block_soff = [&](int j) {
+        const int rr = __builtin_amdgcn_readfirstlane(wave * 32 + j * RowBlock<D>::RPI);
+        return (rr % BMT) * q_tok_bytes + (rr / BMT) * (D * 2);
+    };
+    // the dQ rows that leave at the end of a work: vector memory operations younger than the loads of the
+    // next work's first tile
+    constexpr int kEpilogueStores = RowBlock<D>::N;
     auto load_rows = [&](const DqWork& w) {
+        const int lane_off = RowBlock<D>::lane_offset(lane, q_tok_bytes);
+        RowBlock<D>::load(qf, block_rows(p.q, w), lane_off, block_soff);
+        RowBlock<D>::load(dof, block_rows(p.dout, w), lane_off, block_soff);
         const int tok = row % BMT;
         const int head = w.h0 + row / BMT;
-        const bool valid = tok < w.q_rows;
-        const size_t off = ((size_t)(w.q_row0 + tok) * p.Hq + head) * D;
-        const __bf16* qrow = static_cast<const __bf16*>(p.q) + off;
-        const __bf16* dorow = static_cast<const __bf16*>(p.dout) + off;
-#pragma unroll
-        for (int t = 0; t < KSTEPS; ++t) {
-            u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
-            if (valid) {
-                a = *reinterpret_cast<const u32x4*>(qrow + 16 * t + 8 * hf);
-                b = *reinterpret_cast<const u32x4*>(dorow + 16 * t + 8 * hf);
-            }
-            qf[t] = __builtin_bit_cast(bf16x8, a);
-            dof[t] = __builtin_bit_cast(bf16x8, b);
-        }
         lse2 = INFINITY;  // rows past the item: p = exp2(-inf) = 0
         delta = 0.0f;
-        if (valid) {
+        if (tok < w.q_rows) {
             lse2 = p.lse2[(size_t)head * p.T + w.q_row0 + tok];
             delta = p.delta[(size_t)head * p.T + w.q_row0 + tok];
         }
     };
+    const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
 
     DqWork cur = fetch_dq_work<HPB>(p, work);
     int stage = 0;
     loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
     loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
     load_rows(cur);
+    RowBlock<D>::to_fragments(qf, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);  // stage 1 is still free
+    RowBlock<D>::to_fragments(dof, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);
 
     for (;;) {
         const bool has_next = work + 1 < work_end;
@@ -474,7 +483,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         }
         asm volatile("" ::"v"(lse2), "v"(delta));
         const float my_lse2 = lse2, my_delta = delta;
-        wait_async_loads();
+        wait_async_loads_except<kEpilogueStores>();  // the first tile has landed; the last work's dQ may still be leaving
         __syncthreads();
 
         // One key tile; the last tile of a work is a separate instantiation that alone prefetches for the
@@ -575,15 +584,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
 
         // dQ leaves through the LDS stage that was just processed; every wave must be done reading it first
         __syncthreads();
-        {
-            char* out_stage = smem + (stage ^ 1) * 2 * TILE_BYTES + wave * (32 * D * 2);
-            store_block_rows<D>(out_stage, dq, p.scale, lane, [&](int r) -> __bf16* {
-                const int rr = wave * 32 + r, t = rr % BMT;
-                if (t >= cur.q_rows) return nullptr;
-                return static_cast<__bf16*>(p.dq) + ((size_t)(cur.q_row0 + t) * p.Hq + cur.h0 + rr / BMT) * D;
-            });
-        }
+        const int out_slice = (stage ^ 1) * 2 * TILE_BYTES + slice_in_stage;
+        store_block_rows<D>(smem + out_slice, dq, p.scale, lane, block_rows(p.dq, cur),
+                            RowBlock<D>::lane_offset(lane, q_tok_bytes), block_soff);
         if (!has_next) break;
+        // the next Q and dO rows have arrived meanwhile; the same slice turns them into fragments
+        RowBlock<D>::to_fragments(qf, smem, out_slice, fa, lane);
+        RowBlock<D>::to_fragments(dof, smem, out_slice, fa, lane);
         ++work;
         cur = nxt;
     }

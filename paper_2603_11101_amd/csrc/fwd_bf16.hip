@@ -89,18 +89,27 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         return make_rsrc(static_cast<const __bf16*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D,
                          (unsigned)(w.L - 1) * kv_row_bytes + D * 2);
     };
-    // the stacked row this lane owns: Q fragments with k-slots d = 16 t + 8 hf + 0..7
+    // Q rows of the wave's 32 stacked rows, whole rows per group of lanes; to_fragments() turns them into
+    // the fragments of the row this lane owns (k-slots d = 16 t + 8 hf + 0..7)
     const int row = wave * 32 + l32;
-    auto load_q = [&](bf16x8 (&qf)[KSTEPS], const FwdWork& w) {
-        const int tok = row % BMT;
-        const __bf16* qrow = static_cast<const __bf16*>(p.q) + ((size_t)(w.q_row0 + tok) * p.Hq + w.h0 + row / BMT) * D;
-#pragma unroll
-        for (int t = 0; t < KSTEPS; ++t) {
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (tok < w.q_rows) raw = *reinterpret_cast<const u32x4*>(qrow + 16 * t + 8 * hf);
-            qf[t] = __builtin_bit_cast(bf16x8, raw);
-        }
+    // Stacked row rr = wave * 32 + r is token rr % BMT of head h0 + rr / BMT; seen from the first row of
+    // the work's first head, tokens past q_rows lie beyond the end of the buffer and read as zero.
+    const int q_tok_bytes = p.Hq * D * 2;
+    auto block_rows = [&](const void* tensor, const FwdWork& w) {
+        return RowBlock<D>::rows(static_cast<const __bf16*>(tensor) + ((size_t)w.q_row0 * p.Hq + w.h0) * D,
+                                 (unsigned)(w.q_rows - 1) * q_tok_bytes + HPB * D * 2);
     };
+    auto block_soff = [&](int j) {
+        const int rr = __builtin_amdgcn_readfirstlane(wave * 32 + j * RowBlock<D>::RPI);
+        return (rr % BMT) * q_tok_bytes + (rr / BMT) * (D * 2);
+    };
+    auto load_q = [&](bf16x8 (&qf)[KSTEPS], const FwdWork& w) {
+        RowBlock<D>::load(qf, block_rows(p.q, w), RowBlock<D>::lane_offset(lane, q_tok_bytes), block_soff);
+    };
+    // output rows and the LSE store that leave at the end of a work: vector memory operations younger than
+    // the loads of the next work's first tile
+    constexpr int kEpilogueStores = RowBlock<D>::N + 1;
+    const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
 
     FwdWork cur = fetch_fwd_work<HPB>(p, work);
     int stage = 0;  // LDS stage that holds (or will hold) the tile about to be processed
@@ -108,6 +117,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
     bf16x8 qf[KSTEPS];
     load_q(qf, cur);
+    RowBlock<D>::to_fragments(qf, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);  // stage 1 is still free
 
     for (;;) {
         const bool has_next = work + 1 < work_end;
@@ -115,7 +125,6 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         if (has_next) nxt = fetch_fwd_work<HPB>(p, work + 1);
         const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
         const int tok = row % BMT;
-        const int head = cur.h0 + row / BMT;
         const bool row_valid = tok < cur.q_rows;
         const int vis = RowMask(cur.P, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
 
@@ -132,7 +141,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
 
 #pragma unroll
         for (int t = 0; t < KSTEPS; ++t) settle(qf[t]);
-        wait_async_loads();
+        wait_async_loads_except<kEpilogueStores>();  // the first tile has landed; the last work's output may still be leaving
         __syncthreads();
 
         // One key tile.  The last tile of a work is a separate instantiation: it alone prefetches for the
@@ -265,17 +274,20 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         // O leaves through the LDS stage that was just processed (the other one may already be receiving
         // the first tile of the next work); every wave must be done reading it first
         __syncthreads();
+        const int out_slice = (stage ^ 1) * 2 * TILE_BYTES + slice_in_stage;
+        store_block_rows<D>(smem + out_slice, o, 1.0f / lsum, lane, block_rows(p.out, cur),
+                            RowBlock<D>::lane_offset(lane, q_tok_bytes), block_soff);
         {
-            char* out_stage = smem + (stage ^ 1) * 2 * TILE_BYTES + wave * (32 * D * 2);
-            store_block_rows<D>(out_stage, o, 1.0f / lsum, lane, [&](int r) -> __bf16* {
-                const int rr = wave * 32 + r, t = rr % BMT;
-                if (t >= cur.q_rows) return nullptr;
-                return static_cast<__bf16*>(p.out) + ((size_t)(cur.q_row0 + t) * p.Hq + cur.h0 + rr / BMT) * D;
-            });
+            // LSE of the row this lane owns, from the lanes of the lower half; the others aim past the buffer
+            const __amdgpu_buffer_rsrc_t lse_rows =
+                RowBlock<D>::rows(p.lse + (size_t)cur.h0 * p.T + cur.q_row0, (unsigned)((HPB - 1) * p.T + cur.q_rows) * 4u);
+            const int off = (row_valid && hf == 0) ? ((row / BMT) * p.T + tok) * 4 : 0x7ffffff0;
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (m + __builtin_amdgcn_logf(lsum)) * kLn2), lse_rows,
+                                                  off, 0, 0);
         }
-        if (row_valid && hf == 0)
-            p.lse[(size_t)head * p.T + cur.q_row0 + tok] = (m + __builtin_amdgcn_logf(lsum)) * kLn2;
         if (!has_next) break;
+        // the next Q rows have arrived meanwhile; the same slice turns them into fragments
+        RowBlock<D>::to_fragments(qf, smem, out_slice, fa, lane);
         ++work;
         cur = nxt;
     }

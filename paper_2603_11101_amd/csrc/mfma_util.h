@@ -234,6 +234,13 @@ VA_DEV void buffer_load_lds_4(unsigned lds_dst, int voffset, i32x4 rsrc, int sof
 VA_DEV void settle(const bf16x8& f) { asm volatile("" ::"v"(f)); }
 
 VA_DEV void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Vector memory operations of a wave complete in issue order: waiting until at most YOUNGER are outstanding
+// waits for everything issued before the YOUNGER most recent ones (output rows on their way, say).
+template <int YOUNGER>
+VA_DEV void wait_async_loads_except() {
+    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(YOUNGER) : "memory");
+}
 
 // Copy plan of one swizzled ROWS x D bf16 tile shared by NWAVES waves.  One
 // wave instruction fills 1 KiB of the tile (64 / (D/8) rows); the lane that
@@ -247,22 +254,94 @@ struct AsyncTile {
     static constexpr int INSTR = ROWS / RPI;
     static constexpr int PER_WAVE = INSTR / NWAVES;
     static_assert(INSTR % NWAVES == 0, "tile must divide among the waves");
-    int voff[PER_WAVE];
-    int first;  // first instruction of this wave
+    // Instruction j of a wave fetches rows RPI * j further down than instruction 0.  Their swizzles differ
+    // from those of instruction 0 by the same constant for every lane and wave, so one per-lane offset
+    // serves all instructions: offset(j) = (voff0 ^ (swizzle(RPI j) << 4)) + RPI j rows.
+    static constexpr bool self_check() {
+        for (int w = 0; w < NWAVES; ++w)
+            for (int j = 0; j < PER_WAVE; ++j)
+                for (int x = 0; x < RPI; ++x)
+                    if ((swizzle<D>((w * PER_WAVE + j) * RPI + x) ^ swizzle<D>(w * PER_WAVE * RPI + x)) != swizzle<D>(j * RPI))
+                        return false;
+        return true;
+    }
+    static_assert(self_check(), "the swizzle does not separate into a lane part and an instruction part");
+    int voff0;
+    int first;     // first instruction of this wave
+    int row_step;  // bytes between the rows of consecutive instructions
 
     VA_DEV void init(int wave, int lane, int row_bytes) {
         first = __builtin_amdgcn_readfirstlane(wave * PER_WAVE);
+        row_step = __builtin_amdgcn_readfirstlane(RPI * row_bytes);
         const int pc = lane % CPR;
-#pragma unroll
-        for (int j = 0; j < PER_WAVE; ++j) {
-            const int r = (wave * PER_WAVE + j) * RPI + lane / CPR;
-            voff[j] = r * row_bytes + ((pc ^ swizzle<D>(r)) << 4);
-        }
+        const int r = wave * PER_WAVE * RPI + lane / CPR;
+        voff0 = r * row_bytes + ((pc ^ swizzle<D>(r)) << 4);
     }
-    // tile_lds: LDS address of the tile; soffset: byte offset of the tile's first row in the buffer
+    // tile_lds: LDS address of the tile; soffset: byte offset of the tile's first row in the buffer, which
+    // must lie inside the buffer: the range check compares the per-lane offset with the buffer size minus
+    // the scalar offset in unsigned arithmetic, so rows past the end are only caught through the per-lane part
     VA_DEV void issue(i32x4 rsrc, unsigned tile_lds, int soffset) const {
+        int v = voff0;
+        asm volatile("" : "+v"(v));  // derive the offsets here instead of keeping PER_WAVE of them in registers
 #pragma unroll
-        for (int j = 0; j < PER_WAVE; ++j) buffer_load_lds_16(tile_lds + (first + j) * 1024, voff[j], rsrc, soffset);
+        for (int j = 0; j < PER_WAVE; ++j)
+            buffer_load_lds_16(tile_lds + (first + j) * 1024, (v ^ (swizzle<D>(j * RPI) << 4)) + j * row_step, rsrc, soffset);
+    }
+};
+
+// ---------------------------------------------------------------- operand blocks that stay in registers
+//
+// A wave's 32 x D operand block (Q and dO of the forward and dQ kernels) lives in registers as
+// row-major fragments for a whole work.  Fetching the fragments directly makes every wave instruction
+// touch 32 rows with 32 bytes each, and the address path of the vector cache handles one row (cache
+// line) at a time.  So the block is fetched with whole rows per group of lanes (64 / (D/8) rows per
+// instruction) and turned into fragments through a wave-private, swizzled 32 x D LDS slice.
+template <int D>
+struct RowBlock {
+    static constexpr int CPR = D / 8;     // 16-byte chunks of a row
+    static constexpr int RPI = 64 / CPR;  // rows per wave instruction
+    static constexpr int N = 32 / RPI;    // instructions per block = fragments per lane (D / 16)
+
+    // Per-lane byte offset of the lane's piece in instruction 0: row lane / CPR, chunk lane % CPR.  Meant to
+    // be called where it is used: the lane number is made opaque so that the offset is derived on the spot
+    // instead of occupying a register for the whole kernel.
+    VA_DEV static int lane_offset(int lane, int row_bytes) {
+        asm volatile("" : "+v"(lane));
+        return (lane / CPR) * row_bytes + (lane % CPR) * 16;
+    }
+
+    // The rows of a block in global memory, seen through a raw buffer of `bytes` bytes at `base`: whatever
+    // lies past the end reads as zero and is not written, so ragged blocks need no branch, and an address
+    // is one per-lane constant (lane_offset) plus a wave-uniform offset per instruction.
+    VA_DEV static __amdgpu_buffer_rsrc_t rows(const void* base, unsigned bytes) {
+        // base and bytes are wave-uniform but come out of loaded work records: say so, or every access is
+        // wrapped in a loop over the distinct values of the lanes
+        const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+        const unsigned long long ua = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(a >> 32)) << 32) |
+                                      (unsigned)__builtin_amdgcn_readfirstlane((int)(a & 0xffffffffu));
+        return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(ua), 0,
+                                                 __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000);
+    }
+
+    // soff(j) = byte offset of row j * RPI of the block (wave-uniform; added to the per-lane offset, not
+    // passed as the scalar offset of the access: the range check only catches what the per-lane part
+    // carries past the end).  After the call regs[j] holds chunk lane % CPR of row j * RPI + lane / CPR.
+    // Exactly N load instructions.
+    template <typename RowOffset>
+    VA_DEV static void load(bf16x8 (&regs)[N], __amdgpu_buffer_rsrc_t rsrc, int lane_off, RowOffset soff) {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            regs[j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + soff(j), 0, 0));
+    }
+    // regs as left by load() -> regs[t] = fragment t of row lane % 32 (k-slots d = 16 t + 8 (lane / 32) + 0..7).
+    // `slice` is the byte offset of 32 * D * 2 bytes of LDS that no other wave touches meanwhile.
+    VA_DEV static void to_fragments(bf16x8 (&regs)[N], char* lds, int slice, const FragAddr<D>& fa, int lane) {
+        const int c = lane % CPR;
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            *reinterpret_cast<bf16x8*>(lds + slice + tile_off<D>(j * RPI + lane / CPR, c)) = regs[j];
+#pragma unroll
+        for (int t = 0; t < N; ++t) regs[t] = fa.rowmajor(lds, slice, 0, t);
     }
 };
 
@@ -277,33 +356,75 @@ struct AsyncTile {
 template <int D>
 __host__ __device__ constexpr int out_stage_perm(int row) { return D == 64 ? ((row >> 1) & 15) : (row & 31); }
 
-// row_ptr(r): global address of row r (0..31) of the block, or nullptr if the row must not be written.
-template <int D, typename RowPtr>
-VA_DEV void store_block_rows(char* stage, const f32x16 (&acc)[D / 32], float factor, int lane, RowPtr row_ptr) {
-    constexpr int RB = D * 2, CPR = D / 8;
-    const int row = lane & 31, hf = lane >> 5;
-    const int perm = out_stage_perm<D>(row);
+// Per-lane LDS offsets of the staging pattern, in the closed form used by store_block_rows: the offset
+// of a piece is one lane constant XOR a compile-time constant (plus a compile-time row step), so nothing
+// but the two lane constants has to live in registers.
+template <int D>
+struct OutStage {
+    static constexpr int RB = D * 2, CPR = D / 8, RPI = 64 / CPR, N = 32 / RPI;
+    // write side: lane (row = lane % 32, hf = lane / 32) writes 8-byte unit 8 dt + 2 q + hf of its row
+    static __host__ __device__ constexpr int wbase(int lane) {
+        const int row = lane & 31, hf = lane >> 5;
+        return row * RB + ((hf ^ out_stage_perm<D>(row)) << 3);
+    }
+    static __host__ __device__ constexpr int woff(int lane, int dt, int q) { return wbase(lane) ^ ((8 * dt + 2 * q) << 3); }
+    // read side: instruction `it`, lane (x = lane / CPR, c = lane % CPR) reads 16-byte chunk c of row it * RPI + x
+    static __host__ __device__ constexpr int rbase(int lane) {
+        const int x = lane / CPR, c = lane % CPR;
+        return x * RB + ((c ^ (out_stage_perm<D>(x) >> 1)) << 4);
+    }
+    static __host__ __device__ constexpr int roff(int lane, int it) {
+        return (rbase(lane) ^ ((out_stage_perm<D>(it * RPI) >> 1) << 4)) + it * RPI * RB;
+    }
+    static __host__ __device__ constexpr bool rswap(int lane) { return out_stage_perm<D>(lane / CPR) & 1; }
+    // the closed forms against the plain definition, every lane and piece
+    static constexpr bool self_check() {
+        for (int lane = 0; lane < 64; ++lane) {
+            const int row = lane & 31, hf = lane >> 5;
+            for (int dt = 0; dt < D / 32; ++dt)
+                for (int q = 0; q < 4; ++q)
+                    if (woff(lane, dt, q) != row * RB + (((8 * dt + 2 * q + hf) ^ out_stage_perm<D>(row)) << 3)) return false;
+            for (int it = 0; it < N; ++it) {
+                const int r = it * RPI + lane / CPR, c = lane % CPR, pr = out_stage_perm<D>(r);
+                if (roff(lane, it) != r * RB + ((c ^ (pr >> 1)) << 4)) return false;
+                if (rswap(lane) != bool(pr & 1)) return false;
+            }
+        }
+        return true;
+    }
+    static_assert(self_check(), "staging offsets disagree with the staging layout");
+};
+
+// The rows go out through a raw buffer as in RowBlock (rsrc, lane_off, soff(j) = byte offset of row
+// j * RPI): rows past the end of the buffer are dropped by the hardware.  Exactly RowBlock<D>::N store
+// instructions, whatever the number of valid rows, so that a later wait can count them.
+template <int D, typename RowOffset>
+VA_DEV void store_block_rows(char* stage, const f32x16 (&acc)[D / 32], float factor, int lane,
+                             __amdgpu_buffer_rsrc_t rsrc, int lane_off, RowOffset soff) {
+    using S = OutStage<D>;
+    // This code runs with few registers free.  The lane constants are made opaque here so that they are
+    // derived from the lane number on the spot instead of being kept (or spilled) across the kernel.
+    int l = lane;
+    asm volatile("" : "+v"(l));
+    const int wb = S::wbase(l);
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             f32x4 f = {acc[dt][4 * q] * factor, acc[dt][4 * q + 1] * factor, acc[dt][4 * q + 2] * factor,
                        acc[dt][4 * q + 3] * factor};
-            const int unit = 8 * dt + 2 * q + hf;  // 8-byte unit of the row
-            *reinterpret_cast<bf16x4*>(stage + row * RB + ((unit ^ perm) << 3)) = __builtin_convertvector(f, bf16x4);
-            if (q == 3) __builtin_amdgcn_sched_barrier(0);  // bounded live ranges: this code runs with few registers free
+            *reinterpret_cast<bf16x4*>(stage + (wb ^ ((8 * dt + 2 * q) << 3))) = __builtin_convertvector(f, bf16x4);
+            if (q == 3) __builtin_amdgcn_sched_barrier(0);  // bounded live ranges
         }
     // the wave reads back only what it wrote itself
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    // a real loop on purpose: this code runs with few registers free
-#pragma unroll 1
-    for (int it = 0; it < 32 * CPR / 64; ++it) {
-        const int r = it * (64 / CPR) + lane / CPR, c = lane % CPR;
-        const int pr = out_stage_perm<D>(r);
-        u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * RB + ((c ^ (pr >> 1)) << 4));
-        if (pr & 1) v = u32x4{v[2], v[3], v[0], v[1]};
-        __bf16* dst = row_ptr(r);
-        if (dst) *reinterpret_cast<u32x4*>(dst + c * 8) = v;
+    const int rb = S::rbase(l);
+    const bool swap = S::rswap(l);
+#pragma unroll
+    for (int it = 0; it < S::N; ++it) {
+        u32x4 v = *reinterpret_cast<const u32x4*>(
+            stage + ((rb ^ ((out_stage_perm<D>(it * S::RPI) >> 1) << 4)) + it * S::RPI * S::RB));
+        if (swap) v = u32x4{v[2], v[3], v[0], v[1]};
+        __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, lane_off + soff(it), 0, 0);
     }
 }
 
