@@ -19,6 +19,7 @@
 
 #include "kernels.h"
 #include "mfma_util.h"
+#include "work_fetch.h"
 
 namespace va {
 
@@ -187,7 +188,6 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         const int L = cur.L;
         // this wave's 32 key rows; the lane owns key row jw + l32 (local index in the sample)
         const int jw = cur.kv_row0 - cur.seq_row0 + 32 * wave;
-        const int kv_local = jw + l32;
 
         f32x16 dk[DO_DK ? DT : 1], dv[DO_DV ? DT : 1];
 #pragma unroll
@@ -290,11 +290,24 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int r = 4 * r4 + e;
-                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
-                        if (need_mask && kv_local >= mask.vis_in_sample(q0 + rb + e)) pv = 0.0f;
+                        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
                         s[r] = pv;
                         if (DO_DK) dp[r] = pv * (dp[r] - d4[e]);
                     }
+                }
+                if (need_mask) {
+                    // A branch of its own: folded into the loop above, the visibility arithmetic and the
+                    // selects would run in every block, masked or not.  Passing the key row through an
+                    // opaque statement ties everything below to this side of the branch.
+                    int key = jw + l32;  // key row of this lane, local to the sample
+                    asm volatile("" : "+v"(key));
+                    const int row_base = q0 + 32 * qb + 4 * hf;  // query row of register 0, local to the sample
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (key >= mask.vis_in_sample(row_base + 8 * (r / 4) + r % 4)) {
+                            s[r] = 0.0f;
+                            if (DO_DK) dp[r] = 0.0f;
+                        }
                 }
                 bf16x8 pb[2], dsb[2];
 #pragma unroll
@@ -365,30 +378,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 
 // ------------------------------------------------------------------ dQ
 
-// What one workgroup needs to know about a dQ work (all wave-uniform).
-struct DqWork {
-    int q_row0, q_rows, seq_row0, n_full, n_tiles, P, L, g, h0;
-};
-
-template <int HPB>
-VA_DEV DqWork fetch_dq_work(const AttnParams& p, int work_index) {
-    const int id = p.work_ids[work_index];
-    const WorkItem it = p.items[id / p.works_per_item];
-    const int hc = id % p.works_per_item;
-    const int G = p.Hq / p.Hkv;
-    const int chunks_per_group = G / HPB;
-    DqWork w;
-    w.q_row0 = it.w[0];
-    w.q_rows = it.w[1];
-    w.seq_row0 = it.w[2];
-    w.n_full = it.w[4];
-    w.n_tiles = it.w[5];
-    w.P = it.w[6];
-    w.L = it.w[7];
-    w.g = hc / chunks_per_group;
-    w.h0 = w.g * G + (hc % chunks_per_group) * HPB;
-    return w;
-}
+using DqWork = RowWork;
 
 // Persistent, like the forward: workgroup b runs the works the host assigned to it; the first K/V tile and
 // the Q / dO fragments of the next work are fetched while the last key tile of the current one is processed.
@@ -404,9 +394,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    int work = p.wg_table[2 * blockIdx.x];
-    const int work_end = work + p.wg_table[2 * blockIdx.x + 1];
-    if (work >= work_end) return;
+    const int first_work = p.wg_table[2 * blockIdx.x], num_works = p.wg_table[2 * blockIdx.x + 1];
+    if (num_works <= 0) return;
+    RowWorkStream<HPB> works{p, lane};
 
     const int kv_row_bytes = p.Hkv * D * 2;
     const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
@@ -443,29 +433,37 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         const int lane_off = RowBlock<D>::lane_offset(lane, q_tok_bytes);
         RowBlock<D>::load(qf, block_rows(p.q, w), lane_off, block_soff);
         RowBlock<D>::load(dof, block_rows(p.dout, w), lane_off, block_soff);
-        const int tok = row % BMT;
-        const int head = w.h0 + row / BMT;
-        lse2 = INFINITY;  // rows past the item: p = exp2(-inf) = 0
-        delta = 0.0f;
-        if (tok < w.q_rows) {
-            lse2 = p.lse2[(size_t)head * p.T + w.q_row0 + tok];
-            delta = p.delta[(size_t)head * p.T + w.q_row0 + tok];
-        }
+        // LSE and delta of the row this lane owns, through raw buffers as well; the offset is derived from
+        // the lane number on the spot (see RowBlock::lane_offset)
+        int l = lane;
+        asm volatile("" : "+v"(l));
+        const int rr = wave * 32 + (l & 31), tok = rr % BMT;
+        const size_t first = (size_t)w.h0 * p.T + w.q_row0;
+        const unsigned bytes = (unsigned)((HPB - 1) * p.T + w.q_rows) * 4u;
+        // Rows past the item aim beyond the buffer and read LSE = delta = 0 like their Q and dO rows:
+        // s = 0, p = 1, dP = 0, dS = 0, so they stay finite and contribute nothing (and are never stored).
+        const int off = tok < w.q_rows ? ((rr / BMT) * p.T + tok) * 4 : 0x7ffffff0;
+        lse2 = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(RowBlock<D>::rows(p.lse2 + first, bytes), off, 0, 0));
+        delta = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(RowBlock<D>::rows(p.delta + first, bytes), off, 0, 0));
     };
     const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
 
-    DqWork cur = fetch_dq_work<HPB>(p, work);
+    DqWork cur = works.start(first_work, first_work + num_works);
     int stage = 0;
     loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
     loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
     load_rows(cur);
     RowBlock<D>::to_fragments(qf, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);  // stage 1 is still free
     RowBlock<D>::to_fragments(dof, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);
+    // Every ordinary load is consumed before the loop head, here and at the end of a work, so that the
+    // compiler has no wait of its own to place at the top of a work, where output rows are still leaving.
+    asm volatile("" ::"v"(lse2), "v"(delta));
 
     for (;;) {
-        const bool has_next = work + 1 < work_end;
-        DqWork nxt = cur;
-        if (has_next) nxt = fetch_dq_work<HPB>(p, work + 1);
+        const bool has_next = works.has_next();
+        const DqWork nxt = works.peek_next();
         const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
         const int tok = row % BMT;
         const int vis = RowMask(cur.P, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
@@ -481,15 +479,15 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
             settle(qf[t]);
             settle(dof[t]);
         }
-        asm volatile("" ::"v"(lse2), "v"(delta));
         const float my_lse2 = lse2, my_delta = delta;
         wait_async_loads_except<kEpilogueStores>();  // the first tile has landed; the last work's dQ may still be leaving
         __syncthreads();
 
         // One key tile; the last tile of a work is a separate instantiation that alone prefetches for the
         // next work, so the loop over the other tiles holds no ordinary global load.
-        auto tile = [&](const int kt, auto last_tag) {
+        auto tile = [&](const int kt, auto last_tag, auto masked_tag) {
             constexpr bool last = decltype(last_tag)::value;
+            constexpr bool need_mask = decltype(masked_tag)::value;
             const int j0 = kt * BN;
             const int k_tile = stage * 2 * TILE_BYTES;
             const int v_tile = k_tile + TILE_BYTES;
@@ -506,7 +504,6 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
             // One 32-key block at a time: S^T and dP^T (rows = key rows in registers, columns = query rows in
             // lanes), the elementwise part, then dQ^T += K^T dS^T for these 32 keys.  MFMAs alternate between
             // independent accumulators so that none waits on the one just issued.
-            const bool need_mask = kt >= cur.n_full;
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 f32x16 s, dp;
@@ -579,8 +576,16 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
                 __syncthreads();
             }
         };
-        for (int kt = 0; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{});
-        tile(cur.n_tiles - 1, std::true_type{});
+        // Tiles every row of the block sees completely come first and carry no mask code at all (as a
+        // run-time condition inside one tile body the mask turns into selects that every tile pays for).
+        // The last tile is always treated as masked: it is the ragged one.
+        {
+            const int n_plain = min(cur.n_full, cur.n_tiles - 1);
+            int kt = 0;
+            for (; kt < n_plain; ++kt) tile(kt, std::false_type{}, std::false_type{});
+            for (; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{}, std::true_type{});
+            tile(cur.n_tiles - 1, std::true_type{}, std::true_type{});
+        }
 
         // dQ leaves through the LDS stage that was just processed; every wave must be done reading it first
         __syncthreads();
@@ -591,7 +596,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         // the next Q and dO rows have arrived meanwhile; the same slice turns them into fragments
         RowBlock<D>::to_fragments(qf, smem, out_slice, fa, lane);
         RowBlock<D>::to_fragments(dof, smem, out_slice, fa, lane);
-        ++work;
+        asm volatile("" ::"v"(lse2), "v"(delta));
+        works.advance();
         cur = nxt;
     }
 }

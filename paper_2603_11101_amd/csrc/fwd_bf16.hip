@@ -22,6 +22,7 @@
 
 #include "kernels.h"
 #include "mfma_util.h"
+#include "work_fetch.h"
 
 namespace va {
 
@@ -32,30 +33,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kPrefetch = 4;       // LDS fragment reads in flight ahead of the MFMA that uses them
 constexpr float kMaxLag = 8.0f;  // the softmax reference may trail a row's true maximum by this many powers of two
 
-// What one workgroup needs to know about a work (all wave-uniform).
-struct FwdWork {
-    int q_row0, q_rows, seq_row0, n_full, n_tiles, P, L, g, h0;
-};
-
-template <int HPB>
-VA_DEV FwdWork fetch_fwd_work(const AttnParams& p, int work_index) {
-    const int id = p.work_ids[work_index];
-    const WorkItem it = p.items[id / p.works_per_item];
-    const int hc = id % p.works_per_item;
-    const int G = p.Hq / p.Hkv;
-    const int chunks_per_group = G / HPB;
-    FwdWork w;
-    w.q_row0 = it.w[0];
-    w.q_rows = it.w[1];
-    w.seq_row0 = it.w[2];
-    w.n_full = it.w[4];
-    w.n_tiles = it.w[5];
-    w.P = it.w[6];
-    w.L = it.w[7];
-    w.g = hc / chunks_per_group;
-    w.h0 = w.g * G + (hc % chunks_per_group) * HPB;
-    return w;
-}
+using FwdWork = RowWork;
 
 // Persistent kernel: workgroup b runs the works the host assigned to it, one after the other.  While the
 // last key tile of a work is being processed, the first K/V tile of the next work is already on its way
@@ -72,9 +50,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    int work = p.wg_table[2 * blockIdx.x];
-    const int work_end = work + p.wg_table[2 * blockIdx.x + 1];
-    if (work >= work_end) return;
+    const int first_work = p.wg_table[2 * blockIdx.x], num_works = p.wg_table[2 * blockIdx.x + 1];
+    if (num_works <= 0) return;
+    RowWorkStream<HPB> works{p, lane};
 
     const int kv_row_bytes = p.Hkv * D * 2;
     const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
@@ -111,7 +89,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     constexpr int kEpilogueStores = RowBlock<D>::N + 1;
     const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
 
-    FwdWork cur = fetch_fwd_work<HPB>(p, work);
+    FwdWork cur = works.start(first_work, first_work + num_works);
     int stage = 0;  // LDS stage that holds (or will hold) the tile about to be processed
     loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
     loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
@@ -120,9 +98,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     RowBlock<D>::to_fragments(qf, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);  // stage 1 is still free
 
     for (;;) {
-        const bool has_next = work + 1 < work_end;
-        FwdWork nxt = cur;
-        if (has_next) nxt = fetch_fwd_work<HPB>(p, work + 1);
+        const bool has_next = works.has_next();
+        const FwdWork nxt = works.peek_next();
         const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
         const int tok = row % BMT;
         const bool row_valid = tok < cur.q_rows;
@@ -147,8 +124,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         // One key tile.  The last tile of a work is a separate instantiation: it alone prefetches for the
         // next work, so the loop over the other tiles contains no ordinary global load and the compiler
         // has no reason to wait for memory inside it.
-        auto tile = [&](const int kt, auto last_tag) {
+        auto tile = [&](const int kt, auto last_tag, auto masked_tag) {
             constexpr bool last = decltype(last_tag)::value;
+            constexpr bool masked = decltype(masked_tag)::value;
             const int j0 = kt * BN;
             const int k_tile = stage * 2 * TILE_BYTES;  // byte offsets of this stage's tiles
             const int v_tile = k_tile + TILE_BYTES;
@@ -197,7 +175,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
                 if (has_next) load_q(qf, nxt);
             }
 
-            if (kt >= cur.n_full) {
+            if constexpr (masked) {
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -216,6 +194,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
             mx = pair_max(mx) * c;
             if (__builtin_amdgcn_ballot_w64(mx > m + kMaxLag) != 0) {  // wave-uniform: some row needs a new reference
+                asm volatile("");  // keep this a branch: folded into a select, its multiplications would run on every tile
                 const float m_new = fmaxf(m, mx);
                 const float alpha = __builtin_amdgcn_exp2f(m - m_new);  // m = -inf on the first tile: alpha = 0, O = 0
                 m = m_new;
@@ -267,8 +246,16 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
                 __syncthreads();
             }
         };
-        for (int kt = 0; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{});
-        tile(cur.n_tiles - 1, std::true_type{});
+        // Tiles every row of the block sees completely come first and carry no mask code at all (as a
+        // run-time condition inside one tile body the mask turns into selects that every tile pays for).
+        // The last tile is always treated as masked: it is the ragged one.
+        {
+            const int n_plain = min(cur.n_full, cur.n_tiles - 1);
+            int kt = 0;
+            for (; kt < n_plain; ++kt) tile(kt, std::false_type{}, std::false_type{});
+            for (; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{}, std::true_type{});
+            tile(cur.n_tiles - 1, std::true_type{}, std::true_type{});
+        }
 
         lsum = pair_sum(lsum);
         // O leaves through the LDS stage that was just processed (the other one may already be receiving
@@ -288,7 +275,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         if (!has_next) break;
         // the next Q rows have arrived meanwhile; the same slice turns them into fragments
         RowBlock<D>::to_fragments(qf, smem, out_slice, fa, lane);
-        ++work;
+        works.advance();
         cur = nxt;
     }
 }

@@ -103,11 +103,11 @@ typedef __attribute__((address_space(3))) char lds_char;
 // 16-bit word (i % 4) of the 8 bytes addressed by lane 4 e + i / 4 of the group (measured).  Lane s of
 // a group therefore points at row s / 4, columns 4 (s % 4) .. + 3 of a 4 x 16 block, and lane i gets
 // column i of the block, rows 0..3.  Two reads (rows + 0 and + 8) make one fragment:
-//   offset(j, x, dt) = (tr[j] ^ (dt << 6)) + x * 16 rows.
+//   offset(j, x, dt) = (tr ^ (j << 5) ^ (dt << 6)) + (8 j + 16 x) rows.
 template <int D>
 struct FragAddr {
     int rm;
-    int tr[2];
+    int tr;
 
     static __host__ __device__ constexpr int rm_base(int lane) {
         const int l32 = lane & 31, hf = lane >> 5, sw = swizzle<D>(l32);
@@ -124,8 +124,10 @@ struct FragAddr {
     static __host__ __device__ constexpr int rm_off(int lane, int b, int t) {
         return (rm_base(lane) ^ (t << 5)) + b * 32 * (D * 2);
     }
+    // The second read (rows + 8) needs no base of its own: eight rows further down the swizzle differs
+    // in one chunk bit, so its offset is that of the first read XOR 32, plus eight rows.
     static __host__ __device__ constexpr int tr_off(int lane, int j, int x, int dt) {
-        return (tr_base(lane, j) ^ (dt << 6)) + x * 16 * (D * 2);
+        return ((tr_base(lane, 0) ^ (j << 5)) ^ (dt << 6)) + j * 8 * (D * 2) + x * 16 * (D * 2);
     }
     // the closed forms against the plain definition, every lane and step
     static constexpr bool self_check() {
@@ -146,7 +148,7 @@ struct FragAddr {
     }
     static_assert(self_check(), "fragment address closed forms disagree with the tile layout");
 
-    VA_DEV explicit FragAddr(int lane) : rm(rm_base(lane)), tr{tr_base(lane, 0), tr_base(lane, 1)} {}
+    VA_DEV explicit FragAddr(int lane) : rm(rm_base(lane)), tr(tr_base(lane, 0)) {}
 
     // `lds` is the base of dynamic shared memory, `tile` the byte offset of the tile inside it
     VA_DEV bf16x8 rowmajor(const char* lds, int tile, int b, int t) const {
@@ -156,9 +158,9 @@ struct FragAddr {
         typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
         typedef short s16x8 __attribute__((ext_vector_type(8)));
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4)(lds_char*)(lds + (((tr[0] + tile) ^ (dt << 6)) + x * 16 * (D * 2))));
+            (lds_s16x4)(lds_char*)(lds + (((tr + tile) ^ (dt << 6)) + x * 16 * (D * 2))));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4)(lds_char*)(lds + (((tr[1] + tile) ^ (dt << 6)) + x * 16 * (D * 2))));
+            (lds_s16x4)(lds_char*)(lds + (((tr + tile) ^ ((dt << 6) ^ 32)) + 8 * (D * 2) + x * 16 * (D * 2))));
         return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
 };
