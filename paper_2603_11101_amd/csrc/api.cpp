@@ -1,5 +1,6 @@
 // C-ABI device entry points: argument validation on the host, then kernel
-// launches on the caller's stream.  No allocation, no synchronisation.
+// launches on the caller's stream.  No allocation, no synchronisation (the
+// profiling entry point aside).
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -36,7 +37,12 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
     }
     if (cu[s->num_seqs] != s->total_tokens)
         return fail(VA_EINVAL, "%s: cu_seqlens ends at %d, total_tokens is %d", who, cu[s->num_seqs], s->total_tokens);
-    // element offsets are computed in size_t on the device; the row index itself is int32
+    // Element offsets are computed in size_t on the device, but the kernels address the rows of one sample
+    // (and the LSE rows of one block of heads) through buffers with 32-bit byte offsets.
+    if ((int64_t)s->max_seqlen * s->num_q_heads * s->head_dim * 2 >= (int64_t)1 << 31)
+        return fail(VA_ESIZE, "%s: max_seqlen * num_q_heads * head_dim * 2 must stay below 2^31 bytes", who);
+    if ((int64_t)s->total_tokens * 8 * 4 >= (int64_t)1 << 31)
+        return fail(VA_ESIZE, "%s: total_tokens must stay below 2^26", who);
     return VA_OK;
 }
 

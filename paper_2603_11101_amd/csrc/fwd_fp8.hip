@@ -18,8 +18,11 @@
 // 32 hf + 16 b + r: the 32 probabilities of a lane are 32 consecutive keys,
 // in register order, which is exactly the byte order the second product wants
 // when its V^T operand comes from four 8-row transposing byte reads.
+#include <type_traits>
+
 #include "kernels.h"
 #include "mfma_util.h"
+#include "work_fetch.h"
 
 namespace va {
 
@@ -27,11 +30,13 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kPShift = 8.0f;  // probabilities are stored as p * 2^8 in E4M3 (largest value 256 <= 448)
+constexpr float kPShift = 8.0f;  // probabilities are stored as p * 2^8 in E4M3
+// The softmax reference may trail a row's true maximum by this many powers of two before O is rescaled:
+// the stored probabilities then reach 2^(8 + 0.75) = 431, still below the largest E4M3 value 448.
+constexpr float kMaxLag = 0.75f;
 
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 VA_DEV f32x16 mfma_f8(i32x8 a, i32x8 b, f32x16 c) {
     // formats 0 = E4M3 for both operands; block scales 127 = 2^0
@@ -42,195 +47,338 @@ VA_DEV f32x16 mfma_f8(i32x8 a, i32x8 b, f32x16 c) {
 // c ^ swz(r).  Conflict free for (1) 16 lanes reading one chunk of the rows
 // {x, 32 + x : x in 0..7} (+ 16 b), and (2) 32 lanes reading 8 consecutive rows
 // by 32 bytes with the transposing byte read.
-VA_DEV int swz8(int r) { return (((r >> 1) & 3) << 1) | ((r >> 5) & 1); }
-VA_DEV int off8(int r, int c) { return r * 128 + ((c ^ swz8(r)) << 4); }
+__host__ __device__ constexpr int swz8(int r) { return (((r >> 1) & 3) << 1) | ((r >> 5) & 1); }
+__host__ __device__ constexpr int off8(int r, int c) { return r * 128 + ((c ^ swz8(r)) << 4); }
 
+constexpr int kTileBytes = kFwdKvTile * 128;  // 64 rows of 128 bytes
+
+// Asynchronous copy of one 64 x 128-byte tile by 4 waves (see AsyncTile in mfma_util.h): two wave
+// instructions per wave, 8 rows each; rows 8 apart share their swizzle, so one per-lane offset serves both.
+struct AsyncTile8 {
+    static constexpr bool self_check() {
+        for (int r = 0; r < 56; ++r)
+            if (swz8(r) != swz8(r + 8) && ((r >> 3) & 1) == 0) return false;
+        return true;
+    }
+    int voff0, first, row_step;
+    VA_DEV void init(int wave, int lane, int row_bytes) {
+        first = __builtin_amdgcn_readfirstlane(wave * 2);
+        row_step = __builtin_amdgcn_readfirstlane(8 * row_bytes);
+        const int r = wave * 16 + lane / 8, pc = lane % 8;
+        voff0 = r * row_bytes + ((pc ^ swz8(r)) << 4);
+    }
+    VA_DEV void issue(i32x4 rsrc, unsigned tile_lds, int soffset) const {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) buffer_load_lds_16(tile_lds + (first + j) * 1024, voff0 + j * row_step, rsrc, soffset);
+    }
+};
+
+static_assert(AsyncTile8::self_check(), "rows 8 apart must share their swizzle");
+
+// Per-lane LDS offsets of the two fragment patterns in closed form: one lane constant XOR a
+// compile-time constant, plus a compile-time row step.
+//
+// K fragment (first operand of S^T): A-lane l32 of block b reads tile row a_row + 16 b with
+// a_row = 32 (bit 2 of l32) + 4 (l32 / 8) + l32 % 4, contraction slots d = 64 t + 32 hf + 0..31, i.e. the
+// chunks 4 t + 2 hf and 4 t + 2 hf + 1.
+// V^T fragment (first operand of O^T): column d = 32 dt + l32, keys 32 hf + 0..31 through four
+// transposing byte reads.  In a group of 16 lanes, lane i receives byte (i % 8) of the 8 bytes addressed
+// by lane 2 e + i / 8 as element e (measured); lane s of the group therefore points at row s / 2,
+// columns 8 (s % 2) .. + 7 of an 8 x 16 block.
+struct FragAddr8 {
+    static __host__ __device__ constexpr int a_row(int lane) {
+        const int l32 = lane & 31;
+        return 32 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
+    }
+    static __host__ __device__ constexpr int k_base(int lane) {
+        const int r = a_row(lane), hf = lane >> 5;
+        return r * 128 + (((2 * hf) ^ swz8(r)) << 4);
+    }
+    static __host__ __device__ constexpr int k_off(int lane, int b, int t, int e) {
+        return (k_base(lane) ^ ((4 * t + e) << 4)) + b * 16 * 128;
+    }
+    static __host__ __device__ constexpr int v_base(int lane) {
+        const int hf = lane >> 5, s16 = lane & 15;
+        const int r = 32 * hf + (s16 >> 1);
+        const int chunk = (lane >> 4) & 1;  // chunk of the lane's 8 columns inside a 32-column block
+        return r * 128 + ((chunk ^ swz8(r)) << 4) + 8 * (s16 & 1);
+    }
+    static __host__ __device__ constexpr int v_off(int lane, int x, int dt) {
+        return (v_base(lane) ^ ((2 * dt) << 4)) + x * 8 * 128;
+    }
+    static constexpr bool self_check() {
+        for (int lane = 0; lane < 64; ++lane) {
+            const int hf = lane >> 5, s16 = lane & 15;
+            for (int b = 0; b < 2; ++b)
+                for (int t = 0; t < 2; ++t)
+                    for (int e = 0; e < 2; ++e)
+                        if (k_off(lane, b, t, e) != off8(a_row(lane) + 16 * b, 4 * t + 2 * hf + e)) return false;
+            for (int x = 0; x < 4; ++x)
+                for (int dt = 0; dt < 4; ++dt) {
+                    const int col = 32 * dt + 16 * ((lane >> 4) & 1) + 8 * (s16 & 1);
+                    const int vr = 32 * hf + 8 * x + (s16 >> 1);
+                    if (v_off(lane, x, dt) != off8(vr, col >> 4) + (col & 8)) return false;
+                }
+        }
+        return true;
+    }
+    int kb, vb;
+    VA_DEV explicit FragAddr8(int lane) : kb(k_base(lane)), vb(v_base(lane)) {}
+    VA_DEV i32x8 k_frag(const char* lds, int tile, int b, int t) const {
+        const int at = ((kb + tile) ^ ((4 * t) << 4)) + b * 16 * 128;
+        const i32x4 lo = *reinterpret_cast<const i32x4*>(lds + at);
+        const i32x4 hi = *reinterpret_cast<const i32x4*>(lds + (at ^ 16));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+    VA_DEV i32x8 v_frag(const char* lds, int tile, int dt) const {
+        typedef __attribute__((address_space(3))) i32x2* lds_i32x2;
+        const int at = (vb + tile) ^ ((2 * dt) << 4);
+        i32x8 vf;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const i32x2 two = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2)(lds_char*)(lds + at + x * 8 * 128));
+            vf[2 * x] = two[0];
+            vf[2 * x + 1] = two[1];
+        }
+        return vf;
+    }
+};
+
+static_assert(FragAddr8::self_check(), "fragment address closed forms disagree with the tile layout");
+
+// Persistent like the bf16 forward: workgroup b runs the works the host assigned to it; the first K/V tile
+// and the Q fragments of the next work are fetched while the last key tile of the current one is processed.
 template <int HPB>
-__global__ __launch_bounds__(256) void fwd_fp8_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     constexpr int D = 128;
     constexpr int BMT = kFwdBlockRows / HPB;
     constexpr int BN = kFwdKvTile;
     constexpr int KSTEPS = D / 64;
     constexpr int DT = D / 32;
-    __shared__ __attribute__((aligned(16))) char k_tile[BN * D];
-    __shared__ __attribute__((aligned(16))) char v_tile[BN * D];
+    // two stages of (K tile, V tile), then one 32 x D bf16 slice per wave for the output rows
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int kStaging = 2 * 2 * kTileBytes;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int G = p.Hq / p.Hkv;
-    const int chunks_per_group = G / HPB;
-    const int nhc = p.Hkv * chunks_per_group;
-    const int hc = blockIdx.x % nhc;
-    const WorkItem it = p.items[blockIdx.x / nhc];
-    const int q_row0 = it.w[0], q_rows = it.w[1], seq_row0 = it.w[2];
-    const int n_full = it.w[4], n_tiles = it.w[5], P = it.w[6], L = it.w[7];
-    const int g = hc / chunks_per_group;
-    const int h0 = g * G + (hc % chunks_per_group) * HPB;
+    const int first_work = p.wg_table[2 * blockIdx.x], num_works = p.wg_table[2 * blockIdx.x + 1];
+    if (num_works <= 0) return;
+    RowWorkStream<HPB> works{p, lane};
 
+    const int kv_row_bytes = p.Hkv * D;
+    const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
+    const unsigned smem_lds = lds_addr(smem);
+    AsyncTile8 loader;
+    loader.init(wave, lane, kv_row_bytes);
+    const FragAddr8 fa(lane);
+
+    auto kv_rsrc = [&](const void* base, const RowWork& w) {
+        return make_rsrc(static_cast<const char*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D,
+                         (unsigned)(w.L - 1) * kv_row_bytes + D);
+    };
+    // the stacked row this lane owns
     const int row = wave * 32 + l32;
-    const int head = h0 + row / BMT;
-    const int tok = row % BMT;
-    const bool row_valid = tok < q_rows;
-    const int vis = RowMask(P, L, p.mask_mode).vis(q_row0 - seq_row0 + tok);
-
-    // Q fragments: contraction slots d = 64 t + 32 hf + 0..31
+    const int tok = row % BMT, head_in_block = row / BMT;
+    const int q_tok_bytes = p.Hq * D;
+    // Q fragments of that row, contraction slots d = 64 t + 32 hf + 0..31, through a raw buffer that ends
+    // with the last valid token of the block: rows past it read as zero.  The score factor
+    // scale * q_descale[h] * k_descale[g] * log2(e) of the row comes with them.
     i32x8 qf[KSTEPS];
-    {
-        const char* qrow = static_cast<const char*>(p.q) + ((size_t)(q_row0 + tok) * p.Hq + head) * D;
+    float c_row;
+    auto load_q = [&](const RowWork& w) {
+        const __amdgpu_buffer_rsrc_t rows = RowBlock<D>::rows(
+            static_cast<const char*>(p.q) + ((size_t)w.q_row0 * p.Hq + w.h0) * D,
+            (unsigned)(w.q_rows - 1) * q_tok_bytes + HPB * D);
+        const int off = tok * q_tok_bytes + head_in_block * D + 32 * hf;
 #pragma unroll
         for (int t = 0; t < KSTEPS; ++t) {
-            i32x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
-            if (row_valid) {
-                lo = *reinterpret_cast<const i32x4*>(qrow + 64 * t + 32 * hf);
-                hi = *reinterpret_cast<const i32x4*>(qrow + 64 * t + 32 * hf + 16);
-            }
-            qf[t] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            const u32x4 lo = __builtin_amdgcn_raw_buffer_load_b128(rows, off + 64 * t, 0, 0);
+            const u32x4 hi = __builtin_amdgcn_raw_buffer_load_b128(rows, off + 64 * t + 16, 0, 0);
+            qf[t] = __builtin_bit_cast(i32x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
-    }
-    // scores in base 2: s2 = acc * scale * q_descale[h] * k_descale[g] * log2(e)
-    const float c = p.scale * p.q_descale[head] * p.k_descale[g] * kLog2e;
-    const float v_descale = p.v_descale[g];
+        c_row = p.scale * p.q_descale[w.h0 + head_in_block] * p.k_descale[w.g] * kLog2e;
+    };
+    // output rows and the LSE store that leave at the end of a work: vector memory operations younger than
+    // the loads of the next work's first tile
+    constexpr int kEpilogueStores = RowBlock<D>::N + 1;
+    const int o_tok_bytes = p.Hq * D * 2;
+    auto out_soff = [&](int j) {
+        const int rr = __builtin_amdgcn_readfirstlane(wave * 32 + j * RowBlock<D>::RPI);
+        return (rr % BMT) * o_tok_bytes + (rr / BMT) * (D * 2);
+    };
 
-    f32x16 o[DT];
+    RowWork cur = works.start(first_work, first_work + num_works);
+    int stage = 0;
+    loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
+    loader.issue(kv_rsrc(p.v, cur), smem_lds + kTileBytes, 0);
+    load_q(cur);
+    // Every ordinary load is consumed before the loop head, here and at the end of a work, so that the
+    // compiler has no wait of its own to place at the top of a work, where output rows are still leaving.
+    auto settle_q = [&] {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+        for (int t = 0; t < KSTEPS; ++t) asm volatile("" ::"v"(qf[t]));
+        asm volatile("" ::"v"(c_row));
+    };
+    settle_q();
+
+    for (;;) {
+        const bool has_next = works.has_next();
+        const RowWork nxt = works.peek_next();
+        const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
+        const bool row_valid = tok < cur.q_rows;
+        const int vis = RowMask(cur.P, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
+        const float c = c_row;
+        const float v_descale = p.v_descale[cur.g];
+
+        f32x16 o[DT];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
-    float m = -INFINITY;
-    float lsum = 0.0f;  // sum of p * 2^8, this lane's share
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
+        float m = -INFINITY;  // reference point of the exponentials, base 2
+        float lsum = 0.0f;    // sum of p * 2^8, this lane's share
 
-    const size_t kv_stride = (size_t)p.Hkv * D;
-    const char* k_base = static_cast<const char*>(p.k) + ((size_t)seq_row0 * p.Hkv + g) * D;
-    const char* v_base = static_cast<const char*>(p.v) + ((size_t)seq_row0 * p.Hkv + g) * D;
-
-    // tile row this lane loads as A-lane l32 of block 0 (block 1: + 16)
-    const int a_row = 32 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
-
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        const int j0 = kt * BN;
+        wait_async_loads_except<kEpilogueStores>();  // the first tile has landed; the last work's output may still be leaving
         __syncthreads();
-#pragma unroll
-        for (int i = 0; i < (BN * D / 16) / 256; ++i) {
-            const int cid = tid + i * 256;
-            const int r = cid >> 3, ch = cid & 7;
-            i32x4 kk = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-            if (j0 + r < L) {
-                kk = *reinterpret_cast<const i32x4*>(k_base + (size_t)(j0 + r) * kv_stride + ch * 16);
-                vv = *reinterpret_cast<const i32x4*>(v_base + (size_t)(j0 + r) * kv_stride + ch * 16);
-            }
-            *reinterpret_cast<i32x4*>(k_tile + off8(r, ch)) = kk;
-            *reinterpret_cast<i32x4*>(v_tile + off8(r, ch)) = vv;
-        }
-        __syncthreads();
 
-        f32x16 s[2];
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[b][r] = 0.0f;
-            const int kr = a_row + 16 * b;
-#pragma unroll
-            for (int t = 0; t < KSTEPS; ++t) {
-                const i32x4 lo = *reinterpret_cast<const i32x4*>(k_tile + off8(kr, 4 * t + 2 * hf));
-                const i32x4 hi = *reinterpret_cast<const i32x4*>(k_tile + off8(kr, 4 * t + 2 * hf + 1));
-                s[b] = mfma_f8(__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7), qf[t], s[b]);
+        auto tile = [&](const int kt, auto last_tag, auto masked_tag) {
+            constexpr bool last = decltype(last_tag)::value;
+            constexpr bool masked = decltype(masked_tag)::value;
+            const int j0 = kt * BN;
+            const int k_tile = stage * 2 * kTileBytes;
+            const int v_tile = k_tile + kTileBytes;
+            {
+                const unsigned nk = smem_lds + (stage ^ 1) * 2 * kTileBytes;
+                if constexpr (!last) {
+                    loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
+                    loader.issue(v_rsrc, nk + kTileBytes, (kt + 1) * tile_step);
+                } else if (has_next) {
+                    loader.issue(kv_rsrc(p.k, nxt), nk, 0);
+                    loader.issue(kv_rsrc(p.v, nxt), nk + kTileBytes, 0);
+                }
             }
-        }
-        if (kt >= n_full) {
+            // S^T: two blocks of 32 keys x 32 query rows, alternating so that no MFMA waits for the last one.
+            // Register r of half hf of block b holds key 32 hf + 16 b + r of the tile (see the top of the file).
+            f32x16 s[2];
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (j0 + 32 * hf + 16 * b + r >= vis) s[b][r] = -INFINITY;
-        }
-        float mx = s[0][0];
+                for (int r = 0; r < 16; ++r) s[b][r] = 0.0f;
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+            for (int t = 0; t < KSTEPS; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
-        mx = pair_max(mx);
-        const float m_new = fmaxf(m, mx * c);
-        const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-        m = m_new;
-        float psum = 0.0f;
-        const float shift = kPShift - m_use;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, shift));
-                s[b][r] = pv;
-                psum += pv;
+                for (int b = 0; b < 2; ++b) s[b] = mfma_f8(fa.k_frag(smem, k_tile, b, t), qf[t], s[b]);
+            // the Q fragments are free now: those of the next work can start loading
+            if constexpr (last) {
+                if (has_next) load_q(nxt);
             }
-        lsum = lsum * alpha + psum;
+            if constexpr (masked) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+                for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+                    for (int r = 0; r < 16; ++r)
+                        if (j0 + 32 * hf + 16 * b + r >= vis) s[b][r] = -INFINITY;
+            }
+            // V^T fragments on their way while the softmax runs
+            i32x8 vf[DT];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) vf[dt] = fa.v_frag(smem, v_tile, dt);
 
-        // P^T operand: byte e of the lane = register e % 16 of block e / 16 = key 32 hf + e
-        i32x8 pf;
+            float mx = s[0][0];
 #pragma unroll
-        for (int w = 0; w < 8; ++w) {
-            const int b = w >> 2, r = (w & 3) * 4;
-            int word = __builtin_amdgcn_cvt_pk_fp8_f32(s[b][r], s[b][r + 1], 0, false);
-            word = __builtin_amdgcn_cvt_pk_fp8_f32(s[b][r + 2], s[b][r + 3], word, true);
-            pf[w] = word;
-        }
-        // V^T operand: column d = 32 dt + l32, keys 32 hf + 0..31 through four transposing byte reads.
-        // In a group of 16 lanes, lane i receives byte (i % 8) of the 8 bytes addressed by lane 2 e + i / 8 as
-        // element e (measured); lane s of the group therefore points at row s / 2, columns 8 (s % 2) .. + 7.
-        const int s16 = lane & 15;
+            for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            const int col = 32 * dt + 16 * ((lane >> 4) & 1) + 8 * (s16 & 1);
-            i32x8 vf;
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
+            mx = pair_max(mx) * c;
+            if (__builtin_amdgcn_ballot_w64(mx > m + kMaxLag) != 0) {  // wave-uniform: some row needs a new reference
+                asm volatile("");  // keep this a branch: folded into a select, its multiplications would run on every tile
+                const float m_new = fmaxf(m, mx);
+                // a row that has seen no key yet keeps m = -inf and takes the reference 0 for this tile
+                const float alpha = __builtin_amdgcn_exp2f(m - (m_new == -INFINITY ? 0.0f : m_new));
+                m = m_new;
+                lsum *= alpha;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int vr = 32 * hf + 8 * x + (s16 >> 1);
-                typedef __attribute__((address_space(3))) i32x2* lds_i32x2;
-                const i32x2 two = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-                    (lds_i32x2)(lds_char*)(v_tile + off8(vr, col >> 4) + (col & 8)));
-                vf[2 * x] = two[0];
-                vf[2 * x + 1] = two[1];
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
             }
-            o[dt] = mfma_f8(vf, pf, o[dt]);
-        }
-    }
+            const float shift = kPShift - (m == -INFINITY ? 0.0f : m);
+            float psum = 0.0f;
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, shift));
+                    s[b][r] = pv;
+                    psum += pv;
+                }
+            lsum += psum;
 
-    lsum = pair_sum(lsum);
-    if (row_valid) {
-        // O = v_descale * (V8^T P8) / sum(p * 2^8): the 2^8 of the stored probabilities cancels
-        const float inv = v_descale / lsum;
-        __bf16* orow = static_cast<__bf16*>(p.out) + ((size_t)(q_row0 + tok) * p.Hq + head) * D;
+            // P^T operand: byte e of the lane = register e % 16 of block e / 16 = key 32 hf + e
+            i32x8 pf;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                f32x4 f = {o[dt][4 * r4] * inv, o[dt][4 * r4 + 1] * inv, o[dt][4 * r4 + 2] * inv, o[dt][4 * r4 + 3] * inv};
-                *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * r4 + 4 * hf) = __builtin_convertvector(f, bf16x4);
+            for (int w = 0; w < 8; ++w) {
+                const int b = w >> 2, r = (w & 3) * 4;
+                int word = __builtin_amdgcn_cvt_pk_fp8_f32(s[b][r], s[b][r + 1], 0, false);
+                word = __builtin_amdgcn_cvt_pk_fp8_f32(s[b][r + 2], s[b][r + 3], word, true);
+                pf[w] = word;
             }
-        if (hf == 0)
-            p.lse[(size_t)head * p.T + q_row0 + tok] = (m + __builtin_amdgcn_logf(lsum) - kPShift) * kLn2;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt] = mfma_f8(vf[dt], pf, o[dt]);
+
+            stage ^= 1;
+            if constexpr (!last) {
+                wait_async_loads();
+                __syncthreads();
+            }
+        };
+        {
+            const int n_plain = min(cur.n_full, cur.n_tiles - 1);
+            int kt = 0;
+            for (; kt < n_plain; ++kt) tile(kt, std::false_type{}, std::false_type{});
+            for (; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{}, std::true_type{});
+            tile(cur.n_tiles - 1, std::true_type{}, std::true_type{});
+        }
+
+        lsum = pair_sum(lsum);
+        // O = v_descale * (V8^T P8) / sum(p * 2^8): the 2^8 of the stored probabilities cancels.  The rows
+        // leave through this wave's own staging slice, so no other wave has to be waited for.
+        store_block_rows<D>(smem + kStaging + wave * (32 * D * 2), o, v_descale / lsum, lane,
+                            RowBlock<D>::rows(static_cast<__bf16*>(p.out) + ((size_t)cur.q_row0 * p.Hq + cur.h0) * D,
+                                              (unsigned)(cur.q_rows - 1) * o_tok_bytes + HPB * D * 2),
+                            RowBlock<D>::lane_offset(lane, o_tok_bytes), out_soff);
+        {
+            const __amdgpu_buffer_rsrc_t lse_rows =
+                RowBlock<D>::rows(p.lse + (size_t)cur.h0 * p.T + cur.q_row0, (unsigned)((HPB - 1) * p.T + cur.q_rows) * 4u);
+            const int off = (row_valid && hf == 0) ? (head_in_block * p.T + tok) * 4 : 0x7ffffff0;
+            __builtin_amdgcn_raw_buffer_store_b32(
+                __builtin_bit_cast(unsigned, (m + __builtin_amdgcn_logf(lsum) - kPShift) * kLn2), lse_rows, off, 0, 0);
+        }
+        if (!has_next) break;
+        settle_q();
+        works.advance();
+        cur = nxt;
     }
+}
+
+template <int HPB>
+hipError_t launch_h(const AttnParams& p, hipStream_t stream) {
+    constexpr size_t smem = 2 * 2 * kTileBytes + 4 * 32 * 128 * 2;
+    hipLaunchKernelGGL((fwd_fp8_kernel<HPB>), dim3((unsigned)p.num_workgroups), dim3(256), smem, stream, p);
+    return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_fwd_fp8(const AttnParams& p, hipStream_t stream) {
     if (p.D != 128) return hipErrorNotSupported;
-    const int G = p.Hq / p.Hkv;
-    const int hpb = heads_per_block(p.Hq, p.Hkv);
-    const unsigned grid = (unsigned)p.num_items * (unsigned)(p.Hkv * (G / hpb));
-    if (grid == 0) return hipSuccess;
-    switch (hpb) {
-        case 1: hipLaunchKernelGGL((fwd_fp8_kernel<1>), dim3(grid), dim3(256), 0, stream, p); break;
-        case 2: hipLaunchKernelGGL((fwd_fp8_kernel<2>), dim3(grid), dim3(256), 0, stream, p); break;
-        case 4: hipLaunchKernelGGL((fwd_fp8_kernel<4>), dim3(grid), dim3(256), 0, stream, p); break;
-        default: hipLaunchKernelGGL((fwd_fp8_kernel<8>), dim3(grid), dim3(256), 0, stream, p); break;
+    if (p.num_items == 0) return hipSuccess;
+    switch (heads_per_block(p.Hq, p.Hkv)) {
+        case 1: return launch_h<1>(p, stream);
+        case 2: return launch_h<2>(p, stream);
+        case 4: return launch_h<4>(p, stream);
+        default: return launch_h<8>(p, stream);
     }
-    return hipGetLastError();
 }
 
 }  // namespace va
