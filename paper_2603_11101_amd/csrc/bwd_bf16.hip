@@ -74,9 +74,7 @@ struct DkdvWork {
     int kv_row0, kv_rows, seq_row0, qt_first, qt_count, P, L, g;
 };
 
-template <bool PERSIST>
-VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int work_index) {
-    const int id = PERSIST ? p.work_ids[work_index] : work_index;  // one work per workgroup: heaviest first
+VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int id) {
     const WorkItem it = p.items[id / p.works_per_item];
     DkdvWork w;
     w.kv_row0 = it.w[0];
@@ -90,26 +88,23 @@ VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int work_index) {
     return w;
 }
 
-// Persistent dK/dV kernel.  A work is one key tile of 128 rows of one KV head; each wave owns 32 key rows
-// and keeps their K fragments in registers.  The workgroup walks over the query tiles that see the key
-// tile, for every query head of the group, staging Q, dO, LSE and delta in two LDS stages that are filled
-// asynchronously one step ahead (across works too).
+// dK/dV kernel, one work per workgroup, launched heaviest first.  A work is one key tile of 128 rows of
+// one KV head; each wave owns 32 key rows and keeps their K fragments in registers.  The workgroup walks
+// over the query tiles that see the key tile, for every query head of the group, staging Q, dO, LSE and
+// delta in two LDS stages that are filled asynchronously one step ahead.  (A persistent form that
+// prefetched across works kept K and both accumulators live across the switch and spilled; a two-pass
+// form for D = 256, dV then dK, cost a fifth product and a second launch.)
 //   V_LDS  the V rows of the key tile live in LDS (second operand of dP = dO V^T) instead of registers:
-//          that buys the register room for two workgroups per CU at D = 128
-//   PART   0 = dK and dV in one pass; 1 = dV only; 2 = dK only.  At D = 256 the two accumulators together
-//          (256 registers per lane) leave no room for anything else, so the kernel is launched once per
-//          part there, at the price of recomputing the scores (5 products instead of 4).
-//   PERSIST  true: the workgroup runs the list of works the host assigned to it, prefetching across works;
-//          false: one work per workgroup, launched heaviest first (fewer live registers)
-template <int D, bool V_LDS, int PART, bool PERSIST>
+//          that buys the register room for two workgroups per CU at D = 128 and for both accumulators
+//          (256 registers per lane, in the accumulation registers) at D = 256
+template <int D, bool V_LDS>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnParams p) {
-    constexpr bool DO_DV = PART != 2, DO_DK = PART != 1;
-    constexpr bool V_IN_LDS = V_LDS && DO_DK, V_REGS = !V_LDS && DO_DK;
+    constexpr bool V_IN_LDS = V_LDS, V_REGS = !V_LDS;
     constexpr int BMQ = dkdv_q_tile(D);  // query rows staged per step
     constexpr int QB = BMQ / 32;         // 32-row query blocks per step
     constexpr int KSTEPS = D / 16;
     constexpr int DT = D / 32;
-    constexpr int PF = (D == 128 && PART == 0) ? 2 : kPrefetch;  // D = 128 in one pass has no registers to spare
+    constexpr int PF = D >= 128 ? 2 : kPrefetch;  // fragment reads in flight; D >= 128 has no registers to spare
     constexpr int TILE_BYTES = BMQ * D * 2;
     constexpr int STAGE_BYTES = 2 * TILE_BYTES + 2 * 64 * (int)sizeof(float);  // Q, dO, LSE2[64], delta[64]
     constexpr int AUX = 2 * STAGE_BYTES;  // V tile of the work; output staging at the end of the work
@@ -117,9 +112,6 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    int work = PERSIST ? p.wg_table[2 * blockIdx.x] : (int)blockIdx.x;
-    const int work_end = PERSIST ? work + p.wg_table[2 * blockIdx.x + 1] : work + 1;
-    if (work >= work_end) return;
 
     const int G = p.Hq / p.Hkv;
     const float c = p.scale * kLog2e;
@@ -173,29 +165,26 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         }
     };
 
-    DkdvWork cur = fetch_dkdv_work<PERSIST>(p, work);
+    const DkdvWork cur = fetch_dkdv_work(p, (int)blockIdx.x);
     int stage = 0;
     issue_stage(cur, 0, 0);
     issue_v(cur);
     load_k(cur);
 
-    for (;;) {
-        const bool has_next = PERSIST && work + 1 < work_end;
-        DkdvWork nxt = cur;
-        if (has_next) nxt = fetch_dkdv_work<PERSIST>(p, work + 1);
+    {
         const int n_steps = G * cur.qt_count;
         const RowMask mask(cur.P, cur.L, p.mask_mode);
         const int L = cur.L;
         // this wave's 32 key rows; the lane owns key row jw + l32 (local index in the sample)
         const int jw = cur.kv_row0 - cur.seq_row0 + 32 * wave;
 
-        f32x16 dk[DO_DK ? DT : 1], dv[DO_DV ? DT : 1];
+        f32x16 dk[DT], dv[DT];
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                if (DO_DK) dk[dt][r] = 0.0f;
-                if (DO_DV) dv[dt][r] = 0.0f;
+                dk[dt][r] = 0.0f;
+                dv[dt][r] = 0.0f;
             }
 #pragma unroll
         for (int t = 0; t < KSTEPS; ++t) {
@@ -205,15 +194,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         wait_async_loads();
         __syncthreads();
 
-        // One step; the last step of a work is a separate instantiation that alone prefetches for the next
-        // work, so the loop over the other steps holds no ordinary global load.
+        // One step; the last one is a separate instantiation that prefetches nothing and ends without a barrier.
         auto step = [&](const int n, auto last_tag) {
             constexpr bool last = decltype(last_tag)::value;
-            if constexpr (!last) {
-                issue_stage(cur, n + 1, stage ^ 1);
-            } else if (has_next) {
-                issue_stage(nxt, 0, stage ^ 1);
-            }
+            if constexpr (!last) issue_stage(cur, n + 1, stage ^ 1);
             const int q_tile = stage * STAGE_BYTES;  // byte offsets of this stage's tiles
             const int do_tile = q_tile + TILE_BYTES;
             const float* lse_s = reinterpret_cast<const float*>(smem + q_tile + 2 * TILE_BYTES);
@@ -237,9 +221,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                     dp[r] = 0.0f;
                 }
                 {
-                    constexpr int NS = DO_DK ? 2 * KSTEPS : KSTEPS;  // step i: product i % 2 (0: S, 1: dP) if both
-                    auto prod = [&](int i) { return DO_DK ? i % 2 : 0; };
-                    auto kstep = [&](int i) { return DO_DK ? i / 2 : i; };
+                    constexpr int NS = 2 * KSTEPS;  // step i: product i % 2 (0: S, 1: dP), k-step i / 2
+                    auto prod = [&](int i) { return i % 2; };
+                    auto kstep = [&](int i) { return i / 2; };
                     bf16x8 ring[PF], vring[V_IN_LDS ? PF : 1];
                     auto fetch = [&](int i) {
                         ring[i % PF] = fa.rowmajor(smem, prod(i) ? do_tile : q_tile, qb, kstep(i));
@@ -272,10 +256,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                 // first transposed fragments on their way while the elementwise part runs.
                 // Step i of the last products: which = i % NW (dV from dO^T, dK from Q^T), block (i / NW) % DT,
                 // query rows 16 (i / (NW DT)) .. + 15 of the block.
-                constexpr int NW = (DO_DV ? 1 : 0) + (DO_DK ? 1 : 0);
+                constexpr int NW = 2;
                 constexpr int NT = 2 * DT * NW;
                 auto tfrag = [&](int i) {
-                    const bool is_dk = DO_DK && (!DO_DV || (i % NW) == 1);
+                    const bool is_dk = (i % NW) == 1;
                     return fa.transposed(smem, is_dk ? q_tile : do_tile, 2 * qb + i / (NW * DT), (i / NW) % DT);
                 };
                 bf16x8 tring[PF];
@@ -292,7 +276,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                         const int r = 4 * r4 + e;
                         const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
                         s[r] = pv;
-                        if (DO_DK) dp[r] = pv * (dp[r] - d4[e]);
+                        dp[r] = pv * (dp[r] - d4[e]);
                     }
                 }
                 if (need_mask) {
@@ -306,17 +290,15 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                     for (int r = 0; r < 16; ++r)
                         if (key >= mask.vis_in_sample(row_base + 8 * (r / 4) + r % 4)) {
                             s[r] = 0.0f;
-                            if (DO_DK) dp[r] = 0.0f;
+                            dp[r] = 0.0f;
                         }
                 }
                 bf16x8 pb[2], dsb[2];
 #pragma unroll
                 for (int x = 0; x < 2; ++x) {
-                    if (DO_DV)
-                        pb[x] = to_bf16x8(s[8 * x], s[8 * x + 1], s[8 * x + 2], s[8 * x + 3], s[8 * x + 4], s[8 * x + 5],
+                    pb[x] = to_bf16x8(s[8 * x], s[8 * x + 1], s[8 * x + 2], s[8 * x + 3], s[8 * x + 4], s[8 * x + 5],
                                           s[8 * x + 6], s[8 * x + 7]);
-                    if (DO_DK)
-                        dsb[x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
+                    dsb[x] = to_bf16x8(dp[8 * x], dp[8 * x + 1], dp[8 * x + 2], dp[8 * x + 3], dp[8 * x + 4],
                                            dp[8 * x + 5], dp[8 * x + 6], dp[8 * x + 7]);
                 }
                 // dV^T += dO^T P ; dK^T += Q^T dS  (rows = d, columns = key rows): consecutive MFMAs go to
@@ -325,10 +307,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                 for (int i = 0; i < NT; ++i) {
                     const bf16x8 a = tring[i % PF];
                     if (i + PF < NT) tring[i % PF] = tfrag(i + PF);
-                    const bool is_dk = DO_DK && (!DO_DV || (i % NW) == 1);
+                    const bool is_dk = (i % NW) == 1;
                     const int dt = (i / NW) % DT, x = i / (NW * DT);
-                    if (is_dk) dk[DO_DK ? dt : 0] = mfma32(a, dsb[x], dk[DO_DK ? dt : 0]);
-                    else dv[DO_DV ? dt : 0] = mfma32(a, pb[x], dv[DO_DV ? dt : 0]);
+                    if (is_dk) dk[dt] = mfma32(a, dsb[x], dk[dt]);
+                    else dv[dt] = mfma32(a, pb[x], dv[dt]);
                 }
 #pragma unroll
                 for (int i = 0; i < NT; ++i) {
@@ -356,23 +338,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
             const unsigned bytes = rows_here > 0 ? (unsigned)(rows_here - 1) * row_bytes + D * 2 : 0u;
             const int lane_off = RowBlock<D>::lane_offset(lane, row_bytes);
             auto soff = [&](int j) { return j * RowBlock<D>::RPI * row_bytes; };
-            if constexpr (DO_DK)
-                store_block_rows<D>(out_stage, dk, p.scale, lane,
+            store_block_rows<D>(out_stage, dk, p.scale, lane,
                                     RowBlock<D>::rows(static_cast<__bf16*>(p.dk) + off, bytes), lane_off, soff);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (DO_DV)
-                store_block_rows<D>(out_stage, dv, 1.0f, lane,
+            store_block_rows<D>(out_stage, dv, 1.0f, lane,
                                     RowBlock<D>::rows(static_cast<__bf16*>(p.dv) + off, bytes), lane_off, soff);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (!has_next) break;
-        load_k(nxt);  // after the accumulators are gone: the epilogue has no registers to spare
-        if (V_IN_LDS) {
-            __syncthreads();  // the staging reads are done: the next V tile may land
-            issue_v(nxt);
-        }
-        ++work;
-        cur = nxt;
     }
 }
 
@@ -624,30 +596,18 @@ hipError_t launch_dq_d(const AttnParams& p, hipStream_t stream) {
     }
 }
 
-template <int D, int PART, bool PERSIST>
-hipError_t launch_dkdv_part(const AttnParams& p, hipStream_t stream) {
-    constexpr bool V_LDS = D >= 128;
-    // two stages of (Q tile, dO tile, LSE, delta), then the V tile / output staging region
-    constexpr size_t smem = 2 * (2 * dkdv_q_tile(D) * D * 2 + 2 * 64 * sizeof(float)) + kDkdvKvRows * D * 2;
-    const unsigned grid = PERSIST ? (unsigned)p.num_workgroups : (unsigned)(p.num_items * p.works_per_item);
-    static const hipError_t attr =
-        allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, PART, PERSIST>), smem);
-    if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, PART, PERSIST>), dim3(grid), dim3(256), smem, stream, p);
-    return hipGetLastError();
-}
-
-// D <= 128: one pass, one work per workgroup (the persistent form needs more registers than two
-// workgroups per CU leave).  D = 256: dV pass then dK pass, persistent.
+// One work per workgroup, in item order (heaviest first).
 template <int D>
 hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     if (p.num_items == 0) return hipSuccess;
-    if constexpr (D <= 128) {
-        return launch_dkdv_part<D, 0, false>(p, stream);
-    } else {
-        const hipError_t e = launch_dkdv_part<D, 1, true>(p, stream);
-        return e != hipSuccess ? e : launch_dkdv_part<D, 2, true>(p, stream);
-    }
+    constexpr bool V_LDS = D >= 128;
+    // two stages of (Q tile, dO tile, LSE, delta), then the V tile / output staging region
+    constexpr size_t smem = 2 * (2 * dkdv_q_tile(D) * D * 2 + 2 * 64 * sizeof(float)) + kDkdvKvRows * D * 2;
+    const unsigned grid = (unsigned)(p.num_items * p.works_per_item);
+    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS>), smem);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS>), dim3(grid), dim3(256), smem, stream, p);
+    return hipGetLastError();
 }
 
 template <int D>
