@@ -195,6 +195,19 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same quantisation on the device (the on-device step the per-head
+ * scaling of section 2.2.3 needs before the FP8 forward), bit-identical to
+ * va_quantize_e4m3_per_head for finite inputs:
+ *   x        device in   bfloat16 [T, H, D], 16-byte aligned, D a multiple of 8
+ *   codes    device out  uint8 [T, H, D], 8-byte aligned
+ *   descale  device out  float32 [H]; holds the per-head maxima while the call runs
+ * Four small kernels on `stream`; nothing is allocated, nothing waits.
+ * VA_EINVAL for null pointers or bad sizes, VA_EALIGN, VA_EHIP.
+ */
+int va_quantize_e4m3_per_head_device(const void* x_bf16, int32_t T, int32_t H, int32_t D,
+                                     void* codes, float* descale, void* stream);
+
+/*
  * Measurement aid: runs exactly what varlen_attn_bwd runs, `iters` times, with
  * HIP events recorded on `stream` around each of the three kernels, then waits
  * for the stream (the only entry point that synchronises) and writes the

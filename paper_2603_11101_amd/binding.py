@@ -48,7 +48,8 @@ def _load():
 _lib = _load()
 
 EXPORTS = ["va_last_error", "va_pack_first_fit", "va_bin_layout", "va_tile_shape", "va_worklist_bytes",
-           "va_build_worklist", "va_quantize_e4m3_per_head", "varlen_attn_bwd_workspace_bytes",
+           "va_build_worklist", "va_quantize_e4m3_per_head", "va_quantize_e4m3_per_head_device",
+           "varlen_attn_bwd_workspace_bytes",
            "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_profile", "varlen_attn_fwd_fp8"]
 
 
@@ -157,6 +158,14 @@ def va_quantize_e4m3_per_head(x_bf16_bits):
     _check(_lib.va_quantize_e4m3_per_head(_ptr(x), ctypes.c_int32(T), ctypes.c_int32(H), ctypes.c_int32(D),
                                           _ptr(codes), _ptr(descale)))
     return codes, descale
+
+
+def va_quantize_e4m3_per_head_device(x, codes, descale, stream=None):
+    """x: bfloat16 device tensor [T, H, D]; codes: uint8 device tensor [T, H, D]; descale: float32 device
+    tensor [H].  Enqueues the quantisation on the stream."""
+    T, H, D = x.shape
+    _check(_lib.va_quantize_e4m3_per_head_device(_ptr(x), ctypes.c_int32(T), ctypes.c_int32(H), ctypes.c_int32(D),
+                                                 _ptr(codes), _ptr(descale), _stream_ptr(stream)))
 
 
 def make_shape(total_tokens, num_seqs, num_q_heads, num_kv_heads, head_dim, max_seqlen, mask_mode):

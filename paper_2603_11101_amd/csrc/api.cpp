@@ -301,6 +301,18 @@ int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const v
     return VA_OK;
 }
 
+int va_quantize_e4m3_per_head_device(const void* x, int32_t T, int32_t H, int32_t D, void* codes, float* descale,
+                                     void* stream) {
+    const char* who = "va_quantize_e4m3_per_head_device";
+    if (T < 0 || H <= 0 || D <= 0 || D % 8 != 0 || !descale || (T > 0 && (!x || !codes)))
+        return fail(VA_EINVAL, "%s: null pointer or bad size (D must be a multiple of 8)", who);
+    if (!aligned16(x) || (reinterpret_cast<uintptr_t>(codes) & 7u) != 0 || (reinterpret_cast<uintptr_t>(descale) & 3u) != 0)
+        return fail(VA_EALIGN, "%s: x must be 16-byte, codes 8-byte, descale 4-byte aligned", who);
+    const hipError_t e = launch_quantize_e4m3(x, T, H, D, codes, descale, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    return VA_OK;
+}
+
 int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
                         const float* q_descale, const float* k_descale, const float* v_descale,
                         const int32_t* cu_seqlens, const int32_t* prefix_lens,

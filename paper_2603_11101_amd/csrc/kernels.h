@@ -45,5 +45,7 @@ hipError_t launch_fwd_fp8(const AttnParams& p, hipStream_t stream);
 hipError_t launch_bwd_delta(const AttnParams& p, hipStream_t stream);
 hipError_t launch_bwd_dkdv(const AttnParams& p, hipStream_t stream);
 hipError_t launch_bwd_dq(const AttnParams& p, hipStream_t stream);
+hipError_t launch_quantize_e4m3(const void* x, int32_t T, int32_t H, int32_t D, void* codes, float* descale,
+                                hipStream_t stream);
 
 }  // namespace va

@@ -77,3 +77,34 @@ def test_fp8_uniform_keys_is_exact_for_power_of_two_counts():
         want = vd[:i + 1, 0].astype(np.float64).mean(axis=0)
         for h in range(Hq):
             assert np.allclose(out[i, h], want, rtol=2.0 ** -7, atol=1e-6), (i, h)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("T,H,D", [(1, 1, 64), (77, 3, 64), (513, 8, 128), (300, 5, 256), (0, 4, 128)])
+def test_device_quantiser_is_bit_identical_to_the_oracle(T, H, D):
+    # per-head amax, descale and every code byte: the oracle's nearest-value search decides, the device
+    # uses the conversion instruction after clamping; values hit subnormals, ties and the saturation edge
+    print(f"device quantiser T={T} H={H} D={D}", flush=True)
+    rng = np.random.default_rng(100 + T + H)
+    x = rng.standard_normal((T, H, D)).astype(np.float32)
+    if T > 0:
+        x[0, 0, :8] = [0.0, -0.0, 1e-6, -3e-5, 448.0, -448.0, 1.0, -1.0]
+        x[:, -1, :] *= 1e-3           # a head with a tiny range
+        if H > 1:
+            x[:, 1, :] = 0.0          # an all-zero head: descale 1
+        x.flat[:: 7] *= 37.0          # spread over many binades
+    x = wl.round_to_bf16(x)
+    bits = wl.bf16_bits(x)
+    xt = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(DEV)
+    codes = torch.full((T, H, D), 0xAA, dtype=torch.uint8, device=DEV)
+    descale = torch.full((H,), -1.0, dtype=torch.float32, device=DEV)
+    va.va_quantize_e4m3_per_head_device(xt, codes, descale)
+    torch.cuda.synchronize()
+    if T == 0:  # nothing to look at: every head is "all zero"
+        assert np.array_equal(descale.cpu().numpy(), np.ones(H, dtype=np.float32))
+        return
+    ref_codes, ref_descale = oe.quantize_per_head(x)
+    assert np.array_equal(descale.cpu().numpy().view(np.uint32), ref_descale.astype(np.float32).view(np.uint32))
+    assert np.array_equal(codes.cpu().numpy(), ref_codes)
+    host_codes, host_descale = va.va_quantize_e4m3_per_head(bits)
+    assert np.array_equal(host_codes, ref_codes) and np.array_equal(host_descale, ref_descale.astype(np.float32))
