@@ -165,24 +165,6 @@ struct FragAddr {
     }
 };
 
-// Copy ROWS x D bf16 values from global memory (row stride `gstride` elements)
-// into a swizzled LDS tile with 16-byte accesses; rows >= valid_rows are filled
-// with zeros and never read from memory.
-template <int D, int ROWS, int THREADS>
-VA_DEV void load_tile(char* tile, const __bf16* g, size_t gstride, int valid_rows, int tid) {
-    constexpr int CPR = D / 8;
-    constexpr int CHUNKS = ROWS * CPR;
-    static_assert(CHUNKS % THREADS == 0, "tile must divide among the threads");
-#pragma unroll
-    for (int i = 0; i < CHUNKS / THREADS; ++i) {
-        const int cid = tid + i * THREADS;
-        const int r = cid / CPR, c = cid % CPR;
-        u32x4 val = {0u, 0u, 0u, 0u};
-        if (r < valid_rows) val = *reinterpret_cast<const u32x4*>(g + (size_t)r * gstride + c * 8);
-        *reinterpret_cast<u32x4*>(tile + tile_off<D>(r, c)) = val;
-    }
-}
-
 // ---------------------------------------------------------------- asynchronous tile loads
 //
 // Tiles travel from global memory straight into LDS (buffer_load_dwordx4 ... lds:

@@ -7,7 +7,7 @@ from oracle import attn as oa
 from paper_2603_11101_amd import binding as va
 from paper_2603_11101_amd import workloads as wl
 
-from gpu_util import GpuRun, TOL_GRAD_REL, rel_l2
+from gpu_util import GpuRun, TOL_FWD_REL, TOL_GRAD_REL, TOL_LSE_ABS, max_abs, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -87,3 +87,33 @@ def test_backward_packing_invariance_no_leak_and_determinism():
     keep = np.r_[0:cu[1], cu[2]:cu[3]]
     for n in ("dq", "dk", "dv"):
         assert np.array_equal(getattr(poisoned, n)[keep], getattr(full, n)[keep]), n
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 2, 128), (8, 1, 64)])
+def test_many_tiny_samples_forward_and_backward(Hq, Hkv, D):
+    # thousands of works of one or two tiles each: every persistent workgroup switches works many times,
+    # so descriptors fetched ahead, the wait that lets output rows drain and the cross-work prefetch all
+    # run back to back; lengths 1..70 also put a ragged block at almost every switch
+    rng = np.random.default_rng(5 + D)
+    lens = rng.integers(1, 71, size=1600)
+    lens[::97] = 0                                   # empty samples in between
+    cu, _, q, k, v, do = wl.random_stream(11 + D, [int(x) for x in lens], Hq, Hkv, D)
+    scale = 1.0 / np.sqrt(D)
+    print(f"many tiny samples Hq={Hq} Hkv={Hkv} D={D} T={int(cu[-1])}", flush=True)
+    run = GpuRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale)
+    ref_out, ref_lse = oa.attn_fwd(q, k, v, cu, None, scale=scale)
+    assert rel_l2(run.out, ref_out) <= TOL_FWD_REL and max_abs(run.lse, ref_lse) <= TOL_LSE_ABS
+    ref = oa.attn_bwd(q, k, v, do, cu, None, scale=scale)
+    for n, g, r in zip(("dq", "dk", "dv"), (run.dq, run.dk, run.dv), ref):
+        print(f"  {n} rel-L2 {rel_l2(g, r):.2e}", flush=True)
+        assert rel_l2(g, r) <= TOL_GRAD_REL, n
+    # per sample as well: with 1600 samples a wrong one would vanish in the global norm
+    worst = 0.0
+    for s in range(len(lens)):
+        sl = slice(cu[s], cu[s + 1])
+        if cu[s + 1] > cu[s]:
+            worst = max(worst, rel_l2(run.out[sl], ref_out[sl]), rel_l2(run.dq[sl], ref[0][sl]),
+                        rel_l2(run.dk[sl], ref[1][sl]), rel_l2(run.dv[sl], ref[2][sl]))
+    print(f"  worst per-sample rel-L2 over all samples and tensors {worst:.2e}", flush=True)
+    assert worst <= TOL_GRAD_REL
+    assert run.tail_untouched("out") and run.tail_untouched("dq") and run.tail_untouched("dk")
