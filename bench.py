@@ -38,43 +38,52 @@ def allowed_pairs(lens, prefix):
     return int((prefix * prefix + (lens - prefix) * lens).sum())
 
 
-def build_bin0(name, va, wl):
+def build_bin(name, va, wl, which=0):
+    """Layout of bin `which` of the first-fit packing of the workload's pool (None if there is no such bin)."""
     w = wl.WORKLOADS[name]
     lens, prefix = wl.sample_lengths(name)
-    bin_of, pos, _ = va.va_pack_first_fit(lens, w.budget)
-    idx = np.array(sorted(np.nonzero(bin_of == 0)[0], key=lambda i: pos[i]), dtype=np.int64)
+    bin_of, pos, nbins = va.va_pack_first_fit(lens, w.budget)
+    if which >= nbins:
+        return None
+    idx = np.array(sorted(np.nonzero(bin_of == which)[0], key=lambda i: pos[i]), dtype=np.int64)
     cu, pl, mx = va.va_bin_layout(lens[idx], None if prefix is None else prefix[idx])
     return w, lens[idx], (None if prefix is None else prefix[idx]), cu, pl, mx
 
 
-def cpu_baseline(w, lens, prefix, cu, q, k, v, do, scale, budget_s=20.0):
-    """The oracle as it stands, on the host cores, on the first samples of the
-    same bin: enough samples for roughly `budget_s` seconds of CPU work."""
+def build_bin0(name, va, wl):
+    return build_bin(name, va, wl, 0)
+
+
+def cpu_baseline(name, va, wl, budget_s=12.0, max_s=30.0):
+    """The oracle as it stands, on the host cores: forward + backward of whole bins of the same workload,
+    bin 0 first, until about `budget_s` seconds of CPU work are done (a bin is only started if the rate
+    so far says it ends before `max_s`)."""
     from oracle import attn as oa
-    D, Hq = w.head_dim, w.num_q_heads
     nthreads = oa.num_threads()
-    # calibrate on the first sample, then take as many samples as fit the budget
-    t0 = time.perf_counter()
-    oa.attn_fwd(q, k, v, cu, prefix, scale=scale, sel=[0])
-    oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, sel=[0])
-    t_first = time.perf_counter() - t0
-    flops_first = 14.0 * D * Hq * allowed_pairs(lens[:1], None if prefix is None else prefix[:1])
-    rate = flops_first / max(t_first, 1e-9)
-    sel, flops = [], 0.0
-    for s in range(len(lens)):
-        f = 14.0 * D * Hq * allowed_pairs(lens[s:s + 1], None if prefix is None else prefix[s:s + 1])
-        if sel and (flops + f) / rate > budget_s:
+    flops = tokens = samples = bins = 0
+    dt = 0.0
+    while True:
+        b = build_bin(name, va, wl, bins)
+        if b is None:
             break
-        sel.append(s)
+        w, lens, prefix, cu, pl, mx = b
+        D, Hq, Hkv = w.head_dim, w.num_q_heads, w.num_kv_heads
+        f = 14.0 * D * Hq * allowed_pairs(lens, prefix)
+        if bins > 0 and (dt >= budget_s or dt + f * dt / flops > max_s):
+            break
+        q, k, v, do = wl.tensor_values(w.seed + 1000 * bins, int(cu[-1]), Hq, Hkv, D)
+        scale = 1.0 / float(np.sqrt(D))
+        t0 = time.perf_counter()
+        oa.attn_fwd(q, k, v, cu, prefix, scale=scale)
+        oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale)
+        dt += time.perf_counter() - t0
         flops += f
-    t0 = time.perf_counter()
-    oa.attn_fwd(q, k, v, cu, prefix, scale=scale, sel=sel)
-    oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, sel=sel)
-    dt = time.perf_counter() - t0
-    tokens = int(sum(int(lens[s]) for s in sel))
+        tokens += int(cu[-1])
+        samples += len(lens)
+        bins += 1
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": nthreads, "kind": "oracle",
-            "sample": f"fp64 oracle fwd+bwd on the first {len(sel)} of {len(lens)} samples of the bin "
-                      f"({tokens} tokens, {dt:.1f} s)",
+            "sample": f"fp64 oracle fwd+bwd on the first {bins} bins of the first-fit packing "
+                      f"({samples} samples, {tokens} tokens, {dt:.1f} s)",
             "tokens_per_s": tokens / dt}
 
 
@@ -237,7 +246,7 @@ def main():
                          "(section 3.2; NVIDIA GPU model unstated); no absolute attention numbers",
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, lens, prefix, cu, q, k, v, do, scale)
+        result["cpu_baseline"] = cpu_baseline(args.workload, va, wl)
     print(json.dumps(result))
 
 

@@ -38,7 +38,7 @@ def max_abs(x, ref):
     return float(np.abs(np.asarray(x, dtype=np.float64) - ref).max()) if np.size(ref) else 0.0
 
 
-class GpuRun:
+class DeviceRun:
     """Forward (and backward) of one stream on the GPU; outputs as float64 numpy."""
 
     SENTINEL = 768.0   # exactly representable in bfloat16

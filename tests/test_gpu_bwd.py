@@ -7,7 +7,7 @@ from oracle import attn as oa
 from paper_2603_11101_amd import binding as va
 from paper_2603_11101_amd import workloads as wl
 
-from gpu_util import GpuRun, TOL_FWD_REL, TOL_GRAD_REL, TOL_LSE_ABS, max_abs, rel_l2
+from gpu_util import DeviceRun, TOL_FWD_REL, TOL_GRAD_REL, TOL_LSE_ABS, max_abs, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -35,7 +35,7 @@ def test_tiny_workload_backward():
     q, k, v, do = wl.tensor_values(w.seed, int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim)
     scale = 1.0 / np.sqrt(w.head_dim)
     print("tiny backward", flush=True)
-    run = GpuRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale)
+    run = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale)
     check_bwd(run, oa.attn_bwd(q, k, v, do, cu, None, scale=scale), cu, "tiny")
 
 
@@ -53,7 +53,7 @@ def test_backward_parity(mode, Hq, Hkv, D):
         prefix[3], prefix[7] = 200, 0
     scale = 1.0 / np.sqrt(D)
     print(f"backward parity mode={mode} Hq={Hq} Hkv={Hkv} D={D} seed={seed}", flush=True)
-    run = GpuRun(cu, prefix, mode, q, k, v, do, scale)
+    run = DeviceRun(cu, prefix, mode, q, k, v, do, scale)
     ref = oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=MODES[mode])
     check_bwd(run, ref, cu, f"mode {mode} {Hq}/{Hkv}x{D}")
     # single-token sample (index 4): dQ = dK = 0 up to float32 summation noise in (dP - delta), and
@@ -71,19 +71,19 @@ def test_backward_packing_invariance_no_leak_and_determinism():
     cu, _, q, k, v, do = wl.random_stream(4, lens, Hq, Hkv, D)
     scale = 1.0 / np.sqrt(D)
     print("backward packing invariance", flush=True)
-    full = GpuRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale)
-    again = GpuRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale)
+    full = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale)
+    again = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale)
     for n in ("dq", "dk", "dv"):
         assert np.array_equal(getattr(full, n), getattr(again, n))
     for s, L in enumerate(lens):
         sl = slice(cu[s], cu[s + 1])
-        one = GpuRun(np.array([0, L], dtype=np.int32), None, va.VA_MASK_CAUSAL, q[sl], k[sl], v[sl], do[sl], scale)
+        one = DeviceRun(np.array([0, L], dtype=np.int32), None, va.VA_MASK_CAUSAL, q[sl], k[sl], v[sl], do[sl], scale)
         for n in ("dq", "dk", "dv"):
             assert np.array_equal(getattr(one, n), getattr(full, n)[sl]), (n, s)
     q2, k2, v2, do2 = q.copy(), k.copy(), v.copy(), do.copy()
     bad = slice(cu[1], cu[2])
     q2[bad], k2[bad], v2[bad], do2[bad] = np.nan, np.inf, np.nan, np.nan
-    poisoned = GpuRun(cu, None, va.VA_MASK_CAUSAL, q2, k2, v2, do2, scale)
+    poisoned = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q2, k2, v2, do2, scale)
     keep = np.r_[0:cu[1], cu[2]:cu[3]]
     for n in ("dq", "dk", "dv"):
         assert np.array_equal(getattr(poisoned, n)[keep], getattr(full, n)[keep]), n
@@ -100,7 +100,7 @@ def test_many_tiny_samples_forward_and_backward(Hq, Hkv, D):
     cu, _, q, k, v, do = wl.random_stream(11 + D, [int(x) for x in lens], Hq, Hkv, D)
     scale = 1.0 / np.sqrt(D)
     print(f"many tiny samples Hq={Hq} Hkv={Hkv} D={D} T={int(cu[-1])}", flush=True)
-    run = GpuRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale)
+    run = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale)
     ref_out, ref_lse = oa.attn_fwd(q, k, v, cu, None, scale=scale)
     assert rel_l2(run.out, ref_out) <= TOL_FWD_REL and max_abs(run.lse, ref_lse) <= TOL_LSE_ABS
     ref = oa.attn_bwd(q, k, v, do, cu, None, scale=scale)

@@ -13,7 +13,7 @@ from oracle import packing as op
 from paper_2603_11101_amd import binding as va
 from paper_2603_11101_amd import workloads as wl
 
-from gpu_util import (DEV, GpuRun, TOL_FP8_REL, TOL_FWD_ABS, TOL_FWD_REL, TOL_GRAD_REL, TOL_LSE_ABS, from_dev_bf16,
+from gpu_util import (DEV, DeviceRun, TOL_FP8_REL, TOL_FWD_ABS, TOL_FWD_REL, TOL_GRAD_REL, TOL_LSE_ABS, from_dev_bf16,
                       max_abs, rel_l2)
 
 pytestmark = pytest.mark.gpu
@@ -49,7 +49,7 @@ def test_full_size_forward_backward(name, count):
     q, k, v, do = wl.tensor_values(w.seed, T, Hq, Hkv, D)
     sel = pick(lens, min(count, len(lens)))
     print(f"full size {name}: T={T} samples={len(lens)} checking samples {sel} (lengths {[int(lens[s]) for s in sel]})", flush=True)
-    run = GpuRun(cu, pl, mode, q, k, v, do, scale, max_seqlen=mx)
+    run = DeviceRun(cu, pl, mode, q, k, v, do, scale, max_seqlen=mx)
     print("  gpu done, oracle forward", flush=True)
     ref_out, ref_lse = oa.attn_fwd(q, k, v, cu, pl, scale=scale, sel=sel, mask_mode=omode)
     print("  oracle backward", flush=True)

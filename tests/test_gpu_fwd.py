@@ -8,7 +8,7 @@ from oracle import attn as oa
 from paper_2603_11101_amd import binding as va
 from paper_2603_11101_amd import workloads as wl
 
-from gpu_util import GpuRun, TOL_FWD_ABS, TOL_FWD_REL, TOL_LSE_ABS, max_abs, rel_l2
+from gpu_util import DeviceRun, TOL_FWD_ABS, TOL_FWD_REL, TOL_LSE_ABS, max_abs, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -36,7 +36,7 @@ def test_tiny_workload_forward():
     q, k, v, do = wl.tensor_values(w.seed, int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim)
     scale = 1.0 / np.sqrt(w.head_dim)
     print("tiny forward", flush=True)
-    run = GpuRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale, backward=False)
+    run = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale, backward=False)
     ref_out, ref_lse = oa.attn_fwd(q, k, v, cu, None, scale=scale)
     check_fwd(run, ref_out, ref_lse, cu, "tiny")
 
@@ -55,7 +55,7 @@ def test_forward_parity(mode, Hq, Hkv, D):
         prefix[3], prefix[7] = 200, 0       # whole sample prefix / empty prefix
     scale = 1.0 / np.sqrt(D)
     print(f"forward parity mode={mode} Hq={Hq} Hkv={Hkv} D={D} seed={seed}", flush=True)
-    run = GpuRun(cu, prefix, mode, q, k, v, do, scale, backward=False)
+    run = DeviceRun(cu, prefix, mode, q, k, v, do, scale, backward=False)
     ref_out, ref_lse = oa.attn_fwd(q, k, v, cu, prefix, scale=scale, mask_mode=MODES[mode])
     check_fwd(run, ref_out, ref_lse, cu, f"mode {mode} {Hq}/{Hkv}x{D}")
 
@@ -65,8 +65,8 @@ def test_forward_does_not_depend_on_max_seqlen_slack_and_is_deterministic():
     cu, prefix, q, k, v, do = wl.random_stream(3, [100, 33, 180], Hq, Hkv, D)
     scale = 0.11
     print("max_seqlen slack / determinism", flush=True)
-    a = GpuRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale, max_seqlen=180, backward=False)
-    b = GpuRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale, max_seqlen=360, backward=False)
+    a = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale, max_seqlen=180, backward=False)
+    b = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale, max_seqlen=360, backward=False)
     assert np.array_equal(a.out, b.out) and np.array_equal(a.lse, b.lse)
 
 
@@ -78,15 +78,15 @@ def test_forward_packing_invariance_and_no_leak_on_gpu():
     cu, _, q, k, v, do = wl.random_stream(4, lens, Hq, Hkv, D)
     scale = 1.0 / np.sqrt(D)
     print("packing invariance", flush=True)
-    full = GpuRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale, backward=False)
+    full = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q, k, v, do, scale, backward=False)
     for s, L in enumerate(lens):
         sl = slice(cu[s], cu[s + 1])
-        one = GpuRun(np.array([0, L], dtype=np.int32), None, va.VA_MASK_CAUSAL, q[sl], k[sl], v[sl], do[sl], scale,
+        one = DeviceRun(np.array([0, L], dtype=np.int32), None, va.VA_MASK_CAUSAL, q[sl], k[sl], v[sl], do[sl], scale,
                      backward=False)
         assert np.array_equal(one.out, full.out[sl]) and np.array_equal(one.lse, full.lse[:, sl])
     q2, k2, v2 = q.copy(), k.copy(), v.copy()
     bad = slice(cu[1], cu[2])
     q2[bad], k2[bad], v2[bad] = np.nan, np.inf, np.nan
-    poisoned = GpuRun(cu, None, va.VA_MASK_CAUSAL, q2, k2, v2, do, scale, backward=False)
+    poisoned = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q2, k2, v2, do, scale, backward=False)
     keep = np.r_[0:cu[1], cu[2]:cu[3]]
     assert np.array_equal(poisoned.out[keep], full.out[keep]) and np.array_equal(poisoned.lse[:, keep], full.lse[:, keep])
