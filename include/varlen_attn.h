@@ -208,10 +208,11 @@ int va_quantize_e4m3_per_head_device(const void* x_bf16, int32_t T, int32_t H, i
                                      void* codes, float* descale, void* stream);
 
 /*
- * Measurement aid: runs exactly what varlen_attn_bwd runs, `iters` times, with
- * HIP events recorded on `stream` around each of the three kernels, then waits
- * for the stream (the only entry point that synchronises) and writes the
- * average milliseconds per launch to the host array ms[3] = {delta, dK/dV, dQ}.
+ * Measurement aid: launches each of the three kernels of varlen_attn_bwd
+ * `iters` times back to back (delta, then dK/dV, then dQ, so the results are
+ * those of varlen_attn_bwd) between HIP events recorded on `stream`, waits for
+ * the stream (the only entry point that synchronises) and writes the average
+ * milliseconds per launch to the host array ms[3] = {delta, dK/dV, dQ}.
  * Same arguments and errors as varlen_attn_bwd; iters >= 1.
  */
 int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const void* out, const float* lse,

@@ -258,9 +258,10 @@ int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const v
     ms[0] = ms[1] = ms[2] = 0.0f;
     if (rc || empty) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // All iterations are enqueued before the first wait, so that the stream never runs dry and an event's
-    // time stamp is that of the kernel boundary it sits on.
-    std::vector<hipEvent_t> ev((size_t)iters * 4, nullptr);
+    // Each kernel is launched `iters` times back to back between two events, so that what an event costs
+    // on the stream (several microseconds) is spread over all launches; the last round leaves the same
+    // results as varlen_attn_bwd.
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
     auto destroy = [&] {
         for (auto& x : ev)
             if (x) (void)hipEventDestroy(x);
@@ -270,31 +271,32 @@ int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const v
             destroy();
             return fail(VA_EHIP, "%s: hipEventCreate failed", who);
         }
-    hipError_t e = hipSuccess;
-    for (int32_t i = 0; i < iters && e == hipSuccess; ++i) {
-        hipEvent_t* ei = &ev[(size_t)i * 4];
-        e = hipEventRecord(ei[0], st);
-        if (e == hipSuccess) e = launch_bwd_delta(p, st);
-        if (e == hipSuccess) e = hipEventRecord(ei[1], st);
-        if (e == hipSuccess) {
-            set_worklist(&p, worklist_dkdv, lay_dkdv);
-            e = launch_bwd_dkdv(p, st);
-        }
-        if (e == hipSuccess) e = hipEventRecord(ei[2], st);
-        if (e == hipSuccess) {
-            set_worklist(&p, worklist_dq, lay_dq);
-            e = launch_bwd_dq(p, st);
-        }
-        if (e == hipSuccess) e = hipEventRecord(ei[3], st);
+    // one untimed round first: the stream is busy and the clocks are up when the first event is reached
+    hipError_t e = launch_bwd_delta(p, st);
+    if (e == hipSuccess) {
+        set_worklist(&p, worklist_dkdv, lay_dkdv);
+        e = launch_bwd_dkdv(p, st);
     }
+    if (e == hipSuccess) {
+        set_worklist(&p, worklist_dq, lay_dq);
+        e = launch_bwd_dq(p, st);
+    }
+    if (e == hipSuccess) e = hipEventRecord(ev[0], st);
+    for (int32_t i = 0; i < iters && e == hipSuccess; ++i) e = launch_bwd_delta(p, st);
+    if (e == hipSuccess) e = hipEventRecord(ev[1], st);
+    set_worklist(&p, worklist_dkdv, lay_dkdv);
+    for (int32_t i = 0; i < iters && e == hipSuccess; ++i) e = launch_bwd_dkdv(p, st);
+    if (e == hipSuccess) e = hipEventRecord(ev[2], st);
+    set_worklist(&p, worklist_dq, lay_dq);
+    for (int32_t i = 0; i < iters && e == hipSuccess; ++i) e = launch_bwd_dq(p, st);
+    if (e == hipSuccess) e = hipEventRecord(ev[3], st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     double sum[3] = {0.0, 0.0, 0.0};
-    for (int32_t i = 0; i < iters && e == hipSuccess; ++i)
-        for (int s = 0; s < 3 && e == hipSuccess; ++s) {
-            float t = 0.0f;
-            e = hipEventElapsedTime(&t, ev[(size_t)i * 4 + s], ev[(size_t)i * 4 + s + 1]);
-            sum[s] += t;
-        }
+    for (int s = 0; s < 3 && e == hipSuccess; ++s) {
+        float t = 0.0f;
+        e = hipEventElapsedTime(&t, ev[s], ev[s + 1]);
+        sum[s] = t;
+    }
     destroy();
     if (e != hipSuccess) return fail(VA_EHIP, "%s: %s", who, hipGetErrorString(e));
     for (int s = 0; s < 3; ++s) ms[s] = (float)(sum[s] / iters);
