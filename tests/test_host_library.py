@@ -168,6 +168,7 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     assert call(va.make_shape(**{**ok, "head_dim": 96}))[0] == va.VA_EUNSUPPORTED
     assert call(va.make_shape(**{**ok, "num_q_heads": 3}))[0] == va.VA_EUNSUPPORTED
     assert call(va.make_shape(**{**ok, "max_seqlen": 59}))[0] == va.VA_ESIZE
+    assert call(va.make_shape(**{**ok, "max_seqlen": 1 << 29}))[0] == va.VA_ESIZE       # 32-bit buffer offsets
     assert call(va.make_shape(**{**ok, "total_tokens": 101}))[0] == va.VA_EINVAL
     assert call(va.make_shape(**ok), cu_=np.array([0, 60, 40], dtype=np.int32))[0] == va.VA_EINVAL
     assert call(va.make_shape(**ok), cu_=np.array([1, 40, 100], dtype=np.int32))[0] == va.VA_EINVAL
