@@ -3,8 +3,9 @@
 // FlashAttention scheme for this; the schedule below is this library's own):
 //
 //   1. delta[h, r] = sum_d dO[r,h,d] * O[r,h,d]                (memory bound)
-//   2. dK/dV: one workgroup per (key tile of 128 rows, KV head).  The K and V
-//      fragments of the tile stay in registers; the workgroup walks over the
+//   2. dK/dV: one workgroup per (key tile of 128 rows, KV head).  The K
+//      fragments of the tile stay in registers (the V fragments too at D = 64;
+//      at D >= 128 the V tile stays in LDS); the workgroup walks over the
 //      query tiles that see the key tile, for every query head of the group,
 //      and accumulates dV^T += dO^T P and dK^T += Q^T dS in registers.
 //   3. dQ: one workgroup per (query tile, head group), the mirror image of the
