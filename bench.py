@@ -92,7 +92,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default=WORKLOAD, choices=["vlm", "pi05", "longtail", "tiny"])
+    ap.add_argument("--workload", default=WORKLOAD, choices=["vlm", "pi05", "longtail", "vit", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a device-to-device copy of 256 MiB three times, the reference that scales the "

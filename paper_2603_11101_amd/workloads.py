@@ -8,8 +8,9 @@ without sharing any logic.  It imports neither of them.
 The paper trains VLA backbones on multi-camera robot samples: a few hundred
 image tokens per camera, a short instruction and a handful of state/action
 tokens (section 2.2.1 for the Qwen2.5-VL decoder, section 2.2.2 for pi-0.5).
-Its datasets are not available here, so the five workloads below draw lengths
-with that structure from fixed seeds:
+Its datasets are not available here, so the workloads below draw lengths
+with that structure from fixed seeds (`vit` stands for the vision side, which
+the paper runs through the same variable-length interface, section 2.2.1 (1)):
 
   tiny      3 samples of 17, 64, 95 tokens; 2 q heads / 2 kv heads, D = 64; causal
   vlm       pool of 512 samples: 256 * U{1,2,3} image tokens + U{10..60} text
@@ -20,6 +21,9 @@ with that structure from fixed seeds:
   longtail  pool of 2048: lognormal lengths (median 600, sigma 0.8) clipped to
             [16, 4096]; 16 / 8 heads, D = 128; causal; budget 65536
   vlm_fp8   the `vlm` lengths and values, for the FP8 forward
+  vit       pool of 512 images of side U{16,24,32,38} patches, side^2 tokens
+            each; 16 / 16 heads, D = 128; every token sees its whole image
+            (prefix = length); budget 16384
 
 Tensor values are float32 standard normal draws rounded once to bfloat16
 (round-to-nearest-even), from a stream separate from the one that draws the
@@ -48,6 +52,7 @@ WORKLOADS = {
     "pi05": Workload("pi05", 3, 8, 1, 256, True, 32768, 512),
     "longtail": Workload("longtail", 4, 16, 8, 128, False, 65536, 2048),
     "vlm_fp8": Workload("vlm_fp8", 2, 16, 8, 128, False, 16384, 512),
+    "vit": Workload("vit", 5, 16, 16, 128, True, 16384, 512),
 }
 
 
@@ -65,6 +70,10 @@ def sample_lengths(name: str):
         text = r.integers(20, 201, size=w.pool)
         prefix = 768 + text
         return (prefix + 50).astype(np.int32), prefix.astype(np.int32)
+    if name == "vit":
+        side = r.choice(np.array([16, 24, 32, 38]), size=w.pool)
+        L = (side * side).astype(np.int32)
+        return L, L.copy()
     if name == "longtail":
         z = r.standard_normal(w.pool)
         L = np.clip(np.rint(np.exp(np.log(600.0) + 0.8 * z)), 16, 4096)

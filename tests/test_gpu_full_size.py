@@ -39,7 +39,7 @@ def pick(lens, count):
     return sel[:count]
 
 
-@pytest.mark.parametrize("name,count", [("vlm", 30), ("pi05", 6), ("longtail", 7)])
+@pytest.mark.parametrize("name,count", [("vlm", 30), ("pi05", 6), ("longtail", 7), ("vit", 6)])
 def test_full_size_forward_backward(name, count):
     w, lens, cu, pl, mx = bin0(name)
     T, Hq, Hkv, D = int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim

@@ -105,7 +105,7 @@ def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
 
 def test_worklist_counts_on_the_workloads():
     # closed-form item and key-tile counts for the first bin of each workload
-    for name in ("vlm", "pi05", "longtail"):
+    for name in ("vlm", "pi05", "longtail", "vit"):
         w = wl.WORKLOADS[name]
         lens, prefix = wl.sample_lengths(name)
         b, p, n = va.va_pack_first_fit(lens, w.budget)
