@@ -35,7 +35,17 @@ def allowed_pairs(lens, prefix):
     if prefix is None:
         return int((lens * (lens + 1) // 2).sum())
     prefix = np.asarray(prefix, dtype=np.int64)
+    if prefix.ndim == 2:  # three blocks ending at P, P2, L: each row sees its own block and those before it
+        P, P2 = prefix[:, 0], prefix[:, 1]
+        return int((P * P + (P2 - P) * P2 + (lens - P2) * lens).sum())
     return int((prefix * prefix + (lens - prefix) * lens).sum())
+
+
+def mask_modes(w, va):
+    """(library mask mode, oracle mask mode) of a workload"""
+    if w.three_block:
+        return va.VA_MASK_THREE_BLOCK, 3
+    return (va.VA_MASK_PREFIX_LM, 1) if w.prefix_lm else (va.VA_MASK_CAUSAL, 0)
 
 
 def build_bin(name, va, wl, which=0):
@@ -74,8 +84,8 @@ def cpu_baseline(name, va, wl, budget_s=12.0, max_s=30.0):
         q, k, v, do = wl.tensor_values(w.seed + 1000 * bins, int(cu[-1]), Hq, Hkv, D)
         scale = 1.0 / float(np.sqrt(D))
         t0 = time.perf_counter()
-        oa.attn_fwd(q, k, v, cu, prefix, scale=scale)
-        oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale)
+        oa.attn_fwd(q, k, v, cu, prefix, scale=scale, mask_mode=mask_modes(w, va)[1])
+        oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=mask_modes(w, va)[1])
         dt += time.perf_counter() - t0
         flops += f
         tokens += int(cu[-1])
@@ -92,7 +102,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default=WORKLOAD, choices=["vlm", "pi05", "longtail", "vit", "tiny"])
+    ap.add_argument("--workload", default=WORKLOAD, choices=["vlm", "pi05", "pi0", "longtail", "vit", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a device-to-device copy of 256 MiB three times, the reference that scales the "
@@ -112,7 +122,7 @@ def main():
     dev = "cuda:0"
     w, lens, prefix, cu, pl, mx = build_bin0(args.workload, va, wl)
     T, Hq, Hkv, D = int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim
-    mask = va.VA_MASK_PREFIX_LM if w.prefix_lm else va.VA_MASK_CAUSAL
+    mask = mask_modes(w, va)[0]
     scale = 1.0 / float(np.sqrt(D))
     pairs = allowed_pairs(lens, prefix)
     flops_fwd = 4.0 * D * Hq * pairs
@@ -239,7 +249,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: bin 0 of the first-fit packing, {len(lens)} samples, {T} tokens, "
                                f"{Hq} q heads / {Hkv} kv heads, head_dim {D}, "
-                               f"{'prefix-LM' if w.prefix_lm else 'causal'}, budget {w.budget}",
+                               f"{'three-block' if w.three_block else 'prefix-LM' if w.prefix_lm else 'causal'}, budget {w.budget}",
                    "tokens": T, "samples": int(len(lens)), "pairs_per_head": pairs,
                    "buffer_sets": NUM_BUFFER_SETS},
         "tokens_per_s": T / (ms_per_step * 1e-3),

@@ -31,7 +31,13 @@
  *       VA_MASK_CAUSAL                vis(i) = i + 1
  *       VA_MASK_PREFIX_LM             vis(i) = P if i < P else L
  *       VA_MASK_PREFIX_LM_CAUSAL      vis(i) = P if i < P else i + 1
- *     with P = prefix_lens[s], 0 <= P <= L.
+ *       VA_MASK_THREE_BLOCK           vis(i) = P if i < P, P2 if i < P2, else L
+ *     with P = prefix_lens[s], 0 <= P <= L.  Under VA_MASK_THREE_BLOCK a sample
+ *     is three blocks [0, P), [P, P2), [P2, L), each seeing itself and the
+ *     blocks before it (the prefix / state / action layout of flow-matching
+ *     action experts, the family section 2.2.2 adapts), and prefix_lens holds
+ *     2 * num_seqs entries: P = prefix_lens[2 s], P2 = prefix_lens[2 s + 1],
+ *     0 <= P <= P2 <= L.
  *   - LSE[h, r] = ln sum_j exp(scale * q_r . k_j) over the visible keys
  *     (natural logarithm, scale included).
  */
@@ -55,6 +61,7 @@ extern "C" {
 #define VA_MASK_CAUSAL 0
 #define VA_MASK_PREFIX_LM 1
 #define VA_MASK_PREFIX_LM_CAUSAL 2
+#define VA_MASK_THREE_BLOCK 3
 
 #define VA_PASS_FWD 0
 #define VA_PASS_BWD_DKDV 1
@@ -95,6 +102,8 @@ int va_pack_first_fit(const int32_t* lens, int32_t N, int32_t budget,
  *   lens[n], prefix[n] (prefix may be NULL)  host in, in placement order
  *   cu_seqlens[n+1]   host out, cu_seqlens[0] = 0
  *   prefix_lens[n]    host out (may be NULL when prefix is NULL); VA_EINVAL unless 0 <= P <= L
+ * (one boundary per sample; the two boundaries of VA_MASK_THREE_BLOCK go through it one at a
+ * time, or are handed to va_build_worklist directly)
  *   max_seqlen        host out
  */
 int va_bin_layout(const int32_t* lens, const int32_t* prefix, int32_t n,
@@ -111,7 +120,7 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
 
 /*
  * Work list of one pass over one packed stream, in records of 8 int32 words:
- *   record 0   {magic "VAW2", pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
+ *   record 0   {magic "VAW3", pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
  *   record 1   {num_workgroups, num_works, works_per_item, first item record (2),
  *               first table record, first work-id record, total records, 0}
  *   items      num_items records, heaviest first (ties by sample, then tile)
@@ -121,8 +130,10 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
  * Only tiles holding at least one visible (query, key) pair are listed and no
  * tile spans two samples (the varlen rule of section 2.2.1 (1): compute on
  * valid tokens only).
- *   forward / dQ item: {q_row0, q_rows, seq_row0, kv_len, n_full, n_tiles, P or -1, L}
- *   dK/dV item:        {kv_row0, kv_rows, seq_row0, qt_first, qt_count, 0, P or -1, L}
+ *   forward / dQ item: {q_row0, q_rows, seq_row0, P2 or -1, n_full, n_tiles, P or -1, L}
+ *   dK/dV item:        {kv_row0, kv_rows, seq_row0, qt_first, qt_count, P2 or -1, P or -1, L}
+ * (n_tiles key tiles hold a key some row of the item sees, the first n_full of them
+ * no hidden pair; P and P2 are the sample's block ends, -1 where the mask has none)
  * A work is one item for one head chunk: the query heads one workgroup stacks
  * (forward, dQ) or one KV head (dK/dV), so works_per_item depends on the head
  * counts the list was built for.  The kernels run num_workgroups persistent
@@ -161,7 +172,8 @@ size_t varlen_attn_bwd_workspace_bytes(const va_shape* shape);
  * Forward: O = softmax(scale * Q K^T + mask) V per sample, and LSE.
  *   q, k, v        device in   bfloat16
  *   cu_seqlens     host  in    [num_seqs + 1] (validated here: monotone, [0] = 0, last = T)
- *   prefix_lens    host  in    [num_seqs], NULL allowed for VA_MASK_CAUSAL (validated: 0 <= P <= L);
+ *   prefix_lens    host  in    [num_seqs] ([2 num_seqs] under VA_MASK_THREE_BLOCK), NULL allowed for
+ *                              VA_MASK_CAUSAL (validated: 0 <= P <= L, and P <= P2 <= L);
  *                              the kernels take each sample's P from the work list built from it
  *   scale          positive and finite
  *   worklist       device in   copy of va_build_worklist(VA_PASS_FWD)

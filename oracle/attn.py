@@ -15,6 +15,7 @@ from . import build as _build
 MASK_CAUSAL = 0
 MASK_PREFIX_BIDIR_SUFFIX = 1
 MASK_PREFIX_CAUSAL_SUFFIX = 2
+MASK_THREE_BLOCK = 3     # prefix_lens holds [num_seqs, 2]: the ends (P, P2) of the first two blocks
 
 _lib = None
 

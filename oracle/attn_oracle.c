@@ -21,6 +21,9 @@
  *     vis(i) = i + 1                      causal
  *            = P  if i < P, else L        prefix-LM with prefix length P
  *            = i + 1 if i >= P (mode 2)   prefix-LM, causal suffix
+ *            = P if i < P, P2 if i < P2, else L   (mode 3) three blocks, each seeing
+ *              itself and the blocks before it; prefix_lens then holds the pair
+ *              (P, P2), 0 <= P <= P2 <= L, for every sample
  *     s_ij  = scale * sum_d Q[c+i,h,d] K[c+j,g,d]        for j < vis(i)
  *     m_i   = max_j s_ij,  Z_i = sum_j exp(s_ij - m_i)
  *     LSE[h,c+i] = m_i + ln Z_i
@@ -51,14 +54,29 @@
 #define ORACLE_MASK_CAUSAL 0
 #define ORACLE_MASK_PREFIX_BIDIR_SUFFIX 1
 #define ORACLE_MASK_PREFIX_CAUSAL_SUFFIX 2
+#define ORACLE_MASK_THREE_BLOCK 3
 
-/* number of keys query row i of a sample (length L, prefix P) may attend to */
-static int visible(int i, int L, int P, int mode)
+/* number of keys query row i of a sample (length L, block ends P and P2) may attend to */
+static int visible(int i, int L, int P, int P2, int mode)
 {
     if (mode == ORACLE_MASK_CAUSAL) return i + 1;
     if (i < P) return P;
     if (mode == ORACLE_MASK_PREFIX_BIDIR_SUFFIX) return L;
+    if (mode == ORACLE_MASK_THREE_BLOCK) return i < P2 ? P2 : L;
     return i + 1;
+}
+
+/* block ends of sample s: prefix_lens holds one entry per sample, or the pair (P, P2) in mode 3 */
+static void block_ends(const int32_t *prefix_lens, int mode, int s, int *P, int *P2)
+{
+    *P = 0;
+    *P2 = 0;
+    if (mode == ORACLE_MASK_THREE_BLOCK) {
+        *P = prefix_lens[2 * s];
+        *P2 = prefix_lens[2 * s + 1];
+    } else if (mode != ORACLE_MASK_CAUSAL) {
+        *P = prefix_lens[s];
+    }
 }
 
 int oracle_num_threads(void)
@@ -123,9 +141,10 @@ int oracle_attn_fwd(const float *q, const float *k, const float *v,
             const int g = h / G;
             const int c = cu_seqlens[s];
             const int L = cu_seqlens[s + 1] - c;
-            const int P = (mask_mode == ORACLE_MASK_CAUSAL) ? 0 : prefix_lens[s];
+            int P, P2;
+            block_ends(prefix_lens, mask_mode, s, &P, &P2);
             for (int i = 0; i < L; ++i) {
-                const int nvis = visible(i, L, P, mask_mode);
+                const int nvis = visible(i, L, P, P2, mask_mode);
                 const float *q_row = q + ((size_t)(c + i) * Hq + h) * D;
                 const float *k_base = k + ((size_t)c * Hkv + g) * D;
                 const float *v_base = v + ((size_t)c * Hkv + g) * D;
@@ -176,7 +195,8 @@ int oracle_attn_bwd(const float *q, const float *k, const float *v, const float 
             const int g = w % Hkv;
             const int c = cu_seqlens[s];
             const int L = cu_seqlens[s + 1] - c;
-            const int P = (mask_mode == ORACLE_MASK_CAUSAL) ? 0 : prefix_lens[s];
+            int P, P2;
+            block_ends(prefix_lens, mask_mode, s, &P, &P2);
             const size_t kv_stride = (size_t)Hkv * D;
             const float *k_base = k + ((size_t)c * Hkv + g) * D;
             const float *v_base = v + ((size_t)c * Hkv + g) * D;
@@ -189,7 +209,7 @@ int oracle_attn_bwd(const float *q, const float *k, const float *v, const float 
                 }
             for (int h = g * G; h < (g + 1) * G; ++h) {
                 for (int i = 0; i < L; ++i) {
-                    const int nvis = visible(i, L, P, mask_mode);
+                    const int nvis = visible(i, L, P, P2, mask_mode);
                     const float *q_row = q + ((size_t)(c + i) * Hq + h) * D;
                     const float *do_row = dout + ((size_t)(c + i) * Hq + h) * D;
                     double *dq_row = dq + ((size_t)(c + i) * Hq + h) * D;
@@ -240,14 +260,15 @@ int oracle_attn_probs(const float *q, const float *k, const float *v, const floa
     const int g = h / G;
     const int c = cu_seqlens[s];
     const int L = cu_seqlens[s + 1] - c;
-    const int P = (mask_mode == ORACLE_MASK_CAUSAL) ? 0 : prefix_lens[s];
+    int P, P2;
+    block_ends(prefix_lens, mask_mode, s, &P, &P2);
     const size_t kv_stride = (size_t)Hkv * D;
     const float *k_base = k + ((size_t)c * Hkv + g) * D;
     const float *v_base = v + ((size_t)c * Hkv + g) * D;
     double *p = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
     double *o = (double *)malloc(sizeof(double) * (size_t)D);
     for (int i = 0; i < L; ++i) {
-        const int nvis = visible(i, L, P, mask_mode);
+        const int nvis = visible(i, L, P, P2, mask_mode);
         const float *q_row = q + ((size_t)(c + i) * Hq + h) * D;
         row_softmax(q_row, k_base, kv_stride, nvis, D, scale, p);
         for (int j = 0; j < L; ++j) p_out[(size_t)i * L + j] = j < nvis ? p[j] : 0.0;

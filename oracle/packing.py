@@ -19,9 +19,10 @@ and no tile spans two samples.  Items are 8 int32 words:
     0 q_row0      absolute first row of the tile in the stream
     1 q_rows      valid rows in the tile (<= bm)
     2 seq_row0    first row of the sample (cu_seqlens[s])
-    3 kv_len      keys visible to at least one row of the tile
+    3 block2_end  P2_s under the three-block mask, else -1
     4 n_full      leading key tiles in which every (row, key) pair is allowed
-    5 n_tiles     key tiles visited = ceil(kv_len / bn)
+    5 n_tiles     key tiles visited = ceil(kv_len / bn), kv_len = keys visible
+                  to at least one row of the tile
     6 prefix_len  P_s, or -1 when the stream is causal
     7 seq_len     L_s
 
@@ -32,7 +33,7 @@ and no tile spans two samples.  Items are 8 int32 words:
     3 qt_first    index (within the sample) of the first query tile, of ``bm``
                   rows, that holds a row seeing a key of this tile
     4 qt_count    number of query tiles from qt_first to the end of the sample
-    5 reserved    0
+    5 block2_end  P2_s under the three-block mask, else -1
     6 prefix_len  P_s or -1
     7 seq_len     L_s
 
@@ -48,6 +49,7 @@ PASS_BWD_DQ = 2
 MASK_CAUSAL = 0
 MASK_PREFIX_BIDIR_SUFFIX = 1
 MASK_PREFIX_CAUSAL_SUFFIX = 2
+MASK_THREE_BLOCK = 3      # prefix_lens holds [num_seqs, 2]: the ends (P, P2) of the first two blocks
 
 
 def first_fit(lens, budget):
@@ -89,11 +91,14 @@ def bin_layout(lens, prefix=None):
     for L in lens:
         cu.append(cu[-1] + int(L))
     mx = max([int(L) for L in lens], default=0)
-    pl = None if prefix is None else np.array([int(p) for p in prefix], dtype=np.int32)
+    # one entry per sample, or the pair of block ends of the three-block mask
+    pl = None if prefix is None else np.array([[int(x) for x in np.atleast_1d(p)] for p in prefix], dtype=np.int32)
+    if pl is not None and pl.shape[1:] == (1,):
+        pl = pl[:, 0]
     return np.array(cu, dtype=np.int32), pl, mx
 
 
-def visible(i, L, P, mode):
+def visible(i, L, P, mode, P2=-1):
     """Number of keys local query row i may attend to."""
     if mode == MASK_CAUSAL:
         return i + 1
@@ -101,11 +106,23 @@ def visible(i, L, P, mode):
         return P
     if mode == MASK_PREFIX_BIDIR_SUFFIX:
         return L
+    if mode == MASK_THREE_BLOCK:
+        return P2 if i < P2 else L
     return i + 1
 
 
-def allowed(i, j, L, P, mode):
-    return 0 <= j < visible(i, L, P, mode)
+def allowed(i, j, L, P, mode, P2=-1):
+    return 0 <= j < visible(i, L, P, mode, P2)
+
+
+def block_ends(prefix_lens, mode, s):
+    """(P, P2) of sample s as stored in an item: -1 where the mask has no such boundary."""
+    if mode == MASK_CAUSAL:
+        return -1, -1
+    if mode == MASK_THREE_BLOCK:
+        pair = np.asarray(prefix_lens).reshape(-1, 2)[s]
+        return int(pair[0]), int(pair[1])
+    return int(prefix_lens[s]), -1
 
 
 def _mode(prefix_lens, mask_mode):
@@ -124,14 +141,14 @@ def build_worklist(cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=None):
     for s in range(n):
         c = int(cu_seqlens[s])
         L = int(cu_seqlens[s + 1]) - c
-        P = -1 if mode == MASK_CAUSAL else int(prefix_lens[s])
+        P, P2 = block_ends(prefix_lens, mode, s)
         if pass_id in (PASS_FWD, PASS_BWD_DQ):
             for t in range((L + bm - 1) // bm):
                 rows = range(t * bm, min(L, (t + 1) * bm))
                 kv_len = 0
                 for i in rows:
                     for j in range(L):
-                        if allowed(i, j, L, P, mode):
+                        if allowed(i, j, L, P, mode, P2):
                             kv_len = max(kv_len, j + 1)
                 n_tiles = (kv_len + bn - 1) // bn
                 n_full = 0
@@ -141,22 +158,22 @@ def build_worklist(cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=None):
                     ok = (kt + 1) * bn <= L
                     for i in rows:
                         for j in range(kt * bn, min(L, (kt + 1) * bn)):
-                            ok = ok and allowed(i, j, L, P, mode)
+                            ok = ok and allowed(i, j, L, P, mode, P2)
                     if ok:
                         n_full += 1
-                items.append(((n_tiles, s, t), [c + t * bm, len(rows), c, kv_len, n_full, n_tiles, P, L]))
+                items.append(((n_tiles, s, t), [c + t * bm, len(rows), c, P2, n_full, n_tiles, P, L]))
         else:
             for kt in range((L + bn - 1) // bn):
                 keys = range(kt * bn, min(L, (kt + 1) * bn))
                 first_row = None
                 for i in range(L):
-                    if any(allowed(i, j, L, P, mode) for j in keys):
+                    if any(allowed(i, j, L, P, mode, P2) for j in keys):
                         first_row = i
                         break
                 assert first_row is not None  # every key is seen by its own row
                 qt_first = first_row // bm
                 qt_count = (L + bm - 1) // bm - qt_first
-                items.append(((qt_count, s, kt), [c + kt * bn, len(keys), c, qt_first, qt_count, 0, P, L]))
+                items.append(((qt_count, s, kt), [c + kt * bn, len(keys), c, qt_first, qt_count, P2, P, L]))
     items.sort(key=lambda e: (-e[0][0], e[0][1], e[0][2]))
     if not items:
         return np.zeros((0, 8), dtype=np.int32)
@@ -181,17 +198,19 @@ def check_coverage(items, cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=No
         s = int(sample_of_row[a])
         assert s >= 0 and int(cu_seqlens[s]) == c and int(cu_seqlens[s + 1]) - c == L, "wrong sample fields"
         assert a + rows <= c + L, "tile crosses the end of its sample"
-        assert P == (-1 if mode == MASK_CAUSAL else int(prefix_lens[s])), "wrong prefix"
+        wantP, wantP2 = block_ends(prefix_lens, mode, s)
+        assert P == wantP, "wrong prefix"
         if pass_id in (PASS_FWD, PASS_BWD_DQ):
             assert (a - c) % bm == 0 and rows <= bm
-            kv_len, n_full, n_tiles = w3, w4, w5
-            assert n_tiles == (kv_len + bn - 1) // bn and n_full <= n_tiles and kv_len <= L
+            P2, n_full, n_tiles = w3, w4, w5
+            assert P2 == wantP2, "wrong end of the second block"
+            assert n_full <= n_tiles and (n_tiles - 1) * bn < L
             for kt in range(n_tiles):
                 pairs = 0
                 masked = 0
                 for i in range(a - c, a - c + rows):
                     for j in range(kt * bn, (kt + 1) * bn):
-                        if j < L and allowed(i, j, L, P, mode):
+                        if j < L and allowed(i, j, L, P, mode, P2):
                             pairs += 1
                             key = (s, i, j)
                             seen[key] = seen.get(key, 0) + 1
@@ -202,13 +221,14 @@ def check_coverage(items, cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=No
                     assert masked == 0, "tile marked full holds a masked pair"
         else:
             assert (a - c) % bn == 0 and rows <= bn
-            qt_first, qt_count = w3, w4
+            qt_first, qt_count, P2 = w3, w4, w5
+            assert P2 == wantP2, "wrong end of the second block"
             assert qt_first + qt_count == (L + bm - 1) // bm
             pairs_first = 0
             for qt in range(qt_first, qt_first + qt_count):
                 for i in range(qt * bm, min(L, (qt + 1) * bm)):
                     for j in range(a - c, a - c + rows):
-                        if allowed(i, j, L, P, mode):
+                        if allowed(i, j, L, P, mode, P2):
                             key = (s, i, j)
                             seen[key] = seen.get(key, 0) + 1
                             if qt == qt_first:
@@ -218,16 +238,16 @@ def check_coverage(items, cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=No
     for s in range(n):
         c = int(cu_seqlens[s])
         L = int(cu_seqlens[s + 1]) - c
-        P = -1 if mode == MASK_CAUSAL else int(prefix_lens[s])
+        P, P2 = block_ends(prefix_lens, mode, s)
         for i in range(L):
             for j in range(L):
-                if allowed(i, j, L, P, mode):
+                if allowed(i, j, L, P, mode, P2):
                     total += 1
                     assert seen.get((s, i, j), 0) == 1, f"pair {(s, i, j)} visited {seen.get((s, i, j), 0)} times"
     assert total == len(seen), "a pair outside the mask was visited"
     return total
 
 
-def allowed_pairs(L, P, mode):
+def allowed_pairs(L, P, mode, P2=-1):
     """Number of allowed (query, key) pairs of one sample, by counting."""
-    return sum(visible(i, L, P, mode) for i in range(L))
+    return sum(visible(i, L, P, mode, P2) for i in range(L))

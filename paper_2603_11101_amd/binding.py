@@ -15,7 +15,7 @@ import torch  # noqa: F401
 
 VA_OK = 0
 VA_EINVAL, VA_EUNSUPPORTED, VA_EALIGN, VA_ESIZE, VA_EHIP = -1, -2, -3, -4, -5
-VA_MASK_CAUSAL, VA_MASK_PREFIX_LM, VA_MASK_PREFIX_LM_CAUSAL = 0, 1, 2
+VA_MASK_CAUSAL, VA_MASK_PREFIX_LM, VA_MASK_PREFIX_LM_CAUSAL, VA_MASK_THREE_BLOCK = 0, 1, 2, 3
 VA_PASS_FWD, VA_PASS_BWD_DKDV, VA_PASS_BWD_DQ = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -62,6 +62,19 @@ def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
+def _prefix(prefix_lens, mask_mode, num_seqs):
+    """The prefix_lens argument as the C side reads it: one entry per sample, or the pairs (P, P2)
+    of VA_MASK_THREE_BLOCK, given as [num_seqs, 2] or flat.  The library cannot see the array's
+    length, so it is checked here."""
+    if prefix_lens is None:
+        return None
+    pl = _i32(prefix_lens).reshape(-1)
+    want = 2 * num_seqs if mask_mode == VA_MASK_THREE_BLOCK else num_seqs
+    if mask_mode != VA_MASK_CAUSAL and pl.size != want:
+        raise ValueError(f"prefix_lens holds {pl.size} entries, mask mode {mask_mode} needs {want}")
+    return pl
+
+
 def _ptr(a):
     """Pointer of a numpy array, a torch tensor, or None."""
     if a is None:
@@ -93,8 +106,13 @@ def va_pack_first_fit(lens, budget):
 
 
 def va_bin_layout(lens, prefix=None):
+    """cu_seqlens, prefix_lens, max_seqlen of one bin.  A [n, 2] ``prefix`` (the block ends of
+    VA_MASK_THREE_BLOCK) goes through the library one column at a time and comes back as [n, 2]."""
     lens = _i32(lens)
     n = len(lens)
+    if prefix is not None and np.ndim(prefix) == 2:
+        cols = [va_bin_layout(lens, np.asarray(prefix)[:, j]) for j in range(2)]
+        return cols[0][0], np.stack([cols[0][1], cols[1][1]], axis=1), cols[0][2]
     pre = None if prefix is None else _i32(prefix)
     cu = np.zeros(n + 1, dtype=np.int32)
     pl = None if prefix is None else np.zeros(n, dtype=np.int32)
@@ -123,7 +141,7 @@ def va_build_worklist(cu_seqlens, prefix_lens, mask_mode, pass_id, head_dim, num
     """Returns the whole work list as an int32 array of 8-word records (see ``worklist_items`` and
     ``worklist_schedule`` for its parts)."""
     cu = _i32(cu_seqlens)
-    pl = None if prefix_lens is None else _i32(prefix_lens)
+    pl = _prefix(prefix_lens, mask_mode, len(cu) - 1)
     nbytes = va_worklist_bytes(cu, pass_id, head_dim, num_q_heads, num_kv_heads)
     buf = np.zeros((nbytes // 32, 8), dtype=np.int32)
     n_items = ctypes.c_int32(0)
@@ -179,7 +197,7 @@ def varlen_attn_bwd_workspace_bytes(shape):
 
 def varlen_attn_fwd(q, k, v, cu_seqlens, prefix_lens, worklist, worklist_host, shape, scale, out, lse, stream=None):
     cu = _i32(cu_seqlens)
-    pl = None if prefix_lens is None else _i32(prefix_lens)
+    pl = _prefix(prefix_lens, shape.mask_mode, len(cu) - 1)
     _check(_lib.varlen_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(cu), _ptr(pl), _ptr(worklist), _ptr(worklist_host),
                                 ctypes.byref(shape), ctypes.c_float(scale), _ptr(out), _ptr(lse), _stream_ptr(stream)))
 
@@ -187,7 +205,7 @@ def varlen_attn_fwd(q, k, v, cu_seqlens, prefix_lens, worklist, worklist_host, s
 def varlen_attn_bwd(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
                     worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes, stream=None):
     cu = _i32(cu_seqlens)
-    pl = None if prefix_lens is None else _i32(prefix_lens)
+    pl = _prefix(prefix_lens, shape.mask_mode, len(cu) - 1)
     _check(_lib.varlen_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(cu), _ptr(pl),
                                 _ptr(worklist_dkdv), _ptr(worklist_dkdv_host), _ptr(worklist_dq), _ptr(worklist_dq_host),
                                 ctypes.byref(shape), ctypes.c_float(scale), _ptr(dq), _ptr(dk), _ptr(dv),
@@ -199,7 +217,7 @@ def varlen_attn_bwd_profile(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, wo
                             stream=None, iters=1):
     """Returns average milliseconds per launch of (delta, dK/dV, dQ); waits for the stream."""
     cu = _i32(cu_seqlens)
-    pl = None if prefix_lens is None else _i32(prefix_lens)
+    pl = _prefix(prefix_lens, shape.mask_mode, len(cu) - 1)
     ms = (ctypes.c_float * 3)()
     _check(_lib.varlen_attn_bwd_profile(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(cu), _ptr(pl),
                                         _ptr(worklist_dkdv), _ptr(worklist_dkdv_host), _ptr(worklist_dq),
@@ -212,7 +230,7 @@ def varlen_attn_bwd_profile(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, wo
 def varlen_attn_fwd_fp8(q8, k8, v8, q_descale, k_descale, v_descale, cu_seqlens, prefix_lens, worklist, worklist_host,
                         shape, scale, out, lse, stream=None):
     cu = _i32(cu_seqlens)
-    pl = None if prefix_lens is None else _i32(prefix_lens)
+    pl = _prefix(prefix_lens, shape.mask_mode, len(cu) - 1)
     _check(_lib.varlen_attn_fwd_fp8(_ptr(q8), _ptr(k8), _ptr(v8), _ptr(q_descale), _ptr(k_descale), _ptr(v_descale),
                                     _ptr(cu), _ptr(pl), _ptr(worklist), _ptr(worklist_host), ctypes.byref(shape),
                                     ctypes.c_float(scale), _ptr(out), _ptr(lse), _stream_ptr(stream)))
@@ -226,7 +244,7 @@ class PackedStream:
     def __init__(self, cu_seqlens, prefix_lens, mask_mode, num_q_heads, num_kv_heads, head_dim,
                  max_seqlen=None, device="cuda:0", passes=(VA_PASS_FWD, VA_PASS_BWD_DKDV, VA_PASS_BWD_DQ)):
         self.cu_seqlens = _i32(cu_seqlens)
-        self.prefix_lens = None if prefix_lens is None else _i32(prefix_lens)
+        self.prefix_lens = _prefix(prefix_lens, int(mask_mode), len(self.cu_seqlens) - 1)
         self.mask_mode = int(mask_mode)
         n = len(self.cu_seqlens) - 1
         lens = np.diff(self.cu_seqlens)

@@ -23,7 +23,7 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
     if (s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->num_q_heads % s->num_kv_heads != 0)
         return fail(VA_EUNSUPPORTED, "%s: num_q_heads %d is not a positive multiple of num_kv_heads %d", who,
                     s->num_q_heads, s->num_kv_heads);
-    if (s->mask_mode < VA_MASK_CAUSAL || s->mask_mode > VA_MASK_PREFIX_LM_CAUSAL)
+    if (s->mask_mode < VA_MASK_CAUSAL || s->mask_mode > VA_MASK_THREE_BLOCK)
         return fail(VA_EUNSUPPORTED, "%s: unknown mask mode %d", who, s->mask_mode);
     if (s->num_seqs < 0 || s->total_tokens < 0) return fail(VA_EINVAL, "%s: negative sizes", who);
     if (cu[0] != 0) return fail(VA_EINVAL, "%s: cu_seqlens[0] = %d, expected 0", who, cu[0]);
@@ -32,8 +32,10 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
         if (L < 0) return fail(VA_EINVAL, "%s: cu_seqlens decreases at sample %d", who, i);
         if (L > s->max_seqlen)
             return fail(VA_ESIZE, "%s: sample %d has %d tokens, max_seqlen is %d", who, i, L, s->max_seqlen);
-        if (s->mask_mode != VA_MASK_CAUSAL && (prefix_lens[i] < 0 || prefix_lens[i] > L))
-            return fail(VA_EINVAL, "%s: prefix_lens[%d] = %d outside [0, %d]", who, i, prefix_lens[i], L);
+        int32_t P, P2;
+        block_ends(prefix_lens, s->mask_mode, i, &P, &P2);
+        if (!block_ends_valid(P, P2, L, s->mask_mode))
+            return fail(VA_EINVAL, "%s: block ends (%d, %d) of sample %d outside [0, %d] or out of order", who, P, P2, i, L);
     }
     if (cu[s->num_seqs] != s->total_tokens)
         return fail(VA_EINVAL, "%s: cu_seqlens ends at %d, total_tokens is %d", who, cu[s->num_seqs], s->total_tokens);
@@ -73,19 +75,25 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
     for (int32_t i = 0; i < n; ++i) {
         const int32_t* it = w[lay.item_rec + i].w;
         const int32_t row0 = it[0], nrows = it[1], seq0 = it[2], L = it[7];
+        const int32_t P = it[6], P2 = it[pass == VA_PASS_BWD_DKDV ? 5 : 3];
         const bool ok = nrows > 0 && nrows <= rows && seq0 >= 0 && L > 0 && row0 >= seq0 && row0 + nrows <= seq0 + L &&
-                        seq0 + L <= s->total_tokens && it[6] <= L && (row0 - seq0) % rows == 0;
+                        seq0 + L <= s->total_tokens && (row0 - seq0) % rows == 0 &&
+                        (s->mask_mode == VA_MASK_CAUSAL ? P == -1 : block_ends_valid(P, P2, L, s->mask_mode)) &&
+                        (s->mask_mode == VA_MASK_THREE_BLOCK || P2 == -1);
         if (!ok) return fail(VA_EINVAL, "%s: work item %d is out of bounds", who, i);
         // (seq0, L) must be one of the samples of cu_seqlens
         const int32_t* lo = std::lower_bound(cu, cu + s->num_seqs, seq0);
         while (lo < cu + s->num_seqs && lo[0] == seq0 && lo[1] == seq0) ++lo;  // skip empty samples at this row
         if (lo >= cu + s->num_seqs || lo[0] != seq0 || lo[1] - lo[0] != L)
             return fail(VA_EINVAL, "%s: work item %d does not match a sample of cu_seqlens", who, i);
+        const int32_t Pm = P < 0 ? 0 : P, P2m = P2 < 0 ? 0 : P2;
         if (pass == VA_PASS_BWD_DKDV) {
             if (it[3] < 0 || it[4] <= 0 || it[3] + it[4] != (L + cols - 1) / cols)
                 return fail(VA_EINVAL, "%s: work item %d has a bad query-tile range", who, i);
         } else {
-            if (it[3] <= 0 || it[3] > L || it[5] != (it[3] + cols - 1) / cols || it[4] < 0 || it[4] > it[5])
+            const int32_t r0 = row0 - seq0;
+            const int32_t kv_len = visible(r0 + nrows - 1, L, Pm, P2m, s->mask_mode);
+            if (it[5] != (kv_len + cols - 1) / cols || it[4] < 0 || it[4] > visible(r0, L, Pm, P2m, s->mask_mode) / cols)
                 return fail(VA_EINVAL, "%s: work item %d has a bad key range", who, i);
         }
     }

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
 
 // What one workgroup needs to know about a dK/dV work (all wave-uniform).
 struct DkdvWork {
-    int kv_row0, kv_rows, seq_row0, qt_first, qt_count, P, L, g;
+    int kv_row0, kv_rows, seq_row0, qt_first, qt_count, P2, P, L, g;
 };
 
 VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int id) {
@@ -83,6 +83,7 @@ VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int id) {
     w.seq_row0 = it.w[2];
     w.qt_first = it.w[3];
     w.qt_count = it.w[4];
+    w.P2 = it.w[5];
     w.P = it.w[6];
     w.L = it.w[7];
     w.g = id % p.works_per_item;
@@ -98,7 +99,7 @@ VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int id) {
 //   V_LDS  the V rows of the key tile live in LDS (second operand of dP = dO V^T) instead of registers:
 //          that buys the register room for two workgroups per CU at D = 128 and for both accumulators
 //          (256 registers per lane, in the accumulation registers) at D = 256
-template <int D, bool V_LDS>
+template <int D, bool V_LDS, bool THREE>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnParams p) {
     constexpr bool V_IN_LDS = V_LDS, V_REGS = !V_LDS;
     constexpr int BMQ = dkdv_q_tile(D);  // query rows staged per step
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 
     {
         const int n_steps = G * cur.qt_count;
-        const RowMask mask(cur.P, cur.L, p.mask_mode);
+        const RowMask mask(cur.P, cur.P2, cur.L, p.mask_mode);
         const int L = cur.L;
         // this wave's 32 key rows; the lane owns key row jw + l32 (local index in the sample)
         const int jw = cur.kv_row0 - cur.seq_row0 + 32 * wave;
@@ -209,9 +210,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                 const int i0 = q0 + 32 * qb;  // first query row of the block (local index in the sample)
                 if (i0 >= L) break;
                 const int i1 = min(i0 + 31, L - 1);
-                if (mask.vis(i1) <= jw) continue;  // nothing of this key block is visible
+                if (mask.vis<THREE>(i1) <= jw) continue;  // nothing of this key block is visible
                 // rows past the sample read as zeros and must get p = 0: they count as seeing no key
-                const bool need_mask = mask.vis(i0) < jw + 32 || i0 + 32 > L;
+                const bool need_mask = mask.vis<THREE>(i0) < jw + 32 || i0 + 32 > L;
 
                 // S = Q K^T and dP = dO V^T: rows = query rows (registers), columns = key rows (lanes).
                 // MFMAs alternate between the two accumulators so that none waits on the one just issued.
@@ -289,7 +290,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                     const int row_base = q0 + 32 * qb + 4 * hf;  // query row of register 0, local to the sample
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        if (key >= mask.vis_in_sample(row_base + 8 * (r / 4) + r % 4)) {
+                        if (key >= mask.vis_in_sample<THREE>(row_base + 8 * (r / 4) + r % 4)) {
                             s[r] = 0.0f;
                             dp[r] = 0.0f;
                         }
@@ -439,7 +440,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         const DqWork nxt = works.peek_next();
         const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
         const int tok = row % BMT;
-        const int vis = RowMask(cur.P, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
+        const int vis = RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
 
         f32x16 dq[DT];
 #pragma unroll
@@ -605,9 +606,18 @@ hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     // two stages of (Q tile, dO tile, LSE, delta), then the V tile / output staging region
     constexpr size_t smem = 2 * (2 * dkdv_q_tile(D) * D * 2 + 2 * 64 * sizeof(float)) + kDkdvKvRows * D * 2;
     const unsigned grid = (unsigned)(p.num_items * p.works_per_item);
-    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS>), smem);
-    if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS>), dim3(grid), dim3(256), smem, stream, p);
+    // one instantiation per mask family: the masks without a second block do not pay for it
+    if (p.mask_mode == VA_MASK_THREE_BLOCK) {
+        static const hipError_t attr =
+            allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, true>), smem);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, true>), dim3(grid), dim3(256), smem, stream, p);
+    } else {
+        static const hipError_t attr =
+            allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, false>), smem);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, false>), dim3(grid), dim3(256), smem, stream, p);
+    }
     return hipGetLastError();
 }
 

@@ -15,7 +15,7 @@ struct WorkItem {
 };
 static_assert(sizeof(WorkItem) == 32, "work items are 32 bytes");
 
-constexpr int32_t kWorklistMagic = 0x56415732;  // "VAW2"
+constexpr int32_t kWorklistMagic = 0x56415733;  // "VAW3"
 
 // Work-list layout, in 32-byte records:
 //   record 0   {magic, pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
@@ -49,6 +49,34 @@ constexpr int32_t dkdv_q_tile(int32_t D) { return D >= 128 ? 32 : 64; }
 constexpr int32_t persistent_workgroups(int32_t /*pass*/, int32_t D) { return D <= 128 ? 512 : 256; }
 // Cost of a work in units of inner-loop steps: its steps plus a fixed part for the item switch.
 constexpr int32_t kWorkFixedCost = 2;
+
+// Number of keys local query row i of a sample may see: length L, block ends P and P2 (values below 0
+// stand for "no such boundary" and are taken as 0).
+inline int32_t visible(int32_t i, int32_t L, int32_t P, int32_t P2, int32_t mode) {
+    if (mode == VA_MASK_CAUSAL) return i + 1;
+    if (i < P) return P;
+    if (mode == VA_MASK_PREFIX_LM) return L;
+    if (mode == VA_MASK_THREE_BLOCK) return i < P2 ? P2 : L;
+    return i + 1;
+}
+// Block ends of sample s as stored in the work items (-1 where the mask has no such boundary), from the
+// caller's prefix_lens: one entry per sample, or the pair (P, P2) under VA_MASK_THREE_BLOCK.
+inline void block_ends(const int32_t* prefix_lens, int32_t mode, int32_t s, int32_t* P, int32_t* P2) {
+    *P = -1;
+    *P2 = -1;
+    if (mode == VA_MASK_THREE_BLOCK) {
+        *P = prefix_lens[2 * s];
+        *P2 = prefix_lens[2 * s + 1];
+    } else if (mode != VA_MASK_CAUSAL) {
+        *P = prefix_lens[s];
+    }
+}
+// 0 <= P <= L, and P <= P2 <= L under VA_MASK_THREE_BLOCK
+inline bool block_ends_valid(int32_t P, int32_t P2, int32_t L, int32_t mode) {
+    if (mode == VA_MASK_CAUSAL) return true;
+    if (P < 0 || P > L) return false;
+    return mode != VA_MASK_THREE_BLOCK || (P2 >= P && P2 <= L);
+}
 
 extern thread_local char g_error[512];
 int works_per_item(int32_t pass, int32_t Hq, int32_t Hkv);

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
         const int tok = row % BMT;
         const bool row_valid = tok < cur.q_rows;
-        const int vis = RowMask(cur.P, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
+        const int vis = RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
 
         f32x16 o[DT];
 #pragma unroll

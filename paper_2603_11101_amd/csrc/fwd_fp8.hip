@@ -226,7 +226,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
         const RowWork nxt = works.peek_next();
         const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
         const bool row_valid = tok < cur.q_rows;
-        const int vis = RowMask(cur.P, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
+        const int vis = RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
         const float c = c_row;
         const float v_descale = p.v_descale[cur.g];
 

@@ -25,13 +25,6 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
-// Number of keys local query row i of a sample (length L, prefix P) may see.
-static inline int32_t visible(int32_t i, int32_t L, int32_t P, int32_t mode) {
-    if (mode == VA_MASK_CAUSAL) return i + 1;
-    if (i < P) return P;
-    return mode == VA_MASK_PREFIX_LM ? L : i + 1;
-}
-
 // Heads of one KV group that a forward / dQ workgroup stacks on its 128 rows.
 int heads_per_block(int32_t Hq, int32_t Hkv) {
     const int G = Hq / Hkv;
@@ -169,7 +162,7 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
                       int32_t mask_mode, int32_t pass, int32_t D, int32_t Hq, int32_t Hkv,
                       void* host_out, size_t bytes, int32_t* num_items) {
     if (!host_out || !num_items) return fail(VA_EINVAL, "va_build_worklist: null pointer");
-    if (mask_mode < VA_MASK_CAUSAL || mask_mode > VA_MASK_PREFIX_LM_CAUSAL)
+    if (mask_mode < VA_MASK_CAUSAL || mask_mode > VA_MASK_THREE_BLOCK)
         return fail(VA_EUNSUPPORTED, "va_build_worklist: unknown mask mode %d", mask_mode);
     if (mask_mode != VA_MASK_CAUSAL && !prefix_lens)
         return fail(VA_EINVAL, "va_build_worklist: prefix mask needs prefix_lens");
@@ -187,13 +180,12 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
     std::vector<Keyed> items;
     for (int32_t s = 0; s < n; ++s) {
         const int32_t c = cu[s], L = cu[s + 1] - c;
-        int32_t P = -1;
-        if (mask_mode != VA_MASK_CAUSAL) {
-            P = prefix_lens[s];
-            if (P < 0 || P > L)
-                return fail(VA_EINVAL, "va_build_worklist: prefix_lens[%d] = %d outside [0, %d]", s, P, L);
-        }
-        const int32_t Pm = P < 0 ? 0 : P;
+        int32_t P, P2;
+        block_ends(prefix_lens, mask_mode, s, &P, &P2);
+        if (!block_ends_valid(P, P2, L, mask_mode))
+            return fail(VA_EINVAL, "va_build_worklist: block ends (%d, %d) of sample %d outside [0, %d] or out of order",
+                        P, P2, s, L);
+        const int32_t Pm = P < 0 ? 0 : P, P2m = P2 < 0 ? 0 : P2;
         if (pass == VA_PASS_BWD_DKDV) {
             // item rows are key rows (bm), inner tiles are query tiles (bn)
             const int32_t q_tiles = (L + bn - 1) / bn;
@@ -201,18 +193,20 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
                 int32_t first_row;  // first query row that sees key j0
                 if (mask_mode == VA_MASK_CAUSAL) first_row = j0;
                 else if (j0 < Pm) first_row = 0;
-                else first_row = mask_mode == VA_MASK_PREFIX_LM ? Pm : j0;
+                else if (mask_mode == VA_MASK_PREFIX_LM) first_row = Pm;
+                else if (mask_mode == VA_MASK_THREE_BLOCK) first_row = j0 < P2m ? Pm : P2m;
+                else first_row = j0;
                 const int32_t qt_first = first_row / bn;
-                WorkItem it = {{c + j0, std::min(bm, L - j0), c, qt_first, q_tiles - qt_first, 0, P, L}};
+                WorkItem it = {{c + j0, std::min(bm, L - j0), c, qt_first, q_tiles - qt_first, P2, P, L}};
                 items.push_back({it.w[4], it});
             }
         } else {
             for (int32_t r0 = 0; r0 < L; r0 += bm) {
                 const int32_t rows = std::min(bm, L - r0);
-                const int32_t kv_len = visible(r0 + rows - 1, L, Pm, mask_mode);
+                const int32_t kv_len = visible(r0 + rows - 1, L, Pm, P2m, mask_mode);
                 const int32_t n_tiles = (kv_len + bn - 1) / bn;
-                const int32_t n_full = visible(r0, L, Pm, mask_mode) / bn;
-                WorkItem it = {{c + r0, rows, c, kv_len, n_full, n_tiles, P, L}};
+                const int32_t n_full = visible(r0, L, Pm, P2m, mask_mode) / bn;
+                WorkItem it = {{c + r0, rows, c, P2, n_full, n_tiles, P, L}};
                 items.push_back({n_tiles, it});
             }
         }

@@ -58,13 +58,29 @@ VA_DEV float pair_sum(float x) {
 // non-decreasing: causal i + 1; prefix-LM P for i < P, else L; prefix-LM with causal suffix P for
 // i < P, else i + 1.  Branch-free so that it can sit in per-element code.
 struct RowMask {
-    int P;   // prefix length (0 when causal)
-    int SF;  // L when suffix rows see the whole sample, else 0
+    int P;   // end of the first block (0 when causal)
+    int P2;  // end of the second block (0 unless the mask has three blocks)
+    int SF;  // L when the rows behind the blocks see the whole sample, else 0
     int L;
-    VA_DEV RowMask(int item_P, int item_L, int mode)
-        : P(item_P < 0 ? 0 : item_P), SF(mode == VA_MASK_PREFIX_LM ? item_L : 0), L(item_L) {}
-    VA_DEV int vis(int i) const { return i < P ? P : max(i + 1, SF); }  // any i >= 0
-    VA_DEV int vis_in_sample(int i) const { return i < L ? vis(i) : 0; }  // rows past the sample see nothing
+    VA_DEV RowMask(int item_P, int item_P2, int item_L, int mode)
+        : P(item_P < 0 ? 0 : item_P),
+          P2(item_P2 < 0 ? 0 : item_P2),
+          SF(mode == VA_MASK_PREFIX_LM || mode == VA_MASK_THREE_BLOCK ? item_L : 0),
+          L(item_L) {}
+    // Every arm is computed before it is chosen, so that these stay selects and never become branches.
+    // THREE = false leaves the second block out: for kernels instantiated per mask family, where the
+    // extra select per row would be paid by the masks that have no second block.
+    template <bool THREE = true>
+    VA_DEV int vis(int i) const {  // any i >= 0
+        const int behind = max(i + 1, SF);
+        const int second = (THREE && i < P2) ? P2 : behind;
+        return i < P ? P : second;
+    }
+    template <bool THREE = true>
+    VA_DEV int vis_in_sample(int i) const {  // rows past the sample see nothing
+        const int v = vis<THREE>(i);
+        return i < L ? v : 0;
+    }
 };
 
 // ---------------------------------------------------------------- LDS tiles

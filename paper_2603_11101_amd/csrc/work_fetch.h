@@ -15,7 +15,7 @@ namespace va {
 
 // One work of the forward or dQ kernel: an item and the query heads the workgroup stacks (all wave-uniform).
 struct RowWork {
-    int q_row0, q_rows, seq_row0, n_full, n_tiles, P, L, g, h0;
+    int q_row0, q_rows, seq_row0, P2, n_full, n_tiles, P, L, g, h0;
 };
 
 template <int HPB>
@@ -41,6 +41,7 @@ struct RowWorkStream {
         w.q_row0 = __builtin_amdgcn_readlane(v, 0);
         w.q_rows = __builtin_amdgcn_readlane(v, 1);
         w.seq_row0 = __builtin_amdgcn_readlane(v, 2);
+        w.P2 = __builtin_amdgcn_readlane(v, 3);
         w.n_full = __builtin_amdgcn_readlane(v, 4);
         w.n_tiles = __builtin_amdgcn_readlane(v, 5);
         w.P = __builtin_amdgcn_readlane(v, 6);

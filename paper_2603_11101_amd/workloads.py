@@ -21,6 +21,11 @@ the paper runs through the same variable-length interface, section 2.2.1 (1)):
   longtail  pool of 2048: lognormal lengths (median 600, sigma 0.8) clipped to
             [16, 4096]; 16 / 8 heads, D = 128; causal; budget 65536
   vlm_fp8   the `vlm` lengths and values, for the FP8 forward
+  pi0       pool of 512: three blocks, each seeing itself and those before it:
+            768 image + U{20..200} text tokens, one state token, 50 action
+            tokens; 8 / 1 heads, D = 256; budget 32768; the second value
+            returned by sample_lengths is then [pool, 2]: the ends of the first
+            two blocks
   vit       pool of 512 images of side U{16,24,32,38} patches, side^2 tokens
             each; 16 / 16 heads, D = 128; every token sees its whole image
             (prefix = length); budget 16384
@@ -44,6 +49,7 @@ class Workload:
     prefix_lm: bool
     budget: int
     pool: int
+    three_block: bool = False
 
 
 WORKLOADS = {
@@ -53,6 +59,7 @@ WORKLOADS = {
     "longtail": Workload("longtail", 4, 16, 8, 128, False, 65536, 2048),
     "vlm_fp8": Workload("vlm_fp8", 2, 16, 8, 128, False, 16384, 512),
     "vit": Workload("vit", 5, 16, 16, 128, True, 16384, 512),
+    "pi0": Workload("pi0", 6, 8, 1, 256, True, 32768, 512, three_block=True),
 }
 
 
@@ -74,6 +81,11 @@ def sample_lengths(name: str):
         side = r.choice(np.array([16, 24, 32, 38]), size=w.pool)
         L = (side * side).astype(np.int32)
         return L, L.copy()
+    if name == "pi0":
+        text = r.integers(20, 201, size=w.pool)
+        prefix = 768 + text
+        ends = np.stack([prefix, prefix + 1], axis=1).astype(np.int32)
+        return (prefix + 51).astype(np.int32), ends
     if name == "longtail":
         z = r.standard_normal(w.pool)
         L = np.clip(np.rint(np.exp(np.log(600.0) + 0.8 * z)), 16, 4096)
@@ -122,3 +134,16 @@ def random_stream(seed: int, lens, Hq: int, Hkv: int, D: int, prefix_frac=None):
                            for L in lens], dtype=np.int32)
     q, k, v, do = tensor_values(seed, int(cu[-1]), Hq, Hkv, D)
     return cu, prefix, q, k, v, do
+
+
+def random_block_ends(seed: int, lens) -> np.ndarray:
+    """[num_seqs, 2] int32 ends (P, P2) of the first two of three blocks, 0 <= P <= P2 <= L, for tests
+    of the three-block mask; empty blocks occur."""
+    r = np.random.default_rng(88000 + seed)
+    out = np.zeros((len(lens), 2), dtype=np.int32)
+    for s, L in enumerate(lens):
+        L = int(L)
+        P = int(r.integers(0, L + 1))
+        out[s] = (P, int(r.integers(P, L + 1)))
+    return out
+

@@ -26,8 +26,10 @@ def main():
         bin_of, pos, nb = op.first_fit(lens, w.budget)
         idx = op.bin_members(bin_of, pos, 0)
         L = [int(lens[i]) for i in idx]
-        mode = op.MASK_PREFIX_BIDIR_SUFFIX if w.prefix_lm else op.MASK_CAUSAL
-        if w.prefix_lm:
+        mode = op.MASK_THREE_BLOCK if w.three_block else op.MASK_PREFIX_BIDIR_SUFFIX if w.prefix_lm else op.MASK_CAUSAL
+        if w.three_block:
+            pairs = sum(op.allowed_pairs(int(lens[i]), int(prefix[i][0]), mode, int(prefix[i][1])) for i in idx)
+        elif w.prefix_lm:
             pairs = sum(int(prefix[i]) ** 2 + (int(lens[i]) - int(prefix[i])) * int(lens[i]) for i in idx)
         else:
             pairs = sum(l * (l + 1) // 2 for l in L)

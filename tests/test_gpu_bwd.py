@@ -12,7 +12,7 @@ from gpu_util import DeviceRun, TOL_FWD_REL, TOL_GRAD_REL, TOL_LSE_ABS, max_abs,
 pytestmark = pytest.mark.gpu
 
 MODES = {va.VA_MASK_CAUSAL: oa.MASK_CAUSAL, va.VA_MASK_PREFIX_LM: oa.MASK_PREFIX_BIDIR_SUFFIX,
-         va.VA_MASK_PREFIX_LM_CAUSAL: oa.MASK_PREFIX_CAUSAL_SUFFIX}
+         va.VA_MASK_PREFIX_LM_CAUSAL: oa.MASK_PREFIX_CAUSAL_SUFFIX, va.VA_MASK_THREE_BLOCK: oa.MASK_THREE_BLOCK}
 
 
 def check_bwd(run, ref, cu, label):
@@ -49,6 +49,9 @@ def test_backward_parity(mode, Hq, Hkv, D):
     cu, prefix, q, k, v, do = wl.random_stream(seed, LENS, Hq, Hkv, D, prefix_frac=-1.0)
     if mode == va.VA_MASK_CAUSAL:
         prefix = None
+    elif mode == va.VA_MASK_THREE_BLOCK:
+        prefix = wl.random_block_ends(seed, LENS)
+        prefix[3], prefix[7], prefix[5] = (200, 200), (0, 0), (0, 130)   # one block only, three ways
     else:
         prefix[3], prefix[7] = 200, 0
     scale = 1.0 / np.sqrt(D)

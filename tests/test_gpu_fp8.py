@@ -43,18 +43,20 @@ def run_fp8(cu, prefix, mode, q, k, v, scale):
 
 
 @pytest.mark.parametrize("mode,Hq,Hkv", [(va.VA_MASK_CAUSAL, 4, 2), (va.VA_MASK_PREFIX_LM, 8, 1), (va.VA_MASK_CAUSAL, 2, 2),
-                                         (va.VA_MASK_PREFIX_LM_CAUSAL, 4, 1)])
+                                         (va.VA_MASK_PREFIX_LM_CAUSAL, 4, 1), (va.VA_MASK_THREE_BLOCK, 4, 2)])
 def test_fp8_forward_parity(mode, Hq, Hkv):
     D = 128
     lens = [17, 64, 95, 200, 1, 130, 0, 257]
     cu, prefix, q, k, v, _ = wl.random_stream(50 + Hq + mode, lens, Hq, Hkv, D, prefix_frac=-1.0)
     if mode == va.VA_MASK_CAUSAL:
         prefix = None
+    elif mode == va.VA_MASK_THREE_BLOCK:
+        prefix = wl.random_block_ends(50 + Hq, lens)
     scale = 1.0 / np.sqrt(D)
     print(f"fp8 forward mode={mode} Hq={Hq} Hkv={Hkv}", flush=True)
     out, lse, (qd, kd, vd) = run_fp8(cu, prefix, mode, q, k, v, scale)
     omode = {va.VA_MASK_CAUSAL: oa.MASK_CAUSAL, va.VA_MASK_PREFIX_LM: oa.MASK_PREFIX_BIDIR_SUFFIX,
-             va.VA_MASK_PREFIX_LM_CAUSAL: oa.MASK_PREFIX_CAUSAL_SUFFIX}[mode]
+             va.VA_MASK_PREFIX_LM_CAUSAL: oa.MASK_PREFIX_CAUSAL_SUFFIX, va.VA_MASK_THREE_BLOCK: oa.MASK_THREE_BLOCK}[mode]
     ref_out, ref_lse = oa.attn_fwd(qd, kd, vd, cu, prefix, scale=scale, mask_mode=omode)
     print(f"  out rel-L2 {rel_l2(out, ref_out):.2e} max-abs {max_abs(out, ref_out):.2e} lse max-abs {max_abs(lse, ref_lse):.2e}",
           flush=True)

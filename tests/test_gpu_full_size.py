@@ -39,12 +39,12 @@ def pick(lens, count):
     return sel[:count]
 
 
-@pytest.mark.parametrize("name,count", [("vlm", 30), ("pi05", 6), ("longtail", 7), ("vit", 6)])
+@pytest.mark.parametrize("name,count", [("vlm", 30), ("pi05", 6), ("longtail", 7), ("vit", 6), ("pi0", 5)])
 def test_full_size_forward_backward(name, count):
     w, lens, cu, pl, mx = bin0(name)
     T, Hq, Hkv, D = int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim
-    mode = va.VA_MASK_PREFIX_LM if w.prefix_lm else va.VA_MASK_CAUSAL
-    omode = oa.MASK_PREFIX_BIDIR_SUFFIX if w.prefix_lm else oa.MASK_CAUSAL
+    mode = va.VA_MASK_THREE_BLOCK if w.three_block else va.VA_MASK_PREFIX_LM if w.prefix_lm else va.VA_MASK_CAUSAL
+    omode = oa.MASK_THREE_BLOCK if w.three_block else oa.MASK_PREFIX_BIDIR_SUFFIX if w.prefix_lm else oa.MASK_CAUSAL
     scale = 1.0 / np.sqrt(D)
     q, k, v, do = wl.tensor_values(w.seed, T, Hq, Hkv, D)
     sel = pick(lens, min(count, len(lens)))

@@ -63,14 +63,17 @@ def test_first_fit_random_and_edge_cases():
 HEADS = [(2, 2, 64), (16, 8, 128), (8, 1, 256), (4, 1, 64), (6, 2, 128)]
 
 
-@pytest.mark.parametrize("mode", [va.VA_MASK_CAUSAL, va.VA_MASK_PREFIX_LM, va.VA_MASK_PREFIX_LM_CAUSAL])
+@pytest.mark.parametrize("mode", [va.VA_MASK_CAUSAL, va.VA_MASK_PREFIX_LM, va.VA_MASK_PREFIX_LM_CAUSAL, va.VA_MASK_THREE_BLOCK])
 @pytest.mark.parametrize("Hq,Hkv,D", HEADS)
 def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
     r = np.random.default_rng(Hq * 1000 + D + mode)
     lens = np.concatenate([[1, 0, 300, 129, 64, 17], r.integers(1, 260, size=5)]).astype(np.int32)
     cu, _, _ = va.va_bin_layout(lens)
     prefix = None if mode == va.VA_MASK_CAUSAL else np.array([int(r.integers(0, L + 1)) for L in lens], dtype=np.int32)
-    if prefix is not None:
+    if mode == va.VA_MASK_THREE_BLOCK:
+        prefix = wl.random_block_ends(Hq * 1000 + D, lens)
+        prefix[2], prefix[3], prefix[4] = (300, 300), (0, 0), (0, 64)    # one block only, three ways
+    elif prefix is not None:
         prefix[2], prefix[3] = 300, 0    # degenerate: whole sample is prefix / no prefix at all
     for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DKDV, va.VA_PASS_BWD_DQ):
         rows, cols = va.va_tile_shape(pass_id, D, Hq, Hkv)
@@ -96,6 +99,8 @@ def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
     small = np.array([1, 70, 33, 130], dtype=np.int32)
     cu_s, _, _ = va.va_bin_layout(small)
     pre_s = None if mode == va.VA_MASK_CAUSAL else np.array([1, 40, 0, 97], dtype=np.int32)
+    if mode == va.VA_MASK_THREE_BLOCK:
+        pre_s = np.array([[0, 1], [10, 40], [0, 0], [64, 97]], dtype=np.int32)
     for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DKDV, va.VA_PASS_BWD_DQ):
         rows, cols = va.va_tile_shape(pass_id, D, Hq, Hkv)
         bm, bn = (cols, rows) if pass_id == va.VA_PASS_BWD_DKDV else (rows, cols)
@@ -191,3 +196,23 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     for bad in (other, tampered, wrong_pass, bad_table, bad_id):
         assert call(va.make_shape(**ok), wl_=np.ascontiguousarray(bad))[0] == va.VA_EINVAL
     assert va.varlen_attn_bwd_workspace_bytes(va.make_shape(**ok)) >= 100 * Hq * 4
+
+
+def test_three_block_ends_are_validated():
+    cu = np.array([0, 10, 30], dtype=np.int32)
+    for bad in ([[4, 3], [0, 0]], [[0, 11], [0, 0]], [[-1, 5], [0, 0]], [[0, 0], [5, 21]]):
+        with pytest.raises(va.VarlenAttnError) as e:
+            va.va_build_worklist(cu, np.array(bad, dtype=np.int32), va.VA_MASK_THREE_BLOCK, va.VA_PASS_FWD, 64, 2, 2)
+        assert e.value.code == va.VA_EINVAL and "block ends" in str(e.value)
+    with pytest.raises(ValueError):      # one entry per sample is not enough for this mask
+        va.va_build_worklist(cu, np.array([3, 4], dtype=np.int32), va.VA_MASK_THREE_BLOCK, va.VA_PASS_FWD, 64, 2, 2)
+    with pytest.raises(va.VarlenAttnError) as e:
+        va.va_build_worklist(cu, np.array([3, 4], dtype=np.int32), 4, va.VA_PASS_FWD, 64, 2, 2)
+    assert e.value.code == va.VA_EUNSUPPORTED
+    # both boundaries land in the items: P in word 6, P2 in word 3 (forward, dQ) or 5 (dK/dV)
+    ends = np.array([[2, 7], [20, 20]], dtype=np.int32)
+    for pass_id, word in ((va.VA_PASS_FWD, 3), (va.VA_PASS_BWD_DQ, 3), (va.VA_PASS_BWD_DKDV, 5)):
+        items = va.worklist_items(va.va_build_worklist(cu, ends, va.VA_MASK_THREE_BLOCK, pass_id, 64, 2, 2))
+        for it in items:
+            s = 0 if it[2] == 0 else 1
+            assert (it[6], it[word]) == tuple(ends[s])

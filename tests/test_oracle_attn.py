@@ -283,3 +283,67 @@ def test_sel_restricts_to_chosen_samples_and_zero_length_samples_are_legal():
     sl = slice(cu[2], cu[3])
     assert np.array_equal(out_s[sl], out[sl]) and np.isnan(out_s[:cu[2]]).all() and np.isnan(out_s[cu[3]:]).all()
     assert not np.isnan(out).any() and not np.isnan(lse).any()
+
+
+# ---------------------------------------------------------------- three-block mask
+#
+# Blocks [0, P), [P, P2), [P2, L): a row sees its own block and the blocks before it.  The dense mask
+# below is written from that sentence (by block index), not from the oracle's visible() rule.
+
+def three_block_mask(L, P, P2):
+    block = (np.arange(L) >= P).astype(int) + (np.arange(L) >= P2).astype(int)
+    return block[None, :] <= block[:, None]
+
+
+def test_three_block_against_dense_definition_and_autograd():
+    Hq, Hkv, D = 4, 2, 8
+    lens = [23, 9, 14]
+    ends = np.array([[7, 15], [0, 4], [14, 14]], dtype=np.int32)   # ordinary; empty first block; empty last two
+    cu, _, q, k, v, do = stream(11, lens, Hq, Hkv, D)
+    scale = 0.41
+    out, lse = oa.attn_fwd(q, k, v, cu, ends, scale=scale, mask_mode=oa.MASK_THREE_BLOCK)
+    dq, dk, dv = oa.attn_bwd(q, k, v, do, cu, ends, scale=scale, mask_mode=oa.MASK_THREE_BLOCK)
+    G = Hq // Hkv
+    for s, L in enumerate(lens):
+        c = cu[s]
+        mask = torch.from_numpy(three_block_mask(L, ends[s, 0], ends[s, 1]))
+        tq = torch.tensor(q[c:c + L].astype(np.float64), requires_grad=True)
+        tk = torch.tensor(k[c:c + L].astype(np.float64), requires_grad=True)
+        tv = torch.tensor(v[c:c + L].astype(np.float64), requires_grad=True)
+        sc = torch.einsum("ihd,jhd->hij", tq, tk.repeat_interleave(G, dim=1)) * scale
+        sc = sc.masked_fill(~mask[None], float("-inf"))
+        o = torch.einsum("hij,jhd->ihd", torch.softmax(sc, dim=-1), tv.repeat_interleave(G, dim=1))
+        (o * torch.tensor(do[c:c + L].astype(np.float64))).sum().backward()
+        assert np.allclose(out[c:c + L], o.detach().numpy(), rtol=1e-12, atol=1e-13)
+        assert np.allclose(lse[:, c:c + L], torch.logsumexp(sc, dim=-1).detach().numpy(), rtol=0, atol=1e-12)
+        assert np.allclose(dq[c:c + L], tq.grad.numpy(), rtol=1e-11, atol=1e-12)
+        assert np.allclose(dk[c:c + L], tk.grad.numpy(), rtol=1e-11, atol=1e-12)
+        assert np.allclose(dv[c:c + L], tv.grad.numpy(), rtol=1e-11, atol=1e-12)
+        for h in range(Hq):
+            p, ds = oa.attn_probs(q, k, v, do, cu, ends, s, h, scale=scale, mask_mode=oa.MASK_THREE_BLOCK)
+            assert np.all((p > 0) == mask.numpy())
+            assert np.allclose(p.sum(axis=1), 1.0, atol=1e-14) and np.allclose(ds.sum(axis=1), 0.0, atol=1e-13)
+
+
+def test_three_block_degenerate_cases_reduce_to_the_prefix_mask():
+    Hq, Hkv, D = 2, 1, 8
+    lens = [19, 8]
+    cu, _, q, k, v, do = stream(12, lens, Hq, Hkv, D)
+    P = np.array([6, 3], dtype=np.int32)
+    L = np.array(lens, dtype=np.int32)
+    want = oa.attn_fwd(q, k, v, cu, P, mask_mode=oa.MASK_PREFIX_BIDIR_SUFFIX)
+    gwant = oa.attn_bwd(q, k, v, do, cu, P, mask_mode=oa.MASK_PREFIX_BIDIR_SUFFIX)
+    for ends in (np.stack([P, P], axis=1), np.stack([P, L], axis=1)):    # no middle block; no last block
+        got = oa.attn_fwd(q, k, v, cu, ends, mask_mode=oa.MASK_THREE_BLOCK)
+        ggot = oa.attn_bwd(q, k, v, do, cu, ends, mask_mode=oa.MASK_THREE_BLOCK)
+        assert all(np.array_equal(a, b) for a, b in zip(got + ggot, want + gwant))
+    # uniform keys: LSE_i = scale q_i.k + ln(number of visible keys)
+    k1 = np.repeat(k[:1], len(k), axis=0)
+    ends = np.array([[5, 12], [2, 7]], dtype=np.int32)
+    _, lse = oa.attn_fwd(q, k1, v, cu, ends, scale=0.5, mask_mode=oa.MASK_THREE_BLOCK)
+    for s, Ls in enumerate(lens):
+        for i in range(Ls):
+            nvis = ends[s, 0] if i < ends[s, 0] else ends[s, 1] if i < ends[s, 1] else Ls
+            for h in range(Hq):
+                want_lse = 0.5 * float(q[cu[s] + i, h].astype(np.float64) @ k1[0, 0].astype(np.float64)) + np.log(nvis)
+                assert abs(lse[h, cu[s] + i] - want_lse) < 1e-12

@@ -64,10 +64,30 @@ def test_worklists_cover_every_allowed_pair_exactly_once(mode, bm, bn):
     if items[0, 5] > 1:
         broken = items.copy()
         broken[0, 5] -= 1
-        broken[0, 3] = broken[0, 5] * bn
         broken[0, 4] = min(broken[0, 4], broken[0, 5])
         with pytest.raises(AssertionError):
             op.check_coverage(broken, cu, prefix, op.PASS_FWD, bm, bn, mode)
+
+
+@pytest.mark.parametrize("bm,bn", [(4, 4), (8, 4), (4, 8), (16, 8)])
+def test_three_block_worklists_cover_every_allowed_pair_exactly_once(bm, bn):
+    lens = [1, 13, 0, 8, 21, 4, 30]
+    cu, _, _ = op.bin_layout(lens)
+    ends = np.array([[0, 1], [5, 9], [0, 0], [8, 8], [0, 13], [0, 0], [11, 30]], dtype=np.int32)
+    mode = op.MASK_THREE_BLOCK
+    # pairs by block sizes a, b, c: a^2 + b (a + b) + c (a + b + c)
+    want_pairs = sum(P * P + (P2 - P) * P2 + (L - P2) * L for L, (P, P2) in zip(lens, ends.tolist()))
+    assert want_pairs == sum(op.allowed_pairs(L, P, mode, P2) for L, (P, P2) in zip(lens, ends.tolist()))
+    for pass_id in (op.PASS_FWD, op.PASS_BWD_DKDV, op.PASS_BWD_DQ):
+        items = op.build_worklist(cu, ends, pass_id, bm, bn, mode)
+        assert op.check_coverage(items, cu, ends, pass_id, bm, bn, mode) == want_pairs
+        assert np.all(items[:, 6] >= 0) and np.all(items[:, 5 if pass_id == op.PASS_BWD_DKDV else 3] >= items[:, 6])
+    # a planted defect is caught: the second boundary of one sample moved by one row
+    items = op.build_worklist(cu, ends, op.PASS_FWD, bm, bn, mode)
+    wrong = ends.copy()
+    wrong[1, 1] += 1
+    with pytest.raises(AssertionError):
+        op.check_coverage(items, cu, wrong, op.PASS_FWD, bm, bn, mode)
 
 
 def test_closed_form_counts_causal():
@@ -78,9 +98,9 @@ def test_closed_form_counts_causal():
     bm, bn = 16, 8
     items = op.build_worklist(cu, None, op.PASS_FWD, bm, bn)
     assert len(items) == sum(-(-L // bm) for L in lens)
-    for q_row0, q_rows, c, kv_len, n_full, n_tiles, P, L in items.tolist():
+    for q_row0, q_rows, c, P2, n_full, n_tiles, P, L in items.tolist():
         r0 = q_row0 - c
-        assert kv_len == r0 + q_rows and n_tiles == -(-(r0 + q_rows) // bn) and n_full == (r0 + 1) // bn and P == -1
+        assert P2 == -1 and n_tiles == -(-(r0 + q_rows) // bn) and n_full == (r0 + 1) // bn and P == -1
     assert items[:, 5].sum() == sum(-(-min(L, (t + 1) * bm) // bn) for L in lens for t in range(-(-L // bm)))
     dk = op.build_worklist(cu, None, op.PASS_BWD_DKDV, bm, bn)
     assert len(dk) == sum(-(-L // bn) for L in lens)
@@ -100,7 +120,7 @@ def test_closed_form_counts_prefix_lm():
         first_row = t * bm
         want_len = P if last_row < P else L
         min_vis = P if first_row < P else L
-        assert it[3] == want_len and it[5] == -(-want_len // bn) and it[4] == min_vis // bn and it[6] == P
+        assert it[3] == -1 and it[5] == -(-want_len // bn) and it[4] == min_vis // bn and it[6] == P
     assert op.allowed_pairs(L, P, op.MASK_PREFIX_BIDIR_SUFFIX) == P * P + (L - P) * L
     assert op.allowed_pairs(L, P, op.MASK_CAUSAL) == L * (L + 1) // 2
     assert op.allowed_pairs(L, P, op.MASK_PREFIX_CAUSAL_SUFFIX) == P * P + sum(i + 1 for i in range(P, L))
