@@ -189,8 +189,11 @@ int varlen_attn_fwd(const void* q, const void* k, const void* v,
 
 /*
  * Backward: dQ, dK, dV from dO, recomputing the probabilities from the saved
- * LSE.  Three kernels: delta = rowsum(dO * O); dK/dV per key tile; dQ per query
- * tile.  No atomics; results do not depend on scheduling.
+ * LSE.  delta = rowsum(dO * O) per row; dK/dV per key tile; dQ per query tile.
+ * At head_dim <= 128 the dQ kernel computes delta for its own rows (every row
+ * belongs to exactly one of its works), runs first, and the dK/dV kernel reads
+ * what it wrote: two kernels.  At head_dim 256 a separate pass over O and dO
+ * comes first: three kernels.  No atomics; results do not depend on scheduling.
  *   out, lse            device in   what varlen_attn_fwd wrote
  *   dout                device in   bfloat16 [T, Hq, D]
  *   worklist_dkdv/_dq   device in   va_build_worklist(VA_PASS_BWD_DKDV / VA_PASS_BWD_DQ)
@@ -220,13 +223,16 @@ int va_quantize_e4m3_per_head_device(const void* x_bf16, int32_t T, int32_t H, i
                                      void* codes, float* descale, void* stream);
 
 /*
- * Measurement aid: launches each of the three kernels of varlen_attn_bwd
- * `iters` times back to back (delta, then dK/dV, then dQ, so the results are
- * those of varlen_attn_bwd) between HIP events recorded on `stream`, waits for
- * the stream (the only entry point that synchronises) and writes the average
- * milliseconds per launch to the host array ms[3] = {delta, dK/dV, dQ}.
- * Same arguments and errors as varlen_attn_bwd; iters >= 1.
+ * Measurement aid: runs varlen_attn_bwd once, then launches each of its
+ * kernels `iters` times back to back (the results stay those of
+ * varlen_attn_bwd) between HIP events recorded on `stream`, waits for the
+ * stream (the only entry point that synchronises) and writes the average
+ * milliseconds per launch to the host array ms[3] = {delta, dK/dV, dQ};
+ * ms[0] is the bare distance of two events where no delta kernel exists
+ * (va_bwd_has_delta_kernel).  Same arguments and errors as varlen_attn_bwd;
+ * iters >= 1.
  */
+int va_bwd_has_delta_kernel(int32_t head_dim); /* 1 if varlen_attn_bwd launches the separate delta pass, else 0 */
 int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const void* out, const float* lse,
                             const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
                             const void* worklist_dkdv, const void* worklist_dkdv_host,

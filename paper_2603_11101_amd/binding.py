@@ -49,7 +49,7 @@ _lib = _load()
 
 EXPORTS = ["va_last_error", "va_pack_first_fit", "va_bin_layout", "va_tile_shape", "va_worklist_bytes",
            "va_build_worklist", "va_quantize_e4m3_per_head", "va_quantize_e4m3_per_head_device",
-           "varlen_attn_bwd_workspace_bytes",
+           "varlen_attn_bwd_workspace_bytes", "va_bwd_has_delta_kernel",
            "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_profile", "varlen_attn_fwd_fp8"]
 
 
@@ -193,6 +193,10 @@ def make_shape(total_tokens, num_seqs, num_q_heads, num_kv_heads, head_dim, max_
 
 def varlen_attn_bwd_workspace_bytes(shape):
     return int(_lib.varlen_attn_bwd_workspace_bytes(ctypes.byref(shape)))
+
+
+def va_bwd_has_delta_kernel(head_dim):
+    return bool(_lib.va_bwd_has_delta_kernel(ctypes.c_int32(head_dim)))
 
 
 def varlen_attn_fwd(q, k, v, cu_seqlens, prefix_lens, worklist, worklist_host, shape, scale, out, lse, stream=None):

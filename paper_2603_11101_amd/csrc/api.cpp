@@ -218,6 +218,33 @@ static int prepare_bwd(const char* who, const void* q, const void* k, const void
     return VA_OK;
 }
 
+// The kernels of one backward call, on one stream.  Where the dQ kernel computes delta and the rescaled
+// LSE itself it runs first and the dK/dV kernel, which reads both, after it; otherwise a pass over O and
+// dO comes first.
+static hipError_t launch_backward(AttnParams* p, hipStream_t st, const void* worklist_dkdv, const WorklistLayout& lay_dkdv,
+                                  const void* worklist_dq, const WorklistLayout& lay_dq) {
+    hipError_t e = hipSuccess;
+    if (dq_computes_delta(p->D)) {
+        set_worklist(p, worklist_dq, lay_dq);
+        e = launch_bwd_dq(*p, st);
+        if (e == hipSuccess) {
+            set_worklist(p, worklist_dkdv, lay_dkdv);
+            e = launch_bwd_dkdv(*p, st);
+        }
+        return e;
+    }
+    e = launch_bwd_delta(*p, st);
+    if (e == hipSuccess) {
+        set_worklist(p, worklist_dkdv, lay_dkdv);
+        e = launch_bwd_dkdv(*p, st);
+    }
+    if (e == hipSuccess) {
+        set_worklist(p, worklist_dq, lay_dq);
+        e = launch_bwd_dq(*p, st);
+    }
+    return e;
+}
+
 int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
                     const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
                     const void* worklist_dkdv, const void* worklist_dkdv_host,
@@ -234,18 +261,12 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
                          &p, &lay_dkdv, &lay_dq, &empty);
     if (rc || empty) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_bwd_delta(p, st);
-    if (e == hipSuccess) {
-        set_worklist(&p, worklist_dkdv, lay_dkdv);
-        e = launch_bwd_dkdv(p, st);
-    }
-    if (e == hipSuccess) {
-        set_worklist(&p, worklist_dq, lay_dq);
-        e = launch_bwd_dq(p, st);
-    }
+    const hipError_t e = launch_backward(&p, st, worklist_dkdv, lay_dkdv, worklist_dq, lay_dq);
     if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
     return VA_OK;
 }
+
+int va_bwd_has_delta_kernel(int32_t head_dim) { return dq_computes_delta(head_dim) ? 0 : 1; }
 
 int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const void* out, const float* lse,
                             const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
@@ -280,17 +301,10 @@ int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const v
             return fail(VA_EHIP, "%s: hipEventCreate failed", who);
         }
     // one untimed round first: the stream is busy and the clocks are up when the first event is reached
-    hipError_t e = launch_bwd_delta(p, st);
-    if (e == hipSuccess) {
-        set_worklist(&p, worklist_dkdv, lay_dkdv);
-        e = launch_bwd_dkdv(p, st);
-    }
-    if (e == hipSuccess) {
-        set_worklist(&p, worklist_dq, lay_dq);
-        e = launch_bwd_dq(p, st);
-    }
+    hipError_t e = launch_backward(&p, st, worklist_dkdv, lay_dkdv, worklist_dq, lay_dq);
+    const bool fused = dq_computes_delta(p.D);  // then no delta kernel exists and ms[0] stays (close to) zero
     if (e == hipSuccess) e = hipEventRecord(ev[0], st);
-    for (int32_t i = 0; i < iters && e == hipSuccess; ++i) e = launch_bwd_delta(p, st);
+    for (int32_t i = 0; i < iters && e == hipSuccess && !fused; ++i) e = launch_bwd_delta(p, st);
     if (e == hipSuccess) e = hipEventRecord(ev[1], st);
     set_worklist(&p, worklist_dkdv, lay_dkdv);
     for (int32_t i = 0; i < iters && e == hipSuccess; ++i) e = launch_bwd_dkdv(p, st);

@@ -2,7 +2,10 @@
 // instead of being stored by the forward (paper section 2.2.1 (1) relies on the
 // FlashAttention scheme for this; the schedule below is this library's own):
 //
-//   1. delta[h, r] = sum_d dO[r,h,d] * O[r,h,d]                (memory bound)
+//   1. delta[h, r] = sum_d dO[r,h,d] * O[r,h,d] and LSE * log2(e).  At D <= 128 the dQ kernel
+//      computes both for the rows of each of its works (it holds their dO rows anyway and fetches the
+//      O rows while dQ of the previous work is being staged), so it runs first; at D = 256, where it
+//      has no registers left for the O rows, a memory-bound pass of its own comes first.
 //   2. dK/dV: one workgroup per (key tile of 128 rows, KV head).  The K
 //      fragments of the tile stay in registers (the V fragments too at D = 64;
 //      at D >= 128 the V tile stays in LDS); the workgroup walks over the
@@ -356,7 +359,10 @@ using DqWork = RowWork;
 
 // Persistent, like the forward: workgroup b runs the works the host assigned to it; the first K/V tile and
 // the Q / dO fragments of the next work are fetched while the last key tile of the current one is processed.
-template <int D, int HPB>
+//   FUSE   the kernel computes delta = rowsum(dO * O) and LSE * log2(e) of its own rows (every row of every
+//          head belongs to exactly one work of this kernel) and writes both for the dK/dV kernel, which
+//          then runs after this one; the separate pass over O and dO is not launched.
+template <int D, int HPB, bool FUSE>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParams p) {
     constexpr int BMT = kDqBlockRows / HPB;
     constexpr int BN = kDqKvTile;
@@ -388,7 +394,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     // into the fragments of the row this lane owns, k-slots d = 16 t + 8 hf + 0..7), and its LSE and delta
     const int row = wave * 32 + l32;
     bf16x8 qf[KSTEPS], dof[KSTEPS];
-    float lse2, delta;
+    float lse2, delta;  // FUSE: lse2 holds the natural-log LSE until finish_rows() rescales it
     // Stacked row rr = wave * 32 + r is token rr % BMT of head h0 + rr / BMT; seen from the first row of
     // the work's first head, tokens past q_rows lie beyond the end of the buffer and read as zero.
     const int q_tok_bytes = p.Hq * D * 2;
@@ -402,7 +408,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     };
     // the dQ rows that leave at the end of a work: vector memory operations younger than the loads of the
     // next work's first tile
-    constexpr int kEpilogueStores = RowBlock<D>::N;
+    constexpr int kEpilogueStores = RowBlock<D>::N + (FUSE ? 2 : 0);
     auto load_rows = [&](const DqWork& w) {
         const int lane_off = RowBlock<D>::lane_offset(lane, q_tok_bytes);
         RowBlock<D>::load(qf, block_rows(p.q, w), lane_off, block_soff);
@@ -418,9 +424,41 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         // s = 0, p = 1, dP = 0, dS = 0, so they stay finite and contribute nothing (and are never stored).
         const int off = tok < w.q_rows ? ((rr / BMT) * p.T + tok) * 4 : 0x7ffffff0;
         lse2 = __builtin_bit_cast(
-            float, __builtin_amdgcn_raw_buffer_load_b32(RowBlock<D>::rows(p.lse2 + first, bytes), off, 0, 0));
-        delta = __builtin_bit_cast(
-            float, __builtin_amdgcn_raw_buffer_load_b32(RowBlock<D>::rows(p.delta + first, bytes), off, 0, 0));
+            float, __builtin_amdgcn_raw_buffer_load_b32(RowBlock<D>::rows((FUSE ? p.lse : p.lse2) + first, bytes), off, 0, 0));
+        if constexpr (!FUSE)
+            delta = __builtin_bit_cast(
+                float, __builtin_amdgcn_raw_buffer_load_b32(RowBlock<D>::rows(p.delta + first, bytes), off, 0, 0));
+    };
+    // FUSE: the O rows of the block, requested where the registers of the tile loop are free
+    bf16x8 of[FUSE ? KSTEPS : 1];
+    auto load_o = [&](const DqWork& w) {
+        if constexpr (FUSE)
+            RowBlock<D>::load(of, block_rows(p.out, w), RowBlock<D>::lane_offset(lane, q_tok_bytes), block_soff);
+    };
+    // Q, dO (and O) rows -> fragments of the row this lane owns, through the wave's LDS slice; FUSE: delta
+    // from the fragments (each lane sums its half of the row, the halves meet across lane 32), LSE rescaled,
+    // and both written where the dK/dV kernel reads them.  Exactly two stores when FUSE.
+    auto finish_rows = [&](const DqWork& w, int slice) {
+        RowBlock<D>::to_fragments(qf, smem, slice, fa, lane);
+        RowBlock<D>::to_fragments(dof, smem, slice, fa, lane);
+        if constexpr (FUSE) {
+            RowBlock<D>::to_fragments(of, smem, slice, fa, lane);
+            float acc = 0.0f;
+#pragma unroll
+            for (int t = 0; t < KSTEPS; ++t)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc = __builtin_fmaf((float)of[t][e], (float)dof[t][e], acc);
+            delta = acc + __shfl_xor(acc, 32);
+            lse2 *= kLog2e;
+            int l = lane;
+            asm volatile("" : "+v"(l));
+            const int rr = wave * 32 + (l & 31), tok = rr % BMT;
+            const size_t first = (size_t)w.h0 * p.T + w.q_row0;
+            const unsigned bytes = (unsigned)((HPB - 1) * p.T + w.q_rows) * 4u;
+            const int off = (tok < w.q_rows && l < 32) ? ((rr / BMT) * p.T + tok) * 4 : 0x7ffffff0;
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, delta), RowBlock<D>::rows(p.delta + first, bytes), off, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, lse2), RowBlock<D>::rows(p.lse2 + first, bytes), off, 0, 0);
+        }
     };
     const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
 
@@ -429,8 +467,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
     loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
     load_rows(cur);
-    RowBlock<D>::to_fragments(qf, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);  // stage 1 is still free
-    RowBlock<D>::to_fragments(dof, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);
+    load_o(cur);
+    finish_rows(cur, 2 * TILE_BYTES + slice_in_stage);  // stage 1 is still free
     // Every ordinary load is consumed before the loop head, here and at the end of a work, so that the
     // compiler has no wait of its own to place at the top of a work, where output rows are still leaving.
     asm volatile("" ::"v"(lse2), "v"(delta));
@@ -564,12 +602,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         // dQ leaves through the LDS stage that was just processed; every wave must be done reading it first
         __syncthreads();
         const int out_slice = (stage ^ 1) * 2 * TILE_BYTES + slice_in_stage;
+        if (has_next) load_o(nxt);  // on its way while dQ is staged
         store_block_rows<D>(smem + out_slice, dq, p.scale, lane, block_rows(p.dq, cur),
                             RowBlock<D>::lane_offset(lane, q_tok_bytes), block_soff);
         if (!has_next) break;
         // the next Q and dO rows have arrived meanwhile; the same slice turns them into fragments
-        RowBlock<D>::to_fragments(qf, smem, out_slice, fa, lane);
-        RowBlock<D>::to_fragments(dof, smem, out_slice, fa, lane);
+        finish_rows(nxt, out_slice);
         asm volatile("" ::"v"(lse2), "v"(delta));
         works.advance();
         cur = nxt;
@@ -579,9 +617,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
 template <int D, int HPB>
 hipError_t launch_dq_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
     constexpr size_t smem = 2 * 2 * kDqKvTile * D * 2;  // two stages of (K tile, V tile)
-    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dq_kernel<D, HPB>), smem);
+    constexpr bool FUSE = dq_computes_delta(D);
+    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dq_kernel<D, HPB, FUSE>), smem);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((bwd_dq_kernel<D, HPB>), dim3(grid), dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((bwd_dq_kernel<D, HPB, FUSE>), dim3(grid), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 

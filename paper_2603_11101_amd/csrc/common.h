@@ -45,6 +45,13 @@ constexpr int32_t kDqKvTile = 64;
 constexpr int32_t kDkdvKvRows = 128;
 constexpr int32_t dkdv_q_tile(int32_t D) { return D >= 128 ? 32 : 64; }
 
+// Whether the dQ kernel computes delta = rowsum(dO * O) and LSE * log2(e) itself (and then runs before
+// the dK/dV kernel, which reads both) instead of a separate pass over O and dO.
+#ifndef VA_FUSE_DELTA
+#define VA_FUSE_DELTA 1
+#endif
+constexpr bool dq_computes_delta(int32_t D) { return VA_FUSE_DELTA != 0 && D <= 128; }
+
 // Persistent workgroups launched for a pass: CUs of an MI355X times the workgroups a CU holds.
 constexpr int32_t persistent_workgroups(int32_t /*pass*/, int32_t D) { return D <= 128 ? 512 : 256; }
 // Cost of a work in units of inner-loop steps: its steps plus a fixed part for the item switch.

@@ -336,6 +336,8 @@ struct RowBlock {
     // regs as left by load() -> regs[t] = fragment t of row lane % 32 (k-slots d = 16 t + 8 (lane / 32) + 0..7).
     // `slice` is the byte offset of 32 * D * 2 bytes of LDS that no other wave touches meanwhile.
     VA_DEV static void to_fragments(bf16x8 (&regs)[N], char* lds, int slice, const FragAddr<D>& fa, int lane) {
+        // the write offsets are derived from the lane number on the spot (see lane_offset)
+        asm volatile("" : "+v"(lane));
         const int c = lane % CPR;
 #pragma unroll
         for (int j = 0; j < N; ++j)
