@@ -124,7 +124,9 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
  *   record 1   {num_workgroups, num_works, works_per_item, first item record (2),
  *               first table record, first work-id record, total records, 0}
  *   items      num_items records, heaviest first (ties by sample, then tile)
- *   table      one (first work, count) pair per persistent workgroup, 4 pairs per record
+ *   table      two records per persistent workgroup: the item of its first work, then
+ *              {id of that work, id of its second work, first schedule position,
+ *              number of works, 0, 0, 0, 0}
  *   work ids   num_works words, 8 per record: item * works_per_item + head chunk,
  *              grouped by workgroup in the order the workgroup runs them
  * Only tiles holding at least one visible (query, key) pair are listed and no
@@ -145,7 +147,8 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
  * buffer of at least that size.  The caller copies the buffer to the device
  * unchanged and hands both copies to the device calls, which validate the host
  * copy (records, bounds, that every item lies inside one sample of cu_seqlens,
- * that the table partitions the works) and return VA_EINVAL on a mismatch.
+ * that the table partitions the works and repeats each workgroup's first work
+ * faithfully) and return VA_EINVAL on a mismatch.
  */
 int va_worklist_bytes(const int32_t* cu_seqlens, int32_t num_seqs, int32_t pass, int32_t head_dim,
                       int32_t num_q_heads, int32_t num_kv_heads, size_t* bytes);

@@ -159,10 +159,12 @@ def worklist_items(wl):
 
 
 def worklist_schedule(wl):
-    """(table [num_workgroups, 2] of (first work, count), work ids [num_works]) of a work list."""
+    """(table [num_workgroups, 2] of (first work, count), work ids [num_works]) of a work list.  A table
+    entry is 16 words: the item of the workgroup's first work, that work's id, the id of the second one,
+    then first schedule position and count."""
     flat = wl.reshape(-1)
     P, W = int(wl[1, 0]), int(wl[1, 1])
-    table = flat[8 * wl[1, 4]:8 * wl[1, 4] + 2 * P].reshape(P, 2)
+    table = flat[8 * wl[1, 4]:8 * wl[1, 4] + 16 * P].reshape(P, 16)[:, 10:12]
     ids = flat[8 * wl[1, 5]:8 * wl[1, 5] + W]
     return table, ids
 

@@ -99,15 +99,23 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
     }
     const int32_t* table = w[lay.table_rec].w;
     const int32_t* ids = w[lay.id_rec].w;
-    int32_t at = 0;
-    for (int32_t g = 0; g < lay.num_workgroups; ++g) {
-        if (table[2 * g] != at || table[2 * g + 1] < 0 || table[2 * g + 1] > lay.num_works - at)
-            return fail(VA_EINVAL, "%s: workgroup table does not partition the works", who);
-        at += table[2 * g + 1];
-    }
-    if (at != lay.num_works) return fail(VA_EINVAL, "%s: workgroup table does not partition the works", who);
     for (int32_t i = 0; i < lay.num_works; ++i)
         if (ids[i] < 0 || ids[i] >= lay.num_works) return fail(VA_EINVAL, "%s: work id %d out of range", who, i);
+    int32_t at = 0;
+    for (int32_t g = 0; g < lay.num_workgroups; ++g) {
+        const int32_t* e = table + kTableWordsPerWorkgroup * g;
+        const int32_t count = e[11];
+        if (e[10] != at || count < 0 || count > lay.num_works - at)
+            return fail(VA_EINVAL, "%s: workgroup table does not partition the works", who);
+        if (count > 0) {  // the entry repeats the first descriptor of the workgroup: it must be the validated one
+            const int32_t id0 = ids[at], id1 = ids[at + (count > 1 ? 1 : 0)];
+            if (e[8] != id0 || e[9] != id1 ||
+                std::memcmp(e, w[lay.item_rec + id0 / lay.works_per_item].w, 8 * sizeof(int32_t)) != 0)
+                return fail(VA_EINVAL, "%s: table entry of workgroup %d does not repeat its first work", who, g);
+        }
+        at += count;
+    }
+    if (at != lay.num_works) return fail(VA_EINVAL, "%s: workgroup table does not partition the works", who);
     *layout = lay;
     return VA_OK;
 }

@@ -22,11 +22,14 @@ constexpr int32_t kWorklistMagic = 0x56415733;  // "VAW3"
 //   record 1   {num_workgroups, num_works, works_per_item, first item record (2), first table record,
 //               first work-id record, total records, 0}
 //   items      num_items records, heaviest first
-//   table      one (first work, count) pair per persistent workgroup, 4 pairs per record
+//   table      two records per persistent workgroup: the item of its first work; then {id of that work,
+//              id of its second work, first schedule position, number of works, 0, 0, 0, 0}
 //   work ids   num_works words, 8 per record: item * works_per_item + head chunk, grouped by workgroup
 // A work is one item for one head chunk (forward, dQ: the query heads a workgroup stacks; dK/dV: one
 // KV head).  The kernels are launched with num_workgroups persistent workgroups; the table is a
 // longest-processing-time-first assignment of the works to them, computed on the host.
+constexpr int32_t kTableWordsPerWorkgroup = 16;
+
 struct WorklistLayout {
     int32_t num_workgroups, num_works, works_per_item, num_items;
     int32_t item_rec, table_rec, id_rec, total_recs;

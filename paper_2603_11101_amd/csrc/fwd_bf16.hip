@@ -50,9 +50,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int first_work = p.wg_table[2 * blockIdx.x], num_works = p.wg_table[2 * blockIdx.x + 1];
-    if (num_works <= 0) return;
     RowWorkStream<HPB> works{p, lane};
+    FwdWork cur;
+    if (!works.start((int)blockIdx.x, &cur)) return;
 
     const int kv_row_bytes = p.Hkv * D * 2;
     const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
@@ -89,7 +89,6 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     constexpr int kEpilogueStores = RowBlock<D>::N + 1;
     const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
 
-    FwdWork cur = works.start(first_work, first_work + num_works);
     int stage = 0;  // LDS stage that holds (or will hold) the tile about to be processed
     loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
     loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);

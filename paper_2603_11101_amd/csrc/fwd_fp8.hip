@@ -161,9 +161,9 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int first_work = p.wg_table[2 * blockIdx.x], num_works = p.wg_table[2 * blockIdx.x + 1];
-    if (num_works <= 0) return;
     RowWorkStream<HPB> works{p, lane};
+    RowWork cur;
+    if (!works.start((int)blockIdx.x, &cur)) return;
 
     const int kv_row_bytes = p.Hkv * D;
     const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
@@ -207,7 +207,6 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
         return (rr % BMT) * o_tok_bytes + (rr / BMT) * (D * 2);
     };
 
-    RowWork cur = works.start(first_work, first_work + num_works);
     int stage = 0;
     loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
     loader.issue(kv_rsrc(p.v, cur), smem_lds + kTileBytes, 0);

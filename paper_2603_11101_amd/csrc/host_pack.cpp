@@ -68,7 +68,7 @@ WorklistLayout worklist_layout(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv,
     l.num_items = num_items;
     l.item_rec = 2;
     l.table_rec = l.item_rec + num_items;
-    l.id_rec = l.table_rec + (2 * l.num_workgroups + 7) / 8;
+    l.id_rec = l.table_rec + l.num_workgroups * (kTableWordsPerWorkgroup / 8);
     l.total_recs = l.id_rec + (l.num_works + 7) / 8;
     return l;
 }
@@ -242,8 +242,17 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
     int32_t* ids = out[lay.id_rec].w;
     int32_t at = 0;
     for (int32_t w = 0; w < P; ++w) {
-        table[2 * w] = at;
-        table[2 * w + 1] = (int32_t)mine[w].size();
+        int32_t* e = table + kTableWordsPerWorkgroup * w;
+        const int32_t count = (int32_t)mine[w].size();
+        for (int32_t i = 0; i < kTableWordsPerWorkgroup; ++i) e[i] = 0;
+        if (count > 0) {
+            const WorkItem& first = items[mine[w][0] / lay.works_per_item].it;
+            for (int32_t i = 0; i < 8; ++i) e[i] = first.w[i];
+            e[8] = mine[w][0];
+            e[9] = mine[w][count > 1 ? 1 : 0];
+        }
+        e[10] = at;
+        e[11] = count;
         for (int32_t id : mine[w]) ids[at++] = id;
     }
     *num_items = lay.num_items;

@@ -24,7 +24,7 @@ struct AttnParams {
     const float* k_descale;
     const float* v_descale;
     const WorkItem* items;     // device: item records of the work list
-    const int32_t* wg_table;   // device: (first work, count) per persistent workgroup
+    const int32_t* wg_table;   // device: 16 words per persistent workgroup (first descriptor, ids, range)
     const int32_t* work_ids;   // device: item * works_per_item + head chunk
     int32_t num_items;
     int32_t num_workgroups;

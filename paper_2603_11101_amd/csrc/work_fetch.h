@@ -6,6 +6,9 @@
 // requested three works ahead and the item record two works ahead, each a whole work before its value
 // is needed, so a switch never waits for memory.  What is in flight travels in one vector register:
 // lanes 0..7 the item's words and lane 8 the id of the next work, lane 9 the id of the work after it.
+// The table entry of a workgroup holds its first descriptor in that very form (plus the id of its second
+// work and its range of schedule positions), so the kernel's first loads of Q, K and V are one round
+// trip away from its start instead of three.
 #pragma once
 
 #include "kernels.h"
@@ -51,15 +54,17 @@ struct RowWorkStream {
         return w;
     }
 
-    // Positions first .. end - 1 (end > first).  Returns the first work; the next two are on their way.
-    VA_DEV RowWork start(int first, int end) {
-        work = first;
-        work_end = end;
-        const int id0 = __builtin_amdgcn_readfirstlane(p.work_ids[first]);
-        const int id1 = __builtin_amdgcn_readfirstlane(p.work_ids[min(first + 1, end - 1)]);
-        const int cur_v = load_ahead(id0, first);
-        ahead = load_ahead(id1, first + 2);
-        return unpack(cur_v);
+    // Reads the table entry of workgroup b: words 0..7 the item of its first work, 8 that work's id, 9 the
+    // id of its second work, 10 and 11 its first schedule position and its number of works.  Returns false
+    // if the workgroup has nothing to do; else `first` is its first work and the next two are on their way.
+    VA_DEV bool start(int b, RowWork* first) {
+        const int v = p.wg_table[kTableWordsPerWorkgroup * b + (lane & 15)];
+        work = __builtin_amdgcn_readlane(v, 10);
+        work_end = work + __builtin_amdgcn_readlane(v, 11);
+        if (work_end <= work) return false;
+        ahead = load_ahead(__builtin_amdgcn_readlane(v, 9), work + 2);
+        *first = unpack(v);
+        return true;
     }
     VA_DEV bool has_next() const { return work + 1 < work_end; }
     // Call once at the top of every work: returns the descriptor of work + 1 (meaningless unless

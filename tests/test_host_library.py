@@ -190,10 +190,12 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     tampered[2, 1] = 1000
     wrong_pass = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_BWD_DKDV, D, Hq, Hkv)
     bad_table = wl_h.copy()
-    bad_table[wl_h[1, 4], 1] += 1                      # first workgroup claims one work too many
+    bad_table[wl_h[1, 4] + 1, 3] += 1                  # first workgroup claims one work too many
+    bad_copy = wl_h.copy()
+    bad_copy[wl_h[1, 4], 1] += 1                       # its copy of its first item differs from the item
     bad_id = wl_h.copy()
     bad_id[wl_h[1, 5], 0] = wl_h[1, 1]                 # a work id past the end
-    for bad in (other, tampered, wrong_pass, bad_table, bad_id):
+    for bad in (other, tampered, wrong_pass, bad_table, bad_copy, bad_id):
         assert call(va.make_shape(**ok), wl_=np.ascontiguousarray(bad))[0] == va.VA_EINVAL
     assert va.varlen_attn_bwd_workspace_bytes(va.make_shape(**ok)) >= 100 * Hq * 4
 
