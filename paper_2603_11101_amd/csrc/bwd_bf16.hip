@@ -443,15 +443,23 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         RowBlock<D>::to_fragments(dof, smem, slice, fa, lane);
         if constexpr (FUSE) {
             RowBlock<D>::to_fragments(of, smem, slice, fa, lane);
+            // delta of row i is element (i, i) of dO O^T over the wave's 32 rows: KSTEPS MFMAs instead of
+            // 16 KSTEPS conversions and multiply-adds per lane.  Lane (column i, half hf) holds rows
+            // 8 (r / 4) + 4 hf + r % 4 in its registers, so the diagonal sits in register
+            // 4 (i / 8) + i % 4 of the lane whose half is (i / 4) % 2; the other half contributes zero.
+            f32x16 dd;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dd[r] = 0.0f;
+#pragma unroll
+            for (int t = 0; t < KSTEPS; ++t) dd = mfma32(dof[t], of[t], dd);
+            int l = lane;
+            asm volatile("" : "+v"(l));  // lane constants below are derived here, not kept across the kernel
+            const int want = (l & 31) - 4 * (l >> 5);
             float acc = 0.0f;
 #pragma unroll
-            for (int t = 0; t < KSTEPS; ++t)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc = __builtin_fmaf((float)of[t][e], (float)dof[t][e], acc);
+            for (int r = 0; r < 16; ++r) acc = (8 * (r / 4) + r % 4 == want) ? dd[r] : acc;
             delta = acc + __shfl_xor(acc, 32);
             lse2 *= kLog2e;
-            int l = lane;
-            asm volatile("" : "+v"(l));
             const int rr = wave * 32 + (l & 31), tok = rr % BMT;
             const size_t first = (size_t)w.h0 * p.T + w.q_row0;
             const unsigned bytes = (unsigned)((HPB - 1) * p.T + w.q_rows) * 4u;
