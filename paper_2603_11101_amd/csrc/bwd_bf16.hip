@@ -129,18 +129,34 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 
     // Step n of a work is query tile qt_first + n % qt_count of head g * G + n / qt_count.  Q and dO rows
     // of (sample, head) and the LSE / delta rows are raw buffers: anything past the sample reads as zero.
-    auto issue_stage = [&](const DkdvWork& w, int n, int st_index) {
-        const unsigned st = smem_lds + st_index * STAGE_BYTES;
-        const int head = w.g * G + n / w.qt_count;
-        const int q0 = (w.qt_first + n % w.qt_count) * BMQ;
-        const size_t off = ((size_t)w.seq_row0 * p.Hq + head) * D;
+    // The buffers only change with the head, so they are rebuilt when the tile index wraps and a step
+    // costs a handful of scalar instructions instead of two divisions and four 64-bit address sums.
+    struct StageSource {
+        i32x4 q, dout, aux;  // aux: LSE rows for wave 0, delta rows for wave 1
+        int qt;              // query tile of the stage issued last, relative to qt_first
+        int head;
+    };
+    auto head_buffers = [&](const DkdvWork& w, StageSource& src) {
+        const size_t off = ((size_t)w.seq_row0 * p.Hq + src.head) * D;
         const unsigned q_bytes = (unsigned)(w.L - 1) * q_row_bytes + D * 2;
-        loader.issue(make_rsrc(static_cast<const __bf16*>(p.q) + off, q_bytes), st, q0 * q_row_bytes);
-        loader.issue(make_rsrc(static_cast<const __bf16*>(p.dout) + off, q_bytes), st + TILE_BYTES, q0 * q_row_bytes);
-        if (wave < 2) {  // 64 floats each: lane i fetches row q0 + i
-            const float* src = (wave == 0 ? p.lse2 : p.delta) + (size_t)head * p.T + w.seq_row0;
-            buffer_load_lds_4(st + 2 * TILE_BYTES + wave * 256, lane * 4, make_rsrc(src, (unsigned)w.L * 4), q0 * 4);
+        src.q = make_rsrc(static_cast<const __bf16*>(p.q) + off, q_bytes);
+        src.dout = make_rsrc(static_cast<const __bf16*>(p.dout) + off, q_bytes);
+        src.aux = make_rsrc((wave == 0 ? p.lse2 : p.delta) + (size_t)src.head * p.T + w.seq_row0, (unsigned)w.L * 4);
+    };
+    // issues the stage after the one issued last (the first call issues step 0); returns its first query row
+    auto issue_next_stage = [&](const DkdvWork& w, StageSource& src, int st_index) {
+        if (++src.qt == w.qt_count) {
+            src.qt = 0;
+            ++src.head;
+            head_buffers(w, src);
         }
+        const unsigned st = smem_lds + st_index * STAGE_BYTES;
+        const int q0 = (w.qt_first + src.qt) * BMQ;
+        loader.issue(src.q, st, q0 * q_row_bytes);
+        loader.issue(src.dout, st + TILE_BYTES, q0 * q_row_bytes);
+        if (wave < 2)  // 64 floats each: lane i fetches row q0 + i
+            buffer_load_lds_4(st + 2 * TILE_BYTES + wave * 256, lane * 4, src.aux, q0 * 4);
+        return q0;
     };
     auto issue_v = [&](const DkdvWork& w) {
         if (V_IN_LDS) {
@@ -172,7 +188,11 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 
     const DkdvWork cur = fetch_dkdv_work(p, (int)blockIdx.x);
     int stage = 0;
-    issue_stage(cur, 0, 0);
+    StageSource src;
+    src.qt = -1;
+    src.head = cur.g * G;
+    head_buffers(cur, src);
+    int q0_next = issue_next_stage(cur, src, 0);  // first query row of the stage in flight
     issue_v(cur);
     load_k(cur);
 
@@ -202,12 +222,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         // One step; the last one is a separate instantiation that prefetches nothing and ends without a barrier.
         auto step = [&](const int n, auto last_tag) {
             constexpr bool last = decltype(last_tag)::value;
-            if constexpr (!last) issue_stage(cur, n + 1, stage ^ 1);
+            const int q0 = q0_next;
+            if constexpr (!last) q0_next = issue_next_stage(cur, src, stage ^ 1);
             const int q_tile = stage * STAGE_BYTES;  // byte offsets of this stage's tiles
             const int do_tile = q_tile + TILE_BYTES;
             const float* lse_s = reinterpret_cast<const float*>(smem + q_tile + 2 * TILE_BYTES);
             const float* delta_s = lse_s + 64;
-            const int q0 = (cur.qt_first + n % cur.qt_count) * BMQ;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 const int i0 = q0 + 32 * qb;  // first query row of the block (local index in the sample)
