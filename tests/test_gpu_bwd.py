@@ -120,3 +120,29 @@ def test_many_tiny_samples_forward_and_backward(Hq, Hkv, D):
     print(f"  worst per-sample rel-L2 over all samples and tensors {worst:.2e}", flush=True)
     assert worst <= TOL_GRAD_REL
     assert run.tail_untouched("out") and run.tail_untouched("dq") and run.tail_untouched("dk")
+
+
+@pytest.mark.parametrize("trial", range(8))
+def test_random_configurations_forward_and_backward(trial):
+    # shapes, head groupings, masks and block ends drawn together, so that combinations the fixed
+    # cases above do not pair up are met as well (zero-length samples and one-block samples included)
+    r = np.random.default_rng(4000 + trial)
+    Hkv = int(r.choice([1, 2, 3]))
+    G = int(r.choice([1, 2, 3, 4, 8]))
+    D = int(r.choice([64, 128, 256]))
+    mode = int(r.choice(list(MODES)))
+    lens = [int(x) for x in r.choice([0, 1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 190, 300, 450], size=int(r.integers(2, 7)))]
+    if sum(lens) == 0:
+        lens.append(77)
+    cu, prefix, q, k, v, do = wl.random_stream(5000 + trial, lens, G * Hkv, Hkv, D, prefix_frac=-1.0)
+    if mode == va.VA_MASK_CAUSAL:
+        prefix = None
+    elif mode == va.VA_MASK_THREE_BLOCK:
+        prefix = wl.random_block_ends(5000 + trial, lens)
+    scale = float(r.choice([1.0 / np.sqrt(D), 0.05, 0.2]))
+    print(f"random configuration {trial}: mode={mode} Hq={G * Hkv} Hkv={Hkv} D={D} lens={lens} scale={scale:.3f}", flush=True)
+    run = DeviceRun(cu, prefix, mode, q, k, v, do, scale)
+    ref_out, ref_lse = oa.attn_fwd(q, k, v, cu, prefix, scale=scale, mask_mode=MODES[mode])
+    assert rel_l2(run.out, ref_out) <= TOL_FWD_REL and max_abs(run.lse, ref_lse) <= TOL_LSE_ABS
+    check_bwd(run, oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=MODES[mode]), cu, f"random {trial}")
+    assert run.tail_untouched("out")
