@@ -226,6 +226,13 @@ int va_quantize_e4m3_per_head_device(const void* x_bf16, int32_t T, int32_t H, i
                                      void* codes, float* descale, void* stream);
 
 /*
+ * Whether varlen_attn_bwd at this head_dim launches the separate delta pass
+ * (1) or its dQ kernel computes delta (0); see varlen_attn_bwd.  Host only,
+ * no error cases: any other head_dim answers 1.
+ */
+int va_bwd_has_delta_kernel(int32_t head_dim);
+
+/*
  * Measurement aid: runs varlen_attn_bwd once, then launches each of its
  * kernels `iters` times back to back (the results stay those of
  * varlen_attn_bwd) between HIP events recorded on `stream`, waits for the
@@ -235,7 +242,6 @@ int va_quantize_e4m3_per_head_device(const void* x_bf16, int32_t T, int32_t H, i
  * (va_bwd_has_delta_kernel).  Same arguments and errors as varlen_attn_bwd;
  * iters >= 1.
  */
-int va_bwd_has_delta_kernel(int32_t head_dim); /* 1 if varlen_attn_bwd launches the separate delta pass, else 0 */
 int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const void* out, const float* lse,
                             const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
                             const void* worklist_dkdv, const void* worklist_dkdv_host,
