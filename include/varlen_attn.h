@@ -9,7 +9,8 @@
  * sample attending to itself alone.  Inside a sample the mask is causal
  * (autoregressive decoder, section 2.2.1 (1)) or prefix-LM (the pi-0.5 case of
  * section 2.2.2: a bidirectional prefix, and a suffix that attends the prefix
- * and the whole suffix).
+ * and the whole suffix), with two variants of the latter listed under "Mask"
+ * below.
  *
  * Conventions that hold for every entry point
  *   - Plain C types only.  "host" pointers are ordinary memory; "device"
