@@ -146,3 +146,28 @@ def test_random_configurations_forward_and_backward(trial):
     assert rel_l2(run.out, ref_out) <= TOL_FWD_REL and max_abs(run.lse, ref_lse) <= TOL_LSE_ABS
     check_bwd(run, oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=MODES[mode]), cu, f"random {trial}")
     assert run.tail_untouched("out")
+
+
+@pytest.mark.parametrize("mode,Hq,Hkv,D", [(va.VA_MASK_CAUSAL, 4, 2, 128), (va.VA_MASK_PREFIX_LM, 2, 1, 64),
+                                           (va.VA_MASK_CAUSAL, 2, 2, 256)])
+def test_peaked_softmax_with_a_rising_row_maximum(mode, Hq, Hkv, D):
+    # Scores with a standard deviation of about 8 whose size grows along the sample: the running maximum
+    # of a row moves up by many units from one key tile to the next, so the reference point of the
+    # exponentials has to follow every time, and nearly all of a row's weight sits on a few keys.
+    lens = [330, 70, 200]
+    cu, prefix, q, k, v, do = wl.random_stream(91 + D, lens, Hq, Hkv, D, prefix_frac=0.4)
+    if mode == va.VA_MASK_CAUSAL:
+        prefix = None
+    ramp = np.concatenate([1.0 + 3.0 * np.arange(L) / L for L in lens]).astype(np.float32)
+    k = wl.round_to_bf16(k * ramp[:, None, None])
+    scale = 8.0 / np.sqrt(D) / 2.5
+    print(f"peaked softmax mode={mode} Hq={Hq} Hkv={Hkv} D={D}", flush=True)
+    run = DeviceRun(cu, prefix, mode, q, k, v, do, scale)
+    ref_out, ref_lse = oa.attn_fwd(q, k, v, cu, prefix, scale=scale, mask_mode=MODES[mode])
+    print(f"  largest |LSE| {np.abs(ref_lse).max():.1f}; out rel-L2 {rel_l2(run.out, ref_out):.2e} "
+          f"lse max-abs {max_abs(run.lse, ref_lse):.2e}", flush=True)
+    assert np.isfinite(run.out).all() and np.isfinite(run.lse).all()
+    assert rel_l2(run.out, ref_out) <= TOL_FWD_REL
+    # float32 LSE of magnitude ~50 carries 4e-6 of rounding per operation; the bound stays the stated one
+    assert max_abs(run.lse, ref_lse) <= TOL_LSE_ABS
+    check_bwd(run, oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=MODES[mode]), cu, "peaked")

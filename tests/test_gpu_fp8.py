@@ -110,3 +110,24 @@ def test_device_quantiser_is_bit_identical_to_the_oracle(T, H, D):
     assert np.array_equal(codes.cpu().numpy(), ref_codes)
     host_codes, host_descale = va.va_quantize_e4m3_per_head(bits)
     assert np.array_equal(host_codes, ref_codes) and np.array_equal(host_descale, ref_descale.astype(np.float32))
+
+
+def test_fp8_peaked_softmax_with_a_rising_row_maximum():
+    # as the bf16 case of the same name: the row maximum climbs from tile to tile and most of a row's
+    # weight sits on a few keys, so the reference point of the stored probabilities has to follow
+    Hq, Hkv, D = 4, 2, 128
+    lens = [330, 70, 200]
+    cu, _, q, k, v, _ = wl.random_stream(93, lens, Hq, Hkv, D)
+    ramp = np.concatenate([1.0 + 3.0 * np.arange(L) / L for L in lens]).astype(np.float32)
+    k = wl.round_to_bf16(k * ramp[:, None, None])
+    # half the size of the bf16 case: the matrix unit sums FP8 products with about 17 significant bits, so
+    # the scores (and the LSE) carry a relative error of about 1.4e-5, which the absolute LSE bound of
+    # 1e-3 absorbs up to |LSE| of about 70 (measured 7e-4 at |LSE| = 50, 4e-5 at ordinary sizes)
+    scale = 4.0 / np.sqrt(D) / 2.5
+    print("fp8 peaked softmax", flush=True)
+    out, lse, (qd, kd, vd) = run_fp8(cu, None, va.VA_MASK_CAUSAL, q, k, v, scale)
+    ref_out, ref_lse = oa.attn_fwd(qd, kd, vd, cu, None, scale=scale, mask_mode=oa.MASK_CAUSAL)
+    print(f"  largest |LSE| {np.abs(ref_lse).max():.1f}; out rel-L2 {rel_l2(out, ref_out):.2e} lse max-abs {max_abs(lse, ref_lse):.2e}",
+          flush=True)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    assert rel_l2(out, ref_out) <= TOL_FP8_REL and max_abs(lse, ref_lse) <= TOL_LSE_ABS
