@@ -18,8 +18,8 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
     if (!s || !cu) return fail(VA_EINVAL, "%s: null shape or cu_seqlens", who);
     if (s->mask_mode != VA_MASK_CAUSAL && !prefix_lens)
         return fail(VA_EINVAL, "%s: a prefix mask needs prefix_lens", who);
-    if (s->head_dim != 64 && s->head_dim != 128 && s->head_dim != 256)
-        return fail(VA_EUNSUPPORTED, "%s: head_dim %d not in {64,128,256}", who, s->head_dim);
+    if (!head_dim_supported(s->head_dim))
+        return fail(VA_EUNSUPPORTED, "%s: head_dim %d not in {64,80,128,256}", who, s->head_dim);
     if (s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->num_q_heads % s->num_kv_heads != 0)
         return fail(VA_EUNSUPPORTED, "%s: num_q_heads %d is not a positive multiple of num_kv_heads %d", who,
                     s->num_q_heads, s->num_kv_heads);
@@ -354,6 +354,7 @@ int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
     const char* who = "varlen_attn_fwd_fp8";
     int rc = check_shape(shape, cu_seqlens, prefix_lens, who);
     if (rc) return rc;
+    if (shape->head_dim != 128) return fail(VA_EUNSUPPORTED, "%s: head_dim %d, the FP8 forward exists for 128 only", who, shape->head_dim);
     if ((rc = check_scale(scale, who))) return rc;
     if (shape->total_tokens == 0) return VA_OK;
     if (!q8 || !k8 || !v8 || !q_descale || !k_descale || !v_descale || !out || !lse)

@@ -102,13 +102,17 @@ VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int id) {
 //   V_LDS  the V rows of the key tile live in LDS (second operand of dP = dO V^T) instead of registers:
 //          that buys the register room for two workgroups per CU at D = 128 and for both accumulators
 //          (256 registers per lane, in the accumulation registers) at D = 256
-template <int D, bool V_LDS, bool THREE>
+//   DR     head dimension of the tensors in memory (a multiple of 16, D / 2 < DR <= D); D is then the
+//          geometry of the LDS tiles and register blocks only
+template <int D, bool V_LDS, bool THREE, int DR>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnParams p) {
+    static_assert(DR % 16 == 0 && DR <= D && DR > D / 2, "head dimension and geometry do not match");
+    using Rows = RowBlock<D, DR>;
     constexpr bool V_IN_LDS = V_LDS, V_REGS = !V_LDS;
     constexpr int BMQ = dkdv_q_tile(D);  // query rows staged per step
     constexpr int QB = BMQ / 32;         // 32-row query blocks per step
-    constexpr int KSTEPS = D / 16;
-    constexpr int DT = D / 32;
+    constexpr int KSTEPS = DR / 16;
+    constexpr int DT = (DR + 31) / 32;
     constexpr int PF = D >= 128 ? 2 : kPrefetch;  // fragment reads in flight; D >= 128 has no registers to spare
     constexpr int TILE_BYTES = BMQ * D * 2;
     constexpr int STAGE_BYTES = 2 * TILE_BYTES + 2 * 64 * (int)sizeof(float);  // Q, dO, LSE2[64], delta[64]
@@ -120,10 +124,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 
     const int G = p.Hq / p.Hkv;
     const float c = p.scale * kLog2e;
-    const int q_row_bytes = p.Hq * D * 2;
-    const int kv_row_bytes = p.Hkv * D * 2;
+    const int q_row_bytes = p.Hq * DR * 2;
+    const int kv_row_bytes = p.Hkv * DR * 2;
     const unsigned smem_lds = lds_addr(smem);
-    AsyncTile<D, BMQ, 4> loader;
+    AsyncTile<D, BMQ, 4, DR> loader;
     loader.init(wave, lane, q_row_bytes);
     const FragAddr<D> fa(lane);
 
@@ -137,8 +141,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         int head;
     };
     auto head_buffers = [&](const DkdvWork& w, StageSource& src) {
-        const size_t off = ((size_t)w.seq_row0 * p.Hq + src.head) * D;
-        const unsigned q_bytes = (unsigned)(w.L - 1) * q_row_bytes + D * 2;
+        const size_t off = ((size_t)w.seq_row0 * p.Hq + src.head) * DR;
+        const unsigned q_bytes = (unsigned)(w.L - 1) * q_row_bytes + DR * 2;
         src.q = make_rsrc(static_cast<const __bf16*>(p.q) + off, q_bytes);
         src.dout = make_rsrc(static_cast<const __bf16*>(p.dout) + off, q_bytes);
         src.aux = make_rsrc((wave == 0 ? p.lse2 : p.delta) + (size_t)src.head * p.T + w.seq_row0, (unsigned)w.L * 4);
@@ -160,10 +164,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     };
     auto issue_v = [&](const DkdvWork& w) {
         if (V_IN_LDS) {
-            AsyncTile<D, kDkdvKvRows, 4> v_loader;  // rebuilt per work: not worth registers across the step loop
+            AsyncTile<D, kDkdvKvRows, 4, DR> v_loader;  // rebuilt per work: not worth registers across the step loop
             v_loader.init(wave, lane, kv_row_bytes);
-            const __bf16* v_seq = static_cast<const __bf16*>(p.v) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D;
-            v_loader.issue(make_rsrc(v_seq, (unsigned)(w.L - 1) * kv_row_bytes + D * 2), smem_lds + AUX,
+            const __bf16* v_seq = static_cast<const __bf16*>(p.v) + ((size_t)w.seq_row0 * p.Hkv + w.g) * DR;
+            v_loader.issue(make_rsrc(v_seq, (unsigned)(w.L - 1) * kv_row_bytes + DR * 2), smem_lds + AUX,
                            (w.kv_row0 - w.seq_row0) * kv_row_bytes);
         }
     };
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     bf16x8 kf[KSTEPS], vf[V_REGS ? KSTEPS : 1];
     auto load_k = [&](const DkdvWork& w) {
         const bool valid = 32 * wave + l32 < w.kv_rows;
-        const size_t off = ((size_t)(w.kv_row0 + 32 * wave + l32) * p.Hkv + w.g) * D;
+        const size_t off = ((size_t)(w.kv_row0 + 32 * wave + l32) * p.Hkv + w.g) * DR;
         const __bf16* krow = static_cast<const __bf16*>(p.k) + off;
         const __bf16* vrow = static_cast<const __bf16*>(p.v) + off;
 #pragma unroll
@@ -358,16 +362,16 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
             char* out_stage = smem + AUX + wave * (32 * D * 2);
             // this wave's 32 key rows of KV head g, as far as the sample goes
             const int rows_here = min(max(cur.kv_rows - 32 * wave, 0), 32);
-            const size_t off = ((size_t)(cur.kv_row0 + 32 * wave) * p.Hkv + cur.g) * D;
-            const int row_bytes = p.Hkv * D * 2;
-            const unsigned bytes = rows_here > 0 ? (unsigned)(rows_here - 1) * row_bytes + D * 2 : 0u;
-            const int lane_off = RowBlock<D>::lane_offset(lane, row_bytes);
-            auto soff = [&](int j) { return j * RowBlock<D>::RPI * row_bytes; };
-            store_block_rows<D>(out_stage, dk, p.scale, lane,
-                                    RowBlock<D>::rows(static_cast<__bf16*>(p.dk) + off, bytes), lane_off, soff);
+            const size_t off = ((size_t)(cur.kv_row0 + 32 * wave) * p.Hkv + cur.g) * DR;
+            const int row_bytes = p.Hkv * DR * 2;
+            const unsigned bytes = rows_here > 0 ? (unsigned)(rows_here - 1) * row_bytes + DR * 2 : 0u;
+            const int lane_off = Rows::lane_offset(lane, row_bytes);
+            auto soff = [&](int j) { return j * Rows::RPI * row_bytes; };
+            store_block_rows<D, DT>(out_stage, dk, p.scale, lane,
+                                    Rows::rows(static_cast<__bf16*>(p.dk) + off, bytes), lane_off, soff);
             __builtin_amdgcn_sched_barrier(0);
-            store_block_rows<D>(out_stage, dv, 1.0f, lane,
-                                    RowBlock<D>::rows(static_cast<__bf16*>(p.dv) + off, bytes), lane_off, soff);
+            store_block_rows<D, DT>(out_stage, dv, 1.0f, lane,
+                                    Rows::rows(static_cast<__bf16*>(p.dv) + off, bytes), lane_off, soff);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -382,12 +386,17 @@ using DqWork = RowWork;
 //   FUSE   the kernel computes delta = rowsum(dO * O) and LSE * log2(e) of its own rows (every row of every
 //          head belongs to exactly one work of this kernel) and writes both for the dK/dV kernel, which
 //          then runs after this one; the separate pass over O and dO is not launched.
-template <int D, int HPB, bool FUSE>
+//   DR     head dimension of the tensors in memory (a multiple of 16, D / 2 < DR <= D); D is then the
+//          geometry of the LDS tiles and register blocks only
+template <int D, int HPB, bool FUSE, int DR>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParams p) {
+    static_assert(DR % 16 == 0 && DR <= D && DR > D / 2, "head dimension and geometry do not match");
+    using Rows = RowBlock<D, DR>;
+    constexpr int NQ = D / 16;  // row fragments a block of rows is fetched as (the first KSTEPS are used)
     constexpr int BMT = kDqBlockRows / HPB;
     constexpr int BN = kDqKvTile;
-    constexpr int KSTEPS = D / 16;
-    constexpr int DT = D / 32;
+    constexpr int KSTEPS = DR / 16;
+    constexpr int DT = (DR + 31) / 32;
     constexpr int TILE_BYTES = BN * D * 2;
     constexpr int PF = D == 128 ? 2 : kPrefetch;  // fragment reads in flight; D = 128 has no registers to spare
     extern __shared__ __attribute__((aligned(16))) char smem[];  // two stages, each a K tile then a V tile
@@ -398,41 +407,41 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     DqWork cur;
     if (!works.start((int)blockIdx.x, &cur)) return;
 
-    const int kv_row_bytes = p.Hkv * D * 2;
+    const int kv_row_bytes = p.Hkv * DR * 2;
     const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
     const unsigned smem_lds = lds_addr(smem);
-    AsyncTile<D, BN, 4> loader;
+    AsyncTile<D, BN, 4, DR> loader;
     loader.init(wave, lane, kv_row_bytes);
     const FragAddr<D> fa(lane);
     const float c = p.scale * kLog2e;
 
     auto kv_rsrc = [&](const void* base, const DqWork& w) {
-        return make_rsrc(static_cast<const __bf16*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D,
-                         (unsigned)(w.L - 1) * kv_row_bytes + D * 2);
+        return make_rsrc(static_cast<const __bf16*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * DR,
+                         (unsigned)(w.L - 1) * kv_row_bytes + DR * 2);
     };
     // Q and dO rows of the wave's 32 stacked rows, whole rows per group of lanes (to_fragments() turns them
     // into the fragments of the row this lane owns, k-slots d = 16 t + 8 hf + 0..7), and its LSE and delta
     const int row = wave * 32 + l32;
-    bf16x8 qf[KSTEPS], dof[KSTEPS];
+    bf16x8 qf[NQ], dof[NQ];
     float lse2, delta;  // FUSE: lse2 holds the natural-log LSE until finish_rows() rescales it
     // Stacked row rr = wave * 32 + r is token rr % BMT of head h0 + rr / BMT; seen from the first row of
     // the work's first head, tokens past q_rows lie beyond the end of the buffer and read as zero.
-    const int q_tok_bytes = p.Hq * D * 2;
+    const int q_tok_bytes = p.Hq * DR * 2;
     auto block_rows = [&](const void* tensor, const DqWork& w) {
-        return RowBlock<D>::rows(static_cast<const __bf16*>(tensor) + ((size_t)w.q_row0 * p.Hq + w.h0) * D,
-                                 (unsigned)(w.q_rows - 1) * q_tok_bytes + HPB * D * 2);
+        return Rows::rows(static_cast<const __bf16*>(tensor) + ((size_t)w.q_row0 * p.Hq + w.h0) * DR,
+                          (unsigned)(w.q_rows - 1) * q_tok_bytes + HPB * DR * 2);
     };
     auto block_soff = [&](int j) {
-        const int rr = __builtin_amdgcn_readfirstlane(wave * 32 + j * RowBlock<D>::RPI);
-        return (rr % BMT) * q_tok_bytes + (rr / BMT) * (D * 2);
+        const int rr = __builtin_amdgcn_readfirstlane(wave * 32 + j * Rows::RPI);
+        return (rr % BMT) * q_tok_bytes + (rr / BMT) * (DR * 2);
     };
     // the dQ rows that leave at the end of a work: vector memory operations younger than the loads of the
     // next work's first tile
-    constexpr int kEpilogueStores = RowBlock<D>::N + (FUSE ? 2 : 0);
+    constexpr int kEpilogueStores = Rows::N + (FUSE ? 2 : 0);
     auto load_rows = [&](const DqWork& w) {
-        const int lane_off = RowBlock<D>::lane_offset(lane, q_tok_bytes);
-        RowBlock<D>::load(qf, block_rows(p.q, w), lane_off, block_soff);
-        RowBlock<D>::load(dof, block_rows(p.dout, w), lane_off, block_soff);
+        const int lane_off = Rows::lane_offset(lane, q_tok_bytes);
+        Rows::load(qf, block_rows(p.q, w), lane_off, block_soff);
+        Rows::load(dof, block_rows(p.dout, w), lane_off, block_soff);
         // LSE and delta of the row this lane owns, through raw buffers as well; the offset is derived from
         // the lane number on the spot (see RowBlock::lane_offset)
         int l = lane;
@@ -444,25 +453,25 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         // s = 0, p = 1, dP = 0, dS = 0, so they stay finite and contribute nothing (and are never stored).
         const int off = tok < w.q_rows ? ((rr / BMT) * p.T + tok) * 4 : 0x7ffffff0;
         lse2 = __builtin_bit_cast(
-            float, __builtin_amdgcn_raw_buffer_load_b32(RowBlock<D>::rows((FUSE ? p.lse : p.lse2) + first, bytes), off, 0, 0));
+            float, __builtin_amdgcn_raw_buffer_load_b32(Rows::rows((FUSE ? p.lse : p.lse2) + first, bytes), off, 0, 0));
         if constexpr (!FUSE)
             delta = __builtin_bit_cast(
-                float, __builtin_amdgcn_raw_buffer_load_b32(RowBlock<D>::rows(p.delta + first, bytes), off, 0, 0));
+                float, __builtin_amdgcn_raw_buffer_load_b32(Rows::rows(p.delta + first, bytes), off, 0, 0));
     };
     // FUSE: the O rows of the block, requested where the registers of the tile loop are free
-    bf16x8 of[FUSE ? KSTEPS : 1];
+    bf16x8 of[FUSE ? NQ : 1];
     auto load_o = [&](const DqWork& w) {
         if constexpr (FUSE)
-            RowBlock<D>::load(of, block_rows(p.out, w), RowBlock<D>::lane_offset(lane, q_tok_bytes), block_soff);
+            Rows::load(of, block_rows(p.out, w), Rows::lane_offset(lane, q_tok_bytes), block_soff);
     };
     // Q, dO (and O) rows -> fragments of the row this lane owns, through the wave's LDS slice; FUSE: delta
     // from the fragments (each lane sums its half of the row, the halves meet across lane 32), LSE rescaled,
     // and both written where the dK/dV kernel reads them.  Exactly two stores when FUSE.
     auto finish_rows = [&](const DqWork& w, int slice) {
-        RowBlock<D>::to_fragments(qf, smem, slice, fa, lane);
-        RowBlock<D>::to_fragments(dof, smem, slice, fa, lane);
+        Rows::to_fragments(qf, smem, slice, fa, lane);
+        Rows::to_fragments(dof, smem, slice, fa, lane);
         if constexpr (FUSE) {
-            RowBlock<D>::to_fragments(of, smem, slice, fa, lane);
+            Rows::to_fragments(of, smem, slice, fa, lane);
             // delta of row i is element (i, i) of dO O^T over the wave's 32 rows: KSTEPS MFMAs instead of
             // 16 KSTEPS conversions and multiply-adds per lane.  Lane (column i, half hf) holds rows
             // 8 (r / 4) + 4 hf + r % 4 in its registers, so the diagonal sits in register
@@ -484,8 +493,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
             const size_t first = (size_t)w.h0 * p.T + w.q_row0;
             const unsigned bytes = (unsigned)((HPB - 1) * p.T + w.q_rows) * 4u;
             const int off = (tok < w.q_rows && l < 32) ? ((rr / BMT) * p.T + tok) * 4 : 0x7ffffff0;
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, delta), RowBlock<D>::rows(p.delta + first, bytes), off, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, lse2), RowBlock<D>::rows(p.lse2 + first, bytes), off, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, delta), Rows::rows(p.delta + first, bytes), off, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, lse2), Rows::rows(p.lse2 + first, bytes), off, 0, 0);
         }
     };
     const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
@@ -630,8 +639,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         __syncthreads();
         const int out_slice = (stage ^ 1) * 2 * TILE_BYTES + slice_in_stage;
         if (has_next) load_o(nxt);  // on its way while dQ is staged
-        store_block_rows<D>(smem + out_slice, dq, p.scale, lane, block_rows(p.dq, cur),
-                            RowBlock<D>::lane_offset(lane, q_tok_bytes), block_soff);
+        store_block_rows<D, DT>(smem + out_slice, dq, p.scale, lane, block_rows(p.dq, cur),
+                            Rows::lane_offset(lane, q_tok_bytes), block_soff);
         if (!has_next) break;
         // the next Q and dO rows have arrived meanwhile; the same slice turns them into fragments
         finish_rows(nxt, out_slice);
@@ -641,31 +650,31 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     }
 }
 
-template <int D, int HPB>
+template <int D, int HPB, int DR>
 hipError_t launch_dq_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
     constexpr size_t smem = 2 * 2 * kDqKvTile * D * 2;  // two stages of (K tile, V tile)
     constexpr bool FUSE = dq_computes_delta(D);
-    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dq_kernel<D, HPB, FUSE>), smem);
+    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dq_kernel<D, HPB, FUSE, DR>), smem);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((bwd_dq_kernel<D, HPB, FUSE>), dim3(grid), dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((bwd_dq_kernel<D, HPB, FUSE, DR>), dim3(grid), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, int DR = D>
 hipError_t launch_dq_d(const AttnParams& p, hipStream_t stream) {
     const int hpb = heads_per_block(p.Hq, p.Hkv);
     const unsigned grid = (unsigned)p.num_workgroups;
     if (p.num_items == 0) return hipSuccess;
     switch (hpb) {
-        case 1: return launch_dq_dh<D, 1>(p, stream, grid);
-        case 2: return launch_dq_dh<D, 2>(p, stream, grid);
-        case 4: return launch_dq_dh<D, 4>(p, stream, grid);
-        default: return launch_dq_dh<D, 8>(p, stream, grid);
+        case 1: return launch_dq_dh<D, 1, DR>(p, stream, grid);
+        case 2: return launch_dq_dh<D, 2, DR>(p, stream, grid);
+        case 4: return launch_dq_dh<D, 4, DR>(p, stream, grid);
+        default: return launch_dq_dh<D, 8, DR>(p, stream, grid);
     }
 }
 
 // One work per workgroup, in item order (heaviest first).
-template <int D>
+template <int D, int DR = D>
 hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     if (p.num_items == 0) return hipSuccess;
     constexpr bool V_LDS = D >= 128;
@@ -675,14 +684,14 @@ hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     // one instantiation per mask family: the masks without a second block do not pay for it
     if (p.mask_mode == VA_MASK_THREE_BLOCK) {
         static const hipError_t attr =
-            allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, true>), smem);
+            allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, true, DR>), smem);
         if (attr != hipSuccess) return attr;
-        hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, true>), dim3(grid), dim3(256), smem, stream, p);
+        hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, true, DR>), dim3(grid), dim3(256), smem, stream, p);
     } else {
         static const hipError_t attr =
-            allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, false>), smem);
+            allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, false, DR>), smem);
         if (attr != hipSuccess) return attr;
-        hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, false>), dim3(grid), dim3(256), smem, stream, p);
+        hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, false, DR>), dim3(grid), dim3(256), smem, stream, p);
     }
     return hipGetLastError();
 }
@@ -712,6 +721,7 @@ hipError_t launch_bwd_delta(const AttnParams& p, hipStream_t stream) {
 hipError_t launch_bwd_dkdv(const AttnParams& p, hipStream_t stream) {
     switch (p.D) {
         case 64: return launch_dkdv_d<64>(p, stream);
+        case 80: return launch_dkdv_d<128, 80>(p, stream);
         case 128: return launch_dkdv_d<128>(p, stream);
         case 256: return launch_dkdv_d<256>(p, stream);
         default: return hipErrorInvalidValue;
@@ -721,6 +731,7 @@ hipError_t launch_bwd_dkdv(const AttnParams& p, hipStream_t stream) {
 hipError_t launch_bwd_dq(const AttnParams& p, hipStream_t stream) {
     switch (p.D) {
         case 64: return launch_dq_d<64>(p, stream);
+        case 80: return launch_dq_d<128, 80>(p, stream);
         case 128: return launch_dq_d<128>(p, stream);
         case 256: return launch_dq_d<256>(p, stream);
         default: return hipErrorInvalidValue;

@@ -46,7 +46,12 @@ constexpr int32_t kDqKvTile = 64;
 // A dK/dV workgroup owns kDkdvKvRows key rows of one KV head and visits the
 // query rows that see them kDkdvQTile rows at a time, for every head of the group.
 constexpr int32_t kDkdvKvRows = 128;
-constexpr int32_t dkdv_q_tile(int32_t D) { return D >= 128 ? 32 : 64; }
+// Head dimensions the kernels exist for, and the geometry (values per row of the LDS tiles and register
+// blocks) each runs on: 80, the head dimension of the vision encoder the paper trains (section 2.2.1 (1)),
+// uses the geometry of 128 with 5 of 8 contraction steps and 3 of 4 output blocks.
+constexpr bool head_dim_supported(int32_t D) { return D == 64 || D == 80 || D == 128 || D == 256; }
+constexpr int32_t tile_geometry(int32_t D) { return D <= 64 ? 64 : D <= 128 ? 128 : 256; }
+constexpr int32_t dkdv_q_tile(int32_t D) { return tile_geometry(D) >= 128 ? 32 : 64; }
 
 // Whether the dQ kernel computes delta = rowsum(dO * O) and LSE * log2(e) itself (and then runs before
 // the dK/dV kernel, which reads both) instead of a separate pass over O and dO.

@@ -39,12 +39,18 @@ using FwdWork = RowWork;
 // last key tile of a work is being processed, the first K/V tile of the next work is already on its way
 // into the free LDS stage and the next Q fragments are being loaded, so a work switch costs no memory
 // round trip.
-template <int D, int HPB>
+// D is the geometry of the LDS tiles and register blocks (64, 128 or 256 values per row); DR <= D the
+// head dimension of the tensors in memory, a multiple of 16: products run over DR / 16 k-steps and
+// (DR + 31) / 32 output blocks only, and the chunks of a row from DR / 8 on are neither fetched nor stored.
+template <int D, int HPB, int DR>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnParams p) {
+    static_assert(DR % 16 == 0 && DR <= D && DR > D / 2, "head dimension and geometry do not match");
     constexpr int BMT = kFwdBlockRows / HPB;  // token rows of the work item
     constexpr int BN = kFwdKvTile;
-    constexpr int KSTEPS = D / 16;  // MFMA steps over the head dimension
-    constexpr int DT = D / 32;      // 32-row blocks of O^T
+    constexpr int KSTEPS = DR / 16;        // MFMA steps over the head dimension
+    constexpr int DT = (DR + 31) / 32;     // 32-row blocks of O^T
+    constexpr int NQ = D / 16;             // row fragments a block of rows is fetched as (the first KSTEPS are used)
+    using Rows = RowBlock<D, DR>;
     constexpr int TILE_BYTES = BN * D * 2;
     extern __shared__ __attribute__((aligned(16))) char smem[];  // two stages, each a K tile then a V tile
 
@@ -54,47 +60,47 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     FwdWork cur;
     if (!works.start((int)blockIdx.x, &cur)) return;
 
-    const int kv_row_bytes = p.Hkv * D * 2;
+    const int kv_row_bytes = p.Hkv * DR * 2;
     const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
     const unsigned smem_lds = lds_addr(smem);
-    AsyncTile<D, BN, 4> loader;
+    AsyncTile<D, BN, 4, DR> loader;
     loader.init(wave, lane, kv_row_bytes);
     const FragAddr<D> fa(lane);
     const float c = p.scale * kLog2e;
 
     // K and V rows of one sample and KV head as raw buffers: rows >= L read as zero
     auto kv_rsrc = [&](const void* base, const FwdWork& w) {
-        return make_rsrc(static_cast<const __bf16*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D,
-                         (unsigned)(w.L - 1) * kv_row_bytes + D * 2);
+        return make_rsrc(static_cast<const __bf16*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * DR,
+                         (unsigned)(w.L - 1) * kv_row_bytes + DR * 2);
     };
     // Q rows of the wave's 32 stacked rows, whole rows per group of lanes; to_fragments() turns them into
     // the fragments of the row this lane owns (k-slots d = 16 t + 8 hf + 0..7)
     const int row = wave * 32 + l32;
     // Stacked row rr = wave * 32 + r is token rr % BMT of head h0 + rr / BMT; seen from the first row of
     // the work's first head, tokens past q_rows lie beyond the end of the buffer and read as zero.
-    const int q_tok_bytes = p.Hq * D * 2;
+    const int q_tok_bytes = p.Hq * DR * 2;
     auto block_rows = [&](const void* tensor, const FwdWork& w) {
-        return RowBlock<D>::rows(static_cast<const __bf16*>(tensor) + ((size_t)w.q_row0 * p.Hq + w.h0) * D,
-                                 (unsigned)(w.q_rows - 1) * q_tok_bytes + HPB * D * 2);
+        return Rows::rows(static_cast<const __bf16*>(tensor) + ((size_t)w.q_row0 * p.Hq + w.h0) * DR,
+                          (unsigned)(w.q_rows - 1) * q_tok_bytes + HPB * DR * 2);
     };
     auto block_soff = [&](int j) {
-        const int rr = __builtin_amdgcn_readfirstlane(wave * 32 + j * RowBlock<D>::RPI);
-        return (rr % BMT) * q_tok_bytes + (rr / BMT) * (D * 2);
+        const int rr = __builtin_amdgcn_readfirstlane(wave * 32 + j * Rows::RPI);
+        return (rr % BMT) * q_tok_bytes + (rr / BMT) * (DR * 2);
     };
-    auto load_q = [&](bf16x8 (&qf)[KSTEPS], const FwdWork& w) {
-        RowBlock<D>::load(qf, block_rows(p.q, w), RowBlock<D>::lane_offset(lane, q_tok_bytes), block_soff);
+    auto load_q = [&](bf16x8 (&qf)[NQ], const FwdWork& w) {
+        Rows::load(qf, block_rows(p.q, w), Rows::lane_offset(lane, q_tok_bytes), block_soff);
     };
     // output rows and the LSE store that leave at the end of a work: vector memory operations younger than
     // the loads of the next work's first tile
-    constexpr int kEpilogueStores = RowBlock<D>::N + 1;
+    constexpr int kEpilogueStores = Rows::N + 1;
     const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
 
     int stage = 0;  // LDS stage that holds (or will hold) the tile about to be processed
     loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
     loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
-    bf16x8 qf[KSTEPS];
+    bf16x8 qf[NQ];
     load_q(qf, cur);
-    RowBlock<D>::to_fragments(qf, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);  // stage 1 is still free
+    Rows::to_fragments(qf, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);  // stage 1 is still free
 
     for (;;) {
         const bool has_next = works.has_next();
@@ -261,43 +267,43 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         // the first tile of the next work); every wave must be done reading it first
         __syncthreads();
         const int out_slice = (stage ^ 1) * 2 * TILE_BYTES + slice_in_stage;
-        store_block_rows<D>(smem + out_slice, o, 1.0f / lsum, lane, block_rows(p.out, cur),
-                            RowBlock<D>::lane_offset(lane, q_tok_bytes), block_soff);
+        store_block_rows<D, DT>(smem + out_slice, o, 1.0f / lsum, lane, block_rows(p.out, cur),
+                                Rows::lane_offset(lane, q_tok_bytes), block_soff);
         {
             // LSE of the row this lane owns, from the lanes of the lower half; the others aim past the buffer
             const __amdgpu_buffer_rsrc_t lse_rows =
-                RowBlock<D>::rows(p.lse + (size_t)cur.h0 * p.T + cur.q_row0, (unsigned)((HPB - 1) * p.T + cur.q_rows) * 4u);
+                Rows::rows(p.lse + (size_t)cur.h0 * p.T + cur.q_row0, (unsigned)((HPB - 1) * p.T + cur.q_rows) * 4u);
             const int off = (row_valid && hf == 0) ? ((row / BMT) * p.T + tok) * 4 : 0x7ffffff0;
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, (m + __builtin_amdgcn_logf(lsum)) * kLn2), lse_rows,
                                                   off, 0, 0);
         }
         if (!has_next) break;
         // the next Q rows have arrived meanwhile; the same slice turns them into fragments
-        RowBlock<D>::to_fragments(qf, smem, out_slice, fa, lane);
+        Rows::to_fragments(qf, smem, out_slice, fa, lane);
         works.advance();
         cur = nxt;
     }
 }
 
-template <int D, int HPB>
+template <int D, int HPB, int DR>
 hipError_t launch_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
     constexpr size_t smem = 2 * 2 * kFwdKvTile * D * 2;  // two stages of (K tile, V tile)
-    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&fwd_bf16_kernel<D, HPB>), smem);
+    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&fwd_bf16_kernel<D, HPB, DR>), smem);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((fwd_bf16_kernel<D, HPB>), dim3(grid), dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, HPB, DR>), dim3(grid), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, int DR = D>
 hipError_t launch_d(const AttnParams& p, hipStream_t stream) {
     const int hpb = heads_per_block(p.Hq, p.Hkv);
     const unsigned grid = (unsigned)p.num_workgroups;
     if (p.num_items == 0) return hipSuccess;
     switch (hpb) {
-        case 1: return launch_dh<D, 1>(p, stream, grid);
-        case 2: return launch_dh<D, 2>(p, stream, grid);
-        case 4: return launch_dh<D, 4>(p, stream, grid);
-        default: return launch_dh<D, 8>(p, stream, grid);
+        case 1: return launch_dh<D, 1, DR>(p, stream, grid);
+        case 2: return launch_dh<D, 2, DR>(p, stream, grid);
+        case 4: return launch_dh<D, 4, DR>(p, stream, grid);
+        default: return launch_dh<D, 8, DR>(p, stream, grid);
     }
 }
 
@@ -306,6 +312,7 @@ hipError_t launch_d(const AttnParams& p, hipStream_t stream) {
 hipError_t launch_fwd_bf16(const AttnParams& p, hipStream_t stream) {
     switch (p.D) {
         case 64: return launch_d<64>(p, stream);
+        case 80: return launch_d<128, 80>(p, stream);
         case 128: return launch_d<128>(p, stream);
         case 256: return launch_d<256>(p, stream);
         default: return hipErrorInvalidValue;

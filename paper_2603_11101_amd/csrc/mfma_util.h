@@ -247,7 +247,12 @@ VA_DEV void wait_async_loads_except() {
 // fills chunk position pc of row r fetches chunk pc ^ swizzle(r) of that row, so
 // the swizzle costs nothing.  The per-lane offsets do not depend on which tile
 // of the sample is fetched: that goes into the scalar offset of the load.
-template <int D, int ROWS, int NWAVES>
+//
+// DR < D: the rows in memory hold DR values (DR * 2 bytes, a multiple of 32) and the tile keeps the
+// geometry of D: chunk positions from DR / 8 on are not fetched (their lanes aim past the buffer and the
+// hardware writes zeros).  Row bytes are then no multiple of the tile's row size, so the chunk can no
+// longer be XOR-ed inside the byte offset and travels in a register of its own.
+template <int D, int ROWS, int NWAVES, int DR = D>
 struct AsyncTile {
     static constexpr int CPR = D / 8;
     static constexpr int RPI = 64 / CPR;
@@ -267,6 +272,7 @@ struct AsyncTile {
     }
     static_assert(self_check(), "the swizzle does not separate into a lane part and an instruction part");
     int voff0;
+    int chunk0;    // DR < D only: chunk fetched by instruction 0 (voff0 then holds the row part alone)
     int first;     // first instruction of this wave
     int row_step;  // bytes between the rows of consecutive instructions
 
@@ -275,7 +281,13 @@ struct AsyncTile {
         row_step = __builtin_amdgcn_readfirstlane(RPI * row_bytes);
         const int pc = lane % CPR;
         const int r = wave * PER_WAVE * RPI + lane / CPR;
-        voff0 = r * row_bytes + ((pc ^ swizzle<D>(r)) << 4);
+        if constexpr (DR == D) {
+            voff0 = r * row_bytes + ((pc ^ swizzle<D>(r)) << 4);
+            chunk0 = 0;
+        } else {
+            voff0 = r * row_bytes;
+            chunk0 = pc ^ swizzle<D>(r);
+        }
     }
     // tile_lds: LDS address of the tile; soffset: byte offset of the tile's first row in the buffer, which
     // must lie inside the buffer: the range check compares the per-lane offset with the buffer size minus
@@ -284,8 +296,15 @@ struct AsyncTile {
         int v = voff0;
         asm volatile("" : "+v"(v));  // derive the offsets here instead of keeping PER_WAVE of them in registers
 #pragma unroll
-        for (int j = 0; j < PER_WAVE; ++j)
-            buffer_load_lds_16(tile_lds + (first + j) * 1024, (v ^ (swizzle<D>(j * RPI) << 4)) + j * row_step, rsrc, soffset);
+        for (int j = 0; j < PER_WAVE; ++j) {
+            if constexpr (DR == D) {
+                buffer_load_lds_16(tile_lds + (first + j) * 1024, (v ^ (swizzle<D>(j * RPI) << 4)) + j * row_step, rsrc, soffset);
+            } else {
+                const int c = chunk0 ^ swizzle<D>(j * RPI);
+                const int off = c < DR / 8 ? v + j * row_step + (c << 4) : 0x7ffffff0;
+                buffer_load_lds_16(tile_lds + (first + j) * 1024, off, rsrc, soffset);
+            }
+        }
     }
 };
 
@@ -296,7 +315,9 @@ struct AsyncTile {
 // touch 32 rows with 32 bytes each, and the address path of the vector cache handles one row (cache
 // line) at a time.  So the block is fetched with whole rows per group of lanes (64 / (D/8) rows per
 // instruction) and turned into fragments through a wave-private, swizzled 32 x D LDS slice.
-template <int D>
+// DR < D: rows of DR values in memory, geometry of D in LDS and registers; the lanes of the chunks from
+// DR / 8 on aim past the buffer (they load zeros and store nothing).
+template <int D, int DR = D>
 struct RowBlock {
     static constexpr int CPR = D / 8;     // 16-byte chunks of a row
     static constexpr int RPI = 64 / CPR;  // rows per wave instruction
@@ -307,7 +328,9 @@ struct RowBlock {
     // instead of occupying a register for the whole kernel.
     VA_DEV static int lane_offset(int lane, int row_bytes) {
         asm volatile("" : "+v"(lane));
-        return (lane / CPR) * row_bytes + (lane % CPR) * 16;
+        const int off = (lane / CPR) * row_bytes + (lane % CPR) * 16;
+        if constexpr (DR == D) return off;
+        return lane % CPR < DR / 8 ? off : 0x7ffffff0;
     }
 
     // The rows of a block in global memory, seen through a raw buffer of `bytes` bytes at `base`: whatever
@@ -400,8 +423,10 @@ struct OutStage {
 // The rows go out through a raw buffer as in RowBlock (rsrc, lane_off, soff(j) = byte offset of row
 // j * RPI): rows past the end of the buffer are dropped by the hardware.  Exactly RowBlock<D>::N store
 // instructions, whatever the number of valid rows, so that a later wait can count them.
-template <int D, typename RowOffset>
-VA_DEV void store_block_rows(char* stage, const f32x16 (&acc)[D / 32], float factor, int lane,
+// NB = number of 32-column blocks the accumulator holds ((DR + 31) / 32 when the rows in memory are
+// shorter than the geometry; the lanes of the columns past DR come with a lane_off past the buffer).
+template <int D, int NB = D / 32, typename RowOffset>
+VA_DEV void store_block_rows(char* stage, const f32x16 (&acc)[NB], float factor, int lane,
                              __amdgpu_buffer_rsrc_t rsrc, int lane_off, RowOffset soff) {
     using S = OutStage<D>;
     // This code runs with few registers free.  The lane constants are made opaque here so that they are
@@ -410,7 +435,7 @@ VA_DEV void store_block_rows(char* stage, const f32x16 (&acc)[D / 32], float fac
     asm volatile("" : "+v"(l));
     const int wb = S::wbase(l);
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+    for (int dt = 0; dt < NB; ++dt)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             f32x4 f = {acc[dt][4 * q] * factor, acc[dt][4 * q + 1] * factor, acc[dt][4 * q + 2] * factor,

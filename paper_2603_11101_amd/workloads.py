@@ -27,7 +27,7 @@ the paper runs through the same variable-length interface, section 2.2.1 (1)):
             returned by sample_lengths is then [pool, 2]: the ends of the first
             two blocks
   vit       pool of 512 images of side U{16,24,32,38} patches, side^2 tokens
-            each; 16 / 16 heads, D = 128; every token sees its whole image
+            each; 16 / 16 heads, D = 80 (the encoder's 1280 / 16); every token sees its whole image
             (prefix = length); budget 16384
 
 Tensor values are float32 standard normal draws rounded once to bfloat16
@@ -58,7 +58,7 @@ WORKLOADS = {
     "pi05": Workload("pi05", 3, 8, 1, 256, True, 32768, 512),
     "longtail": Workload("longtail", 4, 16, 8, 128, False, 65536, 2048),
     "vlm_fp8": Workload("vlm_fp8", 2, 16, 8, 128, False, 16384, 512),
-    "vit": Workload("vit", 5, 16, 16, 128, True, 16384, 512),
+    "vit": Workload("vit", 5, 16, 16, 80, True, 16384, 512),
     "pi0": Workload("pi0", 6, 8, 1, 256, True, 32768, 512, three_block=True),
 }
 

@@ -60,7 +60,7 @@ def test_first_fit_random_and_edge_cases():
     assert e.value.code == va.VA_EINVAL
 
 
-HEADS = [(2, 2, 64), (16, 8, 128), (8, 1, 256), (4, 1, 64), (6, 2, 128)]
+HEADS = [(2, 2, 64), (16, 8, 128), (8, 1, 256), (4, 1, 64), (6, 2, 128), (4, 4, 80)]
 
 
 @pytest.mark.parametrize("mode", [va.VA_MASK_CAUSAL, va.VA_MASK_PREFIX_LM, va.VA_MASK_PREFIX_LM_CAUSAL, va.VA_MASK_THREE_BLOCK])
@@ -127,6 +127,7 @@ def test_worklist_counts_on_the_workloads():
 
 
 def test_tile_shape_errors():
+    assert va.va_tile_shape(va.VA_PASS_BWD_DKDV, 80, 4, 4) == va.va_tile_shape(va.VA_PASS_BWD_DKDV, 128, 4, 4)
     for bad in ((va.VA_PASS_FWD, 96, 4, 2), (va.VA_PASS_FWD, 128, 5, 2), (7, 128, 4, 2)):
         with pytest.raises(va.VarlenAttnError) as e:
             va.va_tile_shape(*bad)
