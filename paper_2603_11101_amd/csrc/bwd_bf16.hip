@@ -654,7 +654,7 @@ template <int D, int HPB, int DR>
 hipError_t launch_dq_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
     constexpr size_t smem = 2 * 2 * kDqKvTile * D * 2;  // two stages of (K tile, V tile)
     constexpr bool FUSE = dq_computes_delta(D);
-    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dq_kernel<D, HPB, FUSE, DR>), smem);
+    const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dq_kernel<D, HPB, FUSE, DR>), smem);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((bwd_dq_kernel<D, HPB, FUSE, DR>), dim3(grid), dim3(256), smem, stream, p);
     return hipGetLastError();
@@ -683,13 +683,11 @@ hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     const unsigned grid = (unsigned)(p.num_items * p.works_per_item);
     // one instantiation per mask family: the masks without a second block do not pay for it
     if (p.mask_mode == VA_MASK_THREE_BLOCK) {
-        static const hipError_t attr =
-            allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, true, DR>), smem);
+        const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dkdv_kernel<D, V_LDS, true, DR>), smem);
         if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, true, DR>), dim3(grid), dim3(256), smem, stream, p);
     } else {
-        static const hipError_t attr =
-            allow_dynamic_lds(reinterpret_cast<const void*>(&bwd_dkdv_kernel<D, V_LDS, false, DR>), smem);
+        const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dkdv_kernel<D, V_LDS, false, DR>), smem);
         if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, false, DR>), dim3(grid), dim3(256), smem, stream, p);
     }

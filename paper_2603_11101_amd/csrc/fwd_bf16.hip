@@ -288,7 +288,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
 template <int D, int HPB, int DR>
 hipError_t launch_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
     constexpr size_t smem = 2 * 2 * kFwdKvTile * D * 2;  // two stages of (K tile, V tile)
-    static const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void*>(&fwd_bf16_kernel<D, HPB, DR>), smem);
+    const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&fwd_bf16_kernel<D, HPB, DR>), smem);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((fwd_bf16_kernel<D, HPB, DR>), dim3(grid), dim3(256), smem, stream, p);
     return hipGetLastError();

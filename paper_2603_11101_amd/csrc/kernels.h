@@ -2,6 +2,7 @@
 // translation units.  Every launcher only enqueues on `stream`.
 #pragma once
 
+#include <atomic>
 #include <hip/hip_runtime.h>
 
 #include "common.h"
@@ -34,11 +35,29 @@ struct AttnParams {
     float scale;
 };
 
-// Kernels that need more than the default 64 KiB of dynamic LDS must say so once.
-inline hipError_t allow_dynamic_lds(const void* kernel, size_t bytes) {
-    if (bytes <= 64 * 1024) return hipSuccess;
-    return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-}
+// Kernels that need more than the default 64 KiB of dynamic LDS must say so once per device (a process
+// may drive several).  One DynamicLds object per launch site remembers the devices it has served.
+struct DynamicLds {
+    std::atomic<unsigned long long> served{0};  // bit d: device d has the attribute
+    hipError_t allow(const void* kernel, size_t bytes) {
+        if (bytes <= 64 * 1024) return hipSuccess;
+        int dev = -1;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const bool tracked = dev >= 0 && dev < 64;
+        if (tracked && (served.load(std::memory_order_acquire) >> dev & 1ull)) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess && tracked) served.fetch_or(1ull << dev, std::memory_order_release);
+        return e;
+    }
+};
+// expands to an expression of type hipError_t; the lambda gives every launch site (and every template
+// instantiation of it) a DynamicLds of its own
+#define VA_ALLOW_DYNAMIC_LDS(kernel, bytes)                                   \
+    ([&]() -> hipError_t {                                                    \
+        static ::va::DynamicLds site;                                         \
+        return site.allow(reinterpret_cast<const void*>(kernel), (bytes));    \
+    }())
 
 hipError_t launch_fwd_bf16(const AttnParams& p, hipStream_t stream);
 hipError_t launch_fwd_fp8(const AttnParams& p, hipStream_t stream);
