@@ -54,7 +54,7 @@ extern "C" {
 
 #define VA_OK 0
 #define VA_EINVAL (-1)       /* null pointer, negative size, inconsistent arguments */
-#define VA_EUNSUPPORTED (-2) /* head_dim not in {64,80,128,256}, Hq % Hkv != 0, unknown mask/pass */
+#define VA_EUNSUPPORTED (-2) /* head_dim not in {48,64,80,96,128,160,192,256}, Hq % Hkv != 0, unknown mask/pass */
 #define VA_EALIGN (-3)       /* a tensor pointer is not 16-byte aligned */
 #define VA_ESIZE (-4)        /* output/workspace buffer too small, sample longer than budget or max_seqlen */
 #define VA_EHIP (-5)         /* the HIP runtime refused a launch */
@@ -74,7 +74,7 @@ typedef struct {
     int32_t num_seqs;     /* n */
     int32_t num_q_heads;  /* Hq */
     int32_t num_kv_heads; /* Hkv, Hq % Hkv == 0 */
-    int32_t head_dim;     /* D in {64, 80, 128, 256}; the FP8 forward takes 128 only */
+    int32_t head_dim;     /* D in {48, 64, 80, 96, 128, 160, 192, 256}; the FP8 forward takes 128 only */
     int32_t max_seqlen;   /* >= every sample length; validation only, never changes results */
     int32_t mask_mode;    /* VA_MASK_* ; VA_MASK_CAUSAL ignores prefix_lens */
 } va_shape;

@@ -19,7 +19,7 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
     if (s->mask_mode != VA_MASK_CAUSAL && !prefix_lens)
         return fail(VA_EINVAL, "%s: a prefix mask needs prefix_lens", who);
     if (!head_dim_supported(s->head_dim))
-        return fail(VA_EUNSUPPORTED, "%s: head_dim %d not in {64,80,128,256}", who, s->head_dim);
+        return fail(VA_EUNSUPPORTED, "%s: head_dim %d not in {48,64,80,96,128,160,192,256}", who, s->head_dim);
     if (s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->num_q_heads % s->num_kv_heads != 0)
         return fail(VA_EUNSUPPORTED, "%s: num_q_heads %d is not a positive multiple of num_kv_heads %d", who,
                     s->num_q_heads, s->num_kv_heads);

@@ -38,7 +38,8 @@ constexpr int kPrefetch = 4;  // LDS fragment reads in flight ahead of the MFMA 
 // kDeltaRowsPerGroup rows, all of whose loads are issued before the first is used.
 constexpr int kDeltaRowsPerGroup = 4;
 
-template <int D>
+// DR <= D is the head dimension in memory: the lanes of a group past DR / 8 load nothing and add zero.
+template <int D, int DR>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ dout,
                                                         const float* __restrict__ lse, float* __restrict__ delta,
                                                         float* __restrict__ lse2, int T, int Hq) {
@@ -52,8 +53,13 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
 #pragma unroll
     for (int i = 0; i < R; ++i) {
         const size_t row = row0 + i < rows ? row0 + i : rows - 1;
-        a[i] = *reinterpret_cast<const bf16x8*>(o + row * D + c * 8);
-        b[i] = *reinterpret_cast<const bf16x8*>(dout + row * D + c * 8);
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        a[i] = __builtin_bit_cast(bf16x8, zero);
+        b[i] = __builtin_bit_cast(bf16x8, zero);
+        if (DR == D || c < DR / 8) {
+            a[i] = *reinterpret_cast<const bf16x8*>(o + row * DR + c * 8);
+            b[i] = *reinterpret_cast<const bf16x8*>(dout + row * DR + c * 8);
+        }
     }
 #pragma unroll
     for (int i = 0; i < R; ++i) {
@@ -694,13 +700,13 @@ hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, int DR = D>
 hipError_t launch_delta_d(const AttnParams& p, hipStream_t stream) {
     const size_t rows = (size_t)p.T * p.Hq;
     constexpr int RPB = 256 / (D / 8) * kDeltaRowsPerGroup;
     const unsigned grid = (unsigned)((rows + RPB - 1) / RPB);
     if (grid == 0) return hipSuccess;
-    hipLaunchKernelGGL((bwd_delta_kernel<D>), dim3(grid), dim3(256), 0, stream, static_cast<const __bf16*>(p.out),
+    hipLaunchKernelGGL((bwd_delta_kernel<D, DR>), dim3(grid), dim3(256), 0, stream, static_cast<const __bf16*>(p.out),
                        static_cast<const __bf16*>(p.dout), p.lse, p.delta, p.lse2, p.T, p.Hq);
     return hipGetLastError();
 }
@@ -709,8 +715,13 @@ hipError_t launch_delta_d(const AttnParams& p, hipStream_t stream) {
 
 hipError_t launch_bwd_delta(const AttnParams& p, hipStream_t stream) {
     switch (p.D) {
+        case 48: return launch_delta_d<64, 48>(p, stream);
         case 64: return launch_delta_d<64>(p, stream);
+        case 80: return launch_delta_d<128, 80>(p, stream);
+        case 96: return launch_delta_d<128, 96>(p, stream);
         case 128: return launch_delta_d<128>(p, stream);
+        case 160: return launch_delta_d<256, 160>(p, stream);
+        case 192: return launch_delta_d<256, 192>(p, stream);
         case 256: return launch_delta_d<256>(p, stream);
         default: return hipErrorInvalidValue;
     }
@@ -718,9 +729,13 @@ hipError_t launch_bwd_delta(const AttnParams& p, hipStream_t stream) {
 
 hipError_t launch_bwd_dkdv(const AttnParams& p, hipStream_t stream) {
     switch (p.D) {
+        case 48: return launch_dkdv_d<64, 48>(p, stream);
         case 64: return launch_dkdv_d<64>(p, stream);
         case 80: return launch_dkdv_d<128, 80>(p, stream);
+        case 96: return launch_dkdv_d<128, 96>(p, stream);
         case 128: return launch_dkdv_d<128>(p, stream);
+        case 160: return launch_dkdv_d<256, 160>(p, stream);
+        case 192: return launch_dkdv_d<256, 192>(p, stream);
         case 256: return launch_dkdv_d<256>(p, stream);
         default: return hipErrorInvalidValue;
     }
@@ -728,9 +743,13 @@ hipError_t launch_bwd_dkdv(const AttnParams& p, hipStream_t stream) {
 
 hipError_t launch_bwd_dq(const AttnParams& p, hipStream_t stream) {
     switch (p.D) {
+        case 48: return launch_dq_d<64, 48>(p, stream);
         case 64: return launch_dq_d<64>(p, stream);
         case 80: return launch_dq_d<128, 80>(p, stream);
+        case 96: return launch_dq_d<128, 96>(p, stream);
         case 128: return launch_dq_d<128>(p, stream);
+        case 160: return launch_dq_d<256, 160>(p, stream);
+        case 192: return launch_dq_d<256, 192>(p, stream);
         case 256: return launch_dq_d<256>(p, stream);
         default: return hipErrorInvalidValue;
     }

@@ -48,8 +48,11 @@ constexpr int32_t kDqKvTile = 64;
 constexpr int32_t kDkdvKvRows = 128;
 // Head dimensions the kernels exist for, and the geometry (values per row of the LDS tiles and register
 // blocks) each runs on: 80, the head dimension of the vision encoder the paper trains (section 2.2.1 (1)),
-// uses the geometry of 128 with 5 of 8 contraction steps and 3 of 4 output blocks.
-constexpr bool head_dim_supported(int32_t D) { return D == 64 || D == 80 || D == 128 || D == 256; }
+// uses the geometry of 128 with 5 of 8 contraction steps and 3 of 4 output blocks; the other values in
+// between work the same way.
+constexpr bool head_dim_supported(int32_t D) {
+    return D == 48 || D == 64 || D == 80 || D == 96 || D == 128 || D == 160 || D == 192 || D == 256;
+}
 constexpr int32_t tile_geometry(int32_t D) { return D <= 64 ? 64 : D <= 128 ? 128 : 256; }
 constexpr int32_t dkdv_q_tile(int32_t D) { return tile_geometry(D) >= 128 ? 32 : 64; }
 

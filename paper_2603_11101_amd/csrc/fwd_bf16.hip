@@ -311,9 +311,13 @@ hipError_t launch_d(const AttnParams& p, hipStream_t stream) {
 
 hipError_t launch_fwd_bf16(const AttnParams& p, hipStream_t stream) {
     switch (p.D) {
+        case 48: return launch_d<64, 48>(p, stream);
         case 64: return launch_d<64>(p, stream);
         case 80: return launch_d<128, 80>(p, stream);
+        case 96: return launch_d<128, 96>(p, stream);
         case 128: return launch_d<128>(p, stream);
+        case 160: return launch_d<256, 160>(p, stream);
+        case 192: return launch_d<256, 192>(p, stream);
         case 256: return launch_d<256>(p, stream);
         default: return hipErrorInvalidValue;
     }

@@ -34,7 +34,7 @@ int heads_per_block(int32_t Hq, int32_t Hkv) {
 }
 
 int tile_shape(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t* rows, int32_t* cols) {
-    if (!head_dim_supported(D)) return fail(VA_EUNSUPPORTED, "head_dim %d not in {64,80,128,256}", D);
+    if (!head_dim_supported(D)) return fail(VA_EUNSUPPORTED, "head_dim %d not in {48,64,80,96,128,160,192,256}", D);
     if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0)
         return fail(VA_EUNSUPPORTED, "num_q_heads %d is not a positive multiple of num_kv_heads %d", Hq, Hkv);
     switch (pass) {

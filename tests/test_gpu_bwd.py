@@ -43,7 +43,7 @@ LENS = [17, 64, 95, 200, 1, 130, 0, 257]
 
 
 @pytest.mark.parametrize("mode", list(MODES))
-@pytest.mark.parametrize("Hq,Hkv,D", [(2, 2, 64), (4, 2, 128), (8, 1, 256), (4, 1, 128), (6, 2, 64), (16, 1, 64), (2, 1, 256), (4, 4, 80), (4, 1, 80)])
+@pytest.mark.parametrize("Hq,Hkv,D", [(2, 2, 64), (4, 2, 128), (8, 1, 256), (4, 1, 128), (6, 2, 64), (16, 1, 64), (2, 1, 256), (4, 4, 80), (4, 1, 80), (2, 1, 48), (2, 2, 96), (2, 1, 160), (4, 2, 192)])
 def test_backward_parity(mode, Hq, Hkv, D):
     seed = Hq * 100 + D + mode
     cu, prefix, q, k, v, do = wl.random_stream(seed, LENS, Hq, Hkv, D, prefix_frac=-1.0)
@@ -129,7 +129,7 @@ def test_random_configurations_forward_and_backward(trial):
     r = np.random.default_rng(4000 + trial)
     Hkv = int(r.choice([1, 2, 3]))
     G = int(r.choice([1, 2, 3, 4, 8]))
-    D = int(r.choice([64, 80, 128, 256]))
+    D = int(r.choice([48, 64, 80, 96, 128, 160, 192, 256]))
     mode = int(r.choice(list(MODES)))
     lens = [int(x) for x in r.choice([0, 1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 190, 300, 450], size=int(r.integers(2, 7)))]
     if sum(lens) == 0:

@@ -45,7 +45,7 @@ LENS = [17, 64, 95, 200, 1, 130, 0, 257]
 
 
 @pytest.mark.parametrize("mode", list(MODES))
-@pytest.mark.parametrize("Hq,Hkv,D", [(2, 2, 64), (4, 2, 128), (8, 1, 256), (4, 1, 128), (6, 2, 64), (16, 1, 64), (2, 1, 256), (4, 4, 80), (4, 1, 80)])
+@pytest.mark.parametrize("Hq,Hkv,D", [(2, 2, 64), (4, 2, 128), (8, 1, 256), (4, 1, 128), (6, 2, 64), (16, 1, 64), (2, 1, 256), (4, 4, 80), (4, 1, 80), (2, 1, 48), (2, 2, 96), (2, 1, 160), (4, 2, 192)])
 def test_forward_parity(mode, Hq, Hkv, D):
     seed = Hq * 100 + D + mode
     cu, prefix, q, k, v, do = wl.random_stream(seed, LENS, Hq, Hkv, D, prefix_frac=-1.0)

@@ -60,7 +60,7 @@ def test_first_fit_random_and_edge_cases():
     assert e.value.code == va.VA_EINVAL
 
 
-HEADS = [(2, 2, 64), (16, 8, 128), (8, 1, 256), (4, 1, 64), (6, 2, 128), (4, 4, 80)]
+HEADS = [(2, 2, 64), (16, 8, 128), (8, 1, 256), (4, 1, 64), (6, 2, 128), (4, 4, 80), (2, 1, 192)]
 
 
 @pytest.mark.parametrize("mode", [va.VA_MASK_CAUSAL, va.VA_MASK_PREFIX_LM, va.VA_MASK_PREFIX_LM_CAUSAL, va.VA_MASK_THREE_BLOCK])
@@ -128,7 +128,7 @@ def test_worklist_counts_on_the_workloads():
 
 def test_tile_shape_errors():
     assert va.va_tile_shape(va.VA_PASS_BWD_DKDV, 80, 4, 4) == va.va_tile_shape(va.VA_PASS_BWD_DKDV, 128, 4, 4)
-    for bad in ((va.VA_PASS_FWD, 96, 4, 2), (va.VA_PASS_FWD, 128, 5, 2), (7, 128, 4, 2)):
+    for bad in ((va.VA_PASS_FWD, 112, 4, 2), (va.VA_PASS_FWD, 32, 4, 2), (va.VA_PASS_FWD, 128, 5, 2), (7, 128, 4, 2)):
         with pytest.raises(va.VarlenAttnError) as e:
             va.va_tile_shape(*bad)
         assert e.value.code == va.VA_EUNSUPPORTED
@@ -171,7 +171,7 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
 
     ok = dict(total_tokens=100, num_seqs=2, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, max_seqlen=60,
               mask_mode=va.VA_MASK_CAUSAL)
-    assert call(va.make_shape(**{**ok, "head_dim": 96}))[0] == va.VA_EUNSUPPORTED
+    assert call(va.make_shape(**{**ok, "head_dim": 112}))[0] == va.VA_EUNSUPPORTED
     assert call(va.make_shape(**{**ok, "num_q_heads": 3}))[0] == va.VA_EUNSUPPORTED
     assert call(va.make_shape(**{**ok, "max_seqlen": 59}))[0] == va.VA_ESIZE
     assert call(va.make_shape(**{**ok, "max_seqlen": 1 << 29}))[0] == va.VA_ESIZE       # 32-bit buffer offsets
