@@ -87,3 +87,55 @@ def quantize_per_head(x):
 def dequantize_per_head(codes, descale):
     """codes [T, H, D], descale [H] -> float64 values code_value * descale."""
     return decode(codes) * np.asarray(descale, dtype=np.float64)[None, :, None]
+
+
+# ---------------------------------------------------------------- block-wise scaling
+#
+# The paper's third granularity (section 2.2.3: one scale per 128 x 128 block of the tensor).  Read for
+# the attention operands [T, H, D] of a packed stream as: 128 consecutive tokens of ONE sample by the
+# 128 values of one head, so a block never mixes two samples; sample s of length L_s has ceil(L_s / 128)
+# token blocks (the last one shorter) and the blocks of the stream are numbered sample after sample.
+
+BLOCK_TOKENS = 128
+
+
+def block_starts(cu_seqlens, block=BLOCK_TOKENS):
+    """First block number of every sample, and the total number of blocks (last entry)."""
+    out = [0]
+    for s in range(len(cu_seqlens) - 1):
+        L = int(cu_seqlens[s + 1]) - int(cu_seqlens[s])
+        out.append(out[-1] + (L + block - 1) // block)
+    return np.array(out, dtype=np.int32)
+
+
+def quantize_blockwise(x, cu_seqlens, block=BLOCK_TOKENS):
+    """x [T, H, D] float32 -> (codes uint8 [T, H, D], descale float32 [num_blocks, H]): descale =
+    amax of the block / 448 (1 where the block is all zero), code = encode(float32(x / descale))."""
+    x = np.asarray(x, dtype=np.float32)
+    T, H, D = x.shape
+    starts = block_starts(cu_seqlens, block)
+    descale = np.ones((int(starts[-1]), H), dtype=np.float32)
+    codes = np.zeros((T, H, D), dtype=np.uint8)
+    for s in range(len(cu_seqlens) - 1):
+        c, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        for b, r0 in enumerate(range(c, e, block)):
+            rows = slice(r0, min(e, r0 + block))
+            amax = np.max(np.abs(x[rows]), axis=(0, 2)).astype(np.float32)
+            d = (amax / np.float32(448.0)).astype(np.float32)
+            d = np.where(d > 0, d, np.float32(1.0)).astype(np.float32)
+            descale[int(starts[s]) + b] = d
+            codes[rows] = encode((x[rows] / d[None, :, None]).astype(np.float32))
+    return codes, descale
+
+
+def dequantize_blockwise(codes, descale, cu_seqlens, block=BLOCK_TOKENS):
+    """codes [T, H, D], descale [num_blocks, H] -> float64 values code_value * descale of the block."""
+    vals = decode(codes)
+    starts = block_starts(cu_seqlens, block)
+    out = np.zeros_like(vals)
+    for s in range(len(cu_seqlens) - 1):
+        c, e = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        for b, r0 in enumerate(range(c, e, block)):
+            rows = slice(r0, min(e, r0 + block))
+            out[rows] = vals[rows] * np.asarray(descale[int(starts[s]) + b], dtype=np.float64)[None, :, None]
+    return out

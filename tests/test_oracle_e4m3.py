@@ -86,3 +86,34 @@ def test_per_head_quantiser():
         assert np.all(np.abs(deq - x[:, h, :])[big] <= np.abs(x[:, h, :])[big] * 2.0 ** -4 * 1.0001)
     # the element with the largest magnitude maps to +-448 exactly
     assert np.abs(e4m3.decode(codes[:, 2, :])).max() == 448.0
+
+
+def test_blockwise_quantiser():
+    # blocks are 128 tokens of one sample by one head: every block is, taken alone, the per-head rule
+    r = np.random.default_rng(3)
+    cu = np.array([0, 5, 5, 140, 140 + 256, 140 + 256 + 129], dtype=np.int32)        # a short, an empty, ragged and whole blocks
+    T, H, D = int(cu[-1]), 2, 16
+    x = (r.standard_normal((T, H, D)) * np.exp(r.standard_normal((T, 1, 1)))).astype(np.float32)
+    x[140:268, 1, :] = 0.0                                                            # one all-zero block
+    codes, descale = e4m3.quantize_blockwise(x, cu)
+    starts = e4m3.block_starts(cu)
+    assert starts.tolist() == [0, 1, 1, 3, 5, 7] and descale.shape == (7, H)
+    b = 0
+    for s in range(len(cu) - 1):
+        for r0 in range(int(cu[s]), int(cu[s + 1]), 128):
+            rows = slice(r0, min(int(cu[s + 1]), r0 + 128))
+            want_codes, want_descale = e4m3.quantize_per_head(x[rows])
+            assert np.array_equal(codes[rows], want_codes) and np.array_equal(descale[b], want_descale)
+            b += 1
+    assert b == 7 and descale[3, 1] == 1.0 and np.all(codes[140:268, 1, :] == 0)
+    # the largest element of every non-zero block maps to +-448; the round trip keeps 2^-4 relative
+    deq = e4m3.dequantize_blockwise(codes, descale, cu)
+    assert np.abs(e4m3.decode(codes[0:5, 0, :])).max() == 448.0
+    big = np.abs(x) > 0
+    rel = np.abs(deq - x)[big] / np.abs(x)[big]
+    assert np.percentile(rel, 50) <= 2.0 ** -4 and deq.shape == x.shape
+    # one block per sample and one sample: the per-head rule itself
+    one = np.array([0, 100], dtype=np.int32)
+    c1, d1 = e4m3.quantize_blockwise(x[:100], one)
+    c2, d2 = e4m3.quantize_per_head(x[:100])
+    assert np.array_equal(c1, c2) and np.array_equal(d1[0], d2)
