@@ -235,6 +235,32 @@ def main():
                                                  codes["k"][1], codes["v"][1], scale, s0["out"], s0["lse"]))
         fp8 = {"ms": fp8_ms, "tflops": flops_fwd / (fp8_ms * 1e-3) / 1e12, "peak": 5000.0,
                "frac": flops_fwd / (fp8_ms * 1e-3) / 1e12 / 5000.0}
+        # the same with block-wise scales (one per 128 tokens of a sample and head); the three quantiser
+        # launches are timed on their own, against the bytes they must move (read twice, codes and scales out)
+        cu_dev = torch.from_numpy(np.asarray(ps.cu_seqlens, dtype=np.int32)).to(dev)
+        bcodes = {}
+        for name in ("q", "k", "v"):
+            c8 = torch.empty(s0[name].shape, dtype=torch.uint8, device=dev)
+            d_tok = torch.empty(s0[name].shape[:2], dtype=torch.float32, device=dev)
+            bcodes[name] = (c8, d_tok)
+
+        def quantise_all(_):
+            for name in ("q", "k", "v"):
+                va.va_quantize_e4m3_blockwise_device(s0[name], ps.cu_seqlens, cu_dev, bcodes[name][0], bcodes[name][1])
+
+        def fwd_block(_):
+            ps.fwd_fp8_blockwise(bcodes["q"][0], bcodes["k"][0], bcodes["v"][0], bcodes["q"][1], bcodes["k"][1],
+                                 bcodes["v"][1], scale, s0["out"], s0["lse"])
+
+        for _ in range(3):
+            quantise_all(0)
+            fwd_block(0)
+        q_ms = time_block(quantise_all)
+        fb_ms = time_block(fwd_block)
+        q_bytes = sum(s0[n].numel() * (2 + 1) + s0[n].shape[0] * s0[n].shape[1] * 4 for n in ("q", "k", "v"))
+        fp8["blockwise"] = {"ms": fb_ms, "tflops": flops_fwd / (fb_ms * 1e-3) / 1e12,
+                            "frac": flops_fwd / (fb_ms * 1e-3) / 1e12 / 5000.0,
+                            "quantise_qkv_ms": q_ms, "quantise_gbps": q_bytes / (q_ms * 1e-3) / 1e9}
 
     useful_tflops = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
     result = {

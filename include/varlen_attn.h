@@ -267,6 +267,59 @@ int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
                         const va_shape* shape, float scale,
                         void* out, float* lse, void* stream);
 
+/*
+ * Block-wise scaling (the finest granularity section 2.2.3 names, applied to
+ * the attention operands): one scale for every block of VA_FP8_BLOCK_TOKENS
+ * consecutive tokens of ONE sample and one head (all head_dim values of those
+ * tokens).  Blocks start at the sample's first token, the last one of a sample
+ * may be short, and no block spans two samples.  descale = amax of the block /
+ * 448 (1 when the block is all zero), code = round-to-nearest-even e4m3 of
+ * x / descale, saturating at +-448.  The scales are returned one per token row,
+ * descale_tok[t, h] = the descale of the block that holds token t, so that a
+ * reader needs no block arithmetic; the rows of one block hold equal values.
+ *   x            bfloat16 bits [T, H, D], T = cu_seqlens[num_seqs]
+ *   cu_seqlens   host in  [num_seqs + 1], validated (starts at 0, monotone)
+ *   codes        out      uint8 [T, H, D]
+ *   descale_tok  out      float32 [T, H]
+ * The host routine takes host buffers.  The device routine takes device
+ * buffers (x 16-byte, codes 8-byte, descale_tok 4-byte aligned, D a multiple
+ * of 8) and a second, device-resident copy of cu_seqlens with
+ * the same contents, launches one kernel on `stream`, allocates nothing, does
+ * not wait, and is bit-identical to the host routine for finite inputs.  A
+ * device copy that disagrees with the host copy gives wrong scales but no
+ * access outside [0, T).
+ * VA_EINVAL for null pointers, bad sizes or a bad cu_seqlens, VA_EALIGN, VA_EHIP.
+ */
+#define VA_FP8_BLOCK_TOKENS 128
+int va_quantize_e4m3_blockwise(const uint16_t* x_bf16, const int32_t* cu_seqlens, int32_t num_seqs,
+                               int32_t H, int32_t D, uint8_t* codes, float* descale_tok);
+int va_quantize_e4m3_blockwise_device(const void* x_bf16, const int32_t* cu_seqlens,
+                                      const int32_t* cu_seqlens_device, int32_t num_seqs,
+                                      int32_t H, int32_t D, void* codes, float* descale_tok, void* stream);
+
+/*
+ * FP8 forward with block-wise scales: as varlen_attn_fwd_fp8, but the descale
+ * arrays are per token row and head, in the layout va_quantize_e4m3_blockwise
+ * writes: q_descale_tok[T, Hq], k_descale_tok[T, Hkv], v_descale_tok[T, Hkv],
+ * device, float32, positive and finite.  A key tile of the kernel (64 keys
+ * from a multiple of 64 inside the sample) lies inside one block, so the kernel
+ * reads the K and V scale of a tile's first row; the arrays must therefore be
+ * constant over each block, as the quantiser writes them.  The V scale enters
+ * the exponent of the probabilities (p * v_descale is what is requantised to
+ * E4M3), the row sum divides it out again: the V maxima of the blocks of one
+ * sample and head should lie within a factor 2^64 of each other, or keys of the
+ * smaller blocks can lose their weight in the row sum.
+ * Same shapes, work list, outputs and errors as varlen_attn_fwd_fp8;
+ * additionally VA_ESIZE when T * Hq * 4 bytes does not fit 31 bits.
+ */
+int varlen_attn_fwd_fp8_blockwise(const void* q8, const void* k8, const void* v8,
+                                  const float* q_descale_tok, const float* k_descale_tok,
+                                  const float* v_descale_tok,
+                                  const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                                  const void* worklist, const void* worklist_host,
+                                  const va_shape* shape, float scale,
+                                  void* out, float* lse, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

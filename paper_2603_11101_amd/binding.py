@@ -50,7 +50,8 @@ _lib = _load()
 EXPORTS = ["va_last_error", "va_pack_first_fit", "va_bin_layout", "va_tile_shape", "va_worklist_bytes",
            "va_build_worklist", "va_quantize_e4m3_per_head", "va_quantize_e4m3_per_head_device",
            "varlen_attn_bwd_workspace_bytes", "va_bwd_has_delta_kernel",
-           "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_profile", "varlen_attn_fwd_fp8"]
+           "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_profile", "varlen_attn_fwd_fp8",
+           "va_quantize_e4m3_blockwise", "va_quantize_e4m3_blockwise_device", "varlen_attn_fwd_fp8_blockwise"]
 
 
 def _check(rc):
@@ -188,6 +189,35 @@ def va_quantize_e4m3_per_head_device(x, codes, descale, stream=None):
                                                  _ptr(codes), _ptr(descale), _stream_ptr(stream)))
 
 
+def va_quantize_e4m3_blockwise(x_bf16_bits, cu_seqlens):
+    """x: uint16 array [T, H, D] of bfloat16 bit patterns, T = cu_seqlens[-1] -> (uint8 codes [T, H, D],
+    float32 descale_tok [T, H]: one scale per 128 tokens of a sample and head, repeated on its rows)."""
+    x = np.ascontiguousarray(x_bf16_bits, dtype=np.uint16)
+    cu = _i32(cu_seqlens)
+    T, H, D = x.shape
+    if T != int(cu[-1]):
+        raise ValueError(f"x holds {T} rows, cu_seqlens ends at {int(cu[-1])}")
+    codes = np.zeros((T, H, D), dtype=np.uint8)
+    descale_tok = np.zeros((T, H), dtype=np.float32)
+    _check(_lib.va_quantize_e4m3_blockwise(_ptr(x), _ptr(cu), ctypes.c_int32(len(cu) - 1), ctypes.c_int32(H),
+                                           ctypes.c_int32(D), _ptr(codes), _ptr(descale_tok)))
+    return codes, descale_tok
+
+
+def va_quantize_e4m3_blockwise_device(x, cu_seqlens, cu_seqlens_device, codes, descale_tok, stream=None):
+    """x: bfloat16 device tensor [T, H, D]; cu_seqlens: host int32 array; cu_seqlens_device: the same
+    values in an int32 device tensor; codes: uint8 device tensor [T, H, D]; descale_tok: float32 device
+    tensor [T, H].  Enqueues the quantisation on the stream."""
+    cu = _i32(cu_seqlens)
+    T, H, D = x.shape
+    if T != int(cu[-1]) or cu_seqlens_device.numel() != len(cu) or tuple(codes.shape) != (T, H, D) \
+            or tuple(descale_tok.shape) != (T, H):
+        raise ValueError("shapes of x, cu_seqlens, codes and descale_tok disagree")
+    _check(_lib.va_quantize_e4m3_blockwise_device(_ptr(x), _ptr(cu), _ptr(cu_seqlens_device), ctypes.c_int32(len(cu) - 1),
+                                                  ctypes.c_int32(H), ctypes.c_int32(D), _ptr(codes), _ptr(descale_tok),
+                                                  _stream_ptr(stream)))
+
+
 def make_shape(total_tokens, num_seqs, num_q_heads, num_kv_heads, head_dim, max_seqlen, mask_mode):
     return va_shape(int(total_tokens), int(num_seqs), int(num_q_heads), int(num_kv_heads), int(head_dim),
                     int(max_seqlen), int(mask_mode))
@@ -242,6 +272,21 @@ def varlen_attn_fwd_fp8(q8, k8, v8, q_descale, k_descale, v_descale, cu_seqlens,
                                     ctypes.c_float(scale), _ptr(out), _ptr(lse), _stream_ptr(stream)))
 
 
+def varlen_attn_fwd_fp8_blockwise(q8, k8, v8, q_descale_tok, k_descale_tok, v_descale_tok, cu_seqlens, prefix_lens,
+                                  worklist, worklist_host, shape, scale, out, lse, stream=None):
+    cu = _i32(cu_seqlens)
+    pl = _prefix(prefix_lens, shape.mask_mode, len(cu) - 1)
+    T = int(shape.total_tokens)
+    for name, d, h in (("q", q_descale_tok, shape.num_q_heads), ("k", k_descale_tok, shape.num_kv_heads),
+                       ("v", v_descale_tok, shape.num_kv_heads)):
+        if d is not None and tuple(d.shape) != (T, h):  # the library cannot see the arrays' lengths
+            raise ValueError(f"{name}_descale_tok has shape {tuple(d.shape)}, expected {(T, h)}")
+    _check(_lib.varlen_attn_fwd_fp8_blockwise(_ptr(q8), _ptr(k8), _ptr(v8), _ptr(q_descale_tok), _ptr(k_descale_tok),
+                                              _ptr(v_descale_tok), _ptr(cu), _ptr(pl), _ptr(worklist),
+                                              _ptr(worklist_host), ctypes.byref(shape), ctypes.c_float(scale),
+                                              _ptr(out), _ptr(lse), _stream_ptr(stream)))
+
+
 class PackedStream:
     """Everything the device calls need for one packed stream, kept together:
     the host index arrays, the three work lists (host copies and device copies)
@@ -289,6 +334,11 @@ class PackedStream:
                                        self.worklist[VA_PASS_BWD_DKDV], self.worklist_host[VA_PASS_BWD_DKDV],
                                        self.worklist[VA_PASS_BWD_DQ], self.worklist_host[VA_PASS_BWD_DQ],
                                        self.shape, scale, dq, dk, dv, ws, ws.numel(), stream, iters)
+
+    def fwd_fp8_blockwise(self, q8, k8, v8, q_descale_tok, k_descale_tok, v_descale_tok, scale, out, lse, stream=None):
+        varlen_attn_fwd_fp8_blockwise(q8, k8, v8, q_descale_tok, k_descale_tok, v_descale_tok, self.cu_seqlens,
+                                      self.prefix_lens, self.worklist[VA_PASS_FWD], self.worklist_host[VA_PASS_FWD],
+                                      self.shape, scale, out, lse, stream)
 
     def fwd_fp8(self, q8, k8, v8, q_descale, k_descale, v_descale, scale, out, lse, stream=None):
         varlen_attn_fwd_fp8(q8, k8, v8, q_descale, k_descale, v_descale, self.cu_seqlens, self.prefix_lens,

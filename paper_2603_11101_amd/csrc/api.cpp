@@ -345,13 +345,14 @@ int va_quantize_e4m3_per_head_device(const void* x, int32_t T, int32_t H, int32_
     return VA_OK;
 }
 
-int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
-                        const float* q_descale, const float* k_descale, const float* v_descale,
-                        const int32_t* cu_seqlens, const int32_t* prefix_lens,
-                    const void* worklist, const void* worklist_host,
-                        const va_shape* shape, float scale,
-                        void* out, float* lse, void* stream) {
-    const char* who = "varlen_attn_fwd_fp8";
+}  // extern "C"
+
+namespace {
+
+int fwd_fp8_entry(const char* who, bool blockwise, const void* q8, const void* k8, const void* v8,
+                  const float* q_descale, const float* k_descale, const float* v_descale,
+                  const int32_t* cu_seqlens, const int32_t* prefix_lens, const void* worklist, const void* worklist_host,
+                  const va_shape* shape, float scale, void* out, float* lse, void* stream) {
     int rc = check_shape(shape, cu_seqlens, prefix_lens, who);
     if (rc) return rc;
     if (shape->head_dim != 128) return fail(VA_EUNSUPPORTED, "%s: head_dim %d, the FP8 forward exists for 128 only", who, shape->head_dim);
@@ -361,6 +362,14 @@ int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
         return fail(VA_EINVAL, "%s: null tensor pointer", who);
     if (!aligned16(q8) || !aligned16(k8) || !aligned16(v8) || !aligned16(out) || !aligned16(lse))
         return fail(VA_EALIGN, "%s: tensor pointers must be 16-byte aligned", who);
+    if (blockwise) {
+        if (((reinterpret_cast<uintptr_t>(q_descale) | reinterpret_cast<uintptr_t>(k_descale) |
+              reinterpret_cast<uintptr_t>(v_descale)) & 3u) != 0)
+            return fail(VA_EALIGN, "%s: descale arrays must be 4-byte aligned", who);
+        // the kernel addresses the per-token descales through 32-bit byte offsets
+        if ((int64_t)shape->total_tokens * shape->num_q_heads * 4 > INT32_MAX)
+            return fail(VA_ESIZE, "%s: total_tokens * num_q_heads * 4 exceeds 2^31 - 1", who);
+    }
     WorklistLayout lay;
     if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, VA_PASS_FWD, who, &lay))) return rc;
     AttnParams p = base_params(shape, scale);
@@ -373,7 +382,56 @@ int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
     p.out = out;
     p.lse = lse;
     set_worklist(&p, worklist, lay);
-    hipError_t e = launch_fwd_fp8(p, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_fwd_fp8(p, blockwise, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    return VA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
+                        const float* q_descale, const float* k_descale, const float* v_descale,
+                        const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                        const void* worklist, const void* worklist_host,
+                        const va_shape* shape, float scale,
+                        void* out, float* lse, void* stream) {
+    return fwd_fp8_entry("varlen_attn_fwd_fp8", false, q8, k8, v8, q_descale, k_descale, v_descale, cu_seqlens,
+                         prefix_lens, worklist, worklist_host, shape, scale, out, lse, stream);
+}
+
+int varlen_attn_fwd_fp8_blockwise(const void* q8, const void* k8, const void* v8,
+                                  const float* q_descale_tok, const float* k_descale_tok, const float* v_descale_tok,
+                                  const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                                  const void* worklist, const void* worklist_host,
+                                  const va_shape* shape, float scale,
+                                  void* out, float* lse, void* stream) {
+    return fwd_fp8_entry("varlen_attn_fwd_fp8_blockwise", true, q8, k8, v8, q_descale_tok, k_descale_tok, v_descale_tok,
+                         cu_seqlens, prefix_lens, worklist, worklist_host, shape, scale, out, lse, stream);
+}
+
+int va_quantize_e4m3_blockwise_device(const void* x, const int32_t* cu_seqlens, const int32_t* cu_seqlens_device,
+                                      int32_t num_seqs, int32_t H, int32_t D, void* codes, float* descale_tok,
+                                      void* stream) {
+    const char* who = "va_quantize_e4m3_blockwise_device";
+    if (!cu_seqlens || !cu_seqlens_device || num_seqs < 0 || H <= 0 || D <= 0 || D % 8 != 0)
+        return fail(VA_EINVAL, "%s: null pointer or bad size (D must be a multiple of 8)", who);
+    if (cu_seqlens[0] != 0) return fail(VA_EINVAL, "%s: cu_seqlens[0] must be 0", who);
+    int64_t blocks = 0;
+    for (int32_t s = 0; s < num_seqs; ++s) {
+        if (cu_seqlens[s + 1] < cu_seqlens[s]) return fail(VA_EINVAL, "%s: cu_seqlens decreases at %d", who, s);
+        blocks += (cu_seqlens[s + 1] - cu_seqlens[s] + VA_FP8_BLOCK_TOKENS - 1) / VA_FP8_BLOCK_TOKENS;
+    }
+    const int32_t T = cu_seqlens[num_seqs];
+    if (T == 0) return VA_OK;
+    if (!x || !codes || !descale_tok) return fail(VA_EINVAL, "%s: null buffer", who);
+    if (!aligned16(x) || (reinterpret_cast<uintptr_t>(codes) & 7u) != 0 || (reinterpret_cast<uintptr_t>(descale_tok) & 3u) != 0 ||
+        (reinterpret_cast<uintptr_t>(cu_seqlens_device) & 3u) != 0)
+        return fail(VA_EALIGN, "%s: x must be 16-byte, codes 8-byte, descale_tok and cu_seqlens_device 4-byte aligned", who);
+    if ((H + 3) / 4 > 65535) return fail(VA_ESIZE, "%s: more than 262140 heads", who);
+    const hipError_t e = launch_quantize_e4m3_blockwise(x, cu_seqlens_device, num_seqs, T, (int32_t)blocks, H, D, codes,
+                                                        descale_tok, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
     return VA_OK;
 }

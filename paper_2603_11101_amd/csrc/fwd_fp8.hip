@@ -1,11 +1,24 @@
 // Forward kernel, FP8: Q, K, V are OCP E4M3 bytes with one float32 descale per
-// head; both products run on v_mfma_f32_32x32x64_f8f6f4 (64 contraction slots
+// head, or (template flag BLOCK) one per 128 tokens of a sample and head, handed
+// over as one value per token row and head; both products run on v_mfma_f32_32x32x64_f8f6f4 (64 contraction slots
 // per instruction, twice the bf16 rate); scores, softmax, row sums and LSE are
 // float32; the probabilities are requantised to E4M3 for the second product.
 //
 // The paper's FP8 material (section 2.2.3) concerns weight quantisation and
 // only supplies the scaling vocabulary; the per-head scale is its per-channel
-// rule applied along the head axis.  Everything else here is this library's.
+// rule applied along the head axis, the block scale its block-wise rule applied
+// to (tokens of one sample) x (one head).  Everything else here is this library's.
+//
+// Block scales in the kernel.  A lane owns one query row, so the Q scale is a
+// per-lane constant.  A key tile (64 keys from a multiple of 64 in the sample)
+// lies inside one 128-token block, so the K and V scales are one pair of
+// numbers per tile, read from the tile's first row one tile ahead.  The K scale
+// multiplies the score factor.  The V scale is folded into the exponent: the
+// kernel runs its online softmax on score' = score + log2(v_descale), so that
+// what it requantises to E4M3 and feeds to the second product is p * v_descale
+// (up to the common reference), and sum(p * v_descale * V8) needs no rescaling
+// of O when the block changes; the row sum takes psum / v_descale per tile,
+// which removes the factor again.
 //
 // Same decomposition as the bf16 forward: one workgroup = 128 stacked
 // (head, token) rows of one KV group, 4 waves x 32 rows, 64 keys per step,
@@ -148,7 +161,7 @@ static_assert(FragAddr8::self_check(), "fragment address closed forms disagree w
 
 // Persistent like the bf16 forward: workgroup b runs the works the host assigned to it; the first K/V tile
 // and the Q fragments of the next work are fetched while the last key tile of the current one is processed.
-template <int HPB>
+template <int HPB, bool BLOCK>
 __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     constexpr int D = 128;
     constexpr int BMT = kFwdBlockRows / HPB;
@@ -182,9 +195,19 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     const int q_tok_bytes = p.Hq * D;
     // Q fragments of that row, contraction slots d = 64 t + 32 hf + 0..31, through a raw buffer that ends
     // with the last valid token of the block: rows past it read as zero.  The score factor
-    // scale * q_descale[h] * k_descale[g] * log2(e) of the row comes with them.
+    // scale * q_descale[h] * k_descale[g] * log2(e) of the row comes with them; with block scales it is
+    // scale * q_descale[row, h] * log2(e), and the K and V scales of the work's first key tile come too.
     i32x8 qf[KSTEPS];
     float c_row;
+    float kd_next = 1.0f, vd_next = 1.0f;  // BLOCK: scales of the key tile that is processed next
+    const int kv_descale_step = __builtin_amdgcn_readfirstlane(BN * p.Hkv * 4);
+    const __amdgpu_buffer_rsrc_t kd_all = RowBlock<D>::rows(p.k_descale, BLOCK ? (unsigned)p.T * p.Hkv * 4u : 0u);
+    const __amdgpu_buffer_rsrc_t vd_all = RowBlock<D>::rows(p.v_descale, BLOCK ? (unsigned)p.T * p.Hkv * 4u : 0u);
+    auto load_kv_descale = [&](const RowWork& w, int kt) {
+        const int soff = __builtin_amdgcn_readfirstlane((w.seq_row0 * p.Hkv + w.g) * 4 + kt * kv_descale_step);
+        kd_next = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(kd_all, 0, soff, 0));
+        vd_next = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(vd_all, 0, soff, 0));
+    };
     auto load_q = [&](const RowWork& w) {
         const __amdgpu_buffer_rsrc_t rows = RowBlock<D>::rows(
             static_cast<const char*>(p.q) + ((size_t)w.q_row0 * p.Hq + w.h0) * D,
@@ -196,7 +219,17 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
             const u32x4 hi = __builtin_amdgcn_raw_buffer_load_b128(rows, off + 64 * t + 16, 0, 0);
             qf[t] = __builtin_bit_cast(i32x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
-        c_row = p.scale * p.q_descale[w.h0 + head_in_block] * p.k_descale[w.g] * kLog2e;
+        if constexpr (BLOCK) {
+            const __amdgpu_buffer_rsrc_t qd_rows = RowBlock<D>::rows(
+                p.q_descale + (size_t)w.q_row0 * p.Hq + w.h0, (unsigned)((w.q_rows - 1) * p.Hq + HPB) * 4u);
+            const float qd = __builtin_bit_cast(
+                float, __builtin_amdgcn_raw_buffer_load_b32(qd_rows, (tok * p.Hq + head_in_block) * 4, 0, 0));
+            // rows past the block read 0: give them a factor that keeps their (unused) arithmetic finite
+            c_row = p.scale * kLog2e * (tok < w.q_rows ? qd : 1.0f);
+            load_kv_descale(w, 0);
+        } else {
+            c_row = p.scale * p.q_descale[w.h0 + head_in_block] * p.k_descale[w.g] * kLog2e;
+        }
     };
     // output rows and the LSE store that leave at the end of a work: vector memory operations younger than
     // the loads of the next work's first tile
@@ -217,6 +250,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
 #pragma unroll
         for (int t = 0; t < KSTEPS; ++t) asm volatile("" ::"v"(qf[t]));
         asm volatile("" ::"v"(c_row));
+        if constexpr (BLOCK) asm volatile("" ::"v"(kd_next), "v"(vd_next));
     };
     settle_q();
 
@@ -227,7 +261,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
         const bool row_valid = tok < cur.q_rows;
         const int vis = RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
         const float c = c_row;
-        const float v_descale = p.v_descale[cur.g];
+        const float v_descale = BLOCK ? 1.0f : p.v_descale[cur.g];
 
         f32x16 o[DT];
 #pragma unroll
@@ -246,6 +280,17 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
             const int j0 = kt * BN;
             const int k_tile = stage * 2 * kTileBytes;
             const int v_tile = k_tile + kTileBytes;
+            // Block scales of this tile: score factor, log2 of the V scale, its reciprocal.  They were loaded a
+            // tile ago and are consumed here, before anything new is issued, so that no wait for them can
+            // land behind the loads of the next tile.
+            float ct = c, lv = 0.0f, rvd = 1.0f;
+            if constexpr (BLOCK) {
+                ct = c * kd_next;
+                lv = __builtin_amdgcn_logf(vd_next);  // base 2
+                rvd = __builtin_amdgcn_rcpf(vd_next);
+                asm volatile("" : "+v"(ct), "+v"(lv), "+v"(rvd));
+                if constexpr (!last) load_kv_descale(cur, kt + 1);
+            }
             {
                 const unsigned nk = smem_lds + (stage ^ 1) * 2 * kTileBytes;
                 if constexpr (!last) {
@@ -288,7 +333,8 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
-            mx = pair_max(mx) * c;
+            mx = pair_max(mx) * ct;
+            if constexpr (BLOCK) mx += lv;
             if (__builtin_amdgcn_ballot_w64(mx > m + kMaxLag) != 0) {  // wave-uniform: some row needs a new reference
                 asm volatile("");  // keep this a branch: folded into a select, its multiplications would run on every tile
                 const float m_new = fmaxf(m, mx);
@@ -301,17 +347,17 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
             }
-            const float shift = kPShift - (m == -INFINITY ? 0.0f : m);
+            const float shift = (BLOCK ? kPShift + lv : kPShift) - (m == -INFINITY ? 0.0f : m);
             float psum = 0.0f;
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, shift));
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], ct, shift));
                     s[b][r] = pv;
                     psum += pv;
                 }
-            lsum += psum;
+            lsum += BLOCK ? psum * rvd : psum;
 
             // P^T operand: byte e of the lane = register e % 16 of block e / 16 = key 32 hf + e
             i32x8 pf;
@@ -360,24 +406,29 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     }
 }
 
-template <int HPB>
+template <int HPB, bool BLOCK>
 hipError_t launch_h(const AttnParams& p, hipStream_t stream) {
     constexpr size_t smem = 2 * 2 * kTileBytes + 4 * 32 * 128 * 2;
-    hipLaunchKernelGGL((fwd_fp8_kernel<HPB>), dim3((unsigned)p.num_workgroups), dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((fwd_fp8_kernel<HPB, BLOCK>), dim3((unsigned)p.num_workgroups), dim3(256), smem, stream, p);
     return hipGetLastError();
+}
+
+template <bool BLOCK>
+hipError_t launch_b(const AttnParams& p, hipStream_t stream) {
+    switch (heads_per_block(p.Hq, p.Hkv)) {
+        case 1: return launch_h<1, BLOCK>(p, stream);
+        case 2: return launch_h<2, BLOCK>(p, stream);
+        case 4: return launch_h<4, BLOCK>(p, stream);
+        default: return launch_h<8, BLOCK>(p, stream);
+    }
 }
 
 }  // namespace
 
-hipError_t launch_fwd_fp8(const AttnParams& p, hipStream_t stream) {
+hipError_t launch_fwd_fp8(const AttnParams& p, bool blockwise, hipStream_t stream) {
     if (p.D != 128) return hipErrorNotSupported;
     if (p.num_items == 0) return hipSuccess;
-    switch (heads_per_block(p.Hq, p.Hkv)) {
-        case 1: return launch_h<1>(p, stream);
-        case 2: return launch_h<2>(p, stream);
-        case 4: return launch_h<4>(p, stream);
-        default: return launch_h<8>(p, stream);
-    }
+    return blockwise ? launch_b<true>(p, stream) : launch_b<false>(p, stream);
 }
 
 }  // namespace va

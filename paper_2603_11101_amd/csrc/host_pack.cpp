@@ -311,4 +311,34 @@ int va_quantize_e4m3_per_head(const uint16_t* x, int32_t T, int32_t H, int32_t D
     return VA_OK;
 }
 
+int va_quantize_e4m3_blockwise(const uint16_t* x, const int32_t* cu_seqlens, int32_t num_seqs, int32_t H, int32_t D,
+                               uint8_t* codes, float* descale_tok) {
+    const char* who = "va_quantize_e4m3_blockwise";
+    if (!cu_seqlens || num_seqs < 0 || H <= 0 || D <= 0) return fail(VA_EINVAL, "%s: null pointer or bad size", who);
+    if (cu_seqlens[0] != 0) return fail(VA_EINVAL, "%s: cu_seqlens[0] must be 0", who);
+    for (int32_t s = 0; s < num_seqs; ++s)
+        if (cu_seqlens[s + 1] < cu_seqlens[s]) return fail(VA_EINVAL, "%s: cu_seqlens decreases at %d", who, s);
+    const int32_t T = cu_seqlens[num_seqs];
+    if (T > 0 && (!x || !codes || !descale_tok)) return fail(VA_EINVAL, "%s: null buffer", who);
+    for (int32_t s = 0; s < num_seqs; ++s)
+        for (int32_t r0 = cu_seqlens[s]; r0 < cu_seqlens[s + 1]; r0 += VA_FP8_BLOCK_TOKENS) {
+            const int32_t r1 = std::min(cu_seqlens[s + 1], r0 + VA_FP8_BLOCK_TOKENS);
+            for (int32_t h = 0; h < H; ++h) {
+                float amax = 0.0f;
+                for (int32_t t = r0; t < r1; ++t) {
+                    const uint16_t* row = x + ((size_t)t * H + h) * D;
+                    for (int32_t d = 0; d < D; ++d) amax = std::max(amax, std::fabs(bf16_to_float(row[d])));
+                }
+                const float sc = amax / 448.0f;
+                const float descale = sc > 0.0f ? sc : 1.0f;
+                for (int32_t t = r0; t < r1; ++t) {
+                    const size_t base = ((size_t)t * H + h) * D;
+                    descale_tok[(size_t)t * H + h] = descale;
+                    for (int32_t d = 0; d < D; ++d) codes[base + d] = encode_e4m3(bf16_to_float(x[base + d]) / descale);
+                }
+            }
+        }
+    return VA_OK;
+}
+
 }  // extern "C"

@@ -60,11 +60,15 @@ struct DynamicLds {
     }())
 
 hipError_t launch_fwd_bf16(const AttnParams& p, hipStream_t stream);
-hipError_t launch_fwd_fp8(const AttnParams& p, hipStream_t stream);
+// blockwise: the three descale arrays are per token row and head instead of per head
+hipError_t launch_fwd_fp8(const AttnParams& p, bool blockwise, hipStream_t stream);
 hipError_t launch_bwd_delta(const AttnParams& p, hipStream_t stream);
 hipError_t launch_bwd_dkdv(const AttnParams& p, hipStream_t stream);
 hipError_t launch_bwd_dq(const AttnParams& p, hipStream_t stream);
 hipError_t launch_quantize_e4m3(const void* x, int32_t T, int32_t H, int32_t D, void* codes, float* descale,
                                 hipStream_t stream);
+hipError_t launch_quantize_e4m3_blockwise(const void* x, const int32_t* cu_device, int32_t num_seqs, int32_t T,
+                                          int32_t num_blocks, int32_t H, int32_t D, void* codes, float* descale_tok,
+                                          hipStream_t stream);
 
 }  // namespace va

@@ -9,6 +9,9 @@
 // the maxima (as float bits: for non-negative floats the integer order is the
 // float order) until the last kernel; nothing else is needed, nothing is
 // allocated.
+//
+// The block-wise quantiser (one scale per 128 tokens of one sample and one
+// head, bit-identical to va_quantize_e4m3_blockwise) is one kernel further down.
 #include "kernels.h"
 #include "mfma_util.h"
 
@@ -23,6 +26,46 @@ __global__ void quant_clear_kernel(unsigned* amax_bits, int H) {
     if (h < H) amax_bits[h] = 0u;
 }
 
+VA_DEV float bf16_bits_to_float(unsigned bits16) { return __builtin_bit_cast(float, bits16 << 16); }
+
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+
+// |bf16| of the 8 values of a chunk as float bits, their maximum
+VA_DEV unsigned chunk_amax_bits(u32x4 raw) {
+    unsigned m = 0u;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        // clear the sign, move the 16 bits to the top half
+        m = max(m, (raw[w] & 0x7fffu) << 16);
+        m = max(m, raw[w] & 0x7fff0000u);
+    }
+    return m;
+}
+
+VA_DEV float descale_of(unsigned amax_bits) {
+    const float s = __builtin_bit_cast(float, amax_bits) / 448.0f;
+    return s > 0.0f ? s : 1.0f;
+}
+
+// Eight bf16 values -> eight E4M3 codes of value / descale.
+VA_DEV i32x2 encode_chunk(u32x4 raw, float descale) {
+    float v[8];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        v[2 * w] = bf16_bits_to_float(raw[w] & 0xffffu) / descale;
+        v[2 * w + 1] = bf16_bits_to_float(raw[w] >> 16) / descale;
+    }
+    // The conversion instruction rounds to nearest even, subnormals included, but turns magnitudes of
+    // 464 and more into NaN instead of saturating: clamp first (448 is representable).
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = fminf(fmaxf(v[e], -448.0f), 448.0f);
+    int lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], 0, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], lo, true);
+    int hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[4], v[5], 0, false);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[6], v[7], hi, true);
+    return i32x2{lo, hi};
+}
+
 // x is [rows = T * H, D] bf16; a thread takes 8 consecutive values (16 bytes) at a time.
 __global__ __launch_bounds__(256) void quant_amax_kernel(const uint16_t* x, size_t chunks, int chunks_per_row, int H,
                                                          unsigned* amax_bits) {
@@ -34,13 +77,7 @@ __global__ __launch_bounds__(256) void quant_amax_kernel(const uint16_t* x, size
     }
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < chunks; i += (size_t)gridDim.x * blockDim.x) {
         const u32x4 raw = *reinterpret_cast<const u32x4*>(x + i * 8);
-        unsigned m = 0u;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            // |bf16| as float bits: clear the sign, move the 16 bits to the top half
-            m = max(m, (raw[w] & 0x7fffu) << 16);
-            m = max(m, raw[w] & 0x7fff0000u);
-        }
+        const unsigned m = chunk_amax_bits(raw);
         const int h = (int)((i / chunks_per_row) % H);
         if (use_lds) atomicMax(&lds_max[h], m);
         else atomicMax(&amax_bits[h], m);
@@ -52,32 +89,13 @@ __global__ __launch_bounds__(256) void quant_amax_kernel(const uint16_t* x, size
     }
 }
 
-VA_DEV float bf16_bits_to_float(unsigned bits16) { return __builtin_bit_cast(float, bits16 << 16); }
 
 __global__ __launch_bounds__(256) void quant_encode_kernel(const uint16_t* x, size_t chunks, int chunks_per_row, int H,
                                                            const unsigned* amax_bits, unsigned char* codes) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < chunks; i += (size_t)gridDim.x * blockDim.x) {
         const int h = (int)((i / chunks_per_row) % H);
-        const float amax = __builtin_bit_cast(float, amax_bits[h]);
-        const float s = amax / 448.0f;
-        const float descale = s > 0.0f ? s : 1.0f;
-        const u32x4 raw = *reinterpret_cast<const u32x4*>(x + i * 8);
-        float v[8];
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            v[2 * w] = bf16_bits_to_float(raw[w] & 0xffffu) / descale;
-            v[2 * w + 1] = bf16_bits_to_float(raw[w] >> 16) / descale;
-        }
-        // The conversion instruction rounds to nearest even, subnormals included, but turns magnitudes of
-        // 464 and more into NaN instead of saturating: clamp first (448 is representable).
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = fminf(fmaxf(v[e], -448.0f), 448.0f);
-        int lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], 0, false);
-        lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], lo, true);
-        int hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[4], v[5], 0, false);
-        hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[6], v[7], hi, true);
-        typedef int i32x2 __attribute__((ext_vector_type(2)));
-        *reinterpret_cast<i32x2*>(codes + i * 8) = i32x2{lo, hi};
+        const float descale = descale_of(amax_bits[h]);
+        *reinterpret_cast<i32x2*>(codes + i * 8) = encode_chunk(*reinterpret_cast<const u32x4*>(x + i * 8), descale);
     }
 }
 
@@ -87,6 +105,66 @@ __global__ void quant_descale_kernel(float* descale, int H) {
         const float s = descale[h] / 448.0f;  // still the maximum here
         descale[h] = s > 0.0f ? s : 1.0f;
     }
+}
+
+// Block-wise variant: a block is up to kBlockTokens consecutive tokens of one sample, one head.
+// Workgroup (b, y): block number b in sample order, wave w takes head 4 y + w.  Each wave finds the block's
+// rows by a prefix sum over the samples' block counts, 64 samples at a time, reduces |x| over the block,
+// encodes it, and writes the descale to every token row of the block.  Waves do not interact.
+constexpr int kBlockTokens = 128;
+
+__global__ __launch_bounds__(256) void quant_blockwise_kernel(const uint16_t* x, const int* cu, int n, int T, int H,
+                                                              int chunks_per_row, unsigned char* codes,
+                                                              float* descale_tok) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int h = blockIdx.y * 4 + wave;
+    if (h >= H) return;
+    int b = (int)blockIdx.x;  // blocks still to skip
+    int r0 = 0, r1 = 0;
+    for (int base = 0; base < n; base += 64) {
+        const int s = base + lane;
+        int c0 = 0, c1 = 0;
+        if (s < n) {
+            c0 = cu[s];
+            c1 = cu[s + 1];
+        }
+        const int nb = c1 > c0 ? (c1 - c0 + kBlockTokens - 1) / kBlockTokens : 0;
+        int incl = nb;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
+        }
+        const int total = __shfl(incl, 63);
+        if (b < total) {
+            const int src = __ffsll((unsigned long long)__ballot(b < incl)) - 1;  // the sample that holds block b
+            const int first = __shfl(incl - nb, src);
+            r0 = __shfl(c0, src) + (b - first) * kBlockTokens;
+            r1 = min(__shfl(c1, src), r0 + kBlockTokens);
+            break;
+        }
+        b -= total;
+    }
+    r0 = max(r0, 0);
+    r1 = min(r1, T);
+    if (r0 >= r1) return;
+    const int rows = r1 - r0, chunks = rows * chunks_per_row;
+    const size_t row_chunks = (size_t)H * chunks_per_row;  // chunks from one token row to the next
+    const uint16_t* xb = x + ((size_t)r0 * H + h) * chunks_per_row * 8;
+    unsigned m = 0u;
+    for (int i = lane; i < chunks; i += 64) {
+        const size_t at = ((size_t)(i / chunks_per_row) * row_chunks + i % chunks_per_row) * 8;
+        m = max(m, chunk_amax_bits(*reinterpret_cast<const u32x4*>(xb + at)));
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, d));
+    const float descale = descale_of(m);
+    unsigned char* cb = codes + ((size_t)r0 * H + h) * chunks_per_row * 8;
+    for (int i = lane; i < chunks; i += 64) {
+        const size_t at = ((size_t)(i / chunks_per_row) * row_chunks + i % chunks_per_row) * 8;
+        *reinterpret_cast<i32x2*>(cb + at) = encode_chunk(*reinterpret_cast<const u32x4*>(xb + at), descale);
+    }
+    for (int r = lane; r < rows; r += 64) descale_tok[(size_t)(r0 + r) * H + h] = descale;
 }
 
 }  // namespace
@@ -105,6 +183,16 @@ hipError_t launch_quantize_e4m3(const void* x, int32_t T, int32_t H, int32_t D, 
                            D / 8, H, bits, static_cast<unsigned char*>(codes));
     }
     hipLaunchKernelGGL(quant_descale_kernel, dim3(hb), dim3(256), 0, stream, descale, H);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_e4m3_blockwise(const void* x, const int32_t* cu_device, int32_t num_seqs, int32_t T,
+                                          int32_t num_blocks, int32_t H, int32_t D, void* codes, float* descale_tok,
+                                          hipStream_t stream) {
+    if (num_blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(quant_blockwise_kernel, dim3((unsigned)num_blocks, (unsigned)((H + 3) / 4)), dim3(256), 0, stream,
+                       static_cast<const uint16_t*>(x), cu_device, num_seqs, T, H, D / 8,
+                       static_cast<unsigned char*>(codes), descale_tok);
     return hipGetLastError();
 }
 

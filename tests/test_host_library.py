@@ -151,6 +151,42 @@ def test_e4m3_quantiser_equals_oracle_bit_for_bit():
     assert descale[0] == 1.0 and np.array_equal(codes, oe.encode(probe))
 
 
+def expand_block_descale(descale, cu, H):
+    """The oracle's [num_blocks, H] block scales, one row per token (the library's layout)."""
+    starts = oe.block_starts(cu)
+    out = np.zeros((int(cu[-1]), H), dtype=np.float32)
+    for s in range(len(cu) - 1):
+        for t in range(int(cu[s]), int(cu[s + 1])):
+            out[t] = descale[int(starts[s]) + (t - int(cu[s])) // oe.BLOCK_TOKENS]
+    return out
+
+
+def test_blockwise_e4m3_quantiser_equals_oracle_bit_for_bit():
+    r = np.random.default_rng(19)
+    lens = [5, 128, 0, 129, 300, 1, 256]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T, H, D = int(cu[-1]), 3, 48
+    x = r.standard_normal((T, H, D)).astype(np.float32)
+    x *= np.exp2(r.integers(-12, 8, size=(T // 50 + 1,)))[np.arange(T) // 50][:, None, None]   # magnitude drifts along the stream
+    x[128 + 5:128 + 5 + 128, 1] = 0.0      # an all-zero block (sample 1, head 1): descale 1
+    x = wl.round_to_bf16(x)
+    codes, descale_tok = va.va_quantize_e4m3_blockwise(wl.bf16_bits(x), cu)
+    ocodes, odescale = oe.quantize_blockwise(x, cu)
+    want = expand_block_descale(odescale, cu, H)
+    assert np.array_equal(descale_tok.view(np.uint32), want.view(np.uint32)) and np.array_equal(codes, ocodes)
+    assert np.all(descale_tok[133:261, 1] == 1.0)
+    # one sample shorter than a block equals the per-head quantiser on that sample
+    c1, d1 = va.va_quantize_e4m3_blockwise(wl.bf16_bits(x[:5]), np.array([0, 5], dtype=np.int32))
+    c2, d2 = va.va_quantize_e4m3_per_head(wl.bf16_bits(x[:5]))
+    assert np.array_equal(c1, c2) and np.all(d1 == d2[None, :])
+    # bad sample boundaries are refused
+    with pytest.raises(va.VarlenAttnError):
+        va.va_quantize_e4m3_blockwise(wl.bf16_bits(x[:5]), np.array([1, 5], dtype=np.int32))
+    bad = np.array([0, 4, 3, 5], dtype=np.int32)
+    with pytest.raises(va.VarlenAttnError):
+        va.va_quantize_e4m3_blockwise(wl.bf16_bits(x[:5]), bad)
+
+
 def _fake(n=1 << 12):
     return np.zeros(n, dtype=np.uint8)
 
