@@ -108,18 +108,12 @@ __global__ void quant_descale_kernel(float* descale, int H) {
 }
 
 // Block-wise variant: a block is up to kBlockTokens consecutive tokens of one sample, one head.
-// Workgroup (b, y): block number b in sample order, wave w takes head 4 y + w.  Each wave finds the block's
-// rows by a prefix sum over the samples' block counts, 64 samples at a time, reduces |x| over the block,
-// encodes it, and writes the descale to every token row of the block.  Waves do not interact.
 constexpr int kBlockTokens = 128;
 
-__global__ __launch_bounds__(256) void quant_blockwise_kernel(const uint16_t* x, const int* cu, int n, int T, int H,
-                                                              int chunks_per_row, unsigned char* codes,
-                                                              float* descale_tok) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int h = blockIdx.y * 4 + wave;
-    if (h >= H) return;
-    int b = (int)blockIdx.x;  // blocks still to skip
+// Rows [r0, r1) of block number b in sample order, found by a prefix sum over the samples' block counts,
+// 64 samples at a time; every lane of the wave returns the same pair.  An empty range means "no such
+// block".  The range is clipped to [0, T), whatever cu holds.
+VA_DEV void find_block(const int* cu, int n, int T, int b, int lane, int* r0_out, int* r1_out) {
     int r0 = 0, r1 = 0;
     for (int base = 0; base < n; base += 64) {
         const int s = base + lane;
@@ -145,8 +139,71 @@ __global__ __launch_bounds__(256) void quant_blockwise_kernel(const uint16_t* x,
         }
         b -= total;
     }
-    r0 = max(r0, 0);
-    r1 = min(r1, T);
+    *r0_out = max(r0, 0);
+    *r1_out = min(r1, T);
+}
+
+// Head dimensions up to 256.  Workgroup (b, h): block number b in sample order, head h; wave w takes the
+// rows 32 w .. 32 w + 31 of the block and keeps them in registers (J chunks of 8 values per lane), so x is
+// read once: maximum per wave, the four maxima meet in LDS, then every wave encodes what it holds.
+template <int J>
+__global__ __launch_bounds__(256) void quant_blockwise_kernel(const uint16_t* x, const int* cu, int n, int T, int H,
+                                                              int chunks_per_row, unsigned char* codes,
+                                                              float* descale_tok) {
+    __shared__ unsigned wave_max[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int h = (int)blockIdx.y;
+    int r0, r1;
+    find_block(cu, n, T, (int)blockIdx.x, lane, &r0, &r1);
+    if (r0 >= r1) return;  // the same for the whole workgroup
+    const int w0 = r0 + 32 * wave;
+    const int wrows = max(0, min(32, r1 - w0));  // rows of this wave
+    const int chunks = wrows * chunks_per_row;
+    const int row_bytes = H * chunks_per_row * 16;
+    const size_t first = ((size_t)w0 * H + h) * chunks_per_row;  // first chunk of this wave, in chunks
+    // the ranges end with the wave's last row of this head: nothing outside them can be touched
+    const unsigned span = wrows > 0 ? (unsigned)(wrows - 1) * row_bytes + chunks_per_row * 16 : 0u;
+    const __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(x)) + (wrows > 0 ? first * 16 : 0), 0, (int)span, 0x00020000);
+    const __amdgpu_buffer_rsrc_t dst =
+        __builtin_amdgcn_make_buffer_rsrc(codes + (wrows > 0 ? first * 8 : 0), 0, (int)(span / 2), 0x00020000);
+    u32x4 raw[J];
+    int at[J];  // byte offset of the lane's chunk j in x (half of it in codes), out of range where it has none
+    unsigned m = 0u;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int i = lane + 64 * j;
+        at[j] = i < chunks ? (i / chunks_per_row) * row_bytes + (i % chunks_per_row) * 16 : (int)0x7ffffff0;
+        raw[j] = __builtin_amdgcn_raw_buffer_load_b128(src, at[j], 0, 0);  // zero where out of range
+    }
+#pragma unroll
+    for (int j = 0; j < J; ++j) m = max(m, chunk_amax_bits(raw[j]));
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, d));
+    if (lane == 0) wave_max[wave] = m;
+    __syncthreads();
+    const float descale = descale_of(max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3])));
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        const int off = at[j] == (int)0x7ffffff0 ? at[j] : at[j] / 2;
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, encode_chunk(raw[j], descale)), dst, off, 0, 0);
+    }
+    const int r = r0 + 64 * (wave & 1) + lane;  // waves 0 and 1 write the scales of the block's rows
+    if (wave < 2 && r < r1) descale_tok[(size_t)r * H + h] = descale;
+}
+
+// Any head dimension: workgroup (b, y), wave w takes head 4 y + w and the whole block, reads it twice
+// (maximum, then encoding).  Waves do not interact.
+
+__global__ __launch_bounds__(256) void quant_blockwise_two_pass_kernel(const uint16_t* x, const int* cu, int n, int T,
+                                                                       int H, int chunks_per_row, unsigned char* codes,
+                                                                       float* descale_tok) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int h = blockIdx.y * 4 + wave;
+    if (h >= H) return;
+    int r0, r1;
+    find_block(cu, n, T, (int)blockIdx.x, lane, &r0, &r1);
     if (r0 >= r1) return;
     const int rows = r1 - r0, chunks = rows * chunks_per_row;
     const size_t row_chunks = (size_t)H * chunks_per_row;  // chunks from one token row to the next
@@ -190,9 +247,20 @@ hipError_t launch_quantize_e4m3_blockwise(const void* x, const int32_t* cu_devic
                                           int32_t num_blocks, int32_t H, int32_t D, void* codes, float* descale_tok,
                                           hipStream_t stream) {
     if (num_blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(quant_blockwise_kernel, dim3((unsigned)num_blocks, (unsigned)((H + 3) / 4)), dim3(256), 0, stream,
-                       static_cast<const uint16_t*>(x), cu_device, num_seqs, T, H, D / 8,
-                       static_cast<unsigned char*>(codes), descale_tok);
+    const uint16_t* xs = static_cast<const uint16_t*>(x);
+    unsigned char* cs = static_cast<unsigned char*>(codes);
+    const int cpr = D / 8;
+    const dim3 grid((unsigned)num_blocks, (unsigned)H);
+    // a wave holds 32 rows: 32 * cpr chunks over 64 lanes
+    if (cpr <= 8 && H <= 65535)
+        hipLaunchKernelGGL(quant_blockwise_kernel<4>, grid, dim3(256), 0, stream, xs, cu_device, num_seqs, T, H, cpr, cs, descale_tok);
+    else if (cpr <= 16 && H <= 65535)
+        hipLaunchKernelGGL(quant_blockwise_kernel<8>, grid, dim3(256), 0, stream, xs, cu_device, num_seqs, T, H, cpr, cs, descale_tok);
+    else if (cpr <= 32 && H <= 65535)
+        hipLaunchKernelGGL(quant_blockwise_kernel<16>, grid, dim3(256), 0, stream, xs, cu_device, num_seqs, T, H, cpr, cs, descale_tok);
+    else
+        hipLaunchKernelGGL(quant_blockwise_two_pass_kernel, dim3((unsigned)num_blocks, (unsigned)((H + 3) / 4)), dim3(256), 0,
+                           stream, xs, cu_device, num_seqs, T, H, cpr, cs, descale_tok);
     return hipGetLastError();
 }
 

@@ -51,7 +51,8 @@ def quantise_on_device(x, cu):
 
 
 @pytest.mark.parametrize("lens,H,D", [([1], 1, 64), ([128], 2, 128), ([129, 0, 5], 3, 64), ([300, 17, 256, 1, 700], 5, 128),
-                                      ([0, 0], 4, 128), (list(range(1, 151)), 2, 48), ([1000], 9, 256)])
+                                      ([0, 0], 4, 128), (list(range(1, 151)), 2, 48), ([1000], 9, 256), ([130, 40], 2, 512),
+                                      ([700, 3], 3, 40)])
 def test_device_blockwise_quantiser_is_bit_identical_to_the_oracle(lens, H, D):
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     T = int(cu[-1])
