@@ -255,3 +255,40 @@ def test_three_block_ends_are_validated():
         for it in items:
             s = 0 if it[2] == 0 else 1
             assert (it[6], it[word]) == tuple(ends[s])
+
+
+def test_fp8_entry_points_reject_bad_arguments_on_the_host():
+    # every call fails in validation, before any stream or device pointer is used
+    Hq, Hkv = 4, 2
+    cu = np.array([0, 40, 100], dtype=np.int32)
+    buf, lse = _fake(), np.zeros(1024, dtype=np.float32)
+    f32 = np.zeros(1024, dtype=np.float32)
+
+    def fwd(fn, D=128, qd=f32, q=buf):
+        wl_h = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_FWD, D, Hq, Hkv)
+        shape = va.make_shape(100, 2, Hq, Hkv, D, 60, va.VA_MASK_CAUSAL)
+        rc = fn(va._ptr(q), va._ptr(buf), va._ptr(buf), va._ptr(qd), va._ptr(f32), va._ptr(f32), va._ptr(cu),
+                ctypes.c_void_p(0), va._ptr(wl_h), va._ptr(wl_h), ctypes.byref(shape), ctypes.c_float(0.1),
+                va._ptr(buf), va._ptr(lse), ctypes.c_void_p(0))
+        return rc, va.va_last_error()
+
+    for fn in (va._lib.varlen_attn_fwd_fp8, va._lib.varlen_attn_fwd_fp8_blockwise):
+        rc, msg = fwd(fn, D=64)
+        assert rc == va.VA_EUNSUPPORTED and "128" in msg
+        assert fwd(fn, q=None)[0] == va.VA_EINVAL
+        assert fwd(fn, qd=None)[0] == va.VA_EINVAL
+        assert fwd(fn, q=buf[8:])[0] == va.VA_EALIGN
+    assert fwd(va._lib.varlen_attn_fwd_fp8_blockwise, qd=f32.view(np.uint8)[2:].view(np.uint8))[0] == va.VA_EALIGN
+
+    def quant(cu_=cu, cu_dev=cu, H=2, D=64, x=buf, codes=buf, d=f32):
+        rc = va._lib.va_quantize_e4m3_blockwise_device(va._ptr(x), va._ptr(cu_), va._ptr(cu_dev), ctypes.c_int32(len(cu) - 1),
+                                                       ctypes.c_int32(H), ctypes.c_int32(D), va._ptr(codes), va._ptr(d),
+                                                       ctypes.c_void_p(0))
+        return rc, va.va_last_error()
+
+    assert quant(D=12)[0] == va.VA_EINVAL and quant(H=0)[0] == va.VA_EINVAL
+    assert quant(cu_=np.array([0, 50, 40], dtype=np.int32))[0] == va.VA_EINVAL
+    assert quant(cu_=np.array([1, 50, 60], dtype=np.int32))[0] == va.VA_EINVAL
+    assert quant(cu_dev=None)[0] == va.VA_EINVAL and quant(x=None)[0] == va.VA_EINVAL
+    assert quant(x=buf[8:])[0] == va.VA_EALIGN and quant(codes=buf[4:])[0] == va.VA_EALIGN
+    assert quant(cu_=np.array([0, 0, 0], dtype=np.int32), x=None, codes=None, d=None)[0] == va.VA_OK   # nothing to do
