@@ -16,6 +16,7 @@ MASK_CAUSAL = 0
 MASK_PREFIX_BIDIR_SUFFIX = 1
 MASK_PREFIX_CAUSAL_SUFFIX = 2
 MASK_THREE_BLOCK = 3     # prefix_lens holds [num_seqs, 2]: the ends (P, P2) of the first two blocks
+MASK_SLIDING_WINDOW = 4  # causal, row i sees the keys i - W + 1 .. i; prefix_lens holds W >= 1 per sample
 
 _lib = None
 

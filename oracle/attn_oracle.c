@@ -24,7 +24,9 @@
  *            = P if i < P, P2 if i < P2, else L   (mode 3) three blocks, each seeing
  *              itself and the blocks before it; prefix_lens then holds the pair
  *              (P, P2), 0 <= P <= P2 <= L, for every sample
- *     s_ij  = scale * sum_d Q[c+i,h,d] K[c+j,g,d]        for j < vis(i)
+ *     (mode 4) sliding window of W = prefix_lens[s] >= 1 keys: vis(i) = i + 1 and the
+ *              keys start at lo(i) = max(0, i + 1 - W) instead of 0 (lo = 0 in every other mode)
+ *     s_ij  = scale * sum_d Q[c+i,h,d] K[c+j,g,d]        for lo(i) <= j < vis(i)
  *     m_i   = max_j s_ij,  Z_i = sum_j exp(s_ij - m_i)
  *     LSE[h,c+i] = m_i + ln Z_i
  *     p_ij  = exp(s_ij - m_i) / Z_i
@@ -55,15 +57,23 @@
 #define ORACLE_MASK_PREFIX_BIDIR_SUFFIX 1
 #define ORACLE_MASK_PREFIX_CAUSAL_SUFFIX 2
 #define ORACLE_MASK_THREE_BLOCK 3
+#define ORACLE_MASK_SLIDING_WINDOW 4 /* causal, and at most the W most recent keys: j > i - W */
 
 /* number of keys query row i of a sample (length L, block ends P and P2) may attend to */
 static int visible(int i, int L, int P, int P2, int mode)
 {
-    if (mode == ORACLE_MASK_CAUSAL) return i + 1;
+    if (mode == ORACLE_MASK_CAUSAL || mode == ORACLE_MASK_SLIDING_WINDOW) return i + 1;
     if (i < P) return P;
     if (mode == ORACLE_MASK_PREFIX_BIDIR_SUFFIX) return L;
     if (mode == ORACLE_MASK_THREE_BLOCK) return i < P2 ? P2 : L;
     return i + 1;
+}
+
+/* first key query row i may attend to: 0, except under the sliding window of W keys (W travels in P) */
+static int first_visible(int i, int P, int mode)
+{
+    if (mode == ORACLE_MASK_SLIDING_WINDOW && i + 1 - P > 0) return i + 1 - P;
+    return 0;
 }
 
 /* block ends of sample s: prefix_lens holds one entry per sample, or the pair (P, P2) in mode 3 */
@@ -88,12 +98,12 @@ int oracle_num_threads(void)
 #endif
 }
 
-/* softmax probabilities of one query row; returns LSE. p[0..nvis) filled. */
+/* softmax probabilities of one query row over the keys lo .. nvis - 1; returns LSE. p[lo..nvis) filled. */
 static double row_softmax(const float *q_row, const float *k_base, size_t k_stride,
-                          int nvis, int D, double scale, double *p)
+                          int lo, int nvis, int D, double scale, double *p)
 {
     double m = -INFINITY;
-    for (int j = 0; j < nvis; ++j) {
+    for (int j = lo; j < nvis; ++j) {
         const float *k_row = k_base + (size_t)j * k_stride;
         double s = 0.0;
         for (int d = 0; d < D; ++d) s += (double)q_row[d] * (double)k_row[d];
@@ -102,11 +112,11 @@ static double row_softmax(const float *q_row, const float *k_base, size_t k_stri
         if (s > m) m = s;
     }
     double Z = 0.0;
-    for (int j = 0; j < nvis; ++j) {
+    for (int j = lo; j < nvis; ++j) {
         p[j] = exp(p[j] - m);
         Z += p[j];
     }
-    for (int j = 0; j < nvis; ++j) p[j] /= Z;
+    for (int j = lo; j < nvis; ++j) p[j] /= Z;
     return m + log(Z);
 }
 
@@ -145,15 +155,16 @@ int oracle_attn_fwd(const float *q, const float *k, const float *v,
             block_ends(prefix_lens, mask_mode, s, &P, &P2);
             for (int i = 0; i < L; ++i) {
                 const int nvis = visible(i, L, P, P2, mask_mode);
+                const int lo = first_visible(i, P, mask_mode);
                 const float *q_row = q + ((size_t)(c + i) * Hq + h) * D;
                 const float *k_base = k + ((size_t)c * Hkv + g) * D;
                 const float *v_base = v + ((size_t)c * Hkv + g) * D;
                 const size_t kv_stride = (size_t)Hkv * D;
-                double l = row_softmax(q_row, k_base, kv_stride, nvis, D, scale, p);
+                double l = row_softmax(q_row, k_base, kv_stride, lo, nvis, D, scale, p);
                 lse[(size_t)h * T + (c + i)] = l;
                 double *o_row = out + ((size_t)(c + i) * Hq + h) * D;
                 for (int d = 0; d < D; ++d) o_row[d] = 0.0;
-                for (int j = 0; j < nvis; ++j) {
+                for (int j = lo; j < nvis; ++j) {
                     const float *v_row = v_base + (size_t)j * kv_stride;
                     for (int d = 0; d < D; ++d) o_row[d] += p[j] * (double)v_row[d];
                 }
@@ -210,20 +221,21 @@ int oracle_attn_bwd(const float *q, const float *k, const float *v, const float 
             for (int h = g * G; h < (g + 1) * G; ++h) {
                 for (int i = 0; i < L; ++i) {
                     const int nvis = visible(i, L, P, P2, mask_mode);
+                    const int lo = first_visible(i, P, mask_mode);
                     const float *q_row = q + ((size_t)(c + i) * Hq + h) * D;
                     const float *do_row = dout + ((size_t)(c + i) * Hq + h) * D;
                     double *dq_row = dq + ((size_t)(c + i) * Hq + h) * D;
-                    row_softmax(q_row, k_base, kv_stride, nvis, D, scale, p);
+                    row_softmax(q_row, k_base, kv_stride, lo, nvis, D, scale, p);
                     /* this row's own fp64 output, then delta */
                     for (int d = 0; d < D; ++d) o[d] = 0.0;
-                    for (int j = 0; j < nvis; ++j) {
+                    for (int j = lo; j < nvis; ++j) {
                         const float *v_row = v_base + (size_t)j * kv_stride;
                         for (int d = 0; d < D; ++d) o[d] += p[j] * (double)v_row[d];
                     }
                     double delta = 0.0;
                     for (int d = 0; d < D; ++d) delta += (double)do_row[d] * o[d];
                     for (int d = 0; d < D; ++d) dq_row[d] = 0.0;
-                    for (int j = 0; j < nvis; ++j) {
+                    for (int j = lo; j < nvis; ++j) {
                         const float *k_row = k_base + (size_t)j * kv_stride;
                         const float *v_row = v_base + (size_t)j * kv_stride;
                         double dP = 0.0;
@@ -269,19 +281,20 @@ int oracle_attn_probs(const float *q, const float *k, const float *v, const floa
     double *o = (double *)malloc(sizeof(double) * (size_t)D);
     for (int i = 0; i < L; ++i) {
         const int nvis = visible(i, L, P, P2, mask_mode);
+        const int lo = first_visible(i, P, mask_mode);
         const float *q_row = q + ((size_t)(c + i) * Hq + h) * D;
-        row_softmax(q_row, k_base, kv_stride, nvis, D, scale, p);
-        for (int j = 0; j < L; ++j) p_out[(size_t)i * L + j] = j < nvis ? p[j] : 0.0;
+        row_softmax(q_row, k_base, kv_stride, lo, nvis, D, scale, p);
+        for (int j = 0; j < L; ++j) p_out[(size_t)i * L + j] = j >= lo && j < nvis ? p[j] : 0.0;
         if (ds_out) {
             const float *do_row = dout + ((size_t)(c + i) * Hq + h) * D;
             for (int d = 0; d < D; ++d) o[d] = 0.0;
-            for (int j = 0; j < nvis; ++j)
+            for (int j = lo; j < nvis; ++j)
                 for (int d = 0; d < D; ++d) o[d] += p[j] * (double)v_base[(size_t)j * kv_stride + d];
             double delta = 0.0;
             for (int d = 0; d < D; ++d) delta += (double)do_row[d] * o[d];
             for (int j = 0; j < L; ++j) {
                 double dS = 0.0;
-                if (j < nvis) {
+                if (j >= lo && j < nvis) {
                     double dP = 0.0;
                     for (int d = 0; d < D; ++d) dP += (double)do_row[d] * (double)v_base[(size_t)j * kv_stride + d];
                     dS = p[j] * (dP - delta);

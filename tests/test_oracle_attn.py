@@ -347,3 +347,73 @@ def test_three_block_degenerate_cases_reduce_to_the_prefix_mask():
             for h in range(Hq):
                 want_lse = 0.5 * float(q[cu[s] + i, h].astype(np.float64) @ k1[0, 0].astype(np.float64)) + np.log(nvis)
                 assert abs(lse[h, cu[s] + i] - want_lse) < 1e-12
+
+
+# ---------------------------------------------------------------- sliding window
+#
+# Row i sees the W most recent keys, itself included: 0 <= i - j < W.  The dense mask below is that
+# sentence as a band matrix, not the oracle's first_visible() / visible() pair.
+
+def window_mask(L, W):
+    d = np.arange(L)[:, None] - np.arange(L)[None, :]
+    return (d >= 0) & (d < W)
+
+
+def test_sliding_window_against_dense_definition_and_autograd():
+    Hq, Hkv, D = 4, 2, 8
+    lens = [23, 9, 14, 1]
+    W = np.array([5, 1, 40, 3], dtype=np.int32)         # ordinary; self only; wider than the sample; one token
+    cu, _, q, k, v, do = stream(21, lens, Hq, Hkv, D)
+    scale = 0.37
+    out, lse = oa.attn_fwd(q, k, v, cu, W, scale=scale, mask_mode=oa.MASK_SLIDING_WINDOW)
+    dq, dk, dv = oa.attn_bwd(q, k, v, do, cu, W, scale=scale, mask_mode=oa.MASK_SLIDING_WINDOW)
+    G = Hq // Hkv
+    for s, L in enumerate(lens):
+        c = cu[s]
+        mask = torch.from_numpy(window_mask(L, int(W[s])))
+        tq = torch.tensor(q[c:c + L].astype(np.float64), requires_grad=True)
+        tk = torch.tensor(k[c:c + L].astype(np.float64), requires_grad=True)
+        tv = torch.tensor(v[c:c + L].astype(np.float64), requires_grad=True)
+        sc = torch.einsum("ihd,jhd->hij", tq, tk.repeat_interleave(G, dim=1)) * scale
+        sc = sc.masked_fill(~mask[None], float("-inf"))
+        o = torch.einsum("hij,jhd->ihd", torch.softmax(sc, dim=-1), tv.repeat_interleave(G, dim=1))
+        (o * torch.tensor(do[c:c + L].astype(np.float64))).sum().backward()
+        assert np.allclose(out[c:c + L], o.detach().numpy(), rtol=1e-12, atol=1e-13)
+        assert np.allclose(lse[:, c:c + L], torch.logsumexp(sc, dim=-1).detach().numpy(), rtol=0, atol=1e-12)
+        assert np.allclose(dq[c:c + L], tq.grad.numpy(), rtol=1e-11, atol=1e-12)
+        assert np.allclose(dk[c:c + L], tk.grad.numpy(), rtol=1e-11, atol=1e-12)
+        assert np.allclose(dv[c:c + L], tv.grad.numpy(), rtol=1e-11, atol=1e-12)
+        for h in range(Hq):
+            p, ds = oa.attn_probs(q, k, v, do, cu, W, s, h, scale=scale, mask_mode=oa.MASK_SLIDING_WINDOW)
+            assert np.all((p > 0) == mask.numpy())
+            assert np.allclose(p.sum(axis=1), 1.0, atol=1e-14) and np.allclose(ds.sum(axis=1), 0.0, atol=1e-13)
+
+
+def test_sliding_window_special_cases():
+    Hq, Hkv, D = 2, 1, 8
+    lens = [19, 8]
+    cu, _, q, k, v, do = stream(22, lens, Hq, Hkv, D)
+    # a window as long as the sample (or longer) is the causal mask, bit for bit
+    want = oa.attn_fwd(q, k, v, cu, None, mask_mode=oa.MASK_CAUSAL) + oa.attn_bwd(q, k, v, do, cu, None, mask_mode=oa.MASK_CAUSAL)
+    for W in (np.array(lens, dtype=np.int32), np.array([1000, 1000], dtype=np.int32)):
+        got = oa.attn_fwd(q, k, v, cu, W, mask_mode=oa.MASK_SLIDING_WINDOW) + oa.attn_bwd(q, k, v, do, cu, W, mask_mode=oa.MASK_SLIDING_WINDOW)
+        assert all(np.array_equal(a, b) for a, b in zip(got, want))
+    # W = 1: every row sees itself only: O = V, LSE = scale q.k, dV = sum of dO over the group, dQ = dK = 0
+    one = np.ones(2, dtype=np.int32)
+    out, lse = oa.attn_fwd(q, k, v, cu, one, scale=0.5, mask_mode=oa.MASK_SLIDING_WINDOW)
+    dq, dk, dv = oa.attn_bwd(q, k, v, do, cu, one, scale=0.5, mask_mode=oa.MASK_SLIDING_WINDOW)
+    assert np.array_equal(out, np.repeat(v.astype(np.float64), Hq // Hkv, axis=1))
+    assert np.allclose(lse.T, 0.5 * np.einsum("thd,td->th", q.astype(np.float64), k[:, 0].astype(np.float64)), atol=1e-13)
+    assert np.all(dq == 0) and np.all(dk == 0) and np.allclose(dv[:, 0], do.astype(np.float64).sum(axis=1), atol=1e-14)
+    # uniform keys: LSE_i = scale q_i.k + ln(min(i + 1, W)), O_i = mean of the last min(i + 1, W) values
+    k1 = np.repeat(k[:1], len(k), axis=0)
+    W = np.array([6, 3], dtype=np.int32)
+    out, lse = oa.attn_fwd(q, k1, v, cu, W, scale=0.5, mask_mode=oa.MASK_SLIDING_WINDOW)
+    for s, Ls in enumerate(lens):
+        for i in range(Ls):
+            n = min(i + 1, int(W[s]))
+            want_o = v[cu[s] + i + 1 - n:cu[s] + i + 1, 0].astype(np.float64).mean(axis=0)
+            for h in range(Hq):
+                want_lse = 0.5 * float(q[cu[s] + i, h].astype(np.float64) @ k1[0, 0].astype(np.float64)) + np.log(n)
+                assert abs(lse[h, cu[s] + i] - want_lse) < 1e-12
+                assert np.allclose(out[cu[s] + i, h], want_o, rtol=1e-13, atol=1e-14)
