@@ -39,6 +39,11 @@
  *     action experts, the family section 2.2.2 adapts), and prefix_lens holds
  *     2 * num_seqs entries: P = prefix_lens[2 s], P2 = prefix_lens[2 s + 1],
  *     0 <= P <= P2 <= L.
+ *       VA_MASK_SLIDING_WINDOW        vis(i) = i + 1, and the keys start at
+ *                                     lo(i) = max(0, i + 1 - W) instead of 0
+ *     (causal, at most the W most recent keys, the row's own included), with
+ *     W = prefix_lens[s] >= 1 per sample; a W of L or more is the causal mask.
+ *     Available at head_dim 64, 128 and 256 (VA_EUNSUPPORTED otherwise).
  *   - LSE[h, r] = ln sum_j exp(scale * q_r . k_j) over the visible keys
  *     (natural logarithm, scale included).
  */
@@ -63,6 +68,7 @@ extern "C" {
 #define VA_MASK_PREFIX_LM 1
 #define VA_MASK_PREFIX_LM_CAUSAL 2
 #define VA_MASK_THREE_BLOCK 3
+#define VA_MASK_SLIDING_WINDOW 4
 
 #define VA_PASS_FWD 0
 #define VA_PASS_BWD_DKDV 1
@@ -137,6 +143,13 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
  *   dK/dV item:        {kv_row0, kv_rows, seq_row0, qt_first, qt_count, P2 or -1, P or -1, L}
  * (n_tiles key tiles hold a key some row of the item sees, the first n_full of them
  * no hidden pair; P and P2 are the sample's block ends, -1 where the mask has none)
+ * Under VA_MASK_SLIDING_WINDOW the P word holds the window W, n_full and n_tiles
+ * are those of the causal mask, and the lower edge follows from W: of the tiles
+ * of cols keys below n_tiles an item visits those from lo(first row) / cols on,
+ * and its mask-free tiles are those from ceil(lo(last row) / cols) up to n_full;
+ * qt_count of a dK/dV item ends with the last query tile holding a row that
+ * still sees a key of the item; an item's weight in the order of the list and in
+ * the schedule is the number of tiles it visits.
  * A work is one item for one head chunk: the query heads one workgroup stacks
  * (forward, dQ) or one KV head (dK/dV), so works_per_item depends on the head
  * counts the list was built for.  The kernels run num_workgroups persistent

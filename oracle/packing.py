@@ -39,6 +39,13 @@ and no tile spans two samples.  Items are 8 int32 words:
 
 Order: descending amount of work (n_tiles, resp. qt_count), ties in ascending
 (sample, tile) order.
+
+Sliding window (prefix_len holds the window W): n_full and n_tiles are those of
+the causal mask on the same rows; an item visits the key tiles from the first
+one that holds an allowed pair up to n_tiles, and treats as mask-free those from
+the first one fully inside the window of its last row up to n_full; its amount
+of work is the number of tiles it visits.  qt_count of a dK/dV item ends with
+the last query tile that holds a row seeing a key of the item.
 """
 import numpy as np
 
@@ -50,6 +57,7 @@ MASK_CAUSAL = 0
 MASK_PREFIX_BIDIR_SUFFIX = 1
 MASK_PREFIX_CAUSAL_SUFFIX = 2
 MASK_THREE_BLOCK = 3      # prefix_lens holds [num_seqs, 2]: the ends (P, P2) of the first two blocks
+MASK_SLIDING_WINDOW = 4   # causal, at most the W most recent keys; prefix_lens holds W >= 1 per sample
 
 
 def first_fit(lens, budget):
@@ -100,7 +108,7 @@ def bin_layout(lens, prefix=None):
 
 def visible(i, L, P, mode, P2=-1):
     """Number of keys local query row i may attend to."""
-    if mode == MASK_CAUSAL:
+    if mode in (MASK_CAUSAL, MASK_SLIDING_WINDOW):
         return i + 1
     if i < P:
         return P
@@ -112,6 +120,8 @@ def visible(i, L, P, mode, P2=-1):
 
 
 def allowed(i, j, L, P, mode, P2=-1):
+    if mode == MASK_SLIDING_WINDOW:        # P holds the window
+        return 0 <= i - j < P
     return 0 <= j < visible(i, L, P, mode, P2)
 
 
@@ -151,6 +161,7 @@ def build_worklist(cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=None):
                         if allowed(i, j, L, P, mode, P2):
                             kv_len = max(kv_len, j + 1)
                 n_tiles = (kv_len + bn - 1) // bn
+                upper = MASK_CAUSAL if mode == MASK_SLIDING_WINDOW else mode   # n_full looks at the upper edge only
                 n_full = 0
                 for kt in range(n_tiles):
                     if kt != n_full:
@@ -158,10 +169,12 @@ def build_worklist(cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=None):
                     ok = (kt + 1) * bn <= L
                     for i in rows:
                         for j in range(kt * bn, min(L, (kt + 1) * bn)):
-                            ok = ok and allowed(i, j, L, P, mode, P2)
+                            ok = ok and allowed(i, j, L, P, upper, P2)
                     if ok:
                         n_full += 1
-                items.append(((n_tiles, s, t), [c + t * bm, len(rows), c, P2, n_full, n_tiles, P, L]))
+                visited = sum(1 for kt in range(n_tiles)
+                              if any(allowed(i, j, L, P, mode, P2) for i in rows for j in range(kt * bn, min(L, (kt + 1) * bn))))
+                items.append(((visited, s, t), [c + t * bm, len(rows), c, P2, n_full, n_tiles, P, L]))
         else:
             for kt in range((L + bn - 1) // bn):
                 keys = range(kt * bn, min(L, (kt + 1) * bn))
@@ -172,7 +185,10 @@ def build_worklist(cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=None):
                         break
                 assert first_row is not None  # every key is seen by its own row
                 qt_first = first_row // bm
+                last_row = max(i for i in range(L) if any(allowed(i, j, L, P, mode, P2) for j in keys))
                 qt_count = (L + bm - 1) // bm - qt_first
+                if mode == MASK_SLIDING_WINDOW:
+                    qt_count = last_row // bm - qt_first + 1
                 items.append(((qt_count, s, kt), [c + kt * bn, len(keys), c, qt_first, qt_count, P2, P, L]))
     items.sort(key=lambda e: (-e[0][0], e[0][1], e[0][2]))
     if not items:
@@ -205,7 +221,11 @@ def check_coverage(items, cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=No
             P2, n_full, n_tiles = w3, w4, w5
             assert P2 == wantP2, "wrong end of the second block"
             assert n_full <= n_tiles and (n_tiles - 1) * bn < L
-            for kt in range(n_tiles):
+            kt_first, kt_plain = 0, 0
+            if mode == MASK_SLIDING_WINDOW:   # the lower edge as the interface states it, from W
+                kt_first = max(0, (a - c) + 1 - P) // bn
+                kt_plain = -(-max(0, (a - c + rows - 1) + 1 - P) // bn)
+            for kt in range(kt_first, n_tiles):
                 pairs = 0
                 masked = 0
                 for i in range(a - c, a - c + rows):
@@ -217,14 +237,18 @@ def check_coverage(items, cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=No
                         else:
                             masked += 1
                 assert pairs > 0, "fully masked tile listed"
-                if kt < n_full:
+                if kt_plain <= kt < n_full:
                     assert masked == 0, "tile marked full holds a masked pair"
         else:
             assert (a - c) % bn == 0 and rows <= bn
             qt_first, qt_count, P2 = w3, w4, w5
             assert P2 == wantP2, "wrong end of the second block"
-            assert qt_first + qt_count == (L + bm - 1) // bm
+            if mode == MASK_SLIDING_WINDOW:
+                assert 0 < qt_count and qt_first + qt_count <= (L + bm - 1) // bm
+            else:
+                assert qt_first + qt_count == (L + bm - 1) // bm
             pairs_first = 0
+            pairs_last = 0
             for qt in range(qt_first, qt_first + qt_count):
                 for i in range(qt * bm, min(L, (qt + 1) * bm)):
                     for j in range(a - c, a - c + rows):
@@ -233,7 +257,11 @@ def check_coverage(items, cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=No
                             seen[key] = seen.get(key, 0) + 1
                             if qt == qt_first:
                                 pairs_first += 1
+                            if qt == qt_first + qt_count - 1:
+                                pairs_last += 1
             assert pairs_first > 0, "first listed query tile sees nothing of this key tile"
+            if mode == MASK_SLIDING_WINDOW:
+                assert pairs_last > 0, "last listed query tile sees nothing of this key tile"
     total = 0
     for s in range(n):
         c = int(cu_seqlens[s])
@@ -250,4 +278,6 @@ def check_coverage(items, cu_seqlens, prefix_lens, pass_id, bm, bn, mask_mode=No
 
 def allowed_pairs(L, P, mode, P2=-1):
     """Number of allowed (query, key) pairs of one sample, by counting."""
+    if mode == MASK_SLIDING_WINDOW:
+        return sum(min(i + 1, P) for i in range(L))
     return sum(visible(i, L, P, mode, P2) for i in range(L))

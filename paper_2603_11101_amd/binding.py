@@ -15,7 +15,7 @@ import torch  # noqa: F401
 
 VA_OK = 0
 VA_EINVAL, VA_EUNSUPPORTED, VA_EALIGN, VA_ESIZE, VA_EHIP = -1, -2, -3, -4, -5
-VA_MASK_CAUSAL, VA_MASK_PREFIX_LM, VA_MASK_PREFIX_LM_CAUSAL, VA_MASK_THREE_BLOCK = 0, 1, 2, 3
+VA_MASK_CAUSAL, VA_MASK_PREFIX_LM, VA_MASK_PREFIX_LM_CAUSAL, VA_MASK_THREE_BLOCK, VA_MASK_SLIDING_WINDOW = 0, 1, 2, 3, 4
 VA_PASS_FWD, VA_PASS_BWD_DKDV, VA_PASS_BWD_DQ = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

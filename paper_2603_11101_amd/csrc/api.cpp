@@ -23,8 +23,10 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
     if (s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->num_q_heads % s->num_kv_heads != 0)
         return fail(VA_EUNSUPPORTED, "%s: num_q_heads %d is not a positive multiple of num_kv_heads %d", who,
                     s->num_q_heads, s->num_kv_heads);
-    if (s->mask_mode < VA_MASK_CAUSAL || s->mask_mode > VA_MASK_THREE_BLOCK)
+    if (s->mask_mode < VA_MASK_CAUSAL || s->mask_mode > VA_MASK_SLIDING_WINDOW)
         return fail(VA_EUNSUPPORTED, "%s: unknown mask mode %d", who, s->mask_mode);
+    if (s->mask_mode == VA_MASK_SLIDING_WINDOW && s->head_dim != 64 && s->head_dim != 128 && s->head_dim != 256)
+        return fail(VA_EUNSUPPORTED, "%s: the sliding-window mask exists for head_dim 64, 128 and 256, not %d", who, s->head_dim);
     if (s->num_seqs < 0 || s->total_tokens < 0) return fail(VA_EINVAL, "%s: negative sizes", who);
     if (cu[0] != 0) return fail(VA_EINVAL, "%s: cu_seqlens[0] = %d, expected 0", who, cu[0]);
     for (int32_t i = 0; i < s->num_seqs; ++i) {
@@ -35,7 +37,7 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
         int32_t P, P2;
         block_ends(prefix_lens, s->mask_mode, i, &P, &P2);
         if (!block_ends_valid(P, P2, L, s->mask_mode))
-            return fail(VA_EINVAL, "%s: block ends (%d, %d) of sample %d outside [0, %d] or out of order", who, P, P2, i, L);
+            return fail(VA_EINVAL, "%s: block ends (%d, %d) of sample %d outside [0, %d] or out of order, or a window below 1", who, P, P2, i, L);
     }
     if (cu[s->num_seqs] != s->total_tokens)
         return fail(VA_EINVAL, "%s: cu_seqlens ends at %d, total_tokens is %d", who, cu[s->num_seqs], s->total_tokens);
@@ -88,7 +90,10 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
             return fail(VA_EINVAL, "%s: work item %d does not match a sample of cu_seqlens", who, i);
         const int32_t Pm = P < 0 ? 0 : P, P2m = P2 < 0 ? 0 : P2;
         if (pass == VA_PASS_BWD_DKDV) {
-            if (it[3] < 0 || it[4] <= 0 || it[3] + it[4] != (L + cols - 1) / cols)
+            int32_t qt_end = (L + cols - 1) / cols;
+            if (s->mask_mode == VA_MASK_SLIDING_WINDOW)
+                qt_end = (int32_t)(std::min<int64_t>(L - 1, (int64_t)(row0 - seq0) + nrows - 1 + Pm - 1) / cols) + 1;
+            if (it[3] < 0 || it[4] <= 0 || it[3] + it[4] != qt_end)
                 return fail(VA_EINVAL, "%s: work item %d has a bad query-tile range", who, i);
         } else {
             const int32_t r0 = row0 - seq0;

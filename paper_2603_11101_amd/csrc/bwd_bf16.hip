@@ -110,8 +110,12 @@ VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int id) {
 //          (256 registers per lane, in the accumulation registers) at D = 256
 //   DR     head dimension of the tensors in memory (a multiple of 16, D / 2 < DR <= D); D is then the
 //          geometry of the LDS tiles and register blocks only
-template <int D, bool V_LDS, bool THREE, int DR>
+// FAMILY selects the mask code: 0 the masks with one boundary, 1 the three-block mask, 2 the sliding window
+// (the P word of the work holds the width W; query rows past the window of a key block skip it, and
+// blocks cut by the window's lower edge carry the mask like the diagonal ones).
+template <int D, bool V_LDS, int FAMILY, int DR>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnParams p) {
+    constexpr bool THREE = FAMILY == 1, WINDOW = FAMILY == 2;
     static_assert(DR % 16 == 0 && DR <= D && DR > D / 2, "head dimension and geometry do not match");
     using Rows = RowBlock<D, DR>;
     constexpr bool V_IN_LDS = V_LDS, V_REGS = !V_LDS;
@@ -210,6 +214,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         const int n_steps = G * cur.qt_count;
         const RowMask mask(cur.P, cur.P2, cur.L, p.mask_mode);
         const int L = cur.L;
+        // keys local query row i sees: [lo_of(i), vis_of(i))
+        auto vis_of = [&](int i) { return WINDOW ? i + 1 : mask.vis<THREE>(i); };
+        auto lo_of = [&](int i) { return WINDOW ? max(0, i + 1 - cur.P) : 0; };
         // this wave's 32 key rows; the lane owns key row jw + l32 (local index in the sample)
         const int jw = cur.kv_row0 - cur.seq_row0 + 32 * wave;
 
@@ -243,9 +250,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                 const int i0 = q0 + 32 * qb;  // first query row of the block (local index in the sample)
                 if (i0 >= L) break;
                 const int i1 = min(i0 + 31, L - 1);
-                if (mask.vis<THREE>(i1) <= jw) continue;  // nothing of this key block is visible
+                if (vis_of(i1) <= jw) continue;  // nothing of this key block is visible
+                if (WINDOW && lo_of(i0) >= jw + 32) continue;  // the window of every row has moved past it
                 // rows past the sample read as zeros and must get p = 0: they count as seeing no key
-                const bool need_mask = mask.vis<THREE>(i0) < jw + 32 || i0 + 32 > L;
+                const bool need_mask = vis_of(i0) < jw + 32 || i0 + 32 > L || (WINDOW && lo_of(i1) > jw);
 
                 // S = Q K^T and dP = dO V^T: rows = query rows (registers), columns = key rows (lanes).
                 // MFMAs alternate between the two accumulators so that none waits on the one just issued.
@@ -322,11 +330,21 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                     asm volatile("" : "+v"(key));
                     const int row_base = q0 + 32 * qb + 4 * hf;  // query row of register 0, local to the sample
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (key >= mask.vis_in_sample<THREE>(row_base + 8 * (r / 4) + r % 4)) {
+                    for (int r = 0; r < 16; ++r) {
+                        const int step = 8 * (r / 4) + r % 4;  // query row of register r is row_base + step
+                        bool hidden;
+                        if constexpr (WINDOW) {
+                            // visible iff 0 <= row - key < W and the row lies inside the sample: one unsigned
+                            // comparison on a per-lane difference, one on wave-uniform values
+                            hidden = (unsigned)(row_base - key + step) >= (unsigned)cur.P || step >= L - row_base;
+                        } else {
+                            hidden = key >= mask.vis_in_sample<THREE>(row_base + step);
+                        }
+                        if (hidden) {
                             s[r] = 0.0f;
                             dp[r] = 0.0f;
                         }
+                    }
                 }
                 bf16x8 pb[2], dsb[2];
 #pragma unroll
@@ -394,7 +412,9 @@ using DqWork = RowWork;
 //          then runs after this one; the separate pass over O and dO is not launched.
 //   DR     head dimension of the tensors in memory (a multiple of 16, D / 2 < DR <= D); D is then the
 //          geometry of the LDS tiles and register blocks only
-template <int D, int HPB, bool FUSE, int DR>
+// WINDOW: the sliding-window mask, as in the forward kernel (key tiles below the window of the work's first
+// row are not visited, those reaching below the window of its last row carry the mask).
+template <int D, int HPB, bool FUSE, int DR, bool WINDOW>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParams p) {
     static_assert(DR % 16 == 0 && DR <= D && DR > D / 2, "head dimension and geometry do not match");
     using Rows = RowBlock<D, DR>;
@@ -505,9 +525,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     };
     const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
 
+    // first key tile a work visits: 0 unless the window has moved past it
+    auto first_tile = [&](const DqWork& w) {
+        return WINDOW ? max(0, w.q_row0 - w.seq_row0 + 1 - w.P) / BN : 0;
+    };
     int stage = 0;
-    loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
-    loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
+    loader.issue(kv_rsrc(p.k, cur), smem_lds, first_tile(cur) * tile_step);
+    loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, first_tile(cur) * tile_step);
     load_rows(cur);
     load_o(cur);
     finish_rows(cur, 2 * TILE_BYTES + slice_in_stage);  // stage 1 is still free
@@ -520,7 +544,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         const DqWork nxt = works.peek_next();
         const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
         const int tok = row % BMT;
-        const int vis = RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
+        const int row_in_sample = cur.q_row0 - cur.seq_row0 + tok;
+        const int vis = WINDOW ? row_in_sample + 1 : RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(row_in_sample);
+        const int lo = WINDOW ? max(0, row_in_sample + 1 - cur.P) : 0;
 
         f32x16 dq[DT];
 #pragma unroll
@@ -551,8 +577,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
                     loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
                     loader.issue(v_rsrc, nk + TILE_BYTES, (kt + 1) * tile_step);
                 } else if (has_next) {
-                    loader.issue(kv_rsrc(p.k, nxt), nk, 0);
-                    loader.issue(kv_rsrc(p.v, nxt), nk + TILE_BYTES, 0);
+                    loader.issue(kv_rsrc(p.k, nxt), nk, first_tile(nxt) * tile_step);
+                    loader.issue(kv_rsrc(p.v, nxt), nk + TILE_BYTES, first_tile(nxt) * tile_step);
                 }
             }
             // One 32-key block at a time: S^T and dP^T (rows = key rows in registers, columns = query rows in
@@ -601,7 +627,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -my_lse2));
-                    if (need_mask && j0 + 32 * b + acc_row(r, hf) >= vis) pv = 0.0f;
+                    if (need_mask && (j0 + 32 * b + acc_row(r, hf) >= vis || (WINDOW && j0 + 32 * b + acc_row(r, hf) < lo)))
+                        pv = 0.0f;
                     dp[r] = pv * (dp[r] - my_delta);
                 }
                 bf16x8 dsb[2];
@@ -635,7 +662,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         // The last tile is always treated as masked: it is the ragged one.
         {
             const int n_plain = min(cur.n_full, cur.n_tiles - 1);
-            int kt = 0;
+            int kt = first_tile(cur);
+            if constexpr (WINDOW) {
+                // tiles that reach below the window of the work's last row
+                const int low_end = (max(0, cur.q_row0 - cur.seq_row0 + cur.q_rows - cur.P) + BN - 1) / BN;
+                for (; kt < min(low_end, cur.n_tiles - 1); ++kt) tile(kt, std::false_type{}, std::true_type{});
+            }
             for (; kt < n_plain; ++kt) tile(kt, std::false_type{}, std::false_type{});
             for (; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{}, std::true_type{});
             tile(cur.n_tiles - 1, std::true_type{}, std::true_type{});
@@ -656,14 +688,22 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     }
 }
 
-template <int D, int HPB, int DR>
-hipError_t launch_dq_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
+template <int D, int HPB, int DR, bool WINDOW>
+hipError_t launch_dq_dhw(const AttnParams& p, hipStream_t stream, unsigned grid) {
     constexpr size_t smem = 2 * 2 * kDqKvTile * D * 2;  // two stages of (K tile, V tile)
     constexpr bool FUSE = dq_computes_delta(D);
-    const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dq_kernel<D, HPB, FUSE, DR>), smem);
+    const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dq_kernel<D, HPB, FUSE, DR, WINDOW>), smem);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((bwd_dq_kernel<D, HPB, FUSE, DR>), dim3(grid), dim3(256), smem, stream, p);
+    hipLaunchKernelGGL((bwd_dq_kernel<D, HPB, FUSE, DR, WINDOW>), dim3(grid), dim3(256), smem, stream, p);
     return hipGetLastError();
+}
+
+template <int D, int HPB, int DR>
+hipError_t launch_dq_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
+    if (p.mask_mode != VA_MASK_SLIDING_WINDOW) return launch_dq_dhw<D, HPB, DR, false>(p, stream, grid);
+    // the window instantiations exist for the full-width geometries only
+    if constexpr (DR == D) return launch_dq_dhw<D, HPB, DR, true>(p, stream, grid);
+    return hipErrorNotSupported;
 }
 
 template <int D, int DR = D>
@@ -687,16 +727,25 @@ hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     // two stages of (Q tile, dO tile, LSE, delta), then the V tile / output staging region
     constexpr size_t smem = 2 * (2 * dkdv_q_tile(D) * D * 2 + 2 * 64 * sizeof(float)) + kDkdvKvRows * D * 2;
     const unsigned grid = (unsigned)(p.num_items * p.works_per_item);
-    // one instantiation per mask family: the masks without a second block do not pay for it
+    // one instantiation per mask family: the masks without a second block or a lower edge do not pay for them
+    auto launch = [&](auto family) -> hipError_t {
+        constexpr int FAMILY = decltype(family)::value;
+        const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dkdv_kernel<D, V_LDS, FAMILY, DR>), smem);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, FAMILY, DR>), dim3(grid), dim3(256), smem, stream, p);
+        return hipSuccess;
+    };
+    hipError_t e;
     if (p.mask_mode == VA_MASK_THREE_BLOCK) {
-        const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dkdv_kernel<D, V_LDS, true, DR>), smem);
-        if (attr != hipSuccess) return attr;
-        hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, true, DR>), dim3(grid), dim3(256), smem, stream, p);
+        e = launch(std::integral_constant<int, 1>{});
+    } else if (p.mask_mode == VA_MASK_SLIDING_WINDOW) {
+        // the window instantiations exist for the full-width geometries only
+        if constexpr (DR == D) e = launch(std::integral_constant<int, 2>{});
+        else e = hipErrorNotSupported;
     } else {
-        const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dkdv_kernel<D, V_LDS, false, DR>), smem);
-        if (attr != hipSuccess) return attr;
-        hipLaunchKernelGGL((bwd_dkdv_kernel<D, V_LDS, false, DR>), dim3(grid), dim3(256), smem, stream, p);
+        e = launch(std::integral_constant<int, 0>{});
     }
+    if (e != hipSuccess) return e;
     return hipGetLastError();
 }
 

@@ -71,11 +71,15 @@ constexpr int32_t kWorkFixedCost = 2;
 // Number of keys local query row i of a sample may see: length L, block ends P and P2 (values below 0
 // stand for "no such boundary" and are taken as 0).
 inline int32_t visible(int32_t i, int32_t L, int32_t P, int32_t P2, int32_t mode) {
-    if (mode == VA_MASK_CAUSAL) return i + 1;
+    if (mode == VA_MASK_CAUSAL || mode == VA_MASK_SLIDING_WINDOW) return i + 1;
     if (i < P) return P;
     if (mode == VA_MASK_PREFIX_LM) return L;
     if (mode == VA_MASK_THREE_BLOCK) return i < P2 ? P2 : L;
     return i + 1;
+}
+// First key local query row i may see: 0, except under the sliding window, whose width W travels in P.
+inline int32_t first_visible(int32_t i, int32_t P, int32_t mode) {
+    return mode == VA_MASK_SLIDING_WINDOW && i + 1 - P > 0 ? i + 1 - P : 0;
 }
 // Block ends of sample s as stored in the work items (-1 where the mask has no such boundary), from the
 // caller's prefix_lens: one entry per sample, or the pair (P, P2) under VA_MASK_THREE_BLOCK.
@@ -89,9 +93,10 @@ inline void block_ends(const int32_t* prefix_lens, int32_t mode, int32_t s, int3
         *P = prefix_lens[s];
     }
 }
-// 0 <= P <= L, and P <= P2 <= L under VA_MASK_THREE_BLOCK
+// 0 <= P <= L, and P <= P2 <= L under VA_MASK_THREE_BLOCK; a window width is at least 1
 inline bool block_ends_valid(int32_t P, int32_t P2, int32_t L, int32_t mode) {
     if (mode == VA_MASK_CAUSAL) return true;
+    if (mode == VA_MASK_SLIDING_WINDOW) return P >= 1;
     if (P < 0 || P > L) return false;
     return mode != VA_MASK_THREE_BLOCK || (P2 >= P && P2 <= L);
 }

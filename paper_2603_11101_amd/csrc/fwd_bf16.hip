@@ -42,7 +42,11 @@ using FwdWork = RowWork;
 // D is the geometry of the LDS tiles and register blocks (64, 128 or 256 values per row); DR <= D the
 // head dimension of the tensors in memory, a multiple of 16: products run over DR / 16 k-steps and
 // (DR + 31) / 32 output blocks only, and the chunks of a row from DR / 8 on are neither fetched nor stored.
-template <int D, int HPB, int DR>
+// WINDOW: the sliding-window mask (the P word of a work holds the width W): the keys of local row i start
+// at lo(i) = max(0, i + 1 - W), the key tiles below lo(first row) are not visited, and those below
+// lo(last row), rounded up to a tile, carry the mask like the diagonal ones.  A separate instantiation, so
+// that the other masks pay nothing for the lower edge.
+template <int D, int HPB, int DR, bool WINDOW>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnParams p) {
     static_assert(DR % 16 == 0 && DR <= D && DR > D / 2, "head dimension and geometry do not match");
     constexpr int BMT = kFwdBlockRows / HPB;  // token rows of the work item
@@ -95,9 +99,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     constexpr int kEpilogueStores = Rows::N + 1;
     const int slice_in_stage = wave * (32 * D * 2);  // this wave's private part of a stage
 
+    // first key tile a work visits: 0 unless the window has moved past it
+    auto first_tile = [&](const FwdWork& w) {
+        return WINDOW ? max(0, w.q_row0 - w.seq_row0 + 1 - w.P) / BN : 0;
+    };
     int stage = 0;  // LDS stage that holds (or will hold) the tile about to be processed
-    loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
-    loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, 0);
+    loader.issue(kv_rsrc(p.k, cur), smem_lds, first_tile(cur) * tile_step);
+    loader.issue(kv_rsrc(p.v, cur), smem_lds + TILE_BYTES, first_tile(cur) * tile_step);
     bf16x8 qf[NQ];
     load_q(qf, cur);
     Rows::to_fragments(qf, smem, 2 * TILE_BYTES + slice_in_stage, fa, lane);  // stage 1 is still free
@@ -108,7 +116,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
         const int tok = row % BMT;
         const bool row_valid = tok < cur.q_rows;
-        const int vis = RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
+        const int row_in_sample = cur.q_row0 - cur.seq_row0 + tok;
+        const int vis = WINDOW ? row_in_sample + 1 : RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(row_in_sample);
+        const int lo = WINDOW ? max(0, row_in_sample + 1 - cur.P) : 0;
 
         f32x16 o[DT];
 #pragma unroll
@@ -142,8 +152,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
                     loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
                     loader.issue(v_rsrc, nk + TILE_BYTES, (kt + 1) * tile_step);
                 } else if (has_next) {
-                    loader.issue(kv_rsrc(p.k, nxt), nk, 0);
-                    loader.issue(kv_rsrc(p.v, nxt), nk + TILE_BYTES, 0);
+                    loader.issue(kv_rsrc(p.k, nxt), nk, first_tile(nxt) * tile_step);
+                    loader.issue(kv_rsrc(p.v, nxt), nk + TILE_BYTES, first_tile(nxt) * tile_step);
                 }
             }
 
@@ -185,7 +195,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
                 for (int b = 0; b < 2; ++b)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        if (j0 + 32 * b + acc_row(r, hf) >= vis) s[b][r] = -INFINITY;
+                        if (j0 + 32 * b + acc_row(r, hf) >= vis || (WINDOW && j0 + 32 * b + acc_row(r, hf) < lo))
+                            s[b][r] = -INFINITY;
             }
             // first V^T fragments on their way while the softmax runs.  Step i: keys 16 (i / DT) .. + 15,
             // O^T block i % DT, so consecutive MFMAs go to different accumulators.
@@ -201,7 +212,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
             if (__builtin_amdgcn_ballot_w64(mx > m + kMaxLag) != 0) {  // wave-uniform: some row needs a new reference
                 asm volatile("");  // keep this a branch: folded into a select, its multiplications would run on every tile
                 const float m_new = fmaxf(m, mx);
-                const float alpha = __builtin_amdgcn_exp2f(m - m_new);  // m = -inf on the first tile: alpha = 0, O = 0
+                // m = -inf on the first tile: alpha = 0, O = 0.  Under the window a row may see no key of the
+                // first tiles it visits: it keeps m = -inf and takes the reference 0 until it sees one.
+                const float alpha = __builtin_amdgcn_exp2f(m - (WINDOW && m_new == -INFINITY ? 0.0f : m_new));
                 m = m_new;
                 lsum *= alpha;
 #pragma unroll
@@ -210,11 +223,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
                     for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
             }
             float psum = 0.0f;
+            const float m_ref = WINDOW && m == -INFINITY ? 0.0f : m;
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, -m));
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, -m_ref));
                     s[b][r] = pv;
                     psum += pv;
                 }
@@ -256,7 +270,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
         // The last tile is always treated as masked: it is the ragged one.
         {
             const int n_plain = min(cur.n_full, cur.n_tiles - 1);
-            int kt = 0;
+            int kt = first_tile(cur);
+            if constexpr (WINDOW) {
+                // tiles that reach below the window of the work's last row
+                const int low_end = (max(0, cur.q_row0 - cur.seq_row0 + cur.q_rows - cur.P) + BN - 1) / BN;
+                for (; kt < min(low_end, cur.n_tiles - 1); ++kt) tile(kt, std::false_type{}, std::true_type{});
+            }
             for (; kt < n_plain; ++kt) tile(kt, std::false_type{}, std::false_type{});
             for (; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{}, std::true_type{});
             tile(cur.n_tiles - 1, std::true_type{}, std::true_type{});
@@ -285,13 +304,21 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     }
 }
 
+template <int D, int HPB, int DR, bool WINDOW>
+hipError_t launch_dhw(const AttnParams& p, hipStream_t stream, unsigned grid) {
+    constexpr size_t smem = 2 * 2 * kFwdKvTile * D * 2;  // two stages of (K tile, V tile)
+    const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&fwd_bf16_kernel<D, HPB, DR, WINDOW>), smem);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((fwd_bf16_kernel<D, HPB, DR, WINDOW>), dim3(grid), dim3(256), smem, stream, p);
+    return hipGetLastError();
+}
+
 template <int D, int HPB, int DR>
 hipError_t launch_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
-    constexpr size_t smem = 2 * 2 * kFwdKvTile * D * 2;  // two stages of (K tile, V tile)
-    const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&fwd_bf16_kernel<D, HPB, DR>), smem);
-    if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((fwd_bf16_kernel<D, HPB, DR>), dim3(grid), dim3(256), smem, stream, p);
-    return hipGetLastError();
+    if (p.mask_mode != VA_MASK_SLIDING_WINDOW) return launch_dhw<D, HPB, DR, false>(p, stream, grid);
+    // the window instantiations exist for the full-width geometries only
+    if constexpr (DR == D) return launch_dhw<D, HPB, DR, true>(p, stream, grid);
+    return hipErrorNotSupported;
 }
 
 template <int D, int DR = D>

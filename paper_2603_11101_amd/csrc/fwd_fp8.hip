@@ -161,7 +161,10 @@ static_assert(FragAddr8::self_check(), "fragment address closed forms disagree w
 
 // Persistent like the bf16 forward: workgroup b runs the works the host assigned to it; the first K/V tile
 // and the Q fragments of the next work are fetched while the last key tile of the current one is processed.
-template <int HPB, bool BLOCK>
+// WINDOW: the sliding-window mask, as in the bf16 forward (the P word of a work holds the width W; key
+// tiles below the window of the work's first row are not visited, those reaching below the window of its
+// last row carry the mask).
+template <int HPB, bool BLOCK, bool WINDOW>
 __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     constexpr int D = 128;
     constexpr int BMT = kFwdBlockRows / HPB;
@@ -185,6 +188,10 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     loader.init(wave, lane, kv_row_bytes);
     const FragAddr8 fa(lane);
 
+    // first key tile a work visits: 0 unless the window has moved past it
+    auto first_tile = [&](const RowWork& w) {
+        return WINDOW ? max(0, w.q_row0 - w.seq_row0 + 1 - w.P) / BN : 0;
+    };
     auto kv_rsrc = [&](const void* base, const RowWork& w) {
         return make_rsrc(static_cast<const char*>(base) + ((size_t)w.seq_row0 * p.Hkv + w.g) * D,
                          (unsigned)(w.L - 1) * kv_row_bytes + D);
@@ -226,7 +233,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
                 float, __builtin_amdgcn_raw_buffer_load_b32(qd_rows, (tok * p.Hq + head_in_block) * 4, 0, 0));
             // rows past the block read 0: give them a factor that keeps their (unused) arithmetic finite
             c_row = p.scale * kLog2e * (tok < w.q_rows ? qd : 1.0f);
-            load_kv_descale(w, 0);
+            load_kv_descale(w, first_tile(w));
         } else {
             c_row = p.scale * p.q_descale[w.h0 + head_in_block] * p.k_descale[w.g] * kLog2e;
         }
@@ -241,8 +248,8 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     };
 
     int stage = 0;
-    loader.issue(kv_rsrc(p.k, cur), smem_lds, 0);
-    loader.issue(kv_rsrc(p.v, cur), smem_lds + kTileBytes, 0);
+    loader.issue(kv_rsrc(p.k, cur), smem_lds, first_tile(cur) * tile_step);
+    loader.issue(kv_rsrc(p.v, cur), smem_lds + kTileBytes, first_tile(cur) * tile_step);
     load_q(cur);
     // Every ordinary load is consumed before the loop head, here and at the end of a work, so that the
     // compiler has no wait of its own to place at the top of a work, where output rows are still leaving.
@@ -259,7 +266,9 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
         const RowWork nxt = works.peek_next();
         const i32x4 k_rsrc = kv_rsrc(p.k, cur), v_rsrc = kv_rsrc(p.v, cur);
         const bool row_valid = tok < cur.q_rows;
-        const int vis = RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(cur.q_row0 - cur.seq_row0 + tok);
+        const int row_in_sample = cur.q_row0 - cur.seq_row0 + tok;
+        const int vis = WINDOW ? row_in_sample + 1 : RowMask(cur.P, cur.P2, cur.L, p.mask_mode).vis(row_in_sample);
+        const int lo = WINDOW ? max(0, row_in_sample + 1 - cur.P) : 0;
         const float c = c_row;
         const float v_descale = BLOCK ? 1.0f : p.v_descale[cur.g];
 
@@ -297,8 +306,8 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
                     loader.issue(k_rsrc, nk, (kt + 1) * tile_step);
                     loader.issue(v_rsrc, nk + kTileBytes, (kt + 1) * tile_step);
                 } else if (has_next) {
-                    loader.issue(kv_rsrc(p.k, nxt), nk, 0);
-                    loader.issue(kv_rsrc(p.v, nxt), nk + kTileBytes, 0);
+                    loader.issue(kv_rsrc(p.k, nxt), nk, first_tile(nxt) * tile_step);
+                    loader.issue(kv_rsrc(p.v, nxt), nk + kTileBytes, first_tile(nxt) * tile_step);
                 }
             }
             // S^T: two blocks of 32 keys x 32 query rows, alternating so that no MFMA waits for the last one.
@@ -321,7 +330,7 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
                 for (int b = 0; b < 2; ++b)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        if (j0 + 32 * hf + 16 * b + r >= vis) s[b][r] = -INFINITY;
+                        if (j0 + 32 * hf + 16 * b + r >= vis || (WINDOW && j0 + 32 * hf + 16 * b + r < lo)) s[b][r] = -INFINITY;
             }
             // V^T fragments on their way while the softmax runs
             i32x8 vf[DT];
@@ -379,7 +388,12 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
         };
         {
             const int n_plain = min(cur.n_full, cur.n_tiles - 1);
-            int kt = 0;
+            int kt = first_tile(cur);
+            if constexpr (WINDOW) {
+                // tiles that reach below the window of the work's last row
+                const int low_end = (max(0, cur.q_row0 - cur.seq_row0 + cur.q_rows - cur.P) + BN - 1) / BN;
+                for (; kt < min(low_end, cur.n_tiles - 1); ++kt) tile(kt, std::false_type{}, std::true_type{});
+            }
             for (; kt < n_plain; ++kt) tile(kt, std::false_type{}, std::false_type{});
             for (; kt + 1 < cur.n_tiles; ++kt) tile(kt, std::false_type{}, std::true_type{});
             tile(cur.n_tiles - 1, std::true_type{}, std::true_type{});
@@ -409,7 +423,10 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
 template <int HPB, bool BLOCK>
 hipError_t launch_h(const AttnParams& p, hipStream_t stream) {
     constexpr size_t smem = 2 * 2 * kTileBytes + 4 * 32 * 128 * 2;
-    hipLaunchKernelGGL((fwd_fp8_kernel<HPB, BLOCK>), dim3((unsigned)p.num_workgroups), dim3(256), smem, stream, p);
+    if (p.mask_mode == VA_MASK_SLIDING_WINDOW)
+        hipLaunchKernelGGL((fwd_fp8_kernel<HPB, BLOCK, true>), dim3((unsigned)p.num_workgroups), dim3(256), smem, stream, p);
+    else
+        hipLaunchKernelGGL((fwd_fp8_kernel<HPB, BLOCK, false>), dim3((unsigned)p.num_workgroups), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 

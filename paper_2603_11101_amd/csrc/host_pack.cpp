@@ -162,7 +162,7 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
                       int32_t mask_mode, int32_t pass, int32_t D, int32_t Hq, int32_t Hkv,
                       void* host_out, size_t bytes, int32_t* num_items) {
     if (!host_out || !num_items) return fail(VA_EINVAL, "va_build_worklist: null pointer");
-    if (mask_mode < VA_MASK_CAUSAL || mask_mode > VA_MASK_THREE_BLOCK)
+    if (mask_mode < VA_MASK_CAUSAL || mask_mode > VA_MASK_SLIDING_WINDOW)
         return fail(VA_EUNSUPPORTED, "va_build_worklist: unknown mask mode %d", mask_mode);
     if (mask_mode != VA_MASK_CAUSAL && !prefix_lens)
         return fail(VA_EINVAL, "va_build_worklist: prefix mask needs prefix_lens");
@@ -183,7 +183,7 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
         int32_t P, P2;
         block_ends(prefix_lens, mask_mode, s, &P, &P2);
         if (!block_ends_valid(P, P2, L, mask_mode))
-            return fail(VA_EINVAL, "va_build_worklist: block ends (%d, %d) of sample %d outside [0, %d] or out of order",
+            return fail(VA_EINVAL, "va_build_worklist: block ends (%d, %d) of sample %d outside [0, %d] or out of order, or a window below 1",
                         P, P2, s, L);
         const int32_t Pm = P < 0 ? 0 : P, P2m = P2 < 0 ? 0 : P2;
         if (pass == VA_PASS_BWD_DKDV) {
@@ -191,13 +191,18 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
             const int32_t q_tiles = (L + bn - 1) / bn;
             for (int32_t j0 = 0; j0 < L; j0 += bm) {
                 int32_t first_row;  // first query row that sees key j0
-                if (mask_mode == VA_MASK_CAUSAL) first_row = j0;
+                if (mask_mode == VA_MASK_CAUSAL || mask_mode == VA_MASK_SLIDING_WINDOW) first_row = j0;
                 else if (j0 < Pm) first_row = 0;
                 else if (mask_mode == VA_MASK_PREFIX_LM) first_row = Pm;
                 else if (mask_mode == VA_MASK_THREE_BLOCK) first_row = j0 < P2m ? Pm : P2m;
                 else first_row = j0;
                 const int32_t qt_first = first_row / bn;
-                WorkItem it = {{c + j0, std::min(bm, L - j0), c, qt_first, q_tiles - qt_first, P2, P, L}};
+                int32_t qt_end = q_tiles;  // one past the last query tile with a row that sees a key of the tile
+                if (mask_mode == VA_MASK_SLIDING_WINDOW) {
+                    const int64_t last_row = std::min<int64_t>(L - 1, (int64_t)j0 + std::min(bm, L - j0) - 1 + Pm - 1);
+                    qt_end = (int32_t)(last_row / bn) + 1;
+                }
+                WorkItem it = {{c + j0, std::min(bm, L - j0), c, qt_first, qt_end - qt_first, P2, P, L}};
                 items.push_back({it.w[4], it});
             }
         } else {
@@ -207,7 +212,8 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
                 const int32_t n_tiles = (kv_len + bn - 1) / bn;
                 const int32_t n_full = visible(r0, L, Pm, P2m, mask_mode) / bn;
                 WorkItem it = {{c + r0, rows, c, P2, n_full, n_tiles, P, L}};
-                items.push_back({n_tiles, it});
+                // under the sliding window the key tiles below the first row's window are not visited
+                items.push_back({n_tiles - first_visible(r0, Pm, mask_mode) / bn, it});
             }
         }
     }

@@ -63,7 +63,8 @@ def test_first_fit_random_and_edge_cases():
 HEADS = [(2, 2, 64), (16, 8, 128), (8, 1, 256), (4, 1, 64), (6, 2, 128), (4, 4, 80), (2, 1, 192)]
 
 
-@pytest.mark.parametrize("mode", [va.VA_MASK_CAUSAL, va.VA_MASK_PREFIX_LM, va.VA_MASK_PREFIX_LM_CAUSAL, va.VA_MASK_THREE_BLOCK])
+@pytest.mark.parametrize("mode", [va.VA_MASK_CAUSAL, va.VA_MASK_PREFIX_LM, va.VA_MASK_PREFIX_LM_CAUSAL, va.VA_MASK_THREE_BLOCK,
+                                  va.VA_MASK_SLIDING_WINDOW])
 @pytest.mark.parametrize("Hq,Hkv,D", HEADS)
 def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
     r = np.random.default_rng(Hq * 1000 + D + mode)
@@ -73,6 +74,9 @@ def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
     if mode == va.VA_MASK_THREE_BLOCK:
         prefix = wl.random_block_ends(Hq * 1000 + D, lens)
         prefix[2], prefix[3], prefix[4] = (300, 300), (0, 0), (0, 64)    # one block only, three ways
+    elif mode == va.VA_MASK_SLIDING_WINDOW:
+        prefix = r.integers(1, 200, size=len(lens)).astype(np.int32)
+        prefix[2], prefix[3], prefix[4] = 70, 1, 1000    # a band; self only; wider than the sample
     elif prefix is not None:
         prefix[2], prefix[3] = 300, 0    # degenerate: whole sample is prefix / no prefix at all
     for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DKDV, va.VA_PASS_BWD_DQ):
@@ -88,6 +92,8 @@ def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
         assert table[0, 0] == 0 and np.array_equal(table[1:, 0], np.cumsum(table[:-1, 1])) and table[:, 1].sum() == len(ids)
         # longest-processing-time-first: no workgroup exceeds the mean load by more than the heaviest work
         steps = items[:, 4] * (Hq // Hkv) if pass_id == va.VA_PASS_BWD_DKDV else items[:, 5]
+        if mode == va.VA_MASK_SLIDING_WINDOW and pass_id != va.VA_PASS_BWD_DKDV:   # tiles below the window are not visited
+            steps = items[:, 5] - np.maximum(0, items[:, 0] - items[:, 2] + 1 - items[:, 6]) // cols
         cost = np.repeat(steps, per_item) + 2
         loads = np.array([cost[ids[a:a + n]].sum() for a, n in table])
         assert loads.max() <= cost.sum() / len(table) + cost.max()
@@ -101,6 +107,8 @@ def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
     pre_s = None if mode == va.VA_MASK_CAUSAL else np.array([1, 40, 0, 97], dtype=np.int32)
     if mode == va.VA_MASK_THREE_BLOCK:
         pre_s = np.array([[0, 1], [10, 40], [0, 0], [64, 97]], dtype=np.int32)
+    if mode == va.VA_MASK_SLIDING_WINDOW:
+        pre_s = np.array([3, 40, 1, 65], dtype=np.int32)
     for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DKDV, va.VA_PASS_BWD_DQ):
         rows, cols = va.va_tile_shape(pass_id, D, Hq, Hkv)
         bm, bn = (cols, rows) if pass_id == va.VA_PASS_BWD_DKDV else (rows, cols)
@@ -246,7 +254,7 @@ def test_three_block_ends_are_validated():
     with pytest.raises(ValueError):      # one entry per sample is not enough for this mask
         va.va_build_worklist(cu, np.array([3, 4], dtype=np.int32), va.VA_MASK_THREE_BLOCK, va.VA_PASS_FWD, 64, 2, 2)
     with pytest.raises(va.VarlenAttnError) as e:
-        va.va_build_worklist(cu, np.array([3, 4], dtype=np.int32), 4, va.VA_PASS_FWD, 64, 2, 2)
+        va.va_build_worklist(cu, np.array([3, 4], dtype=np.int32), 5, va.VA_PASS_FWD, 64, 2, 2)
     assert e.value.code == va.VA_EUNSUPPORTED
     # both boundaries land in the items: P in word 6, P2 in word 3 (forward, dQ) or 5 (dK/dV)
     ends = np.array([[2, 7], [20, 20]], dtype=np.int32)
@@ -292,3 +300,17 @@ def test_fp8_entry_points_reject_bad_arguments_on_the_host():
     assert quant(cu_dev=None)[0] == va.VA_EINVAL and quant(x=None)[0] == va.VA_EINVAL
     assert quant(x=buf[8:])[0] == va.VA_EALIGN and quant(codes=buf[4:])[0] == va.VA_EALIGN
     assert quant(cu_=np.array([0, 0, 0], dtype=np.int32), x=None, codes=None, d=None)[0] == va.VA_OK   # nothing to do
+
+
+def test_window_widths_are_validated():
+    cu = np.array([0, 10, 30], dtype=np.int32)
+    for bad in ([0, 5], [4, -1]):
+        with pytest.raises(va.VarlenAttnError) as e:
+            va.va_build_worklist(cu, np.array(bad, dtype=np.int32), va.VA_MASK_SLIDING_WINDOW, va.VA_PASS_FWD, 64, 2, 2)
+        assert e.value.code == va.VA_EINVAL
+    with pytest.raises(va.VarlenAttnError):
+        va.va_build_worklist(cu, None, va.VA_MASK_SLIDING_WINDOW, va.VA_PASS_FWD, 64, 2, 2)
+    # a window as long as the sample lists what the causal mask lists, apart from the W word
+    wide = va.worklist_items(va.va_build_worklist(cu, np.array([10, 99], dtype=np.int32), va.VA_MASK_SLIDING_WINDOW, va.VA_PASS_FWD, 64, 2, 2))
+    causal = va.worklist_items(va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_FWD, 64, 2, 2))
+    assert np.array_equal(np.delete(wide, 6, axis=1), np.delete(causal, 6, axis=1))

@@ -90,6 +90,39 @@ def test_three_block_worklists_cover_every_allowed_pair_exactly_once(bm, bn):
         op.check_coverage(items, cu, wrong, op.PASS_FWD, bm, bn, mode)
 
 
+@pytest.mark.parametrize("bm,bn", [(4, 4), (8, 4), (4, 8), (16, 8)])
+def test_sliding_window_worklists_cover_every_allowed_pair_exactly_once(bm, bn):
+    lens = [1, 13, 0, 8, 21, 4, 30]
+    cu, _, _ = op.bin_layout(lens)
+    W = np.array([1, 5, 3, 8, 1, 100, 11], dtype=np.int32)
+    mode = op.MASK_SLIDING_WINDOW
+    # a band of width W under the diagonal: full rows W, the first W - 1 rows shorter
+    want_pairs = sum(min(L, w) * (min(L, w) + 1) // 2 + max(0, L - w) * w for L, w in zip(lens, W.tolist()))
+    assert want_pairs == sum(op.allowed_pairs(L, w, mode) for L, w in zip(lens, W.tolist()))
+    for pass_id in (op.PASS_FWD, op.PASS_BWD_DKDV, op.PASS_BWD_DQ):
+        items = op.build_worklist(cu, W, pass_id, bm, bn, mode)
+        assert op.check_coverage(items, cu, W, pass_id, bm, bn, mode) == want_pairs
+    # no item visits more tiles than the window can touch: ceil((rows + W - 1) / tile) + 1
+    fwd = op.build_worklist(cu, W, op.PASS_FWD, bm, bn, mode)
+    for q_row0, q_rows, c, _, n_full, n_tiles, w, L in fwd.tolist():
+        first = max(0, q_row0 - c + 1 - w) // bn
+        assert n_tiles - first <= -(-(q_rows + w - 1) // bn) + 1
+    dk = op.build_worklist(cu, W, op.PASS_BWD_DKDV, bm, bn, mode)
+    for kv_row0, kv_rows, c, qt_first, qt_count, _, w, L in dk.tolist():
+        assert qt_first == (kv_row0 - c) // bm and qt_count <= -(-(kv_rows + w - 1) // bm) + 1
+    # planted defects are caught: a window one wider than the lists were built for, and a dropped query tile
+    wrong = W.copy()
+    wrong[4] += 1
+    with pytest.raises(AssertionError):
+        op.check_coverage(fwd, cu, wrong, op.PASS_FWD, bm, bn, mode)
+    broken = dk.copy()
+    row = int(np.argmax(broken[:, 4]))
+    if broken[row, 4] > 1:
+        broken[row, 4] -= 1
+        with pytest.raises(AssertionError):
+            op.check_coverage(broken, cu, W, op.PASS_BWD_DKDV, bm, bn, mode)
+
+
 def test_closed_form_counts_causal():
     # causal: items = sum ceil(L/bm); key tiles of the query tile starting at row r0 with `rows`
     # rows = ceil((r0 + rows) / bn); full tiles = floor((r0 + 1) / bn)
