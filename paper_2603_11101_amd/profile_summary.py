@@ -24,6 +24,10 @@ SHORT = {"fwd_bf16_kernel": "fwd_bf16", "bwd_delta_kernel": "bwd_delta", "bwd_dk
 
 
 def short_name(name):
+    if re.search(r"fwd_fp8_kernel<\d+, true", name):  # second template argument: block-wise scales
+        return "fwd_fp8_blockwise"
+    if "quant_blockwise" in name:
+        return "quant_blockwise"
     for key, val in SHORT.items():
         if key in name:
             return val
