@@ -94,3 +94,40 @@ def test_full_size_fp8_forward():
     for s in range(len(lens)):
         sl = slice(cu[s], cu[s + 1])
         assert rel_l2(got[sl], ref_out[sl]) <= TOL_FP8_REL, f"sample {s}"
+
+
+def test_full_size_fp8_blockwise_forward():
+    # the block-wise scaled path at the size bench.py times it: quantised on the device, codes and
+    # scales bit-identical to the oracle's, attention against the oracle on the dequantised inputs
+    w, lens, cu, pl, mx = bin0("vlm_fp8")
+    T, Hq, Hkv, D = int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim
+    scale = 1.0 / np.sqrt(D)
+    q, k, v, _ = wl.tensor_values(w.seed, T, Hq, Hkv, D, with_dout=False)
+    cu_dev = torch.from_numpy(np.asarray(cu, dtype=np.int32)).to(DEV)
+    dev, deq = [], []
+    print(f"full size fp8, block-wise scales: T={T}", flush=True)
+    for x in (q, k, v):
+        xt = torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).to(DEV)
+        codes = torch.empty(x.shape, dtype=torch.uint8, device=DEV)
+        d_tok = torch.empty(x.shape[:2], dtype=torch.float32, device=DEV)
+        va.va_quantize_e4m3_blockwise_device(xt, cu, cu_dev, codes, d_tok)
+        torch.cuda.synchronize()
+        oc, od = oe.quantize_blockwise(x, cu)
+        assert np.array_equal(codes.cpu().numpy(), oc)
+        starts = oe.block_starts(cu)
+        rows = np.concatenate([int(starts[s]) + np.arange(int(cu[s + 1] - cu[s])) // oe.BLOCK_TOKENS for s in range(len(lens))])
+        assert np.array_equal(d_tok.cpu().numpy(), od[rows])
+        dev.append((codes, d_tok))
+        deq.append(oe.dequantize_blockwise(oc, od, cu).astype(np.float32))
+    ps = va.PackedStream(cu, None, va.VA_MASK_CAUSAL, Hq, Hkv, D, max_seqlen=mx, device=DEV, passes=(va.VA_PASS_FWD,))
+    out = torch.empty((T, Hq, D), dtype=torch.bfloat16, device=DEV)
+    lse = torch.empty((Hq, T), dtype=torch.float32, device=DEV)
+    ps.fwd_fp8_blockwise(dev[0][0], dev[1][0], dev[2][0], dev[0][1], dev[1][1], dev[2][1], scale, out, lse)
+    torch.cuda.synchronize()
+    got, got_lse = from_dev_bf16(out), lse.cpu().numpy().astype(np.float64)
+    ref_out, ref_lse = oa.attn_fwd(deq[0], deq[1], deq[2], cu, None, scale=scale)
+    print(f"  out rel-L2 {rel_l2(got, ref_out):.2e} lse max-abs {max_abs(got_lse, ref_lse):.2e}", flush=True)
+    assert rel_l2(got, ref_out) <= TOL_FP8_REL and max_abs(got_lse, ref_lse) <= TOL_LSE_ABS
+    for s in range(len(lens)):
+        sl = slice(cu[s], cu[s + 1])
+        assert rel_l2(got[sl], ref_out[sl]) <= TOL_FP8_REL, f"sample {s}"
