@@ -155,8 +155,11 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
  * counts the list was built for.  The kernels run num_workgroups persistent
  * workgroups; the table assigns the works to them longest-processing-time
  * first, with a work's cost taken as its inner-loop steps plus a fixed part.
- * Kernels that run one work per workgroup ignore the table and take work ids
- * 0 .. num_works-1 in item order.
+ * Within that, works that read the same rows (the K and V rows of one sample
+ * and KV head in the forward and dQ passes) go to workgroups of one XCD, at
+ * about the same position of their queues, so that the XCD's L2 fetches the
+ * rows once.  Kernels that run one work per workgroup (dK/dV) ignore the table
+ * and take work ids 0 .. num_works-1 in item order.
  * va_worklist_bytes gives the buffer size; va_build_worklist fills a host
  * buffer of at least that size.  The caller copies the buffer to the device
  * unchanged and hands both copies to the device calls, which validate the host

@@ -104,8 +104,12 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
     }
     const int32_t* table = w[lay.table_rec].w;
     const int32_t* ids = w[lay.id_rec].w;
-    for (int32_t i = 0; i < lay.num_works; ++i)
+    std::vector<bool> listed((size_t)lay.num_works, false);
+    for (int32_t i = 0; i < lay.num_works; ++i) {
         if (ids[i] < 0 || ids[i] >= lay.num_works) return fail(VA_EINVAL, "%s: work id %d out of range", who, i);
+        if (listed[ids[i]]) return fail(VA_EINVAL, "%s: work %d is listed twice", who, ids[i]);
+        listed[ids[i]] = true;
+    }
     int32_t at = 0;
     for (int32_t g = 0; g < lay.num_workgroups; ++g) {
         const int32_t* e = table + kTableWordsPerWorkgroup * g;

@@ -65,6 +65,13 @@ constexpr bool dq_computes_delta(int32_t D) { return VA_FUSE_DELTA != 0 && D <= 
 
 // Persistent workgroups launched for a pass: CUs of an MI355X times the workgroups a CU holds.
 constexpr int32_t persistent_workgroups(int32_t /*pass*/, int32_t D) { return D <= 128 ? 512 : 256; }
+// XCDs of an MI355X: workgroup b of a launch runs on XCD b % kXcds, each with its own L2.
+constexpr int32_t kXcds = 8;
+// Whether the forward and dQ schedules keep the works that share K and V rows on one XCD at one time
+// (0: plain longest-processing-time-first over all workgroups).
+#ifndef VA_LOCALITY_SCHEDULE
+#define VA_LOCALITY_SCHEDULE 1
+#endif
 // Cost of a work in units of inner-loop steps: its steps plus a fixed part for the item switch.
 constexpr int32_t kWorkFixedCost = 2;
 

@@ -11,6 +11,8 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <map>
+#include <utility>
 #include <vector>
 
 namespace va {
@@ -226,23 +228,95 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
                lay.total_recs, 0}};
     for (size_t i = 0; i < items.size(); ++i) out[lay.item_rec + i] = items[i].it;
 
-    // Longest-processing-time-first assignment of the works to the persistent workgroups: works in
-    // descending cost order (ties: ascending id), each to the least-loaded workgroup (ties: lowest index).
-    // Items are already sorted by cost and every work of an item costs the same, so id order is cost order.
+    // Assignment of the works to the persistent workgroups.  cost(work) = its inner-loop steps plus a fixed
+    // part; items are sorted by cost and every work of an item costs the same, so id order is cost order.
     const int32_t G = Hq / Hkv;
     const int32_t P = lay.num_workgroups;
     std::vector<int64_t> load((size_t)P, 0);
     std::vector<std::vector<int32_t>> mine((size_t)P);
-    auto heavier = [&](int32_t a, int32_t b) { return load[a] != load[b] ? load[a] > load[b] : a > b; };
-    std::vector<int32_t> heap((size_t)P);
-    for (int32_t w = 0; w < P; ++w) heap[w] = w;  // min-heap on (load, index); all loads 0: already a heap
-    for (int32_t id = 0; id < lay.num_works; ++id) {
-        const int32_t steps = items[id / lay.works_per_item].work * (pass == VA_PASS_BWD_DKDV ? G : 1);
-        std::pop_heap(heap.begin(), heap.end(), heavier);
-        const int32_t w = heap.back();
-        load[w] += steps + kWorkFixedCost;
-        mine[w].push_back(id);
-        std::push_heap(heap.begin(), heap.end(), heavier);
+    auto cost_of = [&](int32_t id) {
+        return (int64_t)items[id / lay.works_per_item].work * (pass == VA_PASS_BWD_DKDV ? G : 1) + kWorkFixedCost;
+    };
+    // Where every query tile of a sample costs the same (no causal structure: whole samples visible), the
+    // plain order below already walks the tiles of a sample one after the other, i.e. is local by itself.
+    bool tiles_differ = false;
+    {
+        std::map<int32_t, int32_t> cost_of_sample;  // first row of the sample -> cost of the first of its items seen
+        for (const Keyed& k : items) {
+            const auto at = cost_of_sample.emplace(k.it.w[2], k.work).first;
+            tiles_differ = tiles_differ || at->second != k.work;
+        }
+    }
+    if (VA_LOCALITY_SCHEDULE != 0 && tiles_differ && pass != VA_PASS_BWD_DKDV && P % kXcds == 0) {
+        // Forward and dQ: all works of one (sample, KV head) stream the same K and V rows.  Workgroup b runs
+        // on XCD b % 8, and each XCD has an L2 of its own, so those works are given to workgroups of one XCD
+        // and placed at about the same position of their queues: they then run at about the same time and
+        // the rows are fetched into that L2 once instead of once per work.  Groups go to the XCDs, and
+        // the works of a group to the workgroups of its XCD, longest processing time first; groups heavier
+        // than a sixteenth of an XCD's share are cut into runs of consecutive query tiles first, so that
+        // few heavy groups (one KV head, long samples) still balance.
+        struct Group {
+            int64_t cost = 0;
+            std::vector<int32_t> works;
+        };
+        const int32_t chunks_per_head = lay.works_per_item / Hkv;  // head chunks that share one KV head
+        int64_t total = 0;
+        for (int32_t id = 0; id < lay.num_works; ++id) total += cost_of(id);
+        const int64_t cap = std::max<int64_t>(1, total / (kXcds * 16));
+        std::vector<Group> groups;
+        {
+            std::map<std::pair<int32_t, int32_t>, int32_t> open;  // (sample's first row, KV head) -> its current group
+            for (int32_t id = 0; id < lay.num_works; ++id) {
+                const int32_t g = (id % lay.works_per_item) / chunks_per_head;
+                const std::pair<int32_t, int32_t> key(items[id / lay.works_per_item].it.w[2], g);
+                auto at = open.find(key);
+                if (at == open.end() || groups[at->second].cost + cost_of(id) > cap) {
+                    open[key] = (int32_t)groups.size();
+                    groups.emplace_back();
+                    at = open.find(key);
+                }
+                groups[at->second].cost += cost_of(id);
+                groups[at->second].works.push_back(id);
+            }
+        }
+        std::vector<int32_t> order(groups.size());
+        for (size_t i = 0; i < order.size(); ++i) order[i] = (int32_t)i;
+        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return groups[a].cost > groups[b].cost; });
+        int64_t xcd_load[kXcds] = {};
+        std::vector<int32_t> of_xcd[kXcds];
+        for (int32_t gi : order) {
+            int32_t x = 0;
+            for (int32_t c = 1; c < kXcds; ++c)
+                if (xcd_load[c] < xcd_load[x]) x = c;
+            xcd_load[x] += groups[gi].cost;
+            of_xcd[x].push_back(gi);
+        }
+        auto heavier = [&](int32_t a, int32_t b) { return load[a] != load[b] ? load[a] > load[b] : a > b; };
+        for (int32_t x = 0; x < kXcds; ++x) {
+            std::vector<int32_t> heap;  // min-heap on (load, index) over the workgroups of this XCD
+            for (int32_t w = x; w < P; w += kXcds) heap.push_back(w);
+            for (int32_t gi : of_xcd[x])
+                for (int32_t id : groups[gi].works) {
+                    std::pop_heap(heap.begin(), heap.end(), heavier);
+                    const int32_t w = heap.back();
+                    load[w] += cost_of(id);
+                    mine[w].push_back(id);
+                    std::push_heap(heap.begin(), heap.end(), heavier);
+                }
+        }
+    } else {
+        // Longest processing time first: works in descending cost order (ties: ascending id), each to the
+        // least-loaded workgroup (ties: lowest index).
+        auto heavier = [&](int32_t a, int32_t b) { return load[a] != load[b] ? load[a] > load[b] : a > b; };
+        std::vector<int32_t> heap((size_t)P);
+        for (int32_t w = 0; w < P; ++w) heap[w] = w;  // min-heap on (load, index); all loads 0: already a heap
+        for (int32_t id = 0; id < lay.num_works; ++id) {
+            std::pop_heap(heap.begin(), heap.end(), heavier);
+            const int32_t w = heap.back();
+            load[w] += cost_of(id);
+            mine[w].push_back(id);
+            std::push_heap(heap.begin(), heap.end(), heavier);
+        }
     }
     int32_t* table = out[lay.table_rec].w;
     int32_t* ids = out[lay.id_rec].w;

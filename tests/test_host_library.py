@@ -314,3 +314,33 @@ def test_window_widths_are_validated():
     wide = va.worklist_items(va.va_build_worklist(cu, np.array([10, 99], dtype=np.int32), va.VA_MASK_SLIDING_WINDOW, va.VA_PASS_FWD, 64, 2, 2))
     causal = va.worklist_items(va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_FWD, 64, 2, 2))
     assert np.array_equal(np.delete(wide, 6, axis=1), np.delete(causal, 6, axis=1))
+
+
+def test_forward_schedule_keeps_the_works_of_a_sample_and_kv_head_on_one_xcd():
+    # causal stream: workgroup b runs on XCD b % 8; the works that stream the same K and V rows should
+    # share an XCD (groups heavier than a sixteenth of an XCD's share may be cut), and stay balanced
+    r = np.random.default_rng(5)
+    lens = r.integers(200, 900, size=40).astype(np.int32)
+    cu, _, _ = va.va_bin_layout(lens)
+    Hq, Hkv, D = 16, 8, 128
+    for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DQ):
+        got = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, pass_id, D, Hq, Hkv)
+        items = va.worklist_items(got)
+        table, ids = va.worklist_schedule(got)
+        per_item = int(got[1, 2])
+        chunks_per_head = per_item // Hkv
+        xcds = {}
+        for b, (first, count) in enumerate(table.tolist()):
+            for wid in ids[first:first + count].tolist():
+                key = (int(items[wid // per_item, 2]), (wid % per_item) // chunks_per_head)
+                xcds.setdefault(key, set()).add(b % 8)
+        assert len(xcds) == len(lens) * Hkv
+        assert sum(len(v) == 1 for v in xcds.values()) >= 0.9 * len(xcds)
+        cost = np.repeat(items[:, 5], per_item) + 2
+        loads = np.array([cost[ids[a:a + n]].sum() for a, n in table])
+        assert loads.max() <= 1.1 * cost.sum() / len(table) + cost.max()
+    # whole samples visible to every row: every query tile of a sample costs the same and the plain
+    # heaviest-first order is used, which hands consecutive works to consecutive workgroups
+    full = va.va_build_worklist(cu, lens, va.VA_MASK_PREFIX_LM, va.VA_PASS_FWD, D, Hq, Hkv)
+    table, ids = va.worklist_schedule(full)
+    assert ids[table[0, 0]] == 0 and ids[table[1, 0]] == 1 and ids[table[7, 0]] == 7
