@@ -43,7 +43,6 @@
  *                                     lo(i) = max(0, i + 1 - W) instead of 0
  *     (causal, at most the W most recent keys, the row's own included), with
  *     W = prefix_lens[s] >= 1 per sample; a W of L or more is the causal mask.
- *     Available at head_dim 64, 128 and 256 (VA_EUNSUPPORTED otherwise).
  *   - LSE[h, r] = ln sum_j exp(scale * q_r . k_j) over the visible keys
  *     (natural logarithm, scale included).
  */

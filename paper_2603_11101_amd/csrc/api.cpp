@@ -25,8 +25,6 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
                     s->num_q_heads, s->num_kv_heads);
     if (s->mask_mode < VA_MASK_CAUSAL || s->mask_mode > VA_MASK_SLIDING_WINDOW)
         return fail(VA_EUNSUPPORTED, "%s: unknown mask mode %d", who, s->mask_mode);
-    if (s->mask_mode == VA_MASK_SLIDING_WINDOW && s->head_dim != 64 && s->head_dim != 128 && s->head_dim != 256)
-        return fail(VA_EUNSUPPORTED, "%s: the sliding-window mask exists for head_dim 64, 128 and 256, not %d", who, s->head_dim);
     if (s->num_seqs < 0 || s->total_tokens < 0) return fail(VA_EINVAL, "%s: negative sizes", who);
     if (cu[0] != 0) return fail(VA_EINVAL, "%s: cu_seqlens[0] = %d, expected 0", who, cu[0]);
     for (int32_t i = 0; i < s->num_seqs; ++i) {

@@ -701,9 +701,7 @@ hipError_t launch_dq_dhw(const AttnParams& p, hipStream_t stream, unsigned grid)
 template <int D, int HPB, int DR>
 hipError_t launch_dq_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
     if (p.mask_mode != VA_MASK_SLIDING_WINDOW) return launch_dq_dhw<D, HPB, DR, false>(p, stream, grid);
-    // the window instantiations exist for the full-width geometries only
-    if constexpr (DR == D) return launch_dq_dhw<D, HPB, DR, true>(p, stream, grid);
-    return hipErrorNotSupported;
+    return launch_dq_dhw<D, HPB, DR, true>(p, stream, grid);
 }
 
 template <int D, int DR = D>
@@ -739,9 +737,7 @@ hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     if (p.mask_mode == VA_MASK_THREE_BLOCK) {
         e = launch(std::integral_constant<int, 1>{});
     } else if (p.mask_mode == VA_MASK_SLIDING_WINDOW) {
-        // the window instantiations exist for the full-width geometries only
-        if constexpr (DR == D) e = launch(std::integral_constant<int, 2>{});
-        else e = hipErrorNotSupported;
+        e = launch(std::integral_constant<int, 2>{});
     } else {
         e = launch(std::integral_constant<int, 0>{});
     }

@@ -316,9 +316,7 @@ hipError_t launch_dhw(const AttnParams& p, hipStream_t stream, unsigned grid) {
 template <int D, int HPB, int DR>
 hipError_t launch_dh(const AttnParams& p, hipStream_t stream, unsigned grid) {
     if (p.mask_mode != VA_MASK_SLIDING_WINDOW) return launch_dhw<D, HPB, DR, false>(p, stream, grid);
-    // the window instantiations exist for the full-width geometries only
-    if constexpr (DR == D) return launch_dhw<D, HPB, DR, true>(p, stream, grid);
-    return hipErrorNotSupported;
+    return launch_dhw<D, HPB, DR, true>(p, stream, grid);
 }
 
 template <int D, int DR = D>
