@@ -131,3 +131,42 @@ def test_full_size_fp8_blockwise_forward():
     for s in range(len(lens)):
         sl = slice(cu[s], cu[s + 1])
         assert rel_l2(got[sl], ref_out[sl]) <= TOL_FP8_REL, f"sample {s}"
+
+
+@pytest.mark.parametrize("window", [None, 1000])
+def test_one_long_sample_on_sampled_rows(window):
+    # one sample of 16 384 tokens: 256 key tiles per query tile, 128 dK/dV works of up to 512 query tiles
+    # each, far beyond what the workloads reach; the oracle evaluates chosen rows one by one
+    from oracle import sampled
+    L, Hq, Hkv, D = 16384, 2, 1, 64
+    cu = np.array([0, L], dtype=np.int32)
+    q, k, v, do = wl.tensor_values(77, L, Hq, Hkv, D)
+    scale = 1.0 / np.sqrt(D)
+    mode = va.VA_MASK_CAUSAL if window is None else va.VA_MASK_SLIDING_WINDOW
+    pl = None if window is None else np.array([window], dtype=np.int32)
+    print(f"one long sample L={L} window={window}", flush=True)
+    run = DeviceRun(cu, pl, mode, q, k, v, do, scale, max_seqlen=L)
+    assert np.isfinite(run.out).all() and np.isfinite(run.lse).all()
+    assert np.isfinite(run.dq).all() and np.isfinite(run.dk).all() and np.isfinite(run.dv).all()
+    rows = [0, 1, 63, 64, 127, 128, 999, 1000, 1001, 4095, 4096, 9999, L - 129, L - 2, L - 1]
+    worst = {"out": 0.0, "lse": 0.0, "dq": 0.0}
+    for i in rows:
+        for h in range(Hq):
+            o_i, lse_i = sampled.row_forward(q, k, v, scale, i, h, window)
+            dq_i = sampled.row_dq(q, k, v, do, scale, i, h, window)
+            worst["out"] = max(worst["out"], max_abs(run.out[i, h], o_i))
+            worst["lse"] = max(worst["lse"], abs(run.lse[h, i] - lse_i))
+            worst["dq"] = max(worst["dq"], rel_l2(run.dq[i, h], dq_i))
+            assert max_abs(run.out[i, h], o_i) <= TOL_FWD_ABS and abs(run.lse[h, i] - lse_i) <= TOL_LSE_ABS, (i, h)
+            if i > 0:     # row 0 sees itself only: dQ = 0, no relative error
+                assert rel_l2(run.dq[i, h], dq_i) <= TOL_GRAD_REL, (i, h)
+    keys = [L - 1, L - 130, L - 2000] if window is None else [0, 64, 5000, L - 1000, L - 1]
+    for j in keys:
+        dk_j, dv_j = sampled.key_row_dk_dv(q, k, v, do, scale, j, 0, window)
+        worst["dk"] = max(worst.get("dk", 0.0), rel_l2(run.dk[j, 0], dk_j))
+        worst["dv"] = max(worst.get("dv", 0.0), rel_l2(run.dv[j, 0], dv_j))
+        assert rel_l2(run.dv[j, 0], dv_j) <= TOL_GRAD_REL, j
+        if j < L - 1 or window is None:
+            assert rel_l2(run.dk[j, 0], dk_j) <= TOL_GRAD_REL, j
+    print("  worst: " + " ".join(f"{n} {x:.2e}" for n, x in worst.items()), flush=True)
+    assert run.tail_untouched("out", "dq", "dk", "dv")

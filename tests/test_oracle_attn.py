@@ -417,3 +417,24 @@ def test_sliding_window_special_cases():
                 want_lse = 0.5 * float(q[cu[s] + i, h].astype(np.float64) @ k1[0, 0].astype(np.float64)) + np.log(n)
                 assert abs(lse[h, cu[s] + i] - want_lse) < 1e-12
                 assert np.allclose(out[cu[s] + i, h], want_o, rtol=1e-13, atol=1e-14)
+
+
+def test_row_by_row_functions_equal_the_oracle():
+    # oracle/sampled.py evaluates chosen rows of one long sample; on a short one it must give what the
+    # C oracle gives for whole samples
+    from oracle import sampled
+    Hq, Hkv, D, L = 4, 2, 8, 70
+    cu, _, q, k, v, do = stream(31, [L], Hq, Hkv, D)
+    scale = 0.3
+    for window, mode, pl in ((None, oa.MASK_CAUSAL, None), (9, oa.MASK_SLIDING_WINDOW, np.array([9], dtype=np.int32))):
+        out, lse = oa.attn_fwd(q, k, v, cu, pl, scale=scale, mask_mode=mode)
+        dq, dk, dv = oa.attn_bwd(q, k, v, do, cu, pl, scale=scale, mask_mode=mode)
+        for i in (0, 1, 8, 9, 33, 69):
+            for h in range(Hq):
+                o_i, lse_i = sampled.row_forward(q, k, v, scale, i, h, window)
+                assert np.allclose(o_i, out[i, h], rtol=1e-12, atol=1e-14) and abs(lse_i - lse[h, i]) < 1e-12
+                assert np.allclose(sampled.row_dq(q, k, v, do, scale, i, h, window), dq[i, h], rtol=1e-11, atol=1e-13)
+        for j in (0, 5, 40, 69):
+            for g in range(Hkv):
+                dk_j, dv_j = sampled.key_row_dk_dv(q, k, v, do, scale, j, g, window)
+                assert np.allclose(dk_j, dk[j, g], rtol=1e-11, atol=1e-13) and np.allclose(dv_j, dv[j, g], rtol=1e-11, atol=1e-13)
