@@ -130,8 +130,11 @@ def main():
     flops_fwd = 4.0 * D * Hq * pairs
     flops_bwd = 10.0 * D * Hq * pairs
 
+    torch.zeros(1, device=dev)  # first touch of the device (context, allocator) is not part of the plan
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ps = va.PackedStream(cu, pl, mask, Hq, Hkv, D, max_seqlen=mx, device=dev)
+    ps = va.PackedStream(cu, pl, mask, Hq, Hkv, D, max_seqlen=mx, device=dev)  # three work lists, built and uploaded
+    torch.cuda.synchronize()
     host_plan_ms = (time.perf_counter() - t0) * 1e3
 
     def dev_bf16(x):
