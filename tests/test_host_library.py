@@ -344,3 +344,12 @@ def test_forward_schedule_keeps_the_works_of_a_sample_and_kv_head_on_one_xcd():
     full = va.va_build_worklist(cu, lens, va.VA_MASK_PREFIX_LM, va.VA_PASS_FWD, D, Hq, Hkv)
     table, ids = va.worklist_schedule(full)
     assert ids[table[0, 0]] == 0 and ids[table[1, 0]] == 1 and ids[table[7, 0]] == 7
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the benchmark is a one-GPU program: asking for more must end with a message, before any device is touched
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
