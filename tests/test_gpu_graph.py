@@ -60,3 +60,59 @@ def test_forward_and_backward_replay_from_a_graph():
         torch.cuda.synchronize()
         for name, got, want in zip(("out", "lse", "dq", "dk", "dv"), outputs, eager[i]):
             assert torch.equal(got, want), f"replay of input set {i}: {name} differs from the eager run"
+
+
+def test_blockwise_fp8_quantise_and_forward_replay_from_a_graph():
+    # the block-wise quantiser (one kernel per tensor, block search on the device) and the FP8 forward that
+    # reads its per-token-row scales: captured together, replayed on changing inputs, against eager runs
+    Hq, Hkv, D = 4, 2, 128
+    lens = [70, 129, 40, 300, 1]
+    scale = 1.0 / np.sqrt(D)
+    print("graph capture and replay, block-wise FP8", flush=True)
+    sets = []
+    for seed in (31, 32, 33):
+        cu, _, q, k, v, _ = wl.random_stream(seed, lens, Hq, Hkv, D)
+        sets.append([to_dev_bf16(x) for x in (q, k, v)])
+    T = int(cu[-1])
+    ps = va.PackedStream(cu, None, va.VA_MASK_CAUSAL, Hq, Hkv, D, device=DEV, passes=(va.VA_PASS_FWD,))
+    cu_dev = torch.from_numpy(np.asarray(cu, dtype=np.int32)).to(DEV)
+    q, k, v = (torch.empty_like(x) for x in sets[0])
+    codes = [torch.empty(x.shape, dtype=torch.uint8, device=DEV) for x in (q, k, v)]
+    scales = [torch.empty(x.shape[:2], dtype=torch.float32, device=DEV) for x in (q, k, v)]
+    out = torch.empty((T, Hq, D), dtype=torch.bfloat16, device=DEV)
+    lse = torch.empty((Hq, T), dtype=torch.float32, device=DEV)
+    outputs = (out, lse, *codes, *scales)
+
+    def load(i):
+        for dst, src in zip((q, k, v), sets[i]):
+            dst.copy_(src)
+        for t in (out, lse, *scales):
+            t.fill_(7.0)
+        for t in codes:
+            t.fill_(0x55)
+
+    def step():
+        for x, c, s in zip((q, k, v), codes, scales):
+            va.va_quantize_e4m3_blockwise_device(x, cu, cu_dev, c, s)
+        ps.fwd_fp8_blockwise(codes[0], codes[1], codes[2], scales[0], scales[1], scales[2], scale, out, lse)
+
+    eager = []
+    for i in range(len(sets)):
+        load(i)
+        step()
+        torch.cuda.synchronize()
+        eager.append([t.clone() for t in outputs])
+    assert not torch.equal(eager[0][0], eager[1][0])
+
+    graph = torch.cuda.CUDAGraph()
+    load(0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        step()
+    for i in (2, 0, 1, 2, 2):
+        load(i)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, (got, want) in enumerate(zip(outputs, eager[i])):
+            assert torch.equal(got, want), f"replay of input set {i}: output {n} differs from the eager run"
