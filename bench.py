@@ -1,20 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark of the packed variable-length attention hot path on one MI355X.
 
-One step = forward + backward (dQ and dK/dV kernels, and a delta pass where the dQ kernel does not
-compute delta itself) of one packed batch:
-the first first-fit bin of the `vlm` workload (causal VLM-backbone layer,
-16 query / 8 KV heads, head_dim 128, 16384-token budget), synthetic N(0,1)
-bf16 inputs resident in HBM before the timed region.  Buffers rotate over
-several independent sets so the inputs of a step are not cache-resident from
-the step before.
+One step = forward + backward (dQ and dK/dV kernels, plus the delta pass where the dQ kernel does not
+compute delta itself) of one packed batch, synthetic N(0,1) bf16 inputs resident in HBM before the
+timed region.  The headline workload is `longtail` (the largest single-GPU configuration: 65 536-token
+budget, heavy-tailed lengths, 16 query / 8 KV heads, head_dim 128, causal), bin 0 of its first-fit packing.
+Buffers rotate over several independent sets ("cold": the inputs of a step are not cache-resident from
+the step before); the same-buffer ("warm") time and the time of a captured-graph replay are reported next
+to it, and so is the mean over the first 8 bins.
 
-Prints ONE JSON line: the metric (useful TFLOP/s: 14 * D * Hq * allowed (q, k)
-pairs per step), tokens/s, a roofline object for the dominant kernel (measured
-live with HIP events on the launch stream) and the CPU oracle's throughput on a
-bounded sample of the same workload.
+Prints ONE JSON line: the metric (useful TFLOP/s: 14 * D * Hq * allowed (q, k) pairs per step), tokens/s,
+per-kernel durations (HIP events around trains of launches of one kernel on the launch stream), a roofline
+object for the dominant kernel against the roof that binds it, the same fields for the other configurations
+(`configs`: vlm, pi05, the FP8 forward on the vlm shapes, and the latency of the tiny configuration), and the
+CPU oracle's throughput on a bounded sample of the headline workload.
+
+Other modes:
+  --profile-leg        only the steps of --workload (plus FP8 forward launches at head_dim 128 and, with
+                       --copy-calibration, three 256 MiB device copies): the program rocprofv3 runs
+  --sweep              packed against padded fixed-length batches (the paper's section 3.2.1 sweep)
 """
 import argparse
+import hashlib
+import glob
 import json
 import os
 import sys
@@ -27,9 +35,12 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
-WORKLOAD = "vlm"
+PEAK_FP8_TFLOPS = 5000.0
+HEADLINE = "longtail"
+OTHER_CONFIGS = ("vlm", "pi05")
 NUM_BUFFER_SETS = 4
 COPY_CALIBRATION_BYTES = 256 << 20
+CLOCK_RAMP_MS = 100.0         # untimed work before the warm-up steps, so that a short run sees the clocks a long one sees
 
 
 def allowed_pairs(lens, prefix):
@@ -62,53 +73,461 @@ def build_bin(name, va, wl, which=0):
     return w, lens[idx], (None if prefix is None else prefix[idx]), cu, pl, mx
 
 
-def build_bin0(name, va, wl):
-    return build_bin(name, va, wl, 0)
+def source_digest():
+    """Digest of the kernel and host sources: profiles/ files carry the one they were measured with."""
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2603_11101_amd", "csrc", "*"))):
+        if path.endswith((".hip", ".cpp", ".h")):
+            h.update(os.path.basename(path).encode())
+            h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
 
 
-def cpu_baseline(name, va, wl, budget_s=12.0, max_s=30.0):
-    """The oracle as it stands, on the host cores: forward + backward of whole bins of the same workload,
-    bin 0 first, until about `budget_s` seconds of CPU work are done (a bin is only started if the rate
-    so far says it ends before `max_s`)."""
+class Case:
+    """One packed batch on the device: work lists, `n_sets` independent buffer sets, algorithmic work."""
+
+    def __init__(self, name, va, wl, torch, which=0, n_sets=NUM_BUFFER_SETS, host_values=True, dev="cuda:0"):
+        self.name, self.va, self.torch = name, va, torch
+        self.w, self.lens, self.prefix, self.cu, self.pl, self.mx = build_bin(name, va, wl, which)
+        w = self.w
+        self.T, self.Hq, self.Hkv, self.D = int(self.cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim
+        T, Hq, Hkv, D = self.T, self.Hq, self.Hkv, self.D
+        self.mask = mask_modes(w, va)[0]
+        self.scale = 1.0 / float(np.sqrt(D))
+        self.pairs = allowed_pairs(self.lens, self.prefix)
+        self.flops_fwd = 4.0 * D * Hq * self.pairs
+        self.flops_bwd = 10.0 * D * Hq * self.pairs
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.ps = va.PackedStream(self.cu, self.pl, self.mask, Hq, Hkv, D, max_seqlen=self.mx, device=dev)
+        torch.cuda.synchronize()
+        self.host_plan_ms = (time.perf_counter() - t0) * 1e3   # three work lists, built and uploaded
+        if host_values:
+            self.host = wl.tensor_values(w.seed, T, Hq, Hkv, D)     # q, k, v, do as float32 holding bf16 values
+            first = [torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).to(dev) for x in self.host]
+        else:
+            g = torch.Generator(device=dev)
+            g.manual_seed(1000 * which + w.seed)
+            first = [torch.randn(shape, device=dev, generator=g).to(torch.bfloat16)
+                     for shape in ((T, Hq, D), (T, Hkv, D), (T, Hkv, D), (T, Hq, D))]
+        self.sets = []
+        for i in range(n_sets):
+            q, k, v, do = first if i == 0 else [x.clone() for x in first]
+            s = {"q": q, "k": k, "v": v, "do": do, "out": torch.empty_like(q),
+                 "lse": torch.empty((Hq, T), dtype=torch.float32, device=dev),
+                 "dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v)}
+            self.sets.append(s)
+        self.ps.workspace()
+        self.fused = not va.va_bwd_has_delta_kernel(D)
+
+    # -- launches
+    def fwd(self, i=0):
+        s = self.sets[i % len(self.sets)]
+        self.ps.fwd(s["q"], s["k"], s["v"], self.scale, s["out"], s["lse"])
+
+    def bwd(self, i=0, stages=None):
+        s = self.sets[i % len(self.sets)]
+        if stages is None:
+            self.ps.bwd(s["q"], s["k"], s["v"], s["out"], s["lse"], s["do"], self.scale, s["dq"], s["dk"], s["dv"])
+        else:
+            self.ps.bwd_stages(s["q"], s["k"], s["v"], s["out"], s["lse"], s["do"], self.scale, s["dq"], s["dk"], s["dv"],
+                               stages)
+
+    def step(self, i=0):
+        self.fwd(i)
+        self.bwd(i)
+
+    # -- timing
+    def clock_ramp(self, ms=CLOCK_RAMP_MS):
+        torch = self.torch
+        t0 = time.perf_counter()
+        i = 0
+        while (time.perf_counter() - t0) * 1e3 < ms:
+            for _ in range(4):
+                self.step(i)
+                i += 1
+            torch.cuda.synchronize()
+
+    def time_steps(self, steps, warmup, rotate=True):
+        """milliseconds per step over exactly `steps` steps, wall clock between two device synchronisations"""
+        torch = self.torch
+        for i in range(warmup):
+            self.step(i if rotate else 0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(i if rotate else 0)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    def time_graph(self, steps):
+        """one step captured into a graph, replayed `steps` times back to back"""
+        torch = self.torch
+        g = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            self.step(0)
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    def time_train(self, launch, iters):
+        """average milliseconds per launch: a warm-up train, then three trains between events with no wait in
+        between (the stream stays busy and the clocks stay up from the first event to the last); median"""
+        torch = self.torch
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for i in range(iters):
+            launch(i)
+        evs[0].record()
+        for blk in range(3):
+            for i in range(iters):
+                launch(i)
+            evs[blk + 1].record()
+        evs[3].synchronize()
+        return float(np.median([evs[b].elapsed_time(evs[b + 1]) / iters for b in range(3)]))
+
+    def kernels(self, iters):
+        """{kernel: {ms, flops, bytes}}: algorithmic work per launch.  Forward 2 products; dK/dV kernel 4 (scores,
+        dP, dV, dK); dQ kernel 1 (dQ; its recomputation of the scores and dP is overhead and is not counted).
+        Bytes: every input read once, every output written once."""
+        va = self.va
+        T, Hq, Hkv, D, pairs = self.T, self.Hq, self.Hkv, self.D, self.pairs
+        self.step(0)  # the workspace holds delta and the rescaled LSE of every set the dK/dV train reads
+        for i in range(1, len(self.sets)):
+            self.step(i)
+        self.time_train(self.fwd, iters)  # the first train of one kernel after the mixed loop runs slow: not taken
+        k = {"fwd_bf16": {"ms": self.time_train(self.fwd, iters), "flops": self.flops_fwd,
+                          "bytes": 2.0 * T * D * (2 * Hq + 2 * Hkv) + 4.0 * T * Hq}}
+        k["bwd_dq"] = {"ms": self.time_train(lambda i: self.bwd(i, va.VA_BWD_STAGE_DQ), iters),
+                       "flops": 2.0 * D * Hq * pairs,
+                       "bytes": (2.0 * T * D * (4 * Hq + 2 * Hkv) + 12.0 * T * Hq if self.fused
+                                 else 2.0 * T * D * (3 * Hq + 2 * Hkv) + 8.0 * T * Hq)}
+        # one workspace serves all buffer sets; they hold the same values, so the delta and rescaled LSE the dQ
+        # train left there are those of every set
+        k["bwd_dkdv"] = {"ms": self.time_train(lambda i: self.bwd(i, va.VA_BWD_STAGE_DKDV), iters),
+                         "flops": 8.0 * D * Hq * pairs,
+                         "bytes": 2.0 * T * D * (2 * Hq + 4 * Hkv) + 8.0 * T * Hq}
+        if not self.fused:
+            k["bwd_delta"] = {"ms": self.time_train(lambda i: self.bwd(i, va.VA_BWD_STAGE_DELTA), iters),
+                              "flops": 2.0 * T * Hq * D, "bytes": 4.0 * T * D * Hq + 12.0 * T * Hq}
+        return k
+
+
+def load_profile_json(kind, workload):
+    path = os.path.join(ROOT, "profiles", f"{kind}_{workload}.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        return json.load(f)
+
+
+def roofline_of(kernels, workload, peak_tflops=PEAK_BF16_TFLOPS):
+    """The dominant kernel against the roof that binds it: the larger of flops / peak and bytes / 8 TB/s."""
+    dominant = max((n for n in kernels if n != "bwd_delta"), key=lambda n: kernels[n]["ms"])
+    kd = kernels[dominant]
+    sec = kd["ms"] * 1e-3
+    t_mfma, t_hbm = kd["flops"] / (peak_tflops * 1e12), kd["bytes"] / (PEAK_HBM_GBPS * 1e9)
+    mfma = {"achieved": kd["flops"] / sec / 1e12, "peak": peak_tflops, "unit": "TFLOP/s"}
+    hbm = {"achieved": kd["bytes"] / sec / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s"}
+    for r in (mfma, hbm):
+        r["frac"] = r["achieved"] / r["peak"]
+    traffic = load_profile_json("hbm_traffic", workload)
+    stale = None if traffic is None else traffic.get("source_digest") != source_digest()
+    t = None if traffic is None else traffic.get(dominant)
+    main, other, bound = (mfma, hbm, "mfma") if t_mfma >= t_hbm else (hbm, mfma, "hbm")
+    return {"bound": bound, "kernel": dominant, **main, "traffic": t,
+            "traffic_over_algorithmic": None if t is None else t / kd["bytes"],
+            "traffic_source": None if traffic is None else f"profiles/hbm_traffic_{workload}.json"
+                              + (" (measured on other sources than this build)" if stale else ""),
+            "algorithmic_bytes": kd["bytes"], "algorithmic_flops": kd["flops"],
+            "floor_us": {"mfma": t_mfma * 1e6, "hbm": t_hbm * 1e6},
+            "other_roof": {"bound": "hbm" if bound == "mfma" else "mfma", **other}}
+
+
+def measure(case, steps, warmup, iters, full=True):
+    """The fields of one configuration."""
+    case.clock_ramp()
+    ms = case.time_steps(steps, warmup, rotate=True)
+    flops = case.flops_fwd + case.flops_bwd
+    w = case.w
+    r = {"workload": f"{case.name}: bin 0 of the first-fit packing, {len(case.lens)} samples, {case.T} tokens, "
+                     f"{case.Hq} q heads / {case.Hkv} kv heads, head_dim {case.D}, "
+                     f"{'three-block' if w.three_block else 'prefix-LM' if w.prefix_lm else 'causal'}, budget {w.budget}",
+         "tokens": case.T, "samples": int(len(case.lens)), "pairs_per_head": case.pairs,
+         "ms_per_step": ms, "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+         "tokens_per_s": case.T / (ms * 1e-3), "mfma_util_useful": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+         "host_plan_ms": case.host_plan_ms}
+    if full:
+        warm = case.time_steps(steps, min(warmup, 5), rotate=False)
+        r["ms_per_step_warm"] = warm
+        r["value_warm"] = flops / (warm * 1e-3) / 1e12
+        gms = case.time_graph(steps)
+        r["ms_per_step_graph"] = gms
+        r["value_graph"] = flops / (gms * 1e-3) / 1e12
+    k = case.kernels(iters)
+    r["kernels_ms"] = {n: k[n]["ms"] for n in k}
+    r["kernels_tflops"] = {n: k[n]["flops"] / (k[n]["ms"] * 1e-3) / 1e12 for n in k}
+    r["kernels_gbps"] = {n: k[n]["bytes"] / (k[n]["ms"] * 1e-3) / 1e9 for n in k}
+    r["roofline"] = roofline_of(k, case.name)
+    # whole step against the floors of section "measurement": every tensor once, every counted product once
+    step_bytes = (2.0 * case.T * case.D * (2 * case.Hq + 2 * case.Hkv) + 4.0 * case.T * case.Hq
+                  + 2.0 * case.T * case.D * (4 * case.Hq + 4 * case.Hkv) + 12.0 * case.T * case.Hq)
+    floor_us = max(flops / (PEAK_BF16_TFLOPS * 1e12), step_bytes / (PEAK_HBM_GBPS * 1e9)) * 1e6
+    r["step_floor_us"] = floor_us
+    r["step_frac_of_floor"] = floor_us / (ms * 1e3)
+    pmc = load_profile_json("pmc", case.name)
+    if pmc is not None:
+        r["rocprof_counters"] = {"file": f"profiles/pmc_{case.name}.json",
+                                 "stale": pmc.get("source_digest") != source_digest(),
+                                 **{n: pmc[n] for n in pmc if n != "source_digest"}}
+    return r
+
+
+def fp8_forward(case, iters):
+    """FP8 (E4M3) forward on the batch of `case` (head_dim 128): per-head quantisation on the device, then
+    trains of launches between events; the same with block-wise scales, and the quantiser itself."""
+    torch, va, ps = case.torch, case.va, case.ps
+    s0, scale, dev = case.sets[0], case.scale, case.sets[0]["q"].device
+    codes = {}
+    for name in ("q", "k", "v"):
+        c8 = torch.empty(s0[name].shape, dtype=torch.uint8, device=dev)
+        descale = torch.empty((s0[name].shape[1],), dtype=torch.float32, device=dev)
+        va.va_quantize_e4m3_per_head_device(s0[name], c8, descale)
+        codes[name] = (c8, descale)
+
+    def fwd(_):
+        ps.fwd_fp8(codes["q"][0], codes["k"][0], codes["v"][0], codes["q"][1], codes["k"][1], codes["v"][1],
+                   scale, s0["out"], s0["lse"])
+
+    for _ in range(3):
+        fwd(0)
+    ms = case.time_train(fwd, iters)
+    T, Hq, Hkv, D = case.T, case.Hq, case.Hkv, case.D
+    k = {"fwd_fp8": {"ms": ms, "flops": case.flops_fwd, "bytes": 1.0 * T * D * (Hq + 2 * Hkv) + 2.0 * T * D * Hq + 4.0 * T * Hq}}
+    r = {"workload": f"{case.name}_fp8: FP8 (E4M3, per-head scales) forward on the {case.name} batch",
+         "ms": ms, "value": case.flops_fwd / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "dtype": "f8e4m3",
+         "roofline": roofline_of(k, case.name, PEAK_FP8_TFLOPS)}
+    cu_dev = torch.from_numpy(np.asarray(ps.cu_seqlens, dtype=np.int32)).to(dev)
+    bcodes = {name: (torch.empty(s0[name].shape, dtype=torch.uint8, device=dev),
+                     torch.empty(s0[name].shape[:2], dtype=torch.float32, device=dev)) for name in ("q", "k", "v")}
+
+    def quantise_all(_):
+        for name in ("q", "k", "v"):
+            va.va_quantize_e4m3_blockwise_device(s0[name], ps.cu_seqlens, cu_dev, bcodes[name][0], bcodes[name][1])
+
+    def fwd_block(_):
+        ps.fwd_fp8_blockwise(bcodes["q"][0], bcodes["k"][0], bcodes["v"][0], bcodes["q"][1], bcodes["k"][1],
+                             bcodes["v"][1], scale, s0["out"], s0["lse"])
+
+    for _ in range(3):
+        quantise_all(0)
+        fwd_block(0)
+    q_ms = case.time_train(quantise_all, iters)
+    fb_ms = case.time_train(fwd_block, iters)
+    q_bytes = sum(s0[n].numel() * (2 + 1) + s0[n].shape[0] * s0[n].shape[1] * 4 for n in ("q", "k", "v"))
+    r["blockwise"] = {"ms": fb_ms, "tflops": case.flops_fwd / (fb_ms * 1e-3) / 1e12,
+                      "frac": case.flops_fwd / (fb_ms * 1e-3) / 1e12 / PEAK_FP8_TFLOPS,
+                      "quantise_qkv_ms": q_ms, "quantise_gbps": q_bytes / (q_ms * 1e-3) / 1e9}
+    return r
+
+
+def tiny_latency(va, wl, torch, reps=200):
+    """Configuration 1 is a latency case: microseconds per forward + backward call pair, eager and as a graph
+    replay, and the host microseconds the two calls take to return; the oracle on one thread beside it."""
+    case = Case("tiny", va, wl, torch, n_sets=1)
+    case.clock_ramp(20.0)
+    eager = case.time_steps(reps, 20, rotate=False) * 1e3
+    graph = case.time_graph(reps) * 1e3
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        case.step(0)
+    host = (time.perf_counter() - t0) / reps * 1e6
+    torch.cuda.synchronize()
+    from oracle import attn as oa
+    q, k, v, do = case.host
+    t0 = time.perf_counter()
+    for _ in range(5):
+        oa.attn_fwd(q, k, v, case.cu, None, scale=case.scale, nthreads=1)
+        oa.attn_bwd(q, k, v, do, case.cu, None, scale=case.scale, nthreads=1)
+    oracle_us = (time.perf_counter() - t0) / 5 * 1e6
+    return {"workload": "tiny: 3 samples of 17, 64, 95 tokens, 2 / 2 heads, head_dim 64, causal",
+            "latency_us": eager, "latency_graph_us": graph, "host_call_us": host,
+            "oracle_1_thread_us": oracle_us}
+
+
+def host_call_cost(case, reps=200):
+    """microseconds the forward + backward calls of one step take on the host (validation and launches)"""
+    torch = case.torch
+    torch.cuda.synchronize()
+    best = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        for i in range(reps):
+            case.step(i)
+        best = min(best, (time.perf_counter() - t0) / reps * 1e6)
+        torch.cuda.synchronize()
+    return best
+
+
+def cpu_baseline(case, va, budget_s=14.0):
+    """The oracle as it stands, on the host cores: forward + backward of the first m samples of the headline
+    batch (a packed stream of its own), m chosen from the rate on the first sample so that the work takes
+    about `budget_s` seconds."""
     from oracle import attn as oa
     nthreads = oa.num_threads()
-    flops = tokens = samples = bins = 0
-    dt = 0.0
-    while True:
-        b = build_bin(name, va, wl, bins)
-        if b is None:
-            break
-        w, lens, prefix, cu, pl, mx = b
-        D, Hq, Hkv = w.head_dim, w.num_q_heads, w.num_kv_heads
-        f = 14.0 * D * Hq * allowed_pairs(lens, prefix)
-        if bins > 0 and (dt >= budget_s or dt + f * dt / flops > max_s):
-            break
-        q, k, v, do = wl.tensor_values(w.seed + 1000 * bins, int(cu[-1]), Hq, Hkv, D)
-        scale = 1.0 / float(np.sqrt(D))
+    w, cu, lens, prefix = case.w, case.cu, case.lens, case.prefix
+    D, Hq = case.D, case.Hq
+    omode = mask_modes(w, va)[1]
+    q, k, v, do = case.host
+
+    def run(m):
+        rows = int(cu[m])
+        sub_cu = np.ascontiguousarray(cu[:m + 1])
+        sub_p = None if prefix is None else np.ascontiguousarray(prefix[:m])
         t0 = time.perf_counter()
-        oa.attn_fwd(q, k, v, cu, prefix, scale=scale, mask_mode=mask_modes(w, va)[1])
-        oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=mask_modes(w, va)[1])
-        dt += time.perf_counter() - t0
-        flops += f
-        tokens += int(cu[-1])
-        samples += len(lens)
-        bins += 1
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": nthreads, "kind": "oracle",
-            "sample": f"fp64 oracle fwd+bwd on the first {bins} bins of the first-fit packing "
-                      f"({samples} samples, {tokens} tokens, {dt:.1f} s)",
-            "tokens_per_s": tokens / dt}
+        oa.attn_fwd(q[:rows], k[:rows], v[:rows], sub_cu, sub_p, scale=case.scale, mask_mode=omode)
+        oa.attn_bwd(q[:rows], k[:rows], v[:rows], do[:rows], sub_cu, sub_p, scale=case.scale, mask_mode=omode)
+        return time.perf_counter() - t0
+
+    def flops(m):
+        return 14.0 * D * Hq * allowed_pairs(lens[:m], None if prefix is None else prefix[:m])
+
+    # rate from a few samples (enough of them to occupy every thread), then as many as fit the budget
+    m0 = min(len(lens), max(4, nthreads // max(1, case.Hkv)))
+    rate = flops(m0) / run(m0)
+    m = m0
+    while m < len(lens) and flops(m + 1) / rate <= budget_s:
+        m += 1
+    dt = run(m)
+    return {"value": flops(m) / dt / 1e12, "unit": "TFLOP/s", "cores": nthreads, "kind": "oracle",
+            "sample": f"fp64 oracle fwd+bwd on the first {m} of {len(lens)} samples of the {case.name} batch "
+                      f"({int(cu[m])} tokens, {dt:.1f} s)",
+            "tokens_per_s": int(cu[m]) / dt}
+
+
+def bins_mean(name, va, wl, torch, steps, warmup, first_ms, nbins=8):
+    """Mean over the first `nbins` bins: total useful flops / total time (bin 0 is the headline case, already
+    timed; the other bins take device-drawn N(0,1) values and two buffer sets)."""
+    flops, tokens, ms_sum, n = 0.0, 0, 0.0, 0
+    per_bin = []
+    for b in range(nbins):
+        if build_bin(name, va, wl, b) is None:
+            break
+        if b == 0:
+            c = None
+            w, lens, prefix, cu, pl, mx = build_bin(name, va, wl, 0)
+            f = 14.0 * w.head_dim * w.num_q_heads * allowed_pairs(lens, prefix)
+            ms, T = first_ms, int(cu[-1])
+        else:
+            c = Case(name, va, wl, torch, which=b, n_sets=2, host_values=False)
+            ms = c.time_steps(max(10, steps // 4), max(3, warmup // 4))
+            f, T = c.flops_fwd + c.flops_bwd, c.T
+        per_bin.append({"bin": b, "tokens": T, "ms_per_step": ms, "tflops": f / (ms * 1e-3) / 1e12})
+        flops, tokens, ms_sum, n = flops + f, tokens + T, ms_sum + ms, n + 1
+        del c
+        torch.cuda.empty_cache()
+    return {"bins": n, "tflops": flops / (ms_sum * 1e-3) / 1e12, "tokens_per_s": tokens / (ms_sum * 1e-3), "per_bin": per_bin}
+
+
+# ---------------------------------------------------------------- packed against padded (section 3.2.1)
+
+SWEEP_HQ, SWEEP_HKV, SWEEP_D = 16, 8, 128
+
+
+def sweep_lengths(batch, seq, pad_rate, rng):
+    mean = (1.0 - pad_rate) * seq
+    half = min(mean - 16, seq - mean, 0.5 * mean)
+    lens = rng.integers(int(mean - half), int(mean + half) + 1, size=batch).astype(np.int64)
+    lens = np.clip(lens, 16, seq)
+    lens[0] = seq
+    return lens
+
+
+def sweep_time(va, torch, lens, steps, dev="cuda:0"):
+    HQ, HKV, D = SWEEP_HQ, SWEEP_HKV, SWEEP_D
+    cu = np.zeros(len(lens) + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    T = int(cu[-1])
+    ps = va.PackedStream(cu, None, va.VA_MASK_CAUSAL, HQ, HKV, D, device=dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(T)
+    q = torch.randn((T, HQ, D), device=dev, generator=g).to(torch.bfloat16)
+    k = torch.randn((T, HKV, D), device=dev, generator=g).to(torch.bfloat16)
+    v = torch.randn((T, HKV, D), device=dev, generator=g).to(torch.bfloat16)
+    do = torch.randn((T, HQ, D), device=dev, generator=g).to(torch.bfloat16)
+    out, dq = torch.empty_like(q), torch.empty_like(q)
+    dk, dv = torch.empty_like(k), torch.empty_like(v)
+    lse = torch.empty((HQ, T), dtype=torch.float32, device=dev)
+    scale = 1.0 / float(np.sqrt(D))
+
+    def step():
+        ps.fwd(q, k, v, scale, out, lse)
+        ps.bwd(q, k, v, out, lse, do, scale, dq, dk, dv)
+
+    step()
+    step()
+    best = float("inf")
+    for _ in range(3):  # best of three short runs: one slow run (clock ramp, allocator) must not decide a row
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            step()
+        e1.record()
+        e1.synchronize()
+        best = min(best, e0.elapsed_time(e1) / steps)
+    return best
+
+
+def sweep(va, torch, quick):
+    """The paper's varlen-against-fixlen sweep with this library: the same kernels once on the packed stream
+    of the true lengths and once on a stream in which every sample is padded to the maximum length (what a
+    fixed-length batch computes), causal, 16 / 8 heads, head_dim 128, forward + backward.  Lengths are seeded:
+    B samples, uniform around (1 - padding rate) * S, clipped to [16, S], one sample forced to S."""
+    HQ, D = SWEEP_HQ, SWEEP_D
+    batches = (8, 32) if quick else (8, 16, 32)
+    seqs = (1024, 8192) if quick else (1024, 2048, 4096, 8192, 16384, 32768)
+    rates = (0.03, 0.5, 0.9) if quick else (0.03, 0.25, 0.5, 0.75, 0.9)
+    rng = np.random.default_rng(7)
+    print(f"{'batch':>5s} {'seq':>6s} {'target':>7s} {'padding':>8s} {'packed_ms':>10s} {'padded_ms':>10s} "
+          f"{'saved':>7s} {'packed_TF':>10s} {'padded_TF':>10s}")
+    for b in batches:
+        for s in seqs:
+            padded = np.full(b, s, dtype=np.int64)
+            steps = max(2, min(10, int(1e9 / (b * s * s))))
+            t_padded = sweep_time(va, torch, padded, steps)
+            for r in rates:
+                lens = sweep_lengths(b, s, r, rng)
+                pad = 1.0 - lens.sum() / float(b * s)
+                t_packed = sweep_time(va, torch, lens, steps)
+                flops = 14.0 * D * HQ * float((lens * (lens + 1) // 2).sum())
+                # the padded batch is credited with the useful pairs only
+                print(f"{b:5d} {s:6d} {r:7.2f} {pad:8.3f} {t_packed:10.3f} {t_padded:10.3f} "
+                      f"{1.0 - t_packed / t_padded:7.1%} {flops / t_packed / 1e9:10.0f} {flops / t_padded / 1e9:10.0f}",
+                      flush=True)
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default=WORKLOAD, choices=["vlm", "pi05", "pi0", "longtail", "vit", "tiny"])
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=HEADLINE, choices=["vlm", "pi05", "pi0", "longtail", "vit"])
+    ap.add_argument("--configs", default=",".join(OTHER_CONFIGS) + ",vlm_fp8,tiny",
+                    help="comma-separated configurations reported beside the headline (or 'none')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bins", action="store_true", help="skip the mean over the first 8 bins")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a device-to-device copy of 256 MiB three times, the reference that scales the "
                          "HBM byte counters of a counter-collection run")
+    ap.add_argument("--profile-leg", action="store_true")
+    ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--quick", action="store_true", help="with --sweep: a 2 x 2 x 3 corner")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -122,195 +541,84 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dev = "cuda:0"
-    w, lens, prefix, cu, pl, mx = build_bin0(args.workload, va, wl)
-    T, Hq, Hkv, D = int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim
-    mask = mask_modes(w, va)[0]
-    scale = 1.0 / float(np.sqrt(D))
-    pairs = allowed_pairs(lens, prefix)
-    flops_fwd = 4.0 * D * Hq * pairs
-    flops_bwd = 10.0 * D * Hq * pairs
-
-    torch.zeros(1, device=dev)  # first touch of the device (context, allocator) is not part of the plan
+    torch.zeros(1, device=dev)  # first touch of the device (context, allocator) is not part of any plan time
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ps = va.PackedStream(cu, pl, mask, Hq, Hkv, D, max_seqlen=mx, device=dev)  # three work lists, built and uploaded
-    torch.cuda.synchronize()
-    host_plan_ms = (time.perf_counter() - t0) * 1e3
 
-    def dev_bf16(x):
-        return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).to(dev)
+    if args.sweep:
+        sweep(va, torch, args.quick)
+        return
 
-    q, k, v, do = wl.tensor_values(w.seed, T, Hq, Hkv, D)
-    sets = []
-    for i in range(NUM_BUFFER_SETS):
-        s = {"q": dev_bf16(q), "k": dev_bf16(k), "v": dev_bf16(v), "do": dev_bf16(do)}
-        s["out"] = torch.empty_like(s["q"])
-        s["lse"] = torch.empty((Hq, T), dtype=torch.float32, device=dev)
-        s["dq"], s["dk"], s["dv"] = torch.empty_like(s["q"]), torch.empty_like(s["k"]), torch.empty_like(s["v"])
-        sets.append(s)
-    ps.workspace()
+    if args.profile_leg:
+        case = Case(args.workload, va, wl, torch, host_values=False)
+        if args.copy_calibration:
+            src = torch.ones(COPY_CALIBRATION_BYTES // 4, dtype=torch.float32, device=dev)
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        case.clock_ramp(30.0)
+        ms = case.time_steps(args.steps, args.warmup)
+        if case.D == 128:
+            fp8_forward(case, max(4, min(args.steps, 20)))
+        print(json.dumps({"profile_leg": args.workload, "steps": args.steps, "ms_per_step": ms}))
+        return
 
-    def step(s):
-        ps.fwd(s["q"], s["k"], s["v"], scale, s["out"], s["lse"])
-        ps.bwd(s["q"], s["k"], s["v"], s["out"], s["lse"], s["do"], scale, s["dq"], s["dk"], s["dv"])
-
-    if args.copy_calibration:
-        src = torch.ones(COPY_CALIBRATION_BYTES // 4, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    for i in range(args.warmup):
-        step(sets[i % NUM_BUFFER_SETS])
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(sets[i % NUM_BUFFER_SETS])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-
-    # per-kernel durations with HIP events on the launch stream, over the same rotation: many launches of one
-    # kernel between two events, so that the cost of an event on the stream is spread over all of them
     iters = max(8, min(args.steps, 40))
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
-
-    def time_block(launch):
-        # a warm-up as long as a block, then three blocks with no wait in between: the stream stays busy
-        # and the clocks stay up from the first event to the last
-        for i in range(iters):
-            launch(i)
-        evs[0].record()
-        for blk in range(3):
-            for i in range(iters):
-                launch(i)
-            evs[blk + 1].record()
-        evs[3].synchronize()
-        return float(np.median([evs[blk].elapsed_time(evs[blk + 1]) / iters for blk in range(3)]))
-
-    def launch_fwd(i):
-        s = sets[i % NUM_BUFFER_SETS]
-        ps.fwd(s["q"], s["k"], s["v"], scale, s["out"], s["lse"])
-
-    time_block(launch_fwd)  # the first train of forward-only launches after the mixed loop runs slow: not taken
-    fwd_ms = time_block(launch_fwd)
-    kms = np.zeros(3)
-    per_set = max(2, iters // NUM_BUFFER_SETS)
-    for i in range(NUM_BUFFER_SETS):
-        s = sets[i]
-        kms += np.array(ps.bwd_profile(s["q"], s["k"], s["v"], s["out"], s["lse"], s["do"], scale,
-                                       s["dq"], s["dk"], s["dv"], iters=per_set))
-    kms /= NUM_BUFFER_SETS
-    # algorithmic work per launch: forward 2 products; dK/dV kernel 4 (scores, dP, dV, dK); dQ kernel 1 (dQ;
-    # its recomputation of the scores and dP is overhead and is not counted)
-    kernels = {
-        "fwd_bf16": {"ms": fwd_ms, "flops": flops_fwd},
-        "bwd_delta": {"ms": float(kms[0]), "flops": 2.0 * T * Hq * D},  # dropped below where no such kernel runs
-        "bwd_dkdv": {"ms": float(kms[1]), "flops": 8.0 * D * Hq * pairs},
-        "bwd_dq": {"ms": float(kms[2]), "flops": 2.0 * D * Hq * pairs},
-    }
-    # algorithmic bytes per launch: every input read once, every output written once
-    fused = not va.va_bwd_has_delta_kernel(D)
-    kernels["fwd_bf16"]["bytes"] = 2.0 * T * D * (2 * Hq + 2 * Hkv) + 4.0 * T * Hq
-    kernels["bwd_dkdv"]["bytes"] = 2.0 * T * D * (2 * Hq + 4 * Hkv) + 8.0 * T * Hq
-    kernels["bwd_dq"]["bytes"] = (2.0 * T * D * (4 * Hq + 2 * Hkv) + 12.0 * T * Hq if fused
-                                  else 2.0 * T * D * (3 * Hq + 2 * Hkv) + 8.0 * T * Hq)
-    kernels["bwd_delta"]["bytes"] = 4.0 * T * D * Hq + 12.0 * T * Hq
-    if not va.va_bwd_has_delta_kernel(D):
-        del kernels["bwd_delta"]
-    dominant = max(("fwd_bf16", "bwd_dkdv", "bwd_dq"), key=lambda n: kernels[n]["ms"])
-    achieved = kernels[dominant]["flops"] / (kernels[dominant]["ms"] * 1e-3) / 1e12
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get(dominant)
-
-    # FP8 (E4M3) forward on the same batch, outside the timed region: per-head quantisation on the device,
-    # then back-to-back launches between events as above
-    fp8 = None
-    if D == 128:
-        codes = {}
-        s0 = sets[0]
-        for name in ("q", "k", "v"):
-            c8 = torch.empty(s0[name].shape, dtype=torch.uint8, device=dev)
-            descale = torch.empty((s0[name].shape[1],), dtype=torch.float32, device=dev)
-            va.va_quantize_e4m3_per_head_device(s0[name], c8, descale)
-            codes[name] = (c8, descale)
-        for _ in range(3):
-            ps.fwd_fp8(codes["q"][0], codes["k"][0], codes["v"][0], codes["q"][1], codes["k"][1], codes["v"][1],
-                       scale, s0["out"], s0["lse"])
-        fp8_ms = time_block(lambda i: ps.fwd_fp8(codes["q"][0], codes["k"][0], codes["v"][0], codes["q"][1],
-                                                 codes["k"][1], codes["v"][1], scale, s0["out"], s0["lse"]))
-        fp8 = {"ms": fp8_ms, "tflops": flops_fwd / (fp8_ms * 1e-3) / 1e12, "peak": 5000.0,
-               "frac": flops_fwd / (fp8_ms * 1e-3) / 1e12 / 5000.0}
-        # the same with block-wise scales (one per 128 tokens of a sample and head); the three quantiser
-        # launches are timed on their own, against the bytes they must move (read twice, codes and scales out)
-        cu_dev = torch.from_numpy(np.asarray(ps.cu_seqlens, dtype=np.int32)).to(dev)
-        bcodes = {}
-        for name in ("q", "k", "v"):
-            c8 = torch.empty(s0[name].shape, dtype=torch.uint8, device=dev)
-            d_tok = torch.empty(s0[name].shape[:2], dtype=torch.float32, device=dev)
-            bcodes[name] = (c8, d_tok)
-
-        def quantise_all(_):
-            for name in ("q", "k", "v"):
-                va.va_quantize_e4m3_blockwise_device(s0[name], ps.cu_seqlens, cu_dev, bcodes[name][0], bcodes[name][1])
-
-        def fwd_block(_):
-            ps.fwd_fp8_blockwise(bcodes["q"][0], bcodes["k"][0], bcodes["v"][0], bcodes["q"][1], bcodes["k"][1],
-                                 bcodes["v"][1], scale, s0["out"], s0["lse"])
-
-        for _ in range(3):
-            quantise_all(0)
-            fwd_block(0)
-        q_ms = time_block(quantise_all)
-        fb_ms = time_block(fwd_block)
-        q_bytes = sum(s0[n].numel() * (2 + 1) + s0[n].shape[0] * s0[n].shape[1] * 4 for n in ("q", "k", "v"))
-        fp8["blockwise"] = {"ms": fb_ms, "tflops": flops_fwd / (fb_ms * 1e-3) / 1e12,
-                            "frac": flops_fwd / (fb_ms * 1e-3) / 1e12 / 5000.0,
-                            "quantise_qkv_ms": q_ms, "quantise_gbps": q_bytes / (q_ms * 1e-3) / 1e9}
-
-    useful_tflops = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+    case = Case(args.workload, va, wl, torch)
+    head = measure(case, args.steps, args.warmup, iters, full=True)
+    head["host_call_us"] = host_call_cost(case)
     result = {
         "metric": "packed varlen attn fwd+bwd useful TFLOP/s",
-        "value": useful_tflops,
+        "value": head["value"],
         "unit": "TFLOP/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: bin 0 of the first-fit packing, {len(lens)} samples, {T} tokens, "
-                               f"{Hq} q heads / {Hkv} kv heads, head_dim {D}, "
-                               f"{'three-block' if w.three_block else 'prefix-LM' if w.prefix_lm else 'causal'}, budget {w.budget}",
-                   "tokens": T, "samples": int(len(lens)), "pairs_per_head": pairs,
-                   "buffer_sets": NUM_BUFFER_SETS},
-        "tokens_per_s": T / (ms_per_step * 1e-3),
-        "mfma_util_useful": useful_tflops / PEAK_BF16_TFLOPS,
-        "host_plan_ms": host_plan_ms,
-        "kernels_ms": {n: kernels[n]["ms"] for n in kernels},
-        "kernels_tflops": {n: kernels[n]["flops"] / (kernels[n]["ms"] * 1e-3) / 1e12 for n in kernels},
-        "fwd_fp8": fp8,
-        "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
-                     # the same launch against the other roof: short samples put this workload at the ridge
-                     "hbm": {"achieved": kernels[dominant]["bytes"] / (kernels[dominant]["ms"] * 1e-3) / 1e9,
-                             "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                             "frac": kernels[dominant]["bytes"] / (kernels[dominant]["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
-                             "algorithmic_bytes": kernels[dominant]["bytes"]}},
-        "kernels_gbps": {n: kernels[n]["bytes"] / (kernels[n]["ms"] * 1e-3) / 1e9 for n in kernels},
+        "config": {"workload": head["workload"], "tokens": head["tokens"], "samples": head["samples"],
+                   "pairs_per_head": head["pairs_per_head"], "buffer_sets": NUM_BUFFER_SETS,
+                   "clock_ramp_ms": CLOCK_RAMP_MS},
+        **{n: head[n] for n in ("tokens_per_s", "mfma_util_useful", "ms_per_step_warm", "value_warm",
+                                "ms_per_step_graph", "value_graph", "host_plan_ms", "host_call_us", "kernels_ms",
+                                "kernels_tflops", "kernels_gbps", "step_floor_us", "step_frac_of_floor")},
+        "roofline": head["roofline"],
+        "source_digest": source_digest(),
         "paper_context": "paper reports 1.88x end-to-end training throughput from packing + varlen attention "
                          "(section 3.2; NVIDIA GPU model unstated); no absolute attention numbers",
     }
+    if "rocprof_counters" in head:
+        result["rocprof_counters"] = head["rocprof_counters"]
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(args.workload, va, wl)
+        result["cpu_baseline"] = cpu_baseline(case, va)
+    first_ms = head["ms_per_step"]
+    del case
+    torch.cuda.empty_cache()
+    if not args.no_bins:
+        result["bins8"] = bins_mean(args.workload, va, wl, torch, args.steps, args.warmup, first_ms)
+    configs = {}
+    wanted = [] if args.configs == "none" else [c for c in args.configs.split(",") if c]
+    for name in wanted:
+        if name == "tiny":
+            configs["tiny"] = tiny_latency(va, wl, torch)
+        elif name.endswith("_fp8"):
+            c = Case(name[:-4], va, wl, torch, n_sets=1)
+            c.clock_ramp()
+            configs[name] = fp8_forward(c, iters)
+            del c
+        elif name != args.workload:
+            c = Case(name, va, wl, torch)
+            configs[name] = measure(c, max(args.steps, 100), args.warmup, iters, full=True)
+            configs[name]["host_call_us"] = host_call_cost(c)
+            del c
+        torch.cuda.empty_cache()
+    if configs:
+        result["configs"] = configs
     print(json.dumps(result))
 
 

@@ -159,14 +159,14 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
  * about the same position of their queues, so that the XCD's L2 fetches the
  * rows once.  Kernels that run one work per workgroup (dK/dV) ignore the table
  * and take work ids 0 .. num_works-1 in item order.
- * va_worklist_bytes gives the buffer size; va_build_worklist fills a host
+ * va_worklist_size gives the buffer size; va_build_worklist fills a host
  * buffer of at least that size.  The caller copies the buffer to the device
  * unchanged and hands both copies to the device calls, which validate the host
  * copy (records, bounds, that every item lies inside one sample of cu_seqlens,
  * that the table partitions the works and repeats each workgroup's first work
  * faithfully) and return VA_EINVAL on a mismatch.
  */
-int va_worklist_bytes(const int32_t* cu_seqlens, int32_t num_seqs, int32_t pass, int32_t head_dim,
+int va_worklist_size(const int32_t* cu_seqlens, int32_t num_seqs, int32_t pass, int32_t head_dim,
                       int32_t num_q_heads, int32_t num_kv_heads, size_t* bytes);
 int va_build_worklist(const int32_t* cu_seqlens, const int32_t* prefix_lens, int32_t num_seqs,
                       int32_t mask_mode, int32_t pass, int32_t head_dim,
@@ -249,23 +249,32 @@ int va_quantize_e4m3_per_head_device(const void* x_bf16, int32_t T, int32_t H, i
 int va_bwd_has_delta_kernel(int32_t head_dim);
 
 /*
- * Measurement aid: runs varlen_attn_bwd once, then launches each of its
- * kernels `iters` times back to back (the results stay those of
- * varlen_attn_bwd) between HIP events recorded on `stream`, waits for the
- * stream (the only entry point that synchronises) and writes the average
- * milliseconds per launch to the host array ms[3] = {delta, dK/dV, dQ};
- * ms[0] is the bare distance of two events where no delta kernel exists
- * (va_bwd_has_delta_kernel).  Same arguments and errors as varlen_attn_bwd;
- * iters >= 1.
+ * The backward restricted to some of its kernels (this library's own; the
+ * paper names no such call).  `stages` is a non-empty combination of
+ *   VA_BWD_STAGE_DELTA  delta = rowsum(dO * O) and LSE * log2(e) into the workspace
+ *   VA_BWD_STAGE_DKDV   dK and dV; reads both arrays from the workspace
+ *   VA_BWD_STAGE_DQ     dQ; at head_dim <= 128 its kernel also writes both arrays
+ *                       (VA_BWD_STAGE_DELTA is then implied and costs nothing extra)
+ * in the order varlen_attn_bwd runs them; VA_BWD_STAGE_ALL is varlen_attn_bwd.
+ * For callers that need one side only (frozen keys and values: dQ alone) and
+ * for timing one kernel at a time with the caller's own events.  A call with
+ * VA_BWD_STAGE_DKDV but without the stage that fills the workspace reads what
+ * an earlier call with the same q, k, v, out, lse, dout and workspace left
+ * there.  Outputs of stages not selected are not touched (their pointers must
+ * still be valid device pointers).  Same arguments and errors as
+ * varlen_attn_bwd; VA_EINVAL for an empty or unknown stage set.
  */
-int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                            const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
-                            const void* worklist_dkdv, const void* worklist_dkdv_host,
-                            const void* worklist_dq, const void* worklist_dq_host,
-                            const va_shape* shape, float scale,
-                            void* dq, void* dk, void* dv,
-                            void* workspace, size_t workspace_bytes, void* stream,
-                            int32_t iters, float* ms);
+#define VA_BWD_STAGE_DELTA 1u
+#define VA_BWD_STAGE_DKDV 2u
+#define VA_BWD_STAGE_DQ 4u
+#define VA_BWD_STAGE_ALL 7u
+int varlen_attn_bwd_stages(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                           const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                           const void* worklist_dkdv, const void* worklist_dkdv_host,
+                           const void* worklist_dq, const void* worklist_dq_host,
+                           const va_shape* shape, float scale,
+                           void* dq, void* dk, void* dv,
+                           void* workspace, size_t workspace_bytes, void* stream, uint32_t stages);
 
 /*
  * FP8 forward: Q, K, V are OCP E4M3 bytes with one float32 descale per head

@@ -17,6 +17,7 @@ VA_OK = 0
 VA_EINVAL, VA_EUNSUPPORTED, VA_EALIGN, VA_ESIZE, VA_EHIP = -1, -2, -3, -4, -5
 VA_MASK_CAUSAL, VA_MASK_PREFIX_LM, VA_MASK_PREFIX_LM_CAUSAL, VA_MASK_THREE_BLOCK, VA_MASK_SLIDING_WINDOW = 0, 1, 2, 3, 4
 VA_PASS_FWD, VA_PASS_BWD_DKDV, VA_PASS_BWD_DQ = 0, 1, 2
+VA_BWD_STAGE_DELTA, VA_BWD_STAGE_DKDV, VA_BWD_STAGE_DQ, VA_BWD_STAGE_ALL = 1, 2, 4, 7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvarlen_attn.so")
@@ -47,10 +48,10 @@ def _load():
 
 _lib = _load()
 
-EXPORTS = ["va_last_error", "va_pack_first_fit", "va_bin_layout", "va_tile_shape", "va_worklist_bytes",
+EXPORTS = ["va_last_error", "va_pack_first_fit", "va_bin_layout", "va_tile_shape", "va_worklist_size",
            "va_build_worklist", "va_quantize_e4m3_per_head", "va_quantize_e4m3_per_head_device",
            "varlen_attn_bwd_workspace_bytes", "va_bwd_has_delta_kernel",
-           "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_profile", "varlen_attn_fwd_fp8",
+           "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_stages", "varlen_attn_fwd_fp8",
            "va_quantize_e4m3_blockwise", "va_quantize_e4m3_blockwise_device", "varlen_attn_fwd_fp8_blockwise"]
 
 
@@ -129,10 +130,10 @@ def va_tile_shape(pass_id, head_dim, num_q_heads, num_kv_heads):
     return rows.value, cols.value
 
 
-def va_worklist_bytes(cu_seqlens, pass_id, head_dim, num_q_heads, num_kv_heads):
+def va_worklist_size(cu_seqlens, pass_id, head_dim, num_q_heads, num_kv_heads):
     cu = _i32(cu_seqlens)
     nbytes = ctypes.c_size_t(0)
-    _check(_lib.va_worklist_bytes(_ptr(cu), ctypes.c_int32(len(cu) - 1), ctypes.c_int32(pass_id),
+    _check(_lib.va_worklist_size(_ptr(cu), ctypes.c_int32(len(cu) - 1), ctypes.c_int32(pass_id),
                                   ctypes.c_int32(head_dim), ctypes.c_int32(num_q_heads),
                                   ctypes.c_int32(num_kv_heads), ctypes.byref(nbytes)))
     return nbytes.value
@@ -143,7 +144,7 @@ def va_build_worklist(cu_seqlens, prefix_lens, mask_mode, pass_id, head_dim, num
     ``worklist_schedule`` for its parts)."""
     cu = _i32(cu_seqlens)
     pl = _prefix(prefix_lens, mask_mode, len(cu) - 1)
-    nbytes = va_worklist_bytes(cu, pass_id, head_dim, num_q_heads, num_kv_heads)
+    nbytes = va_worklist_size(cu, pass_id, head_dim, num_q_heads, num_kv_heads)
     buf = np.zeros((nbytes // 32, 8), dtype=np.int32)
     n_items = ctypes.c_int32(0)
     _check(_lib.va_build_worklist(_ptr(cu), _ptr(pl), ctypes.c_int32(len(cu) - 1), ctypes.c_int32(mask_mode),
@@ -248,19 +249,16 @@ def varlen_attn_bwd(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_d
                                 _ptr(workspace), ctypes.c_size_t(workspace_bytes), _stream_ptr(stream)))
 
 
-def varlen_attn_bwd_profile(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
-                            worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
-                            stream=None, iters=1):
-    """Returns average milliseconds per launch of (delta, dK/dV, dQ); waits for the stream."""
+def varlen_attn_bwd_stages(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
+                           worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
+                           stages, stream=None):
     cu = _i32(cu_seqlens)
     pl = _prefix(prefix_lens, shape.mask_mode, len(cu) - 1)
-    ms = (ctypes.c_float * 3)()
-    _check(_lib.varlen_attn_bwd_profile(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(cu), _ptr(pl),
-                                        _ptr(worklist_dkdv), _ptr(worklist_dkdv_host), _ptr(worklist_dq),
-                                        _ptr(worklist_dq_host), ctypes.byref(shape), ctypes.c_float(scale),
-                                        _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), ctypes.c_size_t(workspace_bytes),
-                                        _stream_ptr(stream), ctypes.c_int32(iters), ms))
-    return float(ms[0]), float(ms[1]), float(ms[2])
+    _check(_lib.varlen_attn_bwd_stages(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(cu), _ptr(pl),
+                                       _ptr(worklist_dkdv), _ptr(worklist_dkdv_host), _ptr(worklist_dq),
+                                       _ptr(worklist_dq_host), ctypes.byref(shape), ctypes.c_float(scale),
+                                       _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), ctypes.c_size_t(workspace_bytes),
+                                       _stream_ptr(stream), ctypes.c_uint32(stages)))
 
 
 def varlen_attn_fwd_fp8(q8, k8, v8, q_descale, k_descale, v_descale, cu_seqlens, prefix_lens, worklist, worklist_host,
@@ -328,12 +326,12 @@ class PackedStream:
                         self.worklist[VA_PASS_BWD_DQ], self.worklist_host[VA_PASS_BWD_DQ],
                         self.shape, scale, dq, dk, dv, ws, ws.numel(), stream)
 
-    def bwd_profile(self, q, k, v, out, lse, dout, scale, dq, dk, dv, stream=None, iters=1):
+    def bwd_stages(self, q, k, v, out, lse, dout, scale, dq, dk, dv, stages, stream=None):
         ws = self.workspace()
-        return varlen_attn_bwd_profile(q, k, v, out, lse, dout, self.cu_seqlens, self.prefix_lens,
-                                       self.worklist[VA_PASS_BWD_DKDV], self.worklist_host[VA_PASS_BWD_DKDV],
-                                       self.worklist[VA_PASS_BWD_DQ], self.worklist_host[VA_PASS_BWD_DQ],
-                                       self.shape, scale, dq, dk, dv, ws, ws.numel(), stream, iters)
+        varlen_attn_bwd_stages(q, k, v, out, lse, dout, self.cu_seqlens, self.prefix_lens,
+                               self.worklist[VA_PASS_BWD_DKDV], self.worklist_host[VA_PASS_BWD_DKDV],
+                               self.worklist[VA_PASS_BWD_DQ], self.worklist_host[VA_PASS_BWD_DQ],
+                               self.shape, scale, dq, dk, dv, ws, ws.numel(), stages, stream)
 
     def fwd_fp8_blockwise(self, q8, k8, v8, q_descale_tok, k_descale_tok, v_descale_tok, scale, out, lse, stream=None):
         varlen_attn_fwd_fp8_blockwise(q8, k8, v8, q_descale_tok, k_descale_tok, v_descale_tok, self.cu_seqlens,

@@ -1,6 +1,5 @@
 // C-ABI device entry points: argument validation on the host, then kernel
-// launches on the caller's stream.  No allocation, no synchronisation (the
-// profiling entry point aside).
+// launches on the caller's stream.  No device allocation, no synchronisation.
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -51,8 +50,8 @@ int check_shape(const va_shape* s, const int32_t* cu, const int32_t* prefix_lens
 // The host copy of a work list is checked against the stream it claims to
 // describe: headers, every item must lie inside one sample of cu_seqlens, and
 // the workgroup table must partition the works.
-int check_worklist(const void* dev, const void* host, const va_shape* s, const int32_t* cu, int32_t pass,
-                   const char* who, WorklistLayout* layout) {
+int check_worklist(const void* dev, const void* host, const va_shape* s, const int32_t* cu, const int32_t* prefix_lens,
+                   int32_t pass, const char* who, WorklistLayout* layout) {
     if (!dev || !host) return fail(VA_EINVAL, "%s: null work list", who);
     const WorkItem* w = static_cast<const WorkItem*>(host);
     int32_t rows, cols;
@@ -86,6 +85,11 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
         while (lo < cu + s->num_seqs && lo[0] == seq0 && lo[1] == seq0) ++lo;  // skip empty samples at this row
         if (lo >= cu + s->num_seqs || lo[0] != seq0 || lo[1] - lo[0] != L)
             return fail(VA_EINVAL, "%s: work item %d does not match a sample of cu_seqlens", who, i);
+        // the kernels take the mask from the item words alone: they must be those of this call's prefix_lens
+        int32_t Ps, P2s;
+        block_ends(prefix_lens, s->mask_mode, (int32_t)(lo - cu), &Ps, &P2s);
+        if (P != Ps || P2 != P2s)
+            return fail(VA_EINVAL, "%s: work item %d was built for other block ends (or another window) than prefix_lens holds", who, i);
         const int32_t Pm = P < 0 ? 0 : P, P2m = P2 < 0 ? 0 : P2;
         if (pass == VA_PASS_BWD_DKDV) {
             int32_t qt_end = (L + cols - 1) / cols;
@@ -102,11 +106,18 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
     }
     const int32_t* table = w[lay.table_rec].w;
     const int32_t* ids = w[lay.id_rec].w;
-    std::vector<bool> listed((size_t)lay.num_works, false);
+    // one bit per work; the buffer belongs to the thread and only ever grows, so a launch allocates nothing
+    // once the thread has seen its largest list
+    thread_local std::vector<uint64_t> listed;
+    const size_t words = ((size_t)lay.num_works + 63) / 64;
+    if (listed.size() < words) listed.resize(words);
+    std::fill(listed.begin(), listed.begin() + words, 0ull);
     for (int32_t i = 0; i < lay.num_works; ++i) {
         if (ids[i] < 0 || ids[i] >= lay.num_works) return fail(VA_EINVAL, "%s: work id %d out of range", who, i);
-        if (listed[ids[i]]) return fail(VA_EINVAL, "%s: work %d is listed twice", who, ids[i]);
-        listed[ids[i]] = true;
+        uint64_t& word = listed[(size_t)ids[i] >> 6];
+        const uint64_t bit = 1ull << (ids[i] & 63);
+        if (word & bit) return fail(VA_EINVAL, "%s: work %d is listed twice", who, ids[i]);
+        word |= bit;
     }
     int32_t at = 0;
     for (int32_t g = 0; g < lay.num_workgroups; ++g) {
@@ -180,7 +191,7 @@ int varlen_attn_fwd(const void* q, const void* k, const void* v,
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
         return fail(VA_EALIGN, "%s: tensor pointers must be 16-byte aligned", who);
     WorklistLayout lay;
-    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, VA_PASS_FWD, who, &lay))) return rc;
+    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, prefix_lens, VA_PASS_FWD, who, &lay))) return rc;
     AttnParams p = base_params(shape, scale);
     p.q = q;
     p.k = k;
@@ -193,7 +204,7 @@ int varlen_attn_fwd(const void* q, const void* k, const void* v,
     return VA_OK;
 }
 
-// Validation shared by varlen_attn_bwd and varlen_attn_bwd_profile; fills the kernel parameters.
+// Validation shared by the backward entry points; fills the kernel parameters.
 static int prepare_bwd(const char* who, const void* q, const void* k, const void* v, const void* out, const float* lse,
                        const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
                        const void* worklist_dkdv, const void* worklist_dkdv_host,
@@ -216,8 +227,8 @@ static int prepare_bwd(const char* who, const void* q, const void* k, const void
     if (workspace_bytes < varlen_attn_bwd_workspace_bytes(shape))
         return fail(VA_ESIZE, "%s: workspace of %zu bytes, need %zu", who, workspace_bytes,
                     varlen_attn_bwd_workspace_bytes(shape));
-    if ((rc = check_worklist(worklist_dkdv, worklist_dkdv_host, shape, cu_seqlens, VA_PASS_BWD_DKDV, who, lay_dkdv))) return rc;
-    if ((rc = check_worklist(worklist_dq, worklist_dq_host, shape, cu_seqlens, VA_PASS_BWD_DQ, who, lay_dq))) return rc;
+    if ((rc = check_worklist(worklist_dkdv, worklist_dkdv_host, shape, cu_seqlens, prefix_lens, VA_PASS_BWD_DKDV, who, lay_dkdv))) return rc;
+    if ((rc = check_worklist(worklist_dq, worklist_dq_host, shape, cu_seqlens, prefix_lens, VA_PASS_BWD_DQ, who, lay_dq))) return rc;
     *p = base_params(shape, scale);
     p->q = q;
     p->k = k;
@@ -233,31 +244,51 @@ static int prepare_bwd(const char* who, const void* q, const void* k, const void
     return VA_OK;
 }
 
-// The kernels of one backward call, on one stream.  Where the dQ kernel computes delta and the rescaled
-// LSE itself it runs first and the dK/dV kernel, which reads both, after it; otherwise a pass over O and
-// dO comes first.
+// The kernels of one backward call, on one stream, restricted to `stages`.  Where the dQ kernel computes
+// delta and the rescaled LSE itself it runs first and the dK/dV kernel, which reads both, after it;
+// otherwise a pass over O and dO comes first.
 static hipError_t launch_backward(AttnParams* p, hipStream_t st, const void* worklist_dkdv, const WorklistLayout& lay_dkdv,
-                                  const void* worklist_dq, const WorklistLayout& lay_dq) {
+                                  const void* worklist_dq, const WorklistLayout& lay_dq, uint32_t stages) {
     hipError_t e = hipSuccess;
-    if (dq_computes_delta(p->D)) {
+    const bool fused = dq_computes_delta(p->D);
+    const bool dq_first = fused && (stages & VA_BWD_STAGE_DQ);
+    if ((stages & VA_BWD_STAGE_DELTA) && !dq_first) e = launch_bwd_delta(*p, st);
+    if (e == hipSuccess && dq_first) {
         set_worklist(p, worklist_dq, lay_dq);
         e = launch_bwd_dq(*p, st);
-        if (e == hipSuccess) {
-            set_worklist(p, worklist_dkdv, lay_dkdv);
-            e = launch_bwd_dkdv(*p, st);
-        }
-        return e;
     }
-    e = launch_bwd_delta(*p, st);
-    if (e == hipSuccess) {
+    if (e == hipSuccess && (stages & VA_BWD_STAGE_DKDV)) {
         set_worklist(p, worklist_dkdv, lay_dkdv);
         e = launch_bwd_dkdv(*p, st);
     }
-    if (e == hipSuccess) {
+    if (e == hipSuccess && (stages & VA_BWD_STAGE_DQ) && !dq_first) {
         set_worklist(p, worklist_dq, lay_dq);
         e = launch_bwd_dq(*p, st);
     }
     return e;
+}
+
+int varlen_attn_bwd_stages(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                           const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                           const void* worklist_dkdv, const void* worklist_dkdv_host,
+                           const void* worklist_dq, const void* worklist_dq_host,
+                           const va_shape* shape, float scale,
+                           void* dq, void* dk, void* dv,
+                           void* workspace, size_t workspace_bytes, void* stream, uint32_t stages) {
+    const char* who = "varlen_attn_bwd";
+    if (stages == 0 || (stages & ~(uint32_t)VA_BWD_STAGE_ALL) != 0)
+        return fail(VA_EINVAL, "%s: stages must be a non-empty combination of VA_BWD_STAGE_*", who);
+    AttnParams p;
+    WorklistLayout lay_dkdv, lay_dq;
+    bool empty = false;
+    int rc = prepare_bwd(who, q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
+                         worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
+                         &p, &lay_dkdv, &lay_dq, &empty);
+    if (rc || empty) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const hipError_t e = launch_backward(&p, st, worklist_dkdv, lay_dkdv, worklist_dq, lay_dq, stages);
+    if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
+    return VA_OK;
 }
 
 int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
@@ -267,78 +298,12 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
                     const va_shape* shape, float scale,
                     void* dq, void* dk, void* dv,
                     void* workspace, size_t workspace_bytes, void* stream) {
-    const char* who = "varlen_attn_bwd";
-    AttnParams p;
-    WorklistLayout lay_dkdv, lay_dq;
-    bool empty = false;
-    int rc = prepare_bwd(who, q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
-                         worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
-                         &p, &lay_dkdv, &lay_dq, &empty);
-    if (rc || empty) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const hipError_t e = launch_backward(&p, st, worklist_dkdv, lay_dkdv, worklist_dq, lay_dq);
-    if (e != hipSuccess) return fail(VA_EHIP, "%s: launch failed: %s", who, hipGetErrorString(e));
-    return VA_OK;
+    return varlen_attn_bwd_stages(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
+                                  worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
+                                  stream, VA_BWD_STAGE_ALL);
 }
 
 int va_bwd_has_delta_kernel(int32_t head_dim) { return dq_computes_delta(head_dim) ? 0 : 1; }
-
-int varlen_attn_bwd_profile(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                            const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
-                            const void* worklist_dkdv, const void* worklist_dkdv_host,
-                            const void* worklist_dq, const void* worklist_dq_host,
-                            const va_shape* shape, float scale,
-                            void* dq, void* dk, void* dv,
-                            void* workspace, size_t workspace_bytes, void* stream,
-                            int32_t iters, float* ms) {
-    const char* who = "varlen_attn_bwd_profile";
-    if (iters < 1 || !ms) return fail(VA_EINVAL, "%s: iters must be >= 1 and ms non-null", who);
-    AttnParams p;
-    WorklistLayout lay_dkdv, lay_dq;
-    bool empty = false;
-    int rc = prepare_bwd(who, q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
-                         worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
-                         &p, &lay_dkdv, &lay_dq, &empty);
-    ms[0] = ms[1] = ms[2] = 0.0f;
-    if (rc || empty) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    // Each kernel is launched `iters` times back to back between two events, so that what an event costs
-    // on the stream (several microseconds) is spread over all launches; the last round leaves the same
-    // results as varlen_attn_bwd.
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
-    auto destroy = [&] {
-        for (auto& x : ev)
-            if (x) (void)hipEventDestroy(x);
-    };
-    for (auto& x : ev)
-        if (hipEventCreate(&x) != hipSuccess) {
-            destroy();
-            return fail(VA_EHIP, "%s: hipEventCreate failed", who);
-        }
-    // one untimed round first: the stream is busy and the clocks are up when the first event is reached
-    hipError_t e = launch_backward(&p, st, worklist_dkdv, lay_dkdv, worklist_dq, lay_dq);
-    const bool fused = dq_computes_delta(p.D);  // then no delta kernel exists and ms[0] stays (close to) zero
-    if (e == hipSuccess) e = hipEventRecord(ev[0], st);
-    for (int32_t i = 0; i < iters && e == hipSuccess && !fused; ++i) e = launch_bwd_delta(p, st);
-    if (e == hipSuccess) e = hipEventRecord(ev[1], st);
-    set_worklist(&p, worklist_dkdv, lay_dkdv);
-    for (int32_t i = 0; i < iters && e == hipSuccess; ++i) e = launch_bwd_dkdv(p, st);
-    if (e == hipSuccess) e = hipEventRecord(ev[2], st);
-    set_worklist(&p, worklist_dq, lay_dq);
-    for (int32_t i = 0; i < iters && e == hipSuccess; ++i) e = launch_bwd_dq(p, st);
-    if (e == hipSuccess) e = hipEventRecord(ev[3], st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    double sum[3] = {0.0, 0.0, 0.0};
-    for (int s = 0; s < 3 && e == hipSuccess; ++s) {
-        float t = 0.0f;
-        e = hipEventElapsedTime(&t, ev[s], ev[s + 1]);
-        sum[s] = t;
-    }
-    destroy();
-    if (e != hipSuccess) return fail(VA_EHIP, "%s: %s", who, hipGetErrorString(e));
-    for (int s = 0; s < 3; ++s) ms[s] = (float)(sum[s] / iters);
-    return VA_OK;
-}
 
 int va_quantize_e4m3_per_head_device(const void* x, int32_t T, int32_t H, int32_t D, void* codes, float* descale,
                                      void* stream) {
@@ -378,7 +343,7 @@ int fwd_fp8_entry(const char* who, bool blockwise, const void* q8, const void* k
             return fail(VA_ESIZE, "%s: total_tokens * num_q_heads * 4 exceeds 2^31 - 1", who);
     }
     WorklistLayout lay;
-    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, VA_PASS_FWD, who, &lay))) return rc;
+    if ((rc = check_worklist(worklist, worklist_host, shape, cu_seqlens, prefix_lens, VA_PASS_FWD, who, &lay))) return rc;
     AttnParams p = base_params(shape, scale);
     p.q = q8;
     p.k = k8;

@@ -58,20 +58,12 @@ constexpr int32_t dkdv_q_tile(int32_t D) { return tile_geometry(D) >= 128 ? 32 :
 
 // Whether the dQ kernel computes delta = rowsum(dO * O) and LSE * log2(e) itself (and then runs before
 // the dK/dV kernel, which reads both) instead of a separate pass over O and dO.
-#ifndef VA_FUSE_DELTA
-#define VA_FUSE_DELTA 1
-#endif
-constexpr bool dq_computes_delta(int32_t D) { return VA_FUSE_DELTA != 0 && D <= 128; }
+constexpr bool dq_computes_delta(int32_t D) { return D <= 128; }
 
 // Persistent workgroups launched for a pass: CUs of an MI355X times the workgroups a CU holds.
 constexpr int32_t persistent_workgroups(int32_t /*pass*/, int32_t D) { return D <= 128 ? 512 : 256; }
 // XCDs of an MI355X: workgroup b of a launch runs on XCD b % kXcds, each with its own L2.
 constexpr int32_t kXcds = 8;
-// Whether the forward and dQ schedules keep the works that share K and V rows on one XCD at one time
-// (0: plain longest-processing-time-first over all workgroups).
-#ifndef VA_LOCALITY_SCHEDULE
-#define VA_LOCALITY_SCHEDULE 1
-#endif
 // Cost of a work in units of inner-loop steps: its steps plus a fixed part for the item switch.
 constexpr int32_t kWorkFixedCost = 2;
 

@@ -145,17 +145,17 @@ static int check_cu(const int32_t* cu, int32_t n, const char* who) {
     return VA_OK;
 }
 
-int va_worklist_bytes(const int32_t* cu, int32_t n, int32_t pass, int32_t D,
+int va_worklist_size(const int32_t* cu, int32_t n, int32_t pass, int32_t D,
                       int32_t Hq, int32_t Hkv, size_t* bytes) {
-    if (!bytes) return fail(VA_EINVAL, "va_worklist_bytes: null pointer");
-    int rc = check_cu(cu, n, "va_worklist_bytes");
+    if (!bytes) return fail(VA_EINVAL, "va_worklist_size: null pointer");
+    int rc = check_cu(cu, n, "va_worklist_size");
     if (rc) return rc;
     int32_t rows, cols;
     rc = tile_shape(pass, D, Hq, Hkv, &rows, &cols);
     if (rc) return rc;
     int64_t items = 0;
     for (int32_t s = 0; s < n; ++s) items += (cu[s + 1] - cu[s] + rows - 1) / rows;
-    if (items * works_per_item(pass, Hq, Hkv) > INT32_MAX / 2) return fail(VA_ESIZE, "va_worklist_bytes: too many works");
+    if (items * works_per_item(pass, Hq, Hkv) > INT32_MAX / 2) return fail(VA_ESIZE, "va_worklist_size: too many works");
     *bytes = (size_t)worklist_layout(pass, D, Hq, Hkv, (int32_t)items).total_recs * sizeof(WorkItem);
     return VA_OK;
 }
@@ -169,7 +169,7 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
     if (mask_mode != VA_MASK_CAUSAL && !prefix_lens)
         return fail(VA_EINVAL, "va_build_worklist: prefix mask needs prefix_lens");
     size_t need;
-    int rc = va_worklist_bytes(cu, n, pass, D, Hq, Hkv, &need);
+    int rc = va_worklist_size(cu, n, pass, D, Hq, Hkv, &need);
     if (rc) return rc;
     if (bytes < need) return fail(VA_ESIZE, "va_build_worklist: buffer of %zu bytes, need %zu", bytes, need);
     int32_t bm, bn;  // rows of an item, rows of the tiles it loops over
@@ -247,7 +247,7 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
             tiles_differ = tiles_differ || at->second != k.work;
         }
     }
-    if (VA_LOCALITY_SCHEDULE != 0 && tiles_differ && pass != VA_PASS_BWD_DKDV && P % kXcds == 0) {
+    if (tiles_differ && pass != VA_PASS_BWD_DKDV && P % kXcds == 0) {
         // Forward and dQ: all works of one (sample, KV head) stream the same K and V rows.  Workgroup b runs
         // on XCD b % 8, and each XCD has an L2 of its own, so those works are given to workgroups of one XCD
         // and placed at about the same position of their queues: they then run at about the same time and
