@@ -18,15 +18,15 @@
  *
  * For sample s occupying rows [c, c+L) of the stream, query head h, KV head
  * g = h / (Hq/Hkv), local query row i:
- *     vis(i) = i + 1                      causal
- *            = P  if i < P, else L        prefix-LM with prefix length P
- *            = i + 1 if i >= P (mode 2)   prefix-LM, causal suffix
- *            = P if i < P, P2 if i < P2, else L   (mode 3) three blocks, each seeing
- *              itself and the blocks before it; prefix_lens then holds the pair
- *              (P, P2), 0 <= P <= P2 <= L, for every sample
- *     (mode 4) sliding window of W = prefix_lens[s] >= 1 keys: vis(i) = i + 1 and the
- *              keys start at lo(i) = max(0, i + 1 - W) instead of 0 (lo = 0 in every other mode)
- *     s_ij  = scale * sum_d Q[c+i,h,d] K[c+j,g,d]        for lo(i) <= j < vis(i)
+ *     A(i)  = the keys j of the sample that row i may attend, by mask mode:
+ *             causal: j <= i.  Prefix-LM with prefix length P: tokens [0, P) form one block, the rest a
+ *             second one, and a row sees its own block and the block before it (a bidirectional prefix, a
+ *             suffix that sees everything).  Mode 2: the same with a causal suffix (a suffix row sees the
+ *             prefix and the suffix keys up to its own).  Mode 3: three blocks [0, P), [P, P2), [P2, L), each
+ *             seeing itself and the blocks before it; prefix_lens then holds the pair (P, P2),
+ *             0 <= P <= P2 <= L, for every sample.  Mode 4: sliding window of W = prefix_lens[s] >= 1
+ *             keys: j <= i and i - j < W.
+ *     s_ij  = scale * sum_d Q[c+i,h,d] K[c+j,g,d]        for j in A(i)
  *     m_i   = max_j s_ij,  Z_i = sum_j exp(s_ij - m_i)
  *     LSE[h,c+i] = m_i + ln Z_i
  *     p_ij  = exp(s_ij - m_i) / Z_i
@@ -59,34 +59,57 @@
 #define ORACLE_MASK_THREE_BLOCK 3
 #define ORACLE_MASK_SLIDING_WINDOW 4 /* causal, and at most the W most recent keys: j > i - W */
 
-/* number of keys query row i of a sample (length L, block ends P and P2) may attend to */
-static int visible(int i, int L, int P, int P2, int mode)
-{
-    if (mode == ORACLE_MASK_CAUSAL || mode == ORACLE_MASK_SLIDING_WINDOW) return i + 1;
-    if (i < P) return P;
-    if (mode == ORACLE_MASK_PREFIX_BIDIR_SUFFIX) return L;
-    if (mode == ORACLE_MASK_THREE_BLOCK) return i < P2 ? P2 : L;
-    return i + 1;
-}
+/*
+ * The mask as a predicate on one (query row i, key j) pair of a sample, stated through the block each token
+ * lies in: block 0 = [0, P), block 1 = [P, P2) (three-block mask only), last block = the rest.
+ *   causal            j <= i
+ *   sliding window    j <= i and i - j < W               (W = prefix_lens[s])
+ *   prefix-LM         block(j) <= block(i)               (two blocks: prefix, suffix; each bidirectional)
+ *   ... causal suffix block(j) < block(i), or both in the prefix, or both in the suffix and j <= i
+ *   three blocks      block(j) <= block(i)
+ */
+typedef struct {
+    int mode;
+    int L;
+    int P;  /* end of block 0; the window W under the sliding-window mask */
+    int P2; /* end of block 1 (three-block mask), else unused */
+} sample_mask;
 
-/* first key query row i may attend to: 0, except under the sliding window of W keys (W travels in P) */
-static int first_visible(int i, int P, int mode)
+static sample_mask mask_of_sample(const int32_t *prefix_lens, int mode, int s, int L)
 {
-    if (mode == ORACLE_MASK_SLIDING_WINDOW && i + 1 - P > 0) return i + 1 - P;
-    return 0;
-}
-
-/* block ends of sample s: prefix_lens holds one entry per sample, or the pair (P, P2) in mode 3 */
-static void block_ends(const int32_t *prefix_lens, int mode, int s, int *P, int *P2)
-{
-    *P = 0;
-    *P2 = 0;
+    sample_mask m = {mode, L, 0, 0};
     if (mode == ORACLE_MASK_THREE_BLOCK) {
-        *P = prefix_lens[2 * s];
-        *P2 = prefix_lens[2 * s + 1];
+        m.P = prefix_lens[2 * s];
+        m.P2 = prefix_lens[2 * s + 1];
     } else if (mode != ORACLE_MASK_CAUSAL) {
-        *P = prefix_lens[s];
+        m.P = prefix_lens[s];
+        m.P2 = m.P; /* two blocks: block 1 is empty */
     }
+    return m;
+}
+
+static int block_of(const sample_mask *m, int x) { return x < m->P ? 0 : x < m->P2 ? 1 : 2; }
+
+static int allowed(const sample_mask *m, int i, int j)
+{
+    switch (m->mode) {
+    case ORACLE_MASK_CAUSAL: return j <= i;
+    case ORACLE_MASK_SLIDING_WINDOW: return j <= i && i - j < m->P;
+    case ORACLE_MASK_PREFIX_BIDIR_SUFFIX:
+    case ORACLE_MASK_THREE_BLOCK: return block_of(m, j) <= block_of(m, i);
+    case ORACLE_MASK_PREFIX_CAUSAL_SUFFIX: {
+        const int bi = block_of(m, i), bj = block_of(m, j);
+        if (bj != bi) return bj < bi;
+        return bi == 0 ? 1 : j <= i;
+    }
+    default: return 0;
+    }
+}
+
+/* a[j] = 1 where query row i may attend key j, for all keys of the sample */
+static void row_mask(const sample_mask *m, int i, unsigned char *a)
+{
+    for (int j = 0; j < m->L; ++j) a[j] = (unsigned char)allowed(m, i, j);
 }
 
 int oracle_num_threads(void)
@@ -98,12 +121,13 @@ int oracle_num_threads(void)
 #endif
 }
 
-/* softmax probabilities of one query row over the keys lo .. nvis - 1; returns LSE. p[lo..nvis) filled. */
+/* softmax probabilities of one query row over the keys j < L with a[j] set; returns LSE. p[j] filled where a[j]. */
 static double row_softmax(const float *q_row, const float *k_base, size_t k_stride,
-                          int lo, int nvis, int D, double scale, double *p)
+                          const unsigned char *a, int L, int D, double scale, double *p)
 {
     double m = -INFINITY;
-    for (int j = lo; j < nvis; ++j) {
+    for (int j = 0; j < L; ++j) {
+        if (!a[j]) continue;
         const float *k_row = k_base + (size_t)j * k_stride;
         double s = 0.0;
         for (int d = 0; d < D; ++d) s += (double)q_row[d] * (double)k_row[d];
@@ -112,11 +136,13 @@ static double row_softmax(const float *q_row, const float *k_base, size_t k_stri
         if (s > m) m = s;
     }
     double Z = 0.0;
-    for (int j = lo; j < nvis; ++j) {
+    for (int j = 0; j < L; ++j) {
+        if (!a[j]) continue;
         p[j] = exp(p[j] - m);
         Z += p[j];
     }
-    for (int j = lo; j < nvis; ++j) p[j] /= Z;
+    for (int j = 0; j < L; ++j)
+        if (a[j]) p[j] /= Z;
     return m + log(Z);
 }
 
@@ -144,6 +170,7 @@ int oracle_attn_fwd(const float *q, const float *k, const float *v,
 #pragma omp parallel
     {
         double *p = (double *)malloc(sizeof(double) * (size_t)(maxL > 0 ? maxL : 1));
+        unsigned char *a = (unsigned char *)malloc((size_t)(maxL > 0 ? maxL : 1));
 #pragma omp for schedule(dynamic, 1)
         for (int w = 0; w < nwork; ++w) {
             const int s = sel ? sel[w / Hq] : w / Hq;
@@ -151,26 +178,26 @@ int oracle_attn_fwd(const float *q, const float *k, const float *v,
             const int g = h / G;
             const int c = cu_seqlens[s];
             const int L = cu_seqlens[s + 1] - c;
-            int P, P2;
-            block_ends(prefix_lens, mask_mode, s, &P, &P2);
+            const sample_mask mask = mask_of_sample(prefix_lens, mask_mode, s, L);
             for (int i = 0; i < L; ++i) {
-                const int nvis = visible(i, L, P, P2, mask_mode);
-                const int lo = first_visible(i, P, mask_mode);
+                row_mask(&mask, i, a);
                 const float *q_row = q + ((size_t)(c + i) * Hq + h) * D;
                 const float *k_base = k + ((size_t)c * Hkv + g) * D;
                 const float *v_base = v + ((size_t)c * Hkv + g) * D;
                 const size_t kv_stride = (size_t)Hkv * D;
-                double l = row_softmax(q_row, k_base, kv_stride, lo, nvis, D, scale, p);
+                double l = row_softmax(q_row, k_base, kv_stride, a, L, D, scale, p);
                 lse[(size_t)h * T + (c + i)] = l;
                 double *o_row = out + ((size_t)(c + i) * Hq + h) * D;
                 for (int d = 0; d < D; ++d) o_row[d] = 0.0;
-                for (int j = lo; j < nvis; ++j) {
+                for (int j = 0; j < L; ++j) {
+                    if (!a[j]) continue;
                     const float *v_row = v_base + (size_t)j * kv_stride;
                     for (int d = 0; d < D; ++d) o_row[d] += p[j] * (double)v_row[d];
                 }
             }
         }
         free(p);
+        free(a);
     }
     return 0;
 }
@@ -199,6 +226,7 @@ int oracle_attn_bwd(const float *q, const float *k, const float *v, const float 
     {
         double *p = (double *)malloc(sizeof(double) * (size_t)(maxL > 0 ? maxL : 1));
         double *o = (double *)malloc(sizeof(double) * (size_t)D);
+        unsigned char *a = (unsigned char *)malloc((size_t)(maxL > 0 ? maxL : 1));
 #pragma omp for schedule(dynamic, 1)
         for (int w = 0; w < nwork; ++w) {
             /* one (sample, KV head) owns its dK, dV rows: no two threads share them */
@@ -206,8 +234,7 @@ int oracle_attn_bwd(const float *q, const float *k, const float *v, const float 
             const int g = w % Hkv;
             const int c = cu_seqlens[s];
             const int L = cu_seqlens[s + 1] - c;
-            int P, P2;
-            block_ends(prefix_lens, mask_mode, s, &P, &P2);
+            const sample_mask mask = mask_of_sample(prefix_lens, mask_mode, s, L);
             const size_t kv_stride = (size_t)Hkv * D;
             const float *k_base = k + ((size_t)c * Hkv + g) * D;
             const float *v_base = v + ((size_t)c * Hkv + g) * D;
@@ -220,22 +247,23 @@ int oracle_attn_bwd(const float *q, const float *k, const float *v, const float 
                 }
             for (int h = g * G; h < (g + 1) * G; ++h) {
                 for (int i = 0; i < L; ++i) {
-                    const int nvis = visible(i, L, P, P2, mask_mode);
-                    const int lo = first_visible(i, P, mask_mode);
+                    row_mask(&mask, i, a);
                     const float *q_row = q + ((size_t)(c + i) * Hq + h) * D;
                     const float *do_row = dout + ((size_t)(c + i) * Hq + h) * D;
                     double *dq_row = dq + ((size_t)(c + i) * Hq + h) * D;
-                    row_softmax(q_row, k_base, kv_stride, lo, nvis, D, scale, p);
+                    row_softmax(q_row, k_base, kv_stride, a, L, D, scale, p);
                     /* this row's own fp64 output, then delta */
                     for (int d = 0; d < D; ++d) o[d] = 0.0;
-                    for (int j = lo; j < nvis; ++j) {
+                    for (int j = 0; j < L; ++j) {
+                        if (!a[j]) continue;
                         const float *v_row = v_base + (size_t)j * kv_stride;
                         for (int d = 0; d < D; ++d) o[d] += p[j] * (double)v_row[d];
                     }
                     double delta = 0.0;
                     for (int d = 0; d < D; ++d) delta += (double)do_row[d] * o[d];
                     for (int d = 0; d < D; ++d) dq_row[d] = 0.0;
-                    for (int j = lo; j < nvis; ++j) {
+                    for (int j = 0; j < L; ++j) {
+                        if (!a[j]) continue;
                         const float *k_row = k_base + (size_t)j * kv_stride;
                         const float *v_row = v_base + (size_t)j * kv_stride;
                         double dP = 0.0;
@@ -254,6 +282,7 @@ int oracle_attn_bwd(const float *q, const float *k, const float *v, const float 
         }
         free(p);
         free(o);
+        free(a);
     }
     return 0;
 }
@@ -272,29 +301,29 @@ int oracle_attn_probs(const float *q, const float *k, const float *v, const floa
     const int g = h / G;
     const int c = cu_seqlens[s];
     const int L = cu_seqlens[s + 1] - c;
-    int P, P2;
-    block_ends(prefix_lens, mask_mode, s, &P, &P2);
+    const sample_mask mask = mask_of_sample(prefix_lens, mask_mode, s, L);
+    unsigned char *a = (unsigned char *)malloc((size_t)(L > 0 ? L : 1));
     const size_t kv_stride = (size_t)Hkv * D;
     const float *k_base = k + ((size_t)c * Hkv + g) * D;
     const float *v_base = v + ((size_t)c * Hkv + g) * D;
     double *p = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
     double *o = (double *)malloc(sizeof(double) * (size_t)D);
     for (int i = 0; i < L; ++i) {
-        const int nvis = visible(i, L, P, P2, mask_mode);
-        const int lo = first_visible(i, P, mask_mode);
+        row_mask(&mask, i, a);
         const float *q_row = q + ((size_t)(c + i) * Hq + h) * D;
-        row_softmax(q_row, k_base, kv_stride, lo, nvis, D, scale, p);
-        for (int j = 0; j < L; ++j) p_out[(size_t)i * L + j] = j >= lo && j < nvis ? p[j] : 0.0;
+        row_softmax(q_row, k_base, kv_stride, a, L, D, scale, p);
+        for (int j = 0; j < L; ++j) p_out[(size_t)i * L + j] = a[j] ? p[j] : 0.0;
         if (ds_out) {
             const float *do_row = dout + ((size_t)(c + i) * Hq + h) * D;
             for (int d = 0; d < D; ++d) o[d] = 0.0;
-            for (int j = lo; j < nvis; ++j)
-                for (int d = 0; d < D; ++d) o[d] += p[j] * (double)v_base[(size_t)j * kv_stride + d];
+            for (int j = 0; j < L; ++j)
+                if (a[j])
+                    for (int d = 0; d < D; ++d) o[d] += p[j] * (double)v_base[(size_t)j * kv_stride + d];
             double delta = 0.0;
             for (int d = 0; d < D; ++d) delta += (double)do_row[d] * o[d];
             for (int j = 0; j < L; ++j) {
                 double dS = 0.0;
-                if (j >= lo && j < nvis) {
+                if (a[j]) {
                     double dP = 0.0;
                     for (int d = 0; d < D; ++d) dP += (double)do_row[d] * (double)v_base[(size_t)j * kv_stride + d];
                     dS = p[j] * (dP - delta);
@@ -305,5 +334,6 @@ int oracle_attn_probs(const float *q, const float *k, const float *v, const floa
     }
     free(p);
     free(o);
+    free(a);
     return 0;
 }

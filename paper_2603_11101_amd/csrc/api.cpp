@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <cstdlib>
 #include <vector>
 
 #include "kernels.h"
@@ -162,6 +163,7 @@ AttnParams base_params(const va_shape* s, float scale) {
     p.D = s->head_dim;
     p.mask_mode = s->mask_mode;
     p.scale = scale;
+    { const char* w = getenv("VA_DKDV_WALK"); p.dkdv_walk = (w && w[0] == '1') ? 1 : 0; }  // EXPERIMENT
     return p;
 }
 

@@ -159,13 +159,23 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     };
     // issues the stage after the one issued last (the first call issues step 0); returns its first query row
     auto issue_next_stage = [&](const DkdvWork& w, StageSource& src, int st_index) {
-        if (++src.qt == w.qt_count) {
-            src.qt = 0;
-            ++src.head;
+        int qt_abs;
+        if (p.dkdv_walk == 0) {
+            if (++src.qt == w.qt_count) {
+                src.qt = 0;
+                ++src.head;
+                head_buffers(w, src);
+            }
+            qt_abs = w.qt_first + src.qt;
+        } else {
+            // query tiles from the last one down, every head of the group at each tile
+            ++src.qt;  // step number
+            src.head = w.g * G + src.qt % G;
             head_buffers(w, src);
+            qt_abs = w.qt_first + w.qt_count - 1 - src.qt / G;
         }
         const unsigned st = smem_lds + st_index * STAGE_BYTES;
-        const int q0 = (w.qt_first + src.qt) * BMQ;
+        const int q0 = qt_abs * BMQ;
         loader.issue(src.q, st, q0 * q_row_bytes);
         loader.issue(src.dout, st + TILE_BYTES, q0 * q_row_bytes);
         if (wave < 2)  // 64 floats each: lane i fetches row q0 + i
@@ -200,7 +210,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         }
     };
 
-    const DkdvWork cur = fetch_dkdv_work(p, (int)blockIdx.x);
+    const DkdvWork cur = fetch_dkdv_work(p, p.work_ids[blockIdx.x]);
     int stage = 0;
     StageSource src;
     src.qt = -1;

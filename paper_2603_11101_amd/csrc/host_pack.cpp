@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <cstdlib>
 #include <map>
 #include <utility>
 #include <vector>
@@ -304,6 +305,46 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
                     std::push_heap(heap.begin(), heap.end(), heavier);
                 }
         }
+    } else if (pass == VA_PASS_BWD_DKDV) {
+        // EXPERIMENT: dispatch order of the one-work-per-workgroup kernel
+        const char* ord = getenv("VA_DKDV_ORDER");
+        std::vector<int32_t> order;
+        if (ord && ord[0] == '1' && lay.num_works > 0) {
+            struct Group { int64_t cost = 0; std::vector<int32_t> works; };
+            std::map<std::pair<int32_t, int32_t>, int32_t> index;
+            std::vector<Group> groups;
+            for (int32_t id = 0; id < lay.num_works; ++id) {
+                const std::pair<int32_t, int32_t> key(items[id / lay.works_per_item].it.w[2], id % lay.works_per_item);
+                auto at = index.find(key);
+                if (at == index.end()) { at = index.emplace(key, (int32_t)groups.size()).first; groups.emplace_back(); }
+                groups[at->second].cost += cost_of(id);
+                groups[at->second].works.push_back(id);
+            }
+            std::vector<int32_t> gorder(groups.size());
+            for (size_t i = 0; i < gorder.size(); ++i) gorder[i] = (int32_t)i;
+            std::stable_sort(gorder.begin(), gorder.end(), [&](int32_t a, int32_t b) { return groups[a].cost > groups[b].cost; });
+            int64_t xl[kXcds] = {};
+            std::vector<int32_t> q[kXcds];
+            for (int32_t gi : gorder) {
+                int32_t x = 0;
+                for (int32_t c = 1; c < kXcds; ++c) if (xl[c] < xl[x]) x = c;
+                xl[x] += groups[gi].cost;
+                for (int32_t id : groups[gi].works) q[x].push_back(id);
+            }
+            size_t head[kXcds] = {}, tail[kXcds];
+            for (int x = 0; x < kXcds; ++x) tail[x] = q[x].size();
+            for (int32_t pos = 0; pos < lay.num_works; ++pos) {
+                int x = pos % kXcds;
+                if (head[x] < tail[x]) { order.push_back(q[x][head[x]++]); continue; }
+                int best = -1;
+                for (int c = 0; c < kXcds; ++c) if (head[c] < tail[c] && (best < 0 || tail[c] - head[c] > tail[best] - head[best])) best = c;
+                order.push_back(q[best][--tail[best]]);
+            }
+        } else {
+            for (int32_t id = 0; id < lay.num_works; ++id) order.push_back(id);
+        }
+        const int32_t per = (lay.num_works + P - 1) / P;
+        for (int32_t i = 0; i < lay.num_works; ++i) mine[i / std::max(per, 1)].push_back(order[i]);
     } else {
         // Longest processing time first: works in descending cost order (ties: ascending id), each to the
         // least-loaded workgroup (ties: lowest index).

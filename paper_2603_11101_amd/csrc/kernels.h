@@ -30,6 +30,7 @@ struct AttnParams {
     int32_t num_items;
     int32_t num_workgroups;
     int32_t works_per_item;
+    int32_t dkdv_walk;  // EXPERIMENT
     int32_t T, Hq, Hkv, D;
     int32_t mask_mode;
     float scale;
