@@ -50,9 +50,38 @@ def row_dq(q, k, v, dout, scale, i, h, window=None):
     return scale * (ds @ kk)
 
 
-def key_row_dk_dv(q, k, v, dout, scale, j, g, window=None):
+def row_stats(q, k, v, dout, scale, window=None, rows_per_pass=256):
+    """(LSE [Hq, L], delta [Hq, L]) of every query row: what key_row_dk_dv needs of the rows that see a key.
+    The same definition as row_forward, evaluated for `rows_per_pass` rows at a time with a dense score
+    matrix and an explicit mask, so that a key near the start of a long sample (seen by every later row)
+    does not cost one pass over the keys per row."""
+    L, Hq, D = q.shape
+    G = Hq // k.shape[1]
+    lse = np.zeros((Hq, L))
+    delta = np.zeros((Hq, L))
+    cols = np.arange(L)
+    for h in range(Hq):
+        kk, vv = k[:, h // G].astype(np.float64), v[:, h // G].astype(np.float64)
+        for r0 in range(0, L, rows_per_pass):
+            rows = np.arange(r0, min(L, r0 + rows_per_pass))
+            s = scale * (q[rows, h].astype(np.float64) @ kk.T)
+            seen = cols[None, :] <= rows[:, None]
+            if window is not None:
+                seen &= rows[:, None] - cols[None, :] < window
+            s = np.where(seen, s, -np.inf)
+            m = s.max(axis=1)
+            e = np.exp(s - m[:, None])
+            z = e.sum(axis=1)
+            lse[h, rows] = m + np.log(z)
+            o = (e / z[:, None]) @ vv
+            delta[h, rows] = (dout[rows, h].astype(np.float64) * o).sum(axis=1)
+    return lse, delta
+
+
+def key_row_dk_dv(q, k, v, dout, scale, j, g, window=None, stats=None):
     """(dK_j [D], dV_j [D]) of key row j, KV head g: sums over every query row that sees key j and over
-    the heads of the group; LSE and delta of those rows are computed here, row by row."""
+    the heads of the group.  LSE and delta of those rows are computed here, row by row, unless `stats`
+    (the pair row_stats returns) hands them over."""
     L, Hq, D = q.shape
     G = Hq // k.shape[1]
     last = L - 1 if window is None else min(L - 1, j + window - 1)
@@ -60,6 +89,14 @@ def key_row_dk_dv(q, k, v, dout, scale, j, g, window=None):
     dv = np.zeros(D)
     kj, vj = k[j, g].astype(np.float64), v[j, g].astype(np.float64)
     for h in range(g * G, (g + 1) * G):
+        if stats is not None:
+            rows = slice(j, last + 1)
+            qi, do = q[rows, h].astype(np.float64), dout[rows, h].astype(np.float64)
+            p = np.exp(scale * (qi @ kj) - stats[0][h, rows])
+            ds = p * (do @ vj - stats[1][h, rows])
+            dk += scale * (ds @ qi)
+            dv += p @ do
+            continue
         for i in range(j, last + 1):
             o, lse = row_forward(q, k, v, scale, i, h, window)
             qi, do = q[i, h].astype(np.float64), dout[i, h].astype(np.float64)

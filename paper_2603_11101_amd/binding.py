@@ -157,7 +157,15 @@ def va_build_worklist(cu_seqlens, prefix_lens, mask_mode, pass_id, head_dim, num
 
 def worklist_items(wl):
     """Item records [num_items, 8] of a work list."""
-    return wl[wl[1, 3]:wl[1, 3] + wl[0, 6]]
+    return wl[2:2 + wl[0, 6]]
+
+
+def worklist_merges(wl):
+    """Merge records [num_merges, 8] of a dK/dV work list: one per key tile whose query tiles were cut into
+    pieces, {kv_row0, kv_rows, first partial slot, pieces, qt_first, qt_count, 0, 0}."""
+    n = int(wl[1, 7])
+    first = int(wl[1, 6]) - n
+    return wl[first:first + n]
 
 
 def worklist_schedule(wl):

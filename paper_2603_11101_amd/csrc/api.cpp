@@ -3,7 +3,6 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
-#include <cstdlib>
 #include <vector>
 
 #include "kernels.h"
@@ -66,18 +65,30 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
     const int32_t n = h[6];
     int64_t expect = 0;
     for (int32_t i = 0; i < s->num_seqs; ++i) expect += (cu[i + 1] - cu[i] + rows - 1) / rows;
-    if (n != expect) return fail(VA_EINVAL, "%s: work list holds %d items, this stream needs %lld", who, n, (long long)expect);
-    const WorklistLayout lay = worklist_layout(pass, s->head_dim, s->num_q_heads, s->num_kv_heads, n);
     const int32_t* h1 = w[1].w;
-    if (h1[0] != lay.num_workgroups || h1[1] != lay.num_works || h1[2] != lay.works_per_item || h1[3] != lay.item_rec ||
+    // split key tiles (dK/dV lists only): every piece is an item more, every split tile has a merge record
+    const int32_t max_slots = pass == VA_PASS_BWD_DKDV ? max_partial_slots(s->head_dim, s->num_kv_heads) : 0;
+    const int32_t num_merges = h1[7];
+    if (num_merges < 0 || num_merges > max_slots / 2 || n < expect || n > expect + max_slots)
+        return fail(VA_EINVAL, "%s: work list holds %d items and %d merge records, this stream has %lld tiles", who, n,
+                    num_merges, (long long)expect);
+    const WorklistLayout lay = worklist_layout(pass, s->head_dim, s->num_q_heads, s->num_kv_heads, n, num_merges);
+    if (h1[0] != lay.num_workgroups || h1[1] != lay.num_works || h1[2] != lay.works_per_item ||
+        (h1[3] & ~(pass == VA_PASS_BWD_DKDV ? kListFlagInStep : 0)) != 0 ||
         h1[4] != lay.table_rec || h1[5] != lay.id_rec || h1[6] != lay.total_recs)
         return fail(VA_EINVAL, "%s: work list schedule header does not match this call", who);
+    // pieces by partial slot: first query tile, number of query tiles, first key row (-1: slot not used)
+    int32_t piece_first[kMaxPartialSlots], piece_count[kMaxPartialSlots], piece_row0[kMaxPartialSlots];
+    for (int32_t i = 0; i < kMaxPartialSlots; ++i) piece_row0[i] = -1;
+    int32_t num_pieces = 0;
     for (int32_t i = 0; i < n; ++i) {
         const int32_t* it = w[lay.item_rec + i].w;
-        const int32_t row0 = it[0], nrows = it[1], seq0 = it[2], L = it[7];
+        const int32_t row0 = it[0], seq0 = it[2], L = it[7];
+        const int32_t nrows = pass == VA_PASS_BWD_DKDV ? dkdv_item_rows(it[1]) : it[1];
+        const int32_t slot = pass == VA_PASS_BWD_DKDV ? dkdv_item_slot(it[1]) : -1;
         const int32_t P = it[6], P2 = it[pass == VA_PASS_BWD_DKDV ? 5 : 3];
         const bool ok = nrows > 0 && nrows <= rows && seq0 >= 0 && L > 0 && row0 >= seq0 && row0 + nrows <= seq0 + L &&
-                        seq0 + L <= s->total_tokens && (row0 - seq0) % rows == 0 &&
+                        seq0 + L <= s->total_tokens && (row0 - seq0) % rows == 0 && it[1] >= 0 && slot < max_slots &&
                         (s->mask_mode == VA_MASK_CAUSAL ? P == -1 : block_ends_valid(P, P2, L, s->mask_mode)) &&
                         (s->mask_mode == VA_MASK_THREE_BLOCK || P2 == -1);
         if (!ok) return fail(VA_EINVAL, "%s: work item %d is out of bounds", who, i);
@@ -96,8 +107,17 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
             int32_t qt_end = (L + cols - 1) / cols;
             if (s->mask_mode == VA_MASK_SLIDING_WINDOW)
                 qt_end = (int32_t)(std::min<int64_t>(L - 1, (int64_t)(row0 - seq0) + nrows - 1 + Pm - 1) / cols) + 1;
-            if (it[3] < 0 || it[4] <= 0 || it[3] + it[4] != qt_end)
+            if (it[3] < 0 || it[4] <= 0 || (slot < 0 ? it[3] + it[4] != qt_end : it[3] + it[4] > qt_end))
                 return fail(VA_EINVAL, "%s: work item %d has a bad query-tile range", who, i);
+            if (slot >= 0) {
+                if (piece_row0[slot] >= 0) return fail(VA_EINVAL, "%s: partial slot %d is used by two items", who, slot);
+                piece_first[slot] = it[3];
+                piece_count[slot] = it[4];
+                piece_row0[slot] = row0;
+                ++num_pieces;
+                // the last piece of a tile must end where the whole tile ends: checked with the merge record below
+                if (it[3] + it[4] == qt_end) piece_count[slot] |= 1 << 30;
+            }
         } else {
             const int32_t r0 = row0 - seq0;
             const int32_t kv_len = visible(r0 + nrows - 1, L, Pm, P2m, s->mask_mode);
@@ -105,6 +125,30 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
                 return fail(VA_EINVAL, "%s: work item %d has a bad key range", who, i);
         }
     }
+    // Merge records: the pieces of a tile occupy consecutive slots, follow each other without gap or overlap from
+    // the tile's first query tile to its last, and share the tile's first key row; every piece belongs to one.
+    int32_t merged = 0;
+    for (int32_t m = 0; m < num_merges; ++m) {
+        const int32_t* r = w[lay.merge_rec + m].w;
+        const int32_t first = r[2], pieces = r[3];
+        if (pieces < 2 || first < 0 || first > max_slots - pieces || dkdv_item_slot(r[1]) != -1)
+            return fail(VA_EINVAL, "%s: merge record %d is out of bounds", who, m);
+        int32_t at = r[4];
+        for (int32_t j = 0; j < pieces; ++j) {
+            const int32_t sl = first + j;
+            const bool last = j == pieces - 1;
+            if (piece_row0[sl] != r[0] || piece_first[sl] != at || (piece_count[sl] >> 30 & 1) != (last ? 1 : 0))
+                return fail(VA_EINVAL, "%s: the pieces of merge record %d do not tile its query range", who, m);
+            at += piece_count[sl] & ((1 << 30) - 1);
+            piece_row0[sl] = -2;  // taken
+        }
+        if (at != r[4] + r[5] || dkdv_item_rows(r[1]) <= 0 || dkdv_item_rows(r[1]) > rows)
+            return fail(VA_EINVAL, "%s: merge record %d has a bad range", who, m);
+        merged += pieces;
+    }
+    if (merged != num_pieces || n - num_pieces + num_merges != expect)
+        return fail(VA_EINVAL, "%s: work list holds %d items (%d pieces, %d merge records), this stream has %lld tiles", who,
+                    n, num_pieces, num_merges, (long long)expect);
     const int32_t* table = w[lay.table_rec].w;
     const int32_t* ids = w[lay.id_rec].w;
     // one bit per work; the buffer belongs to the thread and only ever grows, so a launch allocates nothing
@@ -136,6 +180,7 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
     }
     if (at != lay.num_works) return fail(VA_EINVAL, "%s: workgroup table does not partition the works", who);
     *layout = lay;
+    layout->flags = h1[3];
     return VA_OK;
 }
 
@@ -147,6 +192,9 @@ void set_worklist(AttnParams* p, const void* dev, const WorklistLayout& lay) {
     p->num_items = lay.num_items;
     p->num_workgroups = lay.num_workgroups;
     p->works_per_item = lay.works_per_item;
+    p->merges = recs + lay.merge_rec;
+    p->num_merges = lay.num_merges;
+    p->dkdv_by_ids = (lay.flags & kListFlagInStep) ? 1 : 0;
 }
 
 int check_scale(float scale, const char* who) {
@@ -163,11 +211,15 @@ AttnParams base_params(const va_shape* s, float scale) {
     p.D = s->head_dim;
     p.mask_mode = s->mask_mode;
     p.scale = scale;
-    { const char* w = getenv("VA_DKDV_WALK"); p.dkdv_walk = (w && w[0] == '1') ? 1 : 0; }  // EXPERIMENT
     return p;
 }
 
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// bytes of the two per-row arrays at the start of the backward workspace
+size_t row_stats_bytes(const va_shape* s) {
+    return 2 * round_up((size_t)s->total_tokens * (size_t)s->num_q_heads * sizeof(float), 256);
+}
 
 }  // namespace
 
@@ -175,8 +227,10 @@ extern "C" {
 
 size_t varlen_attn_bwd_workspace_bytes(const va_shape* s) {
     if (!s || s->total_tokens < 0 || s->num_q_heads <= 0) return 0;
-    // delta = rowsum(dO * O) and LSE * log2(e), float32 [Hq, T] each
-    return 2 * round_up((size_t)s->total_tokens * (size_t)s->num_q_heads * sizeof(float), 256);
+    if (s->num_kv_heads <= 0 || !head_dim_supported(s->head_dim)) return 0;
+    // delta = rowsum(dO * O) and LSE * log2(e), float32 [Hq, T] each, then the partial-sum slots of split key tiles
+    return row_stats_bytes(s) + (size_t)max_partial_slots(s->head_dim, s->num_kv_heads) *
+                                    (size_t)partial_slot_bytes(s->head_dim, s->num_kv_heads);
 }
 
 int varlen_attn_fwd(const void* q, const void* k, const void* v,
@@ -242,7 +296,8 @@ static int prepare_bwd(const char* who, const void* q, const void* k, const void
     p->dk = dk;
     p->dv = dv;
     p->delta = static_cast<float*>(workspace);
-    p->lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + varlen_attn_bwd_workspace_bytes(shape) / 2);
+    p->lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + row_stats_bytes(shape) / 2);
+    p->partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + row_stats_bytes(shape));
     return VA_OK;
 }
 

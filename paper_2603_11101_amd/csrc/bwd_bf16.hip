@@ -82,13 +82,15 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
 // What one workgroup needs to know about a dK/dV work (all wave-uniform).
 struct DkdvWork {
     int kv_row0, kv_rows, seq_row0, qt_first, qt_count, P2, P, L, g;
+    int slot;  // partial-sum slot of a piece of a split key tile, -1 for a work that writes dK and dV itself
 };
 
 VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int id) {
     const WorkItem it = p.items[id / p.works_per_item];
     DkdvWork w;
     w.kv_row0 = it.w[0];
-    w.kv_rows = it.w[1];
+    w.kv_rows = dkdv_item_rows(it.w[1]);
+    w.slot = dkdv_item_slot(it.w[1]);
     w.seq_row0 = it.w[2];
     w.qt_first = it.w[3];
     w.qt_count = it.w[4];
@@ -99,7 +101,66 @@ VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int id) {
     return w;
 }
 
-// dK/dV kernel, one work per workgroup, launched heaviest first.  A work is one key tile of 128 rows of
+// This wave's 32 key rows of dK and dV (KV head g of the tile starting at row kv_row0), from the transposed
+// accumulators through `stage` (32 * D * 2 bytes of LDS of the wave's own) out as whole rows; rows past
+// kv_rows are dropped by the buffer's range check.
+template <int D, int DR, int DT = (DR + 31) / 32>
+VA_DEV void store_dkdv_rows(const AttnParams& p, char* stage, int kv_row0, int kv_rows, int g, int wave, int lane,
+                            const f32x16 (&dk)[DT], const f32x16 (&dv)[DT]) {
+    using Rows = RowBlock<D, DR>;
+    const int rows_here = min(max(kv_rows - 32 * wave, 0), 32);
+    const size_t off = ((size_t)(kv_row0 + 32 * wave) * p.Hkv + g) * DR;
+    const int row_bytes = p.Hkv * DR * 2;
+    const unsigned bytes = rows_here > 0 ? (unsigned)(rows_here - 1) * row_bytes + DR * 2 : 0u;
+    const int lane_off = Rows::lane_offset(lane, row_bytes);
+    auto soff = [&](int j) { return j * Rows::RPI * row_bytes; };
+    store_block_rows<D, DT>(stage, dk, p.scale, lane, Rows::rows(static_cast<__bf16*>(p.dk) + off, bytes), lane_off, soff);
+    __builtin_amdgcn_sched_barrier(0);
+    store_block_rows<D, DT>(stage, dv, 1.0f, lane, Rows::rows(static_cast<__bf16*>(p.dv) + off, bytes), lane_off, soff);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Partial sums of a split key tile.  A slot holds, per KV head, dK then dV of the tile in the order the
+// accumulators hold them: [wave][32-column block dt][register quad q][lane] float4, so that a wave
+// instruction moves 1 KiB of consecutive memory.  The merge kernel reads with the same mapping.
+template <int D>
+VA_DEV float* partial_slot(const AttnParams& p, int slot, int g) {
+    return p.partials + ((size_t)slot * p.Hkv + g) * (2 * kDkdvKvRows * D);
+}
+template <int D, int DT>
+VA_DEV void store_partial(float* slot, int wave, int lane, const f32x16 (&dk)[DT], const f32x16 (&dv)[DT]) {
+#pragma unroll
+    for (int which = 0; which < 2; ++which)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x16& a = which ? dv[dt] : dk[dt];
+                const f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+                float* dst = slot + which * (kDkdvKvRows * D) + ((wave * (D / 32) + dt) * 4 + q) * 256 + lane * 4;
+                *reinterpret_cast<f32x4*>(dst) = v;
+            }
+}
+// acc = (first ? 0 : acc) + the slot's values
+template <int D, int DT>
+VA_DEV void add_partial(const float* slot, int wave, int lane, bool first, f32x16 (&dk)[DT], f32x16 (&dv)[DT]) {
+#pragma unroll
+    for (int which = 0; which < 2; ++which)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float* src = slot + which * (kDkdvKvRows * D) + ((wave * (D / 32) + dt) * 4 + q) * 256 + lane * 4;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(src);
+                f32x16& a = which ? dv[dt] : dk[dt];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[4 * q + e] = first ? v[e] : a[4 * q + e] + v[e];
+            }
+}
+
+// dK/dV kernel, one work per workgroup: in item order (heaviest first), or, where the list says so
+// (dkdv_by_ids), in the order of its id array, which places the key tiles of one (sample, KV head) next to
+// each other on one XCD.  A work is one key tile of 128 rows of
 // one KV head; each wave owns 32 key rows and keeps their K fragments in registers.  The workgroup walks
 // over the query tiles that see the key tile, for every query head of the group, staging Q, dO, LSE and
 // delta in two LDS stages that are filled asynchronously one step ahead.  (A persistent form that
@@ -117,7 +178,6 @@ template <int D, bool V_LDS, int FAMILY, int DR>
 __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnParams p) {
     constexpr bool THREE = FAMILY == 1, WINDOW = FAMILY == 2;
     static_assert(DR % 16 == 0 && DR <= D && DR > D / 2, "head dimension and geometry do not match");
-    using Rows = RowBlock<D, DR>;
     constexpr bool V_IN_LDS = V_LDS, V_REGS = !V_LDS;
     constexpr int BMQ = dkdv_q_tile(D);  // query rows staged per step
     constexpr int QB = BMQ / 32;         // 32-row query blocks per step
@@ -141,13 +201,11 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     loader.init(wave, lane, q_row_bytes);
     const FragAddr<D> fa(lane);
 
-    // Step n of a work is query tile qt_first + n % qt_count of head g * G + n / qt_count.  Q and dO rows
+    // Step n of a work is query tile qt_first + qt_count - 1 - n / G of head g * G + n % G.  Q and dO rows
     // of (sample, head) and the LSE / delta rows are raw buffers: anything past the sample reads as zero.
-    // The buffers only change with the head, so they are rebuilt when the tile index wraps and a step
-    // costs a handful of scalar instructions instead of two divisions and four 64-bit address sums.
     struct StageSource {
         i32x4 q, dout, aux;  // aux: LSE rows for wave 0, delta rows for wave 1
-        int qt;              // query tile of the stage issued last, relative to qt_first
+        int step;            // number of the stage issued last
         int head;
     };
     auto head_buffers = [&](const DkdvWork& w, StageSource& src) {
@@ -159,23 +217,16 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     };
     // issues the stage after the one issued last (the first call issues step 0); returns its first query row
     auto issue_next_stage = [&](const DkdvWork& w, StageSource& src, int st_index) {
-        int qt_abs;
-        if (p.dkdv_walk == 0) {
-            if (++src.qt == w.qt_count) {
-                src.qt = 0;
-                ++src.head;
-                head_buffers(w, src);
-            }
-            qt_abs = w.qt_first + src.qt;
-        } else {
-            // query tiles from the last one down, every head of the group at each tile
-            ++src.qt;  // step number
-            src.head = w.g * G + src.qt % G;
-            head_buffers(w, src);
-            qt_abs = w.qt_first + w.qt_count - 1 - src.qt / G;
-        }
+        // Query tiles from the last one down, every head of the group at each tile: the key tiles of one
+        // sample, where they run next to each other on one XCD, then read the same Q and dO rows at about the
+        // same time, whatever their number of query tiles.  One order for every list, so that the sums do not
+        // depend on how a list was scheduled.  src.step counts the steps.
+        ++src.step;
+        src.head = w.g * G + src.step % G;
+        head_buffers(w, src);
+        const int qt = w.qt_count - 1 - src.step / G;
         const unsigned st = smem_lds + st_index * STAGE_BYTES;
-        const int q0 = qt_abs * BMQ;
+        const int q0 = (w.qt_first + qt) * BMQ;
         loader.issue(src.q, st, q0 * q_row_bytes);
         loader.issue(src.dout, st + TILE_BYTES, q0 * q_row_bytes);
         if (wave < 2)  // 64 floats each: lane i fetches row q0 + i
@@ -210,10 +261,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         }
     };
 
-    const DkdvWork cur = fetch_dkdv_work(p, p.work_ids[blockIdx.x]);
+    const DkdvWork cur = fetch_dkdv_work(p, p.dkdv_by_ids ? p.work_ids[blockIdx.x] : (int)blockIdx.x);
     int stage = 0;
     StageSource src;
-    src.qt = -1;
+    src.step = -1;
     src.head = cur.g * G;
     head_buffers(cur, src);
     int q0_next = issue_next_stage(cur, src, 0);  // first query row of the stage in flight
@@ -392,23 +443,30 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 
         // dK and dV leave as whole rows through the V-tile region; every wave must be done with it first
         __syncthreads();
-        {
-            char* out_stage = smem + AUX + wave * (32 * D * 2);
-            // this wave's 32 key rows of KV head g, as far as the sample goes
-            const int rows_here = min(max(cur.kv_rows - 32 * wave, 0), 32);
-            const size_t off = ((size_t)(cur.kv_row0 + 32 * wave) * p.Hkv + cur.g) * DR;
-            const int row_bytes = p.Hkv * DR * 2;
-            const unsigned bytes = rows_here > 0 ? (unsigned)(rows_here - 1) * row_bytes + DR * 2 : 0u;
-            const int lane_off = Rows::lane_offset(lane, row_bytes);
-            auto soff = [&](int j) { return j * Rows::RPI * row_bytes; };
-            store_block_rows<D, DT>(out_stage, dk, p.scale, lane,
-                                    Rows::rows(static_cast<__bf16*>(p.dk) + off, bytes), lane_off, soff);
-            __builtin_amdgcn_sched_barrier(0);
-            store_block_rows<D, DT>(out_stage, dv, 1.0f, lane,
-                                    Rows::rows(static_cast<__bf16*>(p.dv) + off, bytes), lane_off, soff);
-            __builtin_amdgcn_sched_barrier(0);
+        if (cur.slot < 0) {
+            store_dkdv_rows<D, DR>(p, smem + AUX + wave * (32 * D * 2), cur.kv_row0, cur.kv_rows, cur.g, wave, lane, dk, dv);
+        } else {
+            // a piece of a split key tile: the accumulators as they are, float32, into its slot
+            store_partial<D, DT>(partial_slot<D>(p, cur.slot, cur.g), wave, lane, dk, dv);
         }
     }
+}
+
+// Merge kernel of the split key tiles: one workgroup per (merge record, KV head) adds the pieces of the tile
+// in slot order, every lane the registers it would have held in the dK/dV kernel, and writes dK and dV the
+// way that kernel does.  The order is fixed, so the sums do not depend on scheduling.
+template <int D, int DR>
+__global__ __launch_bounds__(256) void bwd_dkdv_merge_kernel(AttnParams p) {
+    constexpr int DT = (DR + 31) / 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = (int)blockIdx.x / p.Hkv, g = (int)blockIdx.x % p.Hkv;
+    const WorkItem rec = p.merges[m];
+    const int kv_row0 = rec.w[0], kv_rows = dkdv_item_rows(rec.w[1]), first = rec.w[2], pieces = rec.w[3];
+    f32x16 dk[DT], dv[DT];
+    add_partial<D, DT>(partial_slot<D>(p, first, g), wave, lane, true, dk, dv);
+    for (int j = 1; j < pieces; ++j) add_partial<D, DT>(partial_slot<D>(p, first + j, g), wave, lane, false, dk, dv);
+    store_dkdv_rows<D, DR>(p, smem + wave * (32 * D * 2), kv_row0, kv_rows, g, wave, lane, dk, dv);
 }
 
 // One work per workgroup, in item order (heaviest first).
@@ -436,6 +494,12 @@ hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
         e = launch(std::integral_constant<int, 0>{});
     }
     if (e != hipSuccess) return e;
+    e = hipGetLastError();
+    if (e != hipSuccess || p.num_merges == 0) return e;
+    constexpr size_t merge_smem = 4 * 32 * D * 2;  // one staging slice per wave
+    const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dkdv_merge_kernel<D, DR>), merge_smem);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((bwd_dkdv_merge_kernel<D, DR>), dim3((unsigned)(p.num_merges * p.Hkv)), dim3(256), merge_smem, stream, p);
     return hipGetLastError();
 }
 

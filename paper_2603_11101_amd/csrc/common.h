@@ -15,24 +15,32 @@ struct WorkItem {
 };
 static_assert(sizeof(WorkItem) == 32, "work items are 32 bytes");
 
-constexpr int32_t kWorklistMagic = 0x56415733;  // "VAW3"
+constexpr int32_t kWorklistMagic = 0x56415734;  // "VAW4"
 
 // Work-list layout, in 32-byte records:
 //   record 0   {magic, pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
-//   record 1   {num_workgroups, num_works, works_per_item, first item record (2), first table record,
-//               first work-id record, total records, 0}
+//   record 1   {num_workgroups, num_works, works_per_item, flags, first table record,
+//               first work-id record, total records, number of merge records}
+//              (items start at record 2; flags: kListFlagInStep)
 //   items      num_items records, heaviest first
 //   table      two records per persistent workgroup: the item of its first work; then {id of that work,
 //              id of its second work, first schedule position, number of works, 0, 0, 0, 0}
 //   work ids   num_works words, 8 per record: item * works_per_item + head chunk, grouped by workgroup
+//   merges     (dK/dV lists only) one record per key tile whose query tiles were split over several items:
+//              {kv_row0, kv_rows, first partial slot, number of pieces, qt_first, qt_count, 0, 0}
 // A work is one item for one head chunk (forward, dQ: the query heads a workgroup stacks; dK/dV: one
 // KV head).  The kernels are launched with num_workgroups persistent workgroups; the table is a
 // longest-processing-time-first assignment of the works to them, computed on the host.
 constexpr int32_t kTableWordsPerWorkgroup = 16;
+// dK/dV list: workgroup b runs the work at position b of the id array (not work b): the order that keeps the
+// key tiles of one (sample, KV head) next to each other on one XCD
+constexpr int32_t kListFlagInStep = 1;
 
 struct WorklistLayout {
     int32_t num_workgroups, num_works, works_per_item, num_items;
     int32_t item_rec, table_rec, id_rec, total_recs;
+    int32_t num_merges, merge_rec;
+    int32_t flags;  // of the list at hand (filled when a list is checked)
 };
 
 // Tile geometry.  A forward / dQ workgroup owns kFwdBlockRows rows of the
@@ -46,6 +54,17 @@ constexpr int32_t kDqKvTile = 64;
 // A dK/dV workgroup owns kDkdvKvRows key rows of one KV head and visits the
 // query rows that see them kDkdvQTile rows at a time, for every head of the group.
 constexpr int32_t kDkdvKvRows = 128;
+// Split key tiles of the dK/dV pass.  Where a few heavy works would leave most of the chip idle at the end
+// of the kernel, the host cuts the query tiles of a key tile into pieces; every piece is an item of its
+// own whose workgroups write float32 partial sums of dK and dV into a slot of the caller's workspace, and
+// a merge kernel adds the pieces of a tile in slot order.  Word 1 of a dK/dV item is
+// kv_rows | (slot + 1) << 8, slot + 1 = 0 for an item that writes dK and dV itself.
+// A slot holds dK then dV of one key tile for every KV head: Hkv * 2 * kDkdvKvRows * geometry floats.
+constexpr int64_t kPartialBudgetBytes = 16 << 20;
+constexpr int32_t kMinPartialSlots = 4, kMaxPartialSlots = 64, kMaxPiecesPerTile = 16;
+constexpr int32_t dkdv_item_rows(int32_t w1) { return w1 & 0xff; }
+constexpr int32_t dkdv_item_slot(int32_t w1) { return (w1 >> 8) - 1; }
+
 // Head dimensions the kernels exist for, and the geometry (values per row of the LDS tiles and register
 // blocks) each runs on: 80, the head dimension of the vision encoder the paper trains (section 2.2.1 (1)),
 // uses the geometry of 128 with 5 of 8 contraction steps and 3 of 4 output blocks; the other values in
@@ -55,6 +74,13 @@ constexpr bool head_dim_supported(int32_t D) {
 }
 constexpr int32_t tile_geometry(int32_t D) { return D <= 64 ? 64 : D <= 128 ? 128 : 256; }
 constexpr int32_t dkdv_q_tile(int32_t D) { return tile_geometry(D) >= 128 ? 32 : 64; }
+constexpr int64_t partial_slot_bytes(int32_t D, int32_t Hkv) {
+    return (int64_t)Hkv * 2 * kDkdvKvRows * tile_geometry(D) * (int64_t)sizeof(float);
+}
+constexpr int32_t max_partial_slots(int32_t D, int32_t Hkv) {
+    const int64_t fit = kPartialBudgetBytes / partial_slot_bytes(D, Hkv);
+    return (int32_t)(fit < kMinPartialSlots ? kMinPartialSlots : fit > kMaxPartialSlots ? kMaxPartialSlots : fit);
+}
 
 // Whether the dQ kernel computes delta = rowsum(dO * O) and LSE * log2(e) itself (and then runs before
 // the dK/dV kernel, which reads both) instead of a separate pass over O and dO.
@@ -102,7 +128,7 @@ inline bool block_ends_valid(int32_t P, int32_t P2, int32_t L, int32_t mode) {
 
 extern thread_local char g_error[512];
 int works_per_item(int32_t pass, int32_t Hq, int32_t Hkv);
-WorklistLayout worklist_layout(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t num_items);
+WorklistLayout worklist_layout(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t num_items, int32_t num_merges = 0);
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int heads_per_block(int32_t Hq, int32_t Hkv);
 int tile_shape(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t* rows, int32_t* cols);

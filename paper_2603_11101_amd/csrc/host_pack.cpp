@@ -11,7 +11,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
-#include <cstdlib>
+#include <functional>
 #include <map>
 #include <utility>
 #include <vector>
@@ -63,7 +63,7 @@ int works_per_item(int32_t pass, int32_t Hq, int32_t Hkv) {
     return Hkv * ((Hq / Hkv) / heads_per_block(Hq, Hkv));
 }
 
-WorklistLayout worklist_layout(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t num_items) {
+WorklistLayout worklist_layout(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv, int32_t num_items, int32_t num_merges) {
     WorklistLayout l;
     l.num_workgroups = persistent_workgroups(pass, D);
     l.works_per_item = works_per_item(pass, Hq, Hkv);
@@ -72,13 +72,84 @@ WorklistLayout worklist_layout(int32_t pass, int32_t D, int32_t Hq, int32_t Hkv,
     l.item_rec = 2;
     l.table_rec = l.item_rec + num_items;
     l.id_rec = l.table_rec + l.num_workgroups * (kTableWordsPerWorkgroup / 8);
-    l.total_recs = l.id_rec + (l.num_works + 7) / 8;
+    l.num_merges = num_merges;
+    l.flags = 0;
+    l.merge_rec = l.id_rec + (l.num_works + 7) / 8;
+    l.total_recs = l.merge_rec + num_merges;
     return l;
 }
 
 }  // namespace va
 
 using namespace va;
+
+namespace {
+
+struct Keyed {
+    int32_t work;  // inner-loop steps of the item per head (the order of the list)
+    WorkItem it;
+};
+
+// dK/dV pass: one workgroup runs one work, and the hardware hands the works to free workgroup slots in list
+// order (heaviest first).  With few heavy works per slot the last round can leave most slots idle (257 equal
+// works on 256 slots take two rounds).  This routine replays that dispatch on `slots` slots and, while the
+// work that finishes last ends later than 1.04 times the lower bound max(mean load, heaviest work) (and, to
+// begin with, later than 1.1 times), cuts the query tiles of its key tile into pieces of about an eighth of
+// the lower bound each.  A piece is an item of its own with a partial-sum slot; `merges` receives one record
+// per split tile.  At most max_slots pieces in all.
+void split_late_tiles(std::vector<Keyed>& items, std::vector<WorkItem>& merges, int32_t G, int32_t Hkv,
+                      int32_t slots, int32_t max_slots) {
+    auto cost = [&](const Keyed& k) { return (int64_t)k.work * G + kWorkFixedCost; };
+    auto heavier = [](const Keyed& a, const Keyed& b) { return a.work > b.work; };
+    int32_t used = 0;
+    std::vector<int64_t> heap;
+    for (int32_t round = 0; round < max_slots; ++round) {
+        std::stable_sort(items.begin(), items.end(), heavier);
+        int64_t total = 0, heaviest = 0, last_finish = 0;
+        int32_t last_item = -1;
+        heap.assign((size_t)slots, 0);  // min-heap of slot loads (all zero: already a heap)
+        for (size_t i = 0; i < items.size(); ++i)
+            for (int32_t g = 0; g < Hkv; ++g) {
+                const int64_t c = cost(items[i]);
+                std::pop_heap(heap.begin(), heap.end(), std::greater<int64_t>());
+                const int64_t finish = heap.back() + c;
+                heap.back() = finish;
+                std::push_heap(heap.begin(), heap.end(), std::greater<int64_t>());
+                total += c;
+                heaviest = std::max(heaviest, c);
+                if (finish > last_finish) {
+                    last_finish = finish;
+                    last_item = (int32_t)i;
+                }
+            }
+        if (last_item < 0) return;
+        const int64_t bound = std::max((total + slots - 1) / slots, heaviest);
+        if (last_finish * 100 <= bound * (used == 0 ? 110 : 104)) return;
+        Keyed& k = items[(size_t)last_item];
+        if (dkdv_item_slot(k.it.w[1]) >= 0) return;  // a piece is not split again
+        const int32_t n = k.it.w[4];                  // query tiles of the item
+        const int32_t per = (int32_t)std::max<int64_t>(1, bound / 8 / G);
+        const int32_t pieces = std::min({(n + per - 1) / per, kMaxPiecesPerTile, max_slots - used});
+        if (pieces < 2) return;
+        const Keyed whole = k;
+        merges.push_back({{whole.it.w[0], whole.it.w[1], used, pieces, whole.it.w[3], whole.it.w[4], 0, 0}});
+        int32_t at = whole.it.w[3];
+        for (int32_t j = 0; j < pieces; ++j) {
+            const int32_t count = n / pieces + (j < n % pieces ? 1 : 0);
+            Keyed piece = whole;
+            piece.work = count;
+            piece.it.w[1] = whole.it.w[1] | (used + j + 1) << 8;
+            piece.it.w[3] = at;
+            piece.it.w[4] = count;
+            at += count;
+            if (j == 0) items[(size_t)last_item] = piece;
+            else items.push_back(piece);
+        }
+        used += pieces;
+    }
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -156,8 +227,10 @@ int va_worklist_size(const int32_t* cu, int32_t n, int32_t pass, int32_t D,
     if (rc) return rc;
     int64_t items = 0;
     for (int32_t s = 0; s < n; ++s) items += (cu[s + 1] - cu[s] + rows - 1) / rows;
-    if (items * works_per_item(pass, Hq, Hkv) > INT32_MAX / 2) return fail(VA_ESIZE, "va_worklist_size: too many works");
-    *bytes = (size_t)worklist_layout(pass, D, Hq, Hkv, (int32_t)items).total_recs * sizeof(WorkItem);
+    // a dK/dV list may hold split key tiles: every piece is one more item, every split tile one merge record
+    const int32_t extra = pass == VA_PASS_BWD_DKDV ? max_partial_slots(D, Hkv) : 0;
+    if ((items + extra) * works_per_item(pass, Hq, Hkv) > INT32_MAX / 2) return fail(VA_ESIZE, "va_worklist_size: too many works");
+    *bytes = (size_t)worklist_layout(pass, D, Hq, Hkv, (int32_t)items + extra, extra / 2).total_recs * sizeof(WorkItem);
     return VA_OK;
 }
 
@@ -176,11 +249,8 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
     int32_t bm, bn;  // rows of an item, rows of the tiles it loops over
     tile_shape(pass, D, Hq, Hkv, &bm, &bn);
 
-    struct Keyed {
-        int32_t work;
-        WorkItem it;
-    };
     std::vector<Keyed> items;
+    std::vector<WorkItem> merges;
     for (int32_t s = 0; s < n; ++s) {
         const int32_t c = cu[s], L = cu[s + 1] - c;
         int32_t P, P2;
@@ -220,14 +290,17 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
             }
         }
     }
+    if (pass == VA_PASS_BWD_DKDV)
+        split_late_tiles(items, merges, Hq / Hkv, Hkv, persistent_workgroups(pass, D), max_partial_slots(D, Hkv));
     std::stable_sort(items.begin(), items.end(), [](const Keyed& a, const Keyed& b) { return a.work > b.work; });
-    const WorklistLayout lay = worklist_layout(pass, D, Hq, Hkv, (int32_t)items.size());
+    const WorklistLayout lay = worklist_layout(pass, D, Hq, Hkv, (int32_t)items.size(), (int32_t)merges.size());
     WorkItem* out = static_cast<WorkItem*>(host_out);
-    std::memset(out, 0, (size_t)lay.total_recs * sizeof(WorkItem));
+    std::memset(out, 0, need);
     out[0] = {{kWorklistMagic, pass, bm, bn, D, mask_mode, lay.num_items, cu[n]}};
-    out[1] = {{lay.num_workgroups, lay.num_works, lay.works_per_item, lay.item_rec, lay.table_rec, lay.id_rec,
-               lay.total_recs, 0}};
+    out[1] = {{lay.num_workgroups, lay.num_works, lay.works_per_item, 0 /* flags, set below */, lay.table_rec, lay.id_rec,
+               lay.total_recs, lay.num_merges}};
     for (size_t i = 0; i < items.size(); ++i) out[lay.item_rec + i] = items[i].it;
+    for (size_t i = 0; i < merges.size(); ++i) out[lay.merge_rec + i] = merges[i];
 
     // Assignment of the works to the persistent workgroups.  cost(work) = its inner-loop steps plus a fixed
     // part; items are sorted by cost and every work of an item costs the same, so id order is cost order.
@@ -306,45 +379,82 @@ int va_build_worklist(const int32_t* cu, const int32_t* prefix_lens, int32_t n,
                 }
         }
     } else if (pass == VA_PASS_BWD_DKDV) {
-        // EXPERIMENT: dispatch order of the one-work-per-workgroup kernel
-        const char* ord = getenv("VA_DKDV_ORDER");
-        std::vector<int32_t> order;
-        if (ord && ord[0] == '1' && lay.num_works > 0) {
-            struct Group { int64_t cost = 0; std::vector<int32_t> works; };
-            std::map<std::pair<int32_t, int32_t>, int32_t> index;
+        // One work per workgroup; workgroup b of the launch runs on XCD b % 8 and takes the work at position b
+        // of the id array.  Item order (heaviest first) balances best but spreads the key tiles of a sample
+        // over all XCDs and over the run of the kernel, so that every tile fetches the sample's Q and dO rows
+        // again (measured: 3.4 times the rows on heavy-tailed lengths).  The other order keeps the tiles of
+        // one (sample, KV head) on one XCD, next to each other, heaviest sample first; the kernel walks the
+        // query tiles downwards, so those tiles then read the same rows at the same time.  It is taken
+        // where a replay of the hardware's dispatch says it ends within 3 % of the item order.
+        std::vector<int32_t> order((size_t)lay.num_works);
+        for (int32_t id = 0; id < lay.num_works; ++id) order[id] = id;
+        if (P % kXcds == 0 && lay.num_works > 0) {
+            struct Group {
+                int64_t cost = 0;
+                std::vector<int32_t> works;
+            };
+            std::map<std::pair<int32_t, int32_t>, int32_t> index;  // (sample's first row, KV head) -> group
             std::vector<Group> groups;
             for (int32_t id = 0; id < lay.num_works; ++id) {
                 const std::pair<int32_t, int32_t> key(items[id / lay.works_per_item].it.w[2], id % lay.works_per_item);
                 auto at = index.find(key);
-                if (at == index.end()) { at = index.emplace(key, (int32_t)groups.size()).first; groups.emplace_back(); }
+                if (at == index.end()) {
+                    at = index.emplace(key, (int32_t)groups.size()).first;
+                    groups.emplace_back();
+                }
                 groups[at->second].cost += cost_of(id);
                 groups[at->second].works.push_back(id);
             }
-            std::vector<int32_t> gorder(groups.size());
-            for (size_t i = 0; i < gorder.size(); ++i) gorder[i] = (int32_t)i;
-            std::stable_sort(gorder.begin(), gorder.end(), [&](int32_t a, int32_t b) { return groups[a].cost > groups[b].cost; });
-            int64_t xl[kXcds] = {};
-            std::vector<int32_t> q[kXcds];
-            for (int32_t gi : gorder) {
+            std::vector<int32_t> by_cost(groups.size());
+            for (size_t i = 0; i < by_cost.size(); ++i) by_cost[i] = (int32_t)i;
+            std::stable_sort(by_cost.begin(), by_cost.end(), [&](int32_t a, int32_t b) { return groups[a].cost > groups[b].cost; });
+            int64_t xcd_load[kXcds] = {};
+            std::vector<int32_t> queue[kXcds];
+            for (int32_t gi : by_cost) {
                 int32_t x = 0;
-                for (int32_t c = 1; c < kXcds; ++c) if (xl[c] < xl[x]) x = c;
-                xl[x] += groups[gi].cost;
-                for (int32_t id : groups[gi].works) q[x].push_back(id);
+                for (int32_t c = 1; c < kXcds; ++c)
+                    if (xcd_load[c] < xcd_load[x]) x = c;
+                xcd_load[x] += groups[gi].cost;
+                queue[x].insert(queue[x].end(), groups[gi].works.begin(), groups[gi].works.end());
             }
+            // position 8 k + x is the k-th work of XCD x; an XCD that has run out takes from the end of the
+            // queue that has most left
+            std::vector<int32_t> local;
             size_t head[kXcds] = {}, tail[kXcds];
-            for (int x = 0; x < kXcds; ++x) tail[x] = q[x].size();
+            for (int32_t x = 0; x < kXcds; ++x) tail[x] = queue[x].size();
             for (int32_t pos = 0; pos < lay.num_works; ++pos) {
-                int x = pos % kXcds;
-                if (head[x] < tail[x]) { order.push_back(q[x][head[x]++]); continue; }
-                int best = -1;
-                for (int c = 0; c < kXcds; ++c) if (head[c] < tail[c] && (best < 0 || tail[c] - head[c] > tail[best] - head[best])) best = c;
-                order.push_back(q[best][--tail[best]]);
+                const int32_t x = pos % kXcds;
+                if (head[x] < tail[x]) {
+                    local.push_back(queue[x][head[x]++]);
+                    continue;
+                }
+                int32_t most = -1;
+                for (int32_t c = 0; c < kXcds; ++c)
+                    if (head[c] < tail[c] && (most < 0 || tail[c] - head[c] > tail[most] - head[most])) most = c;
+                local.push_back(queue[most][--tail[most]]);
             }
-        } else {
-            for (int32_t id = 0; id < lay.num_works; ++id) order.push_back(id);
+            // replay of the dispatch: every XCD hands its positions, in order, to the least-loaded of its slots
+            auto finish_time = [&](const std::vector<int32_t>& ord) {
+                const int32_t per_xcd = P / kXcds;
+                std::vector<int64_t> heap((size_t)P, 0);  // kXcds min-heaps of per_xcd slot loads
+                int64_t finish = 0;
+                for (int32_t pos = 0; pos < lay.num_works; ++pos) {
+                    const auto first = heap.begin() + (pos % kXcds) * per_xcd, last = first + per_xcd;
+                    std::pop_heap(first, last, std::greater<int64_t>());
+                    *(last - 1) += cost_of(ord[pos]);
+                    finish = std::max(finish, *(last - 1));
+                    std::push_heap(first, last, std::greater<int64_t>());
+                }
+                return finish;
+            };
+            if (finish_time(local) * 100 <= finish_time(order) * 103) {
+                order.swap(local);
+                out[1].w[3] |= kListFlagInStep;
+            }
         }
-        const int32_t per = (lay.num_works + P - 1) / P;
-        for (int32_t i = 0; i < lay.num_works; ++i) mine[i / std::max(per, 1)].push_back(order[i]);
+        // the table is not used by this pass; it holds the order in equal runs so that it still partitions the ids
+        const int32_t per = std::max(1, (lay.num_works + P - 1) / P);
+        for (int32_t i = 0; i < lay.num_works; ++i) mine[i / per].push_back(order[i]);
     } else {
         // Longest processing time first: works in descending cost order (ties: ascending id), each to the
         // least-loaded workgroup (ties: lowest index).

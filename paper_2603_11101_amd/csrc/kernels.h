@@ -27,10 +27,13 @@ struct AttnParams {
     const WorkItem* items;     // device: item records of the work list
     const int32_t* wg_table;   // device: 16 words per persistent workgroup (first descriptor, ids, range)
     const int32_t* work_ids;   // device: item * works_per_item + head chunk
+    const WorkItem* merges;    // device: merge records of a dK/dV list (split key tiles)
+    float* partials;           // partial-sum slots of split key tiles, in the backward workspace
+    int32_t num_merges;
+    int32_t dkdv_by_ids;       // dK/dV list: workgroup b runs the work at position b of the id array
     int32_t num_items;
     int32_t num_workgroups;
     int32_t works_per_item;
-    int32_t dkdv_walk;  // EXPERIMENT
     int32_t T, Hq, Hkv, D;
     int32_t mask_mode;
     float scale;

@@ -171,3 +171,26 @@ def test_peaked_softmax_with_a_rising_row_maximum(mode, Hq, Hkv, D):
     # float32 LSE of magnitude ~50 carries 4e-6 of rounding per operation; the bound stays the stated one
     assert max_abs(run.lse, ref_lse) <= TOL_LSE_ABS
     check_bwd(run, oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=MODES[mode]), cu, "peaked")
+
+
+@pytest.mark.parametrize("mode,Hq,Hkv,n,L", [(va.VA_MASK_CAUSAL, 4, 4, 65, 64), (va.VA_MASK_PREFIX_LM, 8, 1, 257, 96)])
+def test_split_key_tiles_against_the_oracle(mode, Hq, Hkv, n, L):
+    # One work more than the 256 workgroup slots of head_dim 256 (260 and 257 equal works): the host cuts the
+    # query tiles of the last key tile into pieces, their workgroups write float32 partial sums into the
+    # workspace and the merge kernel adds them.  Every sample against the oracle, and twice for determinism.
+    D = 256
+    lens = [L] * n
+    cu, prefix, q, k, v, do = wl.random_stream(300 + n, lens, Hq, Hkv, D, prefix_frac=0.6)
+    if mode == va.VA_MASK_CAUSAL:
+        prefix = None
+    scale = 1.0 / np.sqrt(D)
+    print(f"split key tiles mode={mode} Hq={Hq} Hkv={Hkv} samples={n} L={L}", flush=True)
+    run = DeviceRun(cu, prefix, mode, q, k, v, do, scale)
+    dkdv_list = run.ps.worklist_host[va.VA_PASS_BWD_DKDV]
+    assert dkdv_list[1, 7] >= 1, "this case is meant to hold a split tile"
+    print(f"  {int(dkdv_list[1, 7])} split tile(s), {int((va.worklist_items(dkdv_list)[:, 1] >> 8 > 0).sum())} pieces", flush=True)
+    ref = oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=MODES[mode])
+    check_bwd(run, ref, cu, "split")
+    again = DeviceRun(cu, prefix, mode, q, k, v, do, scale)
+    for name in ("dq", "dk", "dv"):
+        assert np.array_equal(getattr(run, name), getattr(again, name)), name

@@ -1,7 +1,8 @@
 """Parity at the full workload sizes, in the launch configuration bench.py
 times: the first first-fit bin of each workload runs on the GPU as a whole; the
-oracle computes a selection of its samples (all heads, all rows, all gradients
-of those samples) and the two are compared element by element.  Work lists and
+oracle computes every sample of the configurations the benchmark reports (vlm,
+pi05, longtail) and a selection of samples of the others (all heads, all rows,
+all gradients of those samples), and the two are compared element by element.  Work lists and
 packing at these sizes are compared bit for bit in the host-library tests."""
 import numpy as np
 import pytest
@@ -39,7 +40,7 @@ def pick(lens, count):
     return sel[:count]
 
 
-@pytest.mark.parametrize("name,count", [("vlm", 30), ("pi05", 6), ("longtail", 7), ("vit", 6), ("pi0", 5)])
+@pytest.mark.parametrize("name,count", [("vlm", 30), ("pi05", 35), ("longtail", 87), ("vit", 6), ("pi0", 5)])
 def test_full_size_forward_backward(name, count):
     w, lens, cu, pl, mx = bin0(name)
     T, Hq, Hkv, D = int(cu[-1]), w.num_q_heads, w.num_kv_heads, w.head_dim
@@ -160,9 +161,12 @@ def test_one_long_sample_on_sampled_rows(window):
             assert max_abs(run.out[i, h], o_i) <= TOL_FWD_ABS and abs(run.lse[h, i] - lse_i) <= TOL_LSE_ABS, (i, h)
             if i > 0:     # row 0 sees itself only: dQ = 0, no relative error
                 assert rel_l2(run.dq[i, h], dq_i) <= TOL_GRAD_REL, (i, h)
-    keys = [L - 1, L - 130, L - 2000] if window is None else [0, 64, 5000, L - 1000, L - 1]
+    # keys near the start of the sample are seen by (nearly) every row: the heaviest dK/dV works
+    keys = [0, 64, 5000, L - 2000, L - 130, L - 1] if window is None else [0, 64, 5000, L - 1000, L - 1]
+    print("  oracle row statistics", flush=True)
+    stats = sampled.row_stats(q, k, v, do, scale, window)
     for j in keys:
-        dk_j, dv_j = sampled.key_row_dk_dv(q, k, v, do, scale, j, 0, window)
+        dk_j, dv_j = sampled.key_row_dk_dv(q, k, v, do, scale, j, 0, window, stats=stats)
         worst["dk"] = max(worst.get("dk", 0.0), rel_l2(run.dk[j, 0], dk_j))
         worst["dv"] = max(worst.get("dv", 0.0), rel_l2(run.dv[j, 0], dv_j))
         assert rel_l2(run.dv[j, 0], dv_j) <= TOL_GRAD_REL, j

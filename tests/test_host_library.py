@@ -90,13 +90,18 @@ def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
         per_item = Hkv if pass_id == va.VA_PASS_BWD_DKDV else got[1, 2]
         assert got[1, 1] == len(items) * per_item and sorted(ids.tolist()) == list(range(len(ids)))
         assert table[0, 0] == 0 and np.array_equal(table[1:, 0], np.cumsum(table[:-1, 1])) and table[:, 1].sum() == len(ids)
-        # longest-processing-time-first: no workgroup exceeds the mean load by more than the heaviest work
-        steps = items[:, 4] * (Hq // Hkv) if pass_id == va.VA_PASS_BWD_DKDV else items[:, 5]
-        if mode == va.VA_MASK_SLIDING_WINDOW and pass_id != va.VA_PASS_BWD_DKDV:   # tiles below the window are not visited
-            steps = items[:, 5] - np.maximum(0, items[:, 0] - items[:, 2] + 1 - items[:, 6]) // cols
-        cost = np.repeat(steps, per_item) + 2
-        loads = np.array([cost[ids[a:a + n]].sum() for a, n in table])
-        assert loads.max() <= cost.sum() / len(table) + cost.max()
+        if pass_id == va.VA_PASS_BWD_DKDV:
+            # one work per workgroup: the id array is the launch order, the item order unless the list says otherwise
+            assert got[1, 3] in (0, 1) and (got[1, 3] == 1 or np.array_equal(ids, np.arange(len(ids))))
+            assert got[1, 7] == 0 and np.all(items[:, 1] >> 8 == 0)       # few works per workgroup slot: nothing is split
+        else:
+            # longest-processing-time-first: no workgroup exceeds the mean load by more than the heaviest work
+            steps = items[:, 5]
+            if mode == va.VA_MASK_SLIDING_WINDOW:   # tiles below the window are not visited
+                steps = items[:, 5] - np.maximum(0, items[:, 0] - items[:, 2] + 1 - items[:, 6]) // cols
+            cost = np.repeat(steps, per_item) + 2
+            loads = np.array([cost[ids[a:a + n]].sum() for a, n in table])
+            assert loads.max() <= cost.sum() / len(table) + cost.max()
         # the oracle names tile sizes by role: bm = query rows, bn = key rows
         bm, bn = (cols, rows) if pass_id == va.VA_PASS_BWD_DKDV else (rows, cols)
         want = op.build_worklist(cu, prefix, pass_id, bm, bn, mode)
@@ -114,6 +119,140 @@ def test_worklists_equal_oracle_and_cover(mode, Hq, Hkv, D):
         bm, bn = (cols, rows) if pass_id == va.VA_PASS_BWD_DKDV else (rows, cols)
         items = va.worklist_items(va.va_build_worklist(cu_s, pre_s, mode, pass_id, D, Hq, Hkv))
         op.check_coverage(items, cu_s, pre_s, pass_id, bm, bn, mode)
+
+
+def whole_tiles(worklist):
+    """Item records of a dK/dV list with the pieces of every split key tile put together again; checks on the
+    way that the pieces of a tile occupy consecutive partial slots and follow each other without gap or overlap."""
+    items = va.worklist_items(worklist)
+    slot = (items[:, 1] >> 8) - 1
+    whole = [it.copy() for it, s in zip(items, slot) if s < 0]
+    taken = set()
+    for rec in va.worklist_merges(worklist):
+        row0, w1, first, pieces, qt_first, qt_count = (int(x) for x in rec[:6])
+        assert pieces >= 2 and w1 >> 8 == 0
+        at = qt_first
+        for j in range(pieces):
+            (i,) = np.nonzero(slot == first + j)[0]
+            assert i not in taken and items[i, 0] == row0 and items[i, 1] & 0xff == w1 and items[i, 3] == at and items[i, 4] > 0
+            taken.add(int(i))
+            at += int(items[i, 4])
+        assert at == qt_first + qt_count
+        it = items[i].copy()
+        it[1], it[3], it[4] = w1, qt_first, qt_count
+        whole.append(it)
+    assert len(taken) == int((slot >= 0).sum())
+    return np.array(whole, dtype=np.int32).reshape(-1, 8)
+
+
+def sorted_rows(a):
+    return a[np.lexsort(a.T[::-1])]
+
+
+def replay_dispatch(cost_in_launch_order, slots):
+    """Finish time when workgroup b runs on XCD b % 8 and every XCD gives its works, in order, to the
+    least-loaded of its slots / 8 workgroup slots."""
+    import heapq
+    heaps = [[0] * (slots // 8) for _ in range(8)]
+    finish = 0
+    for pos, c in enumerate(cost_in_launch_order):
+        h = heaps[pos % 8]
+        t = heapq.heappop(h) + int(c)
+        heapq.heappush(h, t)
+        finish = max(finish, t)
+    return finish
+
+
+def test_heavy_key_tiles_are_split_where_the_last_round_would_idle():
+    # pi05, bin 0: 257 heavy dK/dV works (8 query heads x 27-32 query tiles each) for 256 workgroup slots
+    w = wl.WORKLOADS["pi05"]
+    lens, prefix = wl.sample_lengths("pi05")
+    b, p, n = va.va_pack_first_fit(lens, w.budget)
+    idx = op.bin_members(b, p, 0)
+    cu, pl, mx = va.va_bin_layout(lens[idx], prefix[idx])
+    rows, cols = va.va_tile_shape(va.VA_PASS_BWD_DKDV, w.head_dim, w.num_q_heads, w.num_kv_heads)
+    got = va.va_build_worklist(cu, pl, va.VA_MASK_PREFIX_LM, va.VA_PASS_BWD_DKDV, w.head_dim, w.num_q_heads, w.num_kv_heads)
+    items = va.worklist_items(got)
+    assert got[1, 7] >= 1 and int((items[:, 1] >> 8 > 0).sum()) >= 2
+    assert np.all(np.diff(items[:, 4]) <= 0)                              # still heaviest first
+    # put together again, the list is the oracle's
+    want = op.build_worklist(cu, pl, va.VA_PASS_BWD_DKDV, cols, rows, va.VA_MASK_PREFIX_LM)
+    assert np.array_equal(sorted_rows(whole_tiles(got)), sorted_rows(want))
+    # and the replayed dispatch ends within 10 % of the lower bound, where the unsplit list needs two rounds
+    G = w.num_q_heads // w.num_kv_heads
+    slots = int(got[1, 0])
+    cost = np.repeat(items[:, 4] * G + 2, w.num_kv_heads)
+    bound = max(cost.sum() / slots, np.repeat(want[:, 4] * G + 2, w.num_kv_heads).max())
+    assert replay_dispatch(cost, slots) <= 1.1 * bound
+    assert replay_dispatch(np.repeat(want[:, 4] * G + 2, w.num_kv_heads), slots) > 1.5 * bound
+    # the library accepts its own list and refuses one whose pieces leave a gap
+    Hq, Hkv, D = w.num_q_heads, w.num_kv_heads, w.head_dim
+    shape = va.make_shape(int(cu[-1]), len(cu) - 1, Hq, Hkv, D, mx, va.VA_MASK_PREFIX_LM)
+    need = va.varlen_attn_bwd_workspace_bytes(shape)
+    assert need >= 2 * int(cu[-1]) * Hq * 4 + 2 * rows * D * 4 * Hkv * 4
+    # host-side validation of the device call: lists whose pieces leave a gap, overlap, share a slot, or whose
+    # merge record names another tile are refused before anything is launched (so this runs without a GPU)
+    raw = np.zeros(need + 512, dtype=np.uint8)
+    ws = raw[(-raw.ctypes.data) % 256:][:need]
+    buf = np.zeros(1 << 12, dtype=np.uint8)
+    dq_list = va.va_build_worklist(cu, pl, va.VA_MASK_PREFIX_LM, va.VA_PASS_BWD_DQ, D, Hq, Hkv)
+
+    def call(dkdv_list):
+        lst = np.ascontiguousarray(dkdv_list)
+        return va._lib.varlen_attn_bwd(va._ptr(buf), va._ptr(buf), va._ptr(buf), va._ptr(buf), va._ptr(buf), va._ptr(buf),
+                                       va._ptr(cu), va._ptr(pl), va._ptr(lst), va._ptr(lst), va._ptr(dq_list), va._ptr(dq_list),
+                                       ctypes.byref(shape), ctypes.c_float(0.0625), va._ptr(buf), va._ptr(buf), va._ptr(buf),
+                                       va._ptr(ws), ctypes.c_size_t(need), ctypes.c_void_p(0))
+
+    pieces = np.nonzero(items[:, 1] >> 8 > 0)[0] + 2            # records of the pieces
+    merge = int(got[1, 6]) - int(got[1, 7])                      # record of the first merge record
+    gap, overlap, shared, other_tile, lost = (got.copy() for _ in range(5))
+    gap[pieces[1], 3] += 1                                       # second piece starts one query tile late
+    overlap[pieces[1], 4] += 1                                   # ... or covers one tile too many
+    shared[pieces[1], 1] = shared[pieces[0], 1]                  # two pieces, one slot
+    other_tile[merge, 0] += rows                                 # merge record of a different key tile
+    lost[1, 7] = 0                                               # pieces without their merge record
+    for bad in (gap, overlap, shared, other_tile, lost):
+        assert call(bad) == va.VA_EINVAL, va.va_last_error()
+
+
+def test_split_pieces_cover_every_pair_once():
+    # 65 samples x 4 KV heads = 260 equal works for 256 slots at head_dim 256: the last tile is cut in two
+    Hq, Hkv, D = 4, 4, 256
+    lens = np.full(65, 64, dtype=np.int32)
+    cu, _, _ = va.va_bin_layout(lens)
+    rows, cols = va.va_tile_shape(va.VA_PASS_BWD_DKDV, D, Hq, Hkv)
+    got = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_BWD_DKDV, D, Hq, Hkv)
+    items = va.worklist_items(got)
+    assert got[1, 7] == 1 and int((items[:, 1] >> 8 > 0).sum()) == 2
+    whole = whole_tiles(got)
+    op.check_coverage(whole, cu, None, va.VA_PASS_BWD_DKDV, cols, rows, va.VA_MASK_CAUSAL)
+    assert np.array_equal(sorted_rows(whole), sorted_rows(op.build_worklist(cu, None, va.VA_PASS_BWD_DKDV, cols, rows, va.VA_MASK_CAUSAL)))
+
+
+def test_in_step_launch_order_keeps_a_sample_on_one_xcd():
+    # heavy-tailed lengths, many works per slot: the id array of the dK/dV list is the launch order, and the
+    # key tiles of one (sample, KV head) sit at positions of one XCD (position % 8), next to each other
+    w = wl.WORKLOADS["longtail"]
+    lens, _ = wl.sample_lengths("longtail")
+    b, p, n = va.va_pack_first_fit(lens, w.budget)
+    cu, _, mx = va.va_bin_layout(lens[op.bin_members(b, p, 0)])
+    got = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_BWD_DKDV, w.head_dim, w.num_q_heads, w.num_kv_heads)
+    assert got[1, 3] == 1
+    items = va.worklist_items(got)
+    _, ids = va.worklist_schedule(got)
+    assert sorted(ids.tolist()) == list(range(len(items) * w.num_kv_heads))
+    group = {}
+    for pos, wid in enumerate(ids.tolist()):
+        group.setdefault((int(items[wid // w.num_kv_heads, 2]), wid % w.num_kv_heads), []).append(pos)
+    on_one_xcd = sum(len({pos % 8 for pos in g}) == 1 for g in group.values())
+    assert on_one_xcd >= 0.95 * len(group)
+    adjacent = sum(max(g) - min(g) == 8 * (len(g) - 1) for g in group.values() if len({pos % 8 for pos in g}) == 1)
+    assert adjacent >= 0.9 * on_one_xcd
+    # and the replay of the dispatch says it ends within 3 % of the item order
+    G = w.num_q_heads // w.num_kv_heads
+    cost = np.repeat(items[:, 4] * G + 2, w.num_kv_heads)
+    assert replay_dispatch(cost[ids], int(got[1, 0])) <= 1.03 * replay_dispatch(cost, int(got[1, 0]))
 
 
 def test_worklist_counts_on_the_workloads():
@@ -236,11 +375,13 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     wrong_pass = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_BWD_DKDV, D, Hq, Hkv)
     bad_table = wl_h.copy()
     bad_table[wl_h[1, 4] + 1, 3] += 1                  # first workgroup claims one work too many
+    bad_flag = wl_h.copy()
+    bad_flag[1, 3] = 1                                 # the in-step flag belongs to dK/dV lists
     bad_copy = wl_h.copy()
     bad_copy[wl_h[1, 4], 1] += 1                       # its copy of its first item differs from the item
     bad_id = wl_h.copy()
     bad_id[wl_h[1, 5], 0] = wl_h[1, 1]                 # a work id past the end
-    for bad in (other, tampered, wrong_pass, bad_table, bad_copy, bad_id):
+    for bad in (other, tampered, wrong_pass, bad_table, bad_copy, bad_id, bad_flag):
         assert call(va.make_shape(**ok), wl_=np.ascontiguousarray(bad))[0] == va.VA_EINVAL
     assert va.varlen_attn_bwd_workspace_bytes(va.make_shape(**ok)) >= 100 * Hq * 4
 

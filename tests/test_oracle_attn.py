@@ -434,7 +434,11 @@ def test_row_by_row_functions_equal_the_oracle():
                 o_i, lse_i = sampled.row_forward(q, k, v, scale, i, h, window)
                 assert np.allclose(o_i, out[i, h], rtol=1e-12, atol=1e-14) and abs(lse_i - lse[h, i]) < 1e-12
                 assert np.allclose(sampled.row_dq(q, k, v, do, scale, i, h, window), dq[i, h], rtol=1e-11, atol=1e-13)
+        stats = sampled.row_stats(q, k, v, do, scale, window, rows_per_pass=16)     # several passes, a ragged last one
+        assert np.allclose(stats[0], lse, rtol=1e-12, atol=1e-13)
         for j in (0, 5, 40, 69):
             for g in range(Hkv):
                 dk_j, dv_j = sampled.key_row_dk_dv(q, k, v, do, scale, j, g, window)
+                assert np.allclose(dk_j, dk[j, g], rtol=1e-11, atol=1e-13) and np.allclose(dv_j, dv[j, g], rtol=1e-11, atol=1e-13)
+                dk_j, dv_j = sampled.key_row_dk_dv(q, k, v, do, scale, j, g, window, stats=stats)
                 assert np.allclose(dk_j, dk[j, g], rtol=1e-11, atol=1e-13) and np.allclose(dv_j, dv[j, g], rtol=1e-11, atol=1e-13)
