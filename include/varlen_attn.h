@@ -277,6 +277,31 @@ int varlen_attn_bwd_stages(const void* q, const void* k, const void* v, const vo
                            void* workspace, size_t workspace_bytes, void* stream, uint32_t stages);
 
 /*
+ * varlen_attn_bwd without a workspace argument, for callers that cannot
+ * allocate device memory where they call it (code under HIP graph capture,
+ * serving loops and harnesses that forbid hipMalloc): the scratch the backward
+ * needs lives in a device array inside the library, VA_STATIC_WORKSPACE_BYTES
+ * per GPU the library is used on, held until the process ends.  The call
+ * allocates and frees nothing.  Shapes whose
+ * varlen_attn_bwd_workspace_bytes exceeds that size are refused with
+ * VA_ESIZE (use varlen_attn_bwd then).  All calls on one GPU share the one
+ * array: calls that may overlap there (two streams, two threads) race; calls
+ * on one stream are ordered like any other work.  Nothing in the array needs
+ * a defined value on entry (every word a kernel reads was written earlier in
+ * the same call).  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress); make that call outside a stream capture.
+ * Otherwise arguments, results (bit for bit) and errors are those of
+ * varlen_attn_bwd; VA_EHIP if the address cannot be obtained.
+ */
+#define VA_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+int varlen_attn_bwd_static(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                           const void* dout, const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                           const void* worklist_dkdv, const void* worklist_dkdv_host,
+                           const void* worklist_dq, const void* worklist_dq_host,
+                           const va_shape* shape, float scale,
+                           void* dq, void* dk, void* dv, void* stream);
+
+/*
  * FP8 forward: Q, K, V are OCP E4M3 bytes with one float32 descale per head
  * (device arrays q_descale[Hq], k_descale[Hkv], v_descale[Hkv]).  Scores are
  * (scale * q_descale[h] * k_descale[g]) * (Q8 . K8) in float32; the softmax and

@@ -51,7 +51,7 @@ _lib = _load()
 EXPORTS = ["va_last_error", "va_pack_first_fit", "va_bin_layout", "va_tile_shape", "va_worklist_size",
            "va_build_worklist", "va_quantize_e4m3_per_head", "va_quantize_e4m3_per_head_device",
            "varlen_attn_bwd_workspace_bytes", "va_bwd_has_delta_kernel",
-           "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_stages", "varlen_attn_fwd_fp8",
+           "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_stages", "varlen_attn_bwd_static", "varlen_attn_fwd_fp8",
            "va_quantize_e4m3_blockwise", "va_quantize_e4m3_blockwise_device", "varlen_attn_fwd_fp8_blockwise"]
 
 
@@ -257,6 +257,16 @@ def varlen_attn_bwd(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_d
                                 _ptr(workspace), ctypes.c_size_t(workspace_bytes), _stream_ptr(stream)))
 
 
+def varlen_attn_bwd_static(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
+                           worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, stream=None):
+    cu = _i32(cu_seqlens)
+    pl = _prefix(prefix_lens, shape.mask_mode, len(cu) - 1)
+    _check(_lib.varlen_attn_bwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(dout), _ptr(cu), _ptr(pl),
+                                       _ptr(worklist_dkdv), _ptr(worklist_dkdv_host), _ptr(worklist_dq),
+                                       _ptr(worklist_dq_host), ctypes.byref(shape), ctypes.c_float(scale),
+                                       _ptr(dq), _ptr(dk), _ptr(dv), _stream_ptr(stream)))
+
+
 def varlen_attn_bwd_stages(q, k, v, out, lse, dout, cu_seqlens, prefix_lens, worklist_dkdv, worklist_dkdv_host,
                            worklist_dq, worklist_dq_host, shape, scale, dq, dk, dv, workspace, workspace_bytes,
                            stages, stream=None):
@@ -333,6 +343,12 @@ class PackedStream:
                         self.worklist[VA_PASS_BWD_DKDV], self.worklist_host[VA_PASS_BWD_DKDV],
                         self.worklist[VA_PASS_BWD_DQ], self.worklist_host[VA_PASS_BWD_DQ],
                         self.shape, scale, dq, dk, dv, ws, ws.numel(), stream)
+
+    def bwd_static(self, q, k, v, out, lse, dout, scale, dq, dk, dv, stream=None):
+        varlen_attn_bwd_static(q, k, v, out, lse, dout, self.cu_seqlens, self.prefix_lens,
+                               self.worklist[VA_PASS_BWD_DKDV], self.worklist_host[VA_PASS_BWD_DKDV],
+                               self.worklist[VA_PASS_BWD_DQ], self.worklist_host[VA_PASS_BWD_DQ],
+                               self.shape, scale, dq, dk, dv, stream)
 
     def bwd_stages(self, q, k, v, out, lse, dout, scale, dq, dk, dv, stages, stream=None):
         ws = self.workspace()
