@@ -84,7 +84,8 @@ typedef struct {
     int32_t mask_mode;    /* VA_MASK_* ; VA_MASK_CAUSAL ignores prefix_lens */
 } va_shape;
 
-/* Message of the last failing call on this thread (static storage). */
+/* Message of the last failing call on this thread (static storage).  This library's own; no passage of the
+ * paper. */
 const char* va_last_error(void);
 
 /* ------------------------------------------------------------------ host, integers only */
@@ -104,7 +105,9 @@ int va_pack_first_fit(const int32_t* lens, int32_t N, int32_t budget,
                       int32_t* bin_of_sample, int32_t* pos_in_bin, int32_t* num_bins);
 
 /*
- * Layout of one bin: exclusive prefix sums of its samples' lengths.
+ * Layout of one bin (section 2.2.1 (2): the samples of a bin are concatenated
+ * end to end, and the variable-length interface of 2.2.1 (1) is told where each
+ * one starts): exclusive prefix sums of its samples' lengths.
  *   lens[n], prefix[n] (prefix may be NULL)  host in, in placement order
  *   cu_seqlens[n+1]   host out, cu_seqlens[0] = 0
  *   prefix_lens[n]    host out (may be NULL when prefix is NULL); VA_EINVAL unless 0 <= P <= L
@@ -116,6 +119,7 @@ int va_bin_layout(const int32_t* lens, const int32_t* prefix, int32_t n,
                   int32_t* cu_seqlens, int32_t* prefix_lens, int32_t* max_seqlen);
 
 /*
+ * (This library's own; the paper names no tiling.)
  * Tile shape the kernels of `pass` use for these head counts: *rows is the
  * number of token rows of a work item (query rows for VA_PASS_FWD and
  * VA_PASS_BWD_DQ, key rows for VA_PASS_BWD_DKDV) and *cols the number of token
@@ -126,20 +130,21 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
 
 /*
  * Work list of one pass over one packed stream, in records of 8 int32 words:
- *   record 0   {magic "VAW3", pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
- *   record 1   {num_workgroups, num_works, works_per_item, first item record (2),
- *               first table record, first work-id record, total records, 0}
- *   items      num_items records, heaviest first (ties by sample, then tile)
+ *   record 0   {magic "VAW4", pass, rows, cols, head_dim, mask_mode, num_items, total_tokens}
+ *   record 1   {num_workgroups, num_works, works_per_item, flags, first table record,
+ *               first work-id record, total records, number of merge records}
+ *   items      num_items records from record 2 on, heaviest first (ties by sample, then tile)
  *   table      two records per persistent workgroup: the item of its first work, then
  *              {id of that work, id of its second work, first schedule position,
  *              number of works, 0, 0, 0, 0}
  *   work ids   num_works words, 8 per record: item * works_per_item + head chunk,
  *              grouped by workgroup in the order the workgroup runs them
+ *   merges     (dK/dV lists) one record per split key tile, see below
  * Only tiles holding at least one visible (query, key) pair are listed and no
  * tile spans two samples (the varlen rule of section 2.2.1 (1): compute on
  * valid tokens only).
  *   forward / dQ item: {q_row0, q_rows, seq_row0, P2 or -1, n_full, n_tiles, P or -1, L}
- *   dK/dV item:        {kv_row0, kv_rows, seq_row0, qt_first, qt_count, P2 or -1, P or -1, L}
+ *   dK/dV item:        {kv_row0, kv_rows | (slot + 1) << 8, seq_row0, qt_first, qt_count, P2 or -1, P or -1, L}
  * (n_tiles key tiles hold a key some row of the item sees, the first n_full of them
  * no hidden pair; P and P2 are the sample's block ends, -1 where the mask has none)
  * Under VA_MASK_SLIDING_WINDOW the P word holds the window W, n_full and n_tiles
@@ -151,20 +156,35 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
  * the schedule is the number of tiles it visits.
  * A work is one item for one head chunk: the query heads one workgroup stacks
  * (forward, dQ) or one KV head (dK/dV), so works_per_item depends on the head
- * counts the list was built for.  The kernels run num_workgroups persistent
- * workgroups; the table assigns the works to them longest-processing-time
- * first, with a work's cost taken as its inner-loop steps plus a fixed part.
+ * counts the list was built for.  The forward and dQ kernels run num_workgroups
+ * persistent workgroups; the table assigns the works to them longest-processing-
+ * time first, with a work's cost taken as its inner-loop steps plus a fixed part.
  * Within that, works that read the same rows (the K and V rows of one sample
- * and KV head in the forward and dQ passes) go to workgroups of one XCD, at
- * about the same position of their queues, so that the XCD's L2 fetches the
- * rows once.  Kernels that run one work per workgroup (dK/dV) ignore the table
- * and take work ids 0 .. num_works-1 in item order.
- * va_worklist_size gives the buffer size; va_build_worklist fills a host
- * buffer of at least that size.  The caller copies the buffer to the device
- * unchanged and hands both copies to the device calls, which validate the host
- * copy (records, bounds, that every item lies inside one sample of cu_seqlens,
- * that the table partitions the works and repeats each workgroup's first work
- * faithfully) and return VA_EINVAL on a mismatch.
+ * and KV head) go to workgroups of one XCD, at about the same position of their
+ * queues, so that the XCD's L2 fetches the rows once.
+ * The dK/dV kernel runs one work per workgroup and ignores the table.  Workgroup
+ * b of its launch runs work b (item order), or, when flags has bit 0 set, the
+ * work at position b of the id array: an order that puts the key tiles of one
+ * (sample, KV head) next to each other on one XCD, chosen by the builder where a
+ * replay of the hardware's dispatch says it ends within 3 % of item order.
+ * Split key tiles: where few heavy dK/dV works per workgroup slot would leave
+ * most of the chip idle in the last round (257 equal works on 256 slots), the
+ * builder cuts the query tiles of the work that ends last into pieces.  Each
+ * piece is an item of its own (qt_first, qt_count: its part of the tile's query
+ * tiles; slot >= 0: the partial-sum slot of the workspace its workgroups write
+ * float32 dK and dV sums to; slot + 1 = 0 marks an item that writes dK and dV
+ * itself), and a merge record {kv_row0, kv_rows, first slot, pieces, qt_first,
+ * qt_count of the whole tile, 0, 0} tells the merge kernel to add the pieces, in
+ * slot order, into dK and dV.  The pieces of a tile hold consecutive slots.
+ * va_worklist_size gives the buffer size (an upper bound: it does not know the
+ * mask); va_build_worklist fills a host buffer of at least that size.  The
+ * caller copies the buffer to the device unchanged and hands both copies to the
+ * device calls, which validate the host copy (records, bounds, that every item
+ * lies inside one sample of cu_seqlens and carries the block ends of
+ * prefix_lens, that the table partitions the works and repeats each
+ * workgroup's first work faithfully, that the pieces of a split tile cover its
+ * query tiles once) and return VA_EINVAL on a mismatch.  The device copy must
+ * be a byte copy of the validated host copy: the kernels read it unchecked.
  */
 int va_worklist_size(const int32_t* cu_seqlens, int32_t num_seqs, int32_t pass, int32_t head_dim,
                       int32_t num_q_heads, int32_t num_kv_heads, size_t* bytes);
@@ -184,11 +204,19 @@ int va_quantize_e4m3_per_head(const uint16_t* x_bf16, int32_t T, int32_t H, int3
 
 /* ------------------------------------------------------------------ device */
 
-/* Bytes of device scratch varlen_attn_bwd needs for these shapes. */
+/*
+ * Bytes of device scratch varlen_attn_bwd needs for these shapes (this library's
+ * own): delta and LSE * log2(e), float32 [Hq, T] each, then the partial-sum
+ * slots of split key tiles (see va_build_worklist; reserved whether a list
+ * splits a tile or not, 16 MiB at most head counts).  0 for a null or
+ * unsupported shape.
+ */
 size_t varlen_attn_bwd_workspace_bytes(const va_shape* shape);
 
 /*
- * Forward: O = softmax(scale * Q K^T + mask) V per sample, and LSE.
+ * Forward (section 2.2.1 (1): attention on the valid tokens of the packed
+ * stream of 2.2.1 (2), sample by sample; masks of 2.2.1 (1) and 2.2.2):
+ * O = softmax(scale * Q K^T + mask) V per sample, and LSE.
  *   q, k, v        device in   bfloat16
  *   cu_seqlens     host  in    [num_seqs + 1] (validated here: monotone, [0] = 0, last = T)
  *   prefix_lens    host  in    [num_seqs] ([2 num_seqs] under VA_MASK_THREE_BLOCK), NULL allowed for
@@ -207,8 +235,10 @@ int varlen_attn_fwd(const void* q, const void* k, const void* v,
                     void* out, float* lse, void* stream);
 
 /*
- * Backward: dQ, dK, dV from dO, recomputing the probabilities from the saved
- * LSE.  delta = rowsum(dO * O) per row; dK/dV per key tile; dQ per query tile.
+ * Backward of the same operation (the training step of section 2.2.1 needs the
+ * gradients of what the forward computes; the paper prints no formula, the
+ * schedule is this library's own): dQ, dK, dV from dO, recomputing the
+ * probabilities from the saved LSE.  delta = rowsum(dO * O) per row; dK/dV per key tile; dQ per query tile.
  * At head_dim <= 128 the dQ kernel computes delta for its own rows (every row
  * belongs to exactly one of its works), runs first, and the dK/dV kernel reads
  * what it wrote: two kernels.  At head_dim 256 a separate pass over O and dO
@@ -231,7 +261,9 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
 /*
  * The same quantisation on the device (the on-device step the per-head
  * scaling of section 2.2.3 needs before the FP8 forward), bit-identical to
- * va_quantize_e4m3_per_head for finite inputs:
+ * va_quantize_e4m3_per_head (non-finite inputs included: in both a NaN
+ * becomes the NaN code 0x7F at its own place and stays out of the maximum, and
+ * an infinity makes the descale of its head infinite):
  *   x        device in   bfloat16 [T, H, D], 16-byte aligned, D a multiple of 8
  *   codes    device out  uint8 [T, H, D], 8-byte aligned
  *   descale  device out  float32 [H]; holds the per-head maxima while the call runs
@@ -242,6 +274,7 @@ int va_quantize_e4m3_per_head_device(const void* x_bf16, int32_t T, int32_t H, i
                                      void* codes, float* descale, void* stream);
 
 /*
+ * (This library's own, for harnesses that account for the backward kernel by kernel.)
  * Whether varlen_attn_bwd at this head_dim launches the separate delta pass
  * (1) or its dQ kernel computes delta (0); see varlen_attn_bwd.  Host only,
  * no error cases: any other head_dim answers 1.
@@ -307,7 +340,14 @@ int varlen_attn_bwd_static(const void* q, const void* k, const void* v, const vo
  * (scale * q_descale[h] * k_descale[g]) * (Q8 . K8) in float32; the softmax and
  * LSE are float32; the probabilities are requantised to E4M3 (times 256) for
  * the second product; the row sum uses the unquantised probabilities.
- * Output bfloat16 O and float32 LSE as in varlen_attn_fwd.
+ * Output bfloat16 O and float32 LSE as in varlen_attn_fwd.  head_dim 128 only.
+ * (Scaling vocabulary of section 2.2.3; applying FP8 to the attention operands
+ * is this library's extension: the paper quantises weights.)
+ * Accuracy of the LSE: the matrix unit sums E4M3 products with about 17
+ * significant bits, so the LSE carries a relative error of about 1.4e-5: within
+ * 1e-3 absolute up to |LSE| of about 70, beyond that in proportion (the bfloat16
+ * forward holds 1e-5 there).  Scores that large come from peaked softmaxes with
+ * scale * |q| * |k| far above the 1 / sqrt(head_dim) the workloads use.
  */
 int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
                         const float* q_descale, const float* k_descale, const float* v_descale,
@@ -334,7 +374,8 @@ int varlen_attn_fwd_fp8(const void* q8, const void* k8, const void* v8,
  * buffers (x 16-byte, codes 8-byte, descale_tok 4-byte aligned, D a multiple
  * of 8) and a second, device-resident copy of cu_seqlens with
  * the same contents, launches one kernel on `stream`, allocates nothing, does
- * not wait, and is bit-identical to the host routine for finite inputs.  A
+ * not wait, and is bit-identical to the host routine (NaN and infinity treated
+ * as in the per-head pair).  A
  * device copy that disagrees with the host copy gives wrong scales but no
  * access outside [0, T).
  * VA_EINVAL for null pointers, bad sizes or a bad cu_seqlens, VA_EALIGN, VA_EHIP.

@@ -30,14 +30,17 @@ VA_DEV float bf16_bits_to_float(unsigned bits16) { return __builtin_bit_cast(flo
 
 typedef int i32x2 __attribute__((ext_vector_type(2)));
 
-// |bf16| of the 8 values of a chunk as float bits, their maximum
+// |bf16| of the 8 values of a chunk as float bits, their maximum.  NaN patterns (above the bits of infinity)
+// count as zero, as in the host routine, whose maximum drops them: a NaN in the input turns into the NaN
+// code at its own place and leaves the scale of its head or block alone.
 VA_DEV unsigned chunk_amax_bits(u32x4 raw) {
     unsigned m = 0u;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
         // clear the sign, move the 16 bits to the top half
-        m = max(m, (raw[w] & 0x7fffu) << 16);
-        m = max(m, raw[w] & 0x7fff0000u);
+        const unsigned lo = (raw[w] & 0x7fffu) << 16, hi = raw[w] & 0x7fff0000u;
+        m = max(m, lo > 0x7f800000u ? 0u : lo);
+        m = max(m, hi > 0x7f800000u ? 0u : hi);
     }
     return m;
 }
@@ -56,13 +59,21 @@ VA_DEV i32x2 encode_chunk(u32x4 raw, float descale) {
         v[2 * w + 1] = bf16_bits_to_float(raw[w] >> 16) / descale;
     }
     // The conversion instruction rounds to nearest even, subnormals included, but turns magnitudes of
-    // 464 and more into NaN instead of saturating: clamp first (448 is representable).
+    // 464 and more into NaN instead of saturating: clamp first (448 is representable).  The clamp would
+    // also turn a NaN into -448; a NaN (the value itself, or infinity over an infinite scale) gets the
+    // NaN code 0x7F of the host routine instead.
+    unsigned nan_lo = 0u, nan_hi = 0u;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = fminf(fmaxf(v[e], -448.0f), 448.0f);
+    for (int e = 0; e < 8; ++e) {
+        if (v[e] != v[e]) (e < 4 ? nan_lo : nan_hi) |= 0xffu << (8 * (e & 3));
+        v[e] = fminf(fmaxf(v[e], -448.0f), 448.0f);
+    }
     int lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], 0, false);
     lo = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], lo, true);
     int hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[4], v[5], 0, false);
     hi = __builtin_amdgcn_cvt_pk_fp8_f32(v[6], v[7], hi, true);
+    lo = (int)(((unsigned)lo & ~nan_lo) | (0x7f7f7f7fu & nan_lo));
+    hi = (int)(((unsigned)hi & ~nan_hi) | (0x7f7f7f7fu & nan_hi));
     return i32x2{lo, hi};
 }
 

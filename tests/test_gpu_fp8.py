@@ -82,6 +82,33 @@ def test_fp8_uniform_keys_is_exact_for_power_of_two_counts():
 
 
 @pytest.mark.gpu
+def test_device_quantisers_equal_the_host_routines_on_non_finite_inputs():
+    # a NaN of either sign in one head, infinities in another: the device routines return the bytes and
+    # scales of the host routines (whose behaviour the host-library tests tie to the oracle's quantiser)
+    T, H, D = 300, 3, 64
+    r = np.random.default_rng(8)
+    bits = wl.bf16_bits(wl.round_to_bf16(r.standard_normal((T, H, D)).astype(np.float32) * 3.0)).copy()
+    bits[T // 3, 0, 5], bits[T - 1, 0, D - 1] = 0x7fc0, 0xffc1
+    bits[1, 1, 0], bits[T // 2, 1, 7] = 0x7f80, 0xff80
+    cu = np.array([0, 130, 131, 300], dtype=np.int32)
+    print("device quantisers, non-finite inputs", flush=True)
+    xt = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(DEV)
+    codes = torch.full((T, H, D), 0xAA, dtype=torch.uint8, device=DEV)
+    descale = torch.full((H,), -1.0, dtype=torch.float32, device=DEV)
+    va.va_quantize_e4m3_per_head_device(xt, codes, descale)
+    bcodes = torch.full((T, H, D), 0xAA, dtype=torch.uint8, device=DEV)
+    bdescale = torch.full((T, H), -1.0, dtype=torch.float32, device=DEV)
+    va.va_quantize_e4m3_blockwise_device(xt, cu, torch.from_numpy(cu).to(DEV), bcodes, bdescale)
+    torch.cuda.synchronize()
+    hc, hd = va.va_quantize_e4m3_per_head(bits)
+    assert np.array_equal(codes.cpu().numpy(), hc) and np.array_equal(descale.cpu().numpy().view(np.uint32), hd.view(np.uint32))
+    assert hc[T // 3, 0, 5] == 0x7F and hc[T - 1, 0, D - 1] == 0x7F and np.isfinite(hd[0]) and np.isinf(hd[1])
+    hbc, hbd = va.va_quantize_e4m3_blockwise(bits, cu)
+    assert np.array_equal(bcodes.cpu().numpy(), hbc)
+    assert np.array_equal(bdescale.cpu().numpy().view(np.uint32), hbd.view(np.uint32))
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("T,H,D", [(1, 1, 64), (77, 3, 64), (513, 8, 128), (300, 5, 256), (0, 4, 128)])
 def test_device_quantiser_is_bit_identical_to_the_oracle(T, H, D):
     # per-head amax, descale and every code byte: the oracle's nearest-value search decides, the device

@@ -298,6 +298,43 @@ def test_e4m3_quantiser_equals_oracle_bit_for_bit():
     assert descale[0] == 1.0 and np.array_equal(codes, oe.encode(probe))
 
 
+def with_non_finite(seed, T, H, D):
+    """bf16 bit patterns [T, H, D] with a NaN of either sign planted in head 0 and infinities in head 1;
+    returns (bits, mask of the NaN positions)"""
+    r = np.random.default_rng(seed)
+    x = wl.bf16_bits(wl.round_to_bf16(r.standard_normal((T, H, D)).astype(np.float32) * 3.0)).copy()
+    nan = np.zeros(x.shape, dtype=bool)
+    nan[T // 3, 0, 5] = nan[T - 1, 0, D - 1] = True
+    x[T // 3, 0, 5], x[T - 1, 0, D - 1] = 0x7fc0, 0xffc1
+    x[1, 1, 0], x[T // 2, 1, 7] = 0x7f80, 0xff80
+    return x, nan
+
+
+def test_quantisers_keep_a_nan_out_of_the_scale():
+    # A NaN becomes the NaN code at its own place and does not touch the scale of its head or block: every
+    # other element is quantised as if the NaN were a zero (the oracle's quantiser on the cleaned array).
+    # An infinity makes the scale of its head infinite: finite values go to code 0, the infinity itself to NaN.
+    T, H, D = 40, 3, 16
+    x, nan = with_non_finite(3, T, H, D)
+    cleaned = x.copy()
+    cleaned[nan] = 0
+    codes, descale = va.va_quantize_e4m3_per_head(x)
+    with np.errstate(invalid="ignore"):      # the infinities of head 1 divide to NaN in the oracle as well
+        ocodes, odescale = oe.quantize_per_head(wl.bits_to_f32(cleaned))
+    assert np.all(codes[nan] == 0x7F)
+    assert np.array_equal(codes[:, 0][~nan[:, 0]], ocodes[:, 0][~nan[:, 0]]) and descale[0] == odescale[0]
+    assert np.array_equal(codes[:, 2], ocodes[:, 2]) and descale[2] == odescale[2]
+    inf = (x[:, 1] & 0x7fff) == 0x7f80
+    assert np.isinf(descale[1]) and np.all(codes[:, 1][inf] == 0x7F) and np.all(codes[:, 1][~inf] & 0x7f == 0)
+    # block-wise: the same per block
+    cu = np.array([0, 13, 40], dtype=np.int32)
+    bcodes, bdescale = va.va_quantize_e4m3_blockwise(x, cu)
+    with np.errstate(invalid="ignore"):
+        ocodes, odescale = oe.quantize_blockwise(wl.bits_to_f32(cleaned), cu)
+    assert np.all(bcodes[nan] == 0x7F) and np.array_equal(bcodes[:, 0][~nan[:, 0]], ocodes[:, 0][~nan[:, 0]])
+    assert np.array_equal(bcodes[:, 2], ocodes[:, 2])
+
+
 def expand_block_descale(descale, cu, H):
     """The oracle's [num_blocks, H] block scales, one row per token (the library's layout)."""
     starts = oe.block_starts(cu)
