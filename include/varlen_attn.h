@@ -165,8 +165,9 @@ int va_tile_shape(int32_t pass, int32_t head_dim, int32_t num_q_heads, int32_t n
  * The dK/dV kernel runs one work per workgroup and ignores the table.  Workgroup
  * b of its launch runs work b (item order), or, when flags has bit 0 set, the
  * work at position b of the id array: an order that puts the key tiles of one
- * (sample, KV head) next to each other on one XCD, chosen by the builder where a
- * replay of the hardware's dispatch says it ends within 3 % of item order.
+ * (sample, KV head) next to each other on one XCD, chosen by the builder where
+ * the list holds at least four works per workgroup slot and a replay of the
+ * hardware's dispatch says it ends within 3 % of item order.
  * Split key tiles: where few heavy dK/dV works per workgroup slot would leave
  * most of the chip idle in the last round (257 equal works on 256 slots), the
  * builder cuts the query tiles of the work that ends last into pieces.  Each
