@@ -362,8 +362,11 @@ def tiny_latency(va, wl, torch, reps=200):
 
 
 def host_call_cost(case, reps=200):
-    """microseconds the forward + backward calls of one step take on the host (validation and launches)"""
-    torch = case.torch
+    """(microseconds the forward + backward calls of one step take on the host through the Python binding,
+    the same through the bare C ABI with arguments marshalled once): validation of the three work lists and
+    the kernel launches; the second figure leaves out what ctypes and numpy add per call."""
+    import ctypes
+    torch, va = case.torch, case.va
     torch.cuda.synchronize()
     best = float("inf")
     for _ in range(3):
@@ -372,7 +375,24 @@ def host_call_cost(case, reps=200):
             case.step(i)
         best = min(best, (time.perf_counter() - t0) / reps * 1e6)
         torch.cuda.synchronize()
-    return best
+    ps, s = case.ps, case.sets[0]
+    P = va._ptr
+    lists = {pid: (P(ps.worklist[pid]), P(ps.worklist_host[pid])) for pid in ps.worklist}
+    shape, scale = ctypes.byref(ps.shape), ctypes.c_float(case.scale)
+    cu, pl, stream = P(ps.cu_seqlens), P(ps.prefix_lens), va._stream_ptr(None)
+    ws = ps.workspace()
+    fwd_args = (P(s["q"]), P(s["k"]), P(s["v"]), cu, pl, *lists[va.VA_PASS_FWD], shape, scale, P(s["out"]), P(s["lse"]), stream)
+    bwd_args = (P(s["q"]), P(s["k"]), P(s["v"]), P(s["out"]), P(s["lse"]), P(s["do"]), cu, pl, *lists[va.VA_PASS_BWD_DKDV],
+                *lists[va.VA_PASS_BWD_DQ], shape, scale, P(s["dq"]), P(s["dk"]), P(s["dv"]), P(ws), ctypes.c_size_t(ws.numel()), stream)
+    bare = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        for i in range(reps):
+            rc = va._lib.varlen_attn_fwd(*fwd_args) | va._lib.varlen_attn_bwd(*bwd_args)
+        bare = min(bare, (time.perf_counter() - t0) / reps * 1e6)
+        torch.cuda.synchronize()
+        assert rc == 0
+    return best, bare
 
 
 def cpu_baseline(case, va, budget_s=14.0):
@@ -567,7 +587,7 @@ def main():
     iters = max(8, min(args.steps, 40))
     case = Case(args.workload, va, wl, torch)
     head = measure(case, args.steps, args.warmup, iters, full=True)
-    head["host_call_us"] = host_call_cost(case)
+    head["host_call_us"], head["host_call_us_c_abi"] = host_call_cost(case)
     result = {
         "metric": "packed varlen attn fwd+bwd useful TFLOP/s",
         "value": head["value"],
@@ -585,7 +605,7 @@ def main():
                    "pairs_per_head": head["pairs_per_head"], "buffer_sets": NUM_BUFFER_SETS,
                    "clock_ramp_ms": CLOCK_RAMP_MS},
         **{n: head[n] for n in ("tokens_per_s", "mfma_util_useful", "ms_per_step_warm", "value_warm",
-                                "ms_per_step_graph", "value_graph", "host_plan_ms", "host_call_us", "kernels_ms",
+                                "ms_per_step_graph", "value_graph", "host_plan_ms", "host_call_us", "host_call_us_c_abi", "kernels_ms",
                                 "kernels_tflops", "kernels_gbps", "step_floor_us", "step_frac_of_floor")},
         "roofline": head["roofline"],
         "source_digest": source_digest(),
@@ -614,7 +634,7 @@ def main():
         elif name != args.workload:
             c = Case(name, va, wl, torch)
             configs[name] = measure(c, max(args.steps, 100), args.warmup, iters, full=True)
-            configs[name]["host_call_us"] = host_call_cost(c)
+            configs[name]["host_call_us"], configs[name]["host_call_us_c_abi"] = host_call_cost(c)
             del c
         torch.cuda.empty_cache()
     if configs:

@@ -101,12 +101,12 @@ VA_DEV DkdvWork fetch_dkdv_work(const AttnParams& p, int id) {
     return w;
 }
 
-// This wave's 32 key rows of dK and dV (KV head g of the tile starting at row kv_row0), from the transposed
-// accumulators through `stage` (32 * D * 2 bytes of LDS of the wave's own) out as whole rows; rows past
+// This wave's 32 key rows of dK or dV (KV head g of the tile starting at row kv_row0), from the transposed
+// accumulator through `stage` (32 * D * 2 bytes of LDS of the wave's own) out as whole rows; rows past
 // kv_rows are dropped by the buffer's range check.
 template <int D, int DR, int DT = (DR + 31) / 32>
-VA_DEV void store_dkdv_rows(const AttnParams& p, char* stage, int kv_row0, int kv_rows, int g, int wave, int lane,
-                            const f32x16 (&dk)[DT], const f32x16 (&dv)[DT]) {
+VA_DEV void store_kv_rows(const AttnParams& p, char* stage, void* tensor, float factor, int kv_row0, int kv_rows, int g,
+                          int wave, int lane, const f32x16 (&acc)[DT]) {
     using Rows = RowBlock<D, DR>;
     const int rows_here = min(max(kv_rows - 32 * wave, 0), 32);
     const size_t off = ((size_t)(kv_row0 + 32 * wave) * p.Hkv + g) * DR;
@@ -114,10 +114,14 @@ VA_DEV void store_dkdv_rows(const AttnParams& p, char* stage, int kv_row0, int k
     const unsigned bytes = rows_here > 0 ? (unsigned)(rows_here - 1) * row_bytes + DR * 2 : 0u;
     const int lane_off = Rows::lane_offset(lane, row_bytes);
     auto soff = [&](int j) { return j * Rows::RPI * row_bytes; };
-    store_block_rows<D, DT>(stage, dk, p.scale, lane, Rows::rows(static_cast<__bf16*>(p.dk) + off, bytes), lane_off, soff);
+    store_block_rows<D, DT>(stage, acc, factor, lane, Rows::rows(static_cast<__bf16*>(tensor) + off, bytes), lane_off, soff);
     __builtin_amdgcn_sched_barrier(0);
-    store_block_rows<D, DT>(stage, dv, 1.0f, lane, Rows::rows(static_cast<__bf16*>(p.dv) + off, bytes), lane_off, soff);
-    __builtin_amdgcn_sched_barrier(0);
+}
+template <int D, int DR, int DT = (DR + 31) / 32>
+VA_DEV void store_dkdv_rows(const AttnParams& p, char* stage, int kv_row0, int kv_rows, int g, int wave, int lane,
+                            const f32x16 (&dk)[DT], const f32x16 (&dv)[DT]) {
+    store_kv_rows<D, DR>(p, stage, p.dk, p.scale, kv_row0, kv_rows, g, wave, lane, dk);
+    store_kv_rows<D, DR>(p, stage, p.dv, 1.0f, kv_row0, kv_rows, g, wave, lane, dv);
 }
 
 // Partial sums of a split key tile.  A slot holds, per KV head, dK then dV of the tile in the order the
@@ -141,21 +145,18 @@ VA_DEV void store_partial(float* slot, int wave, int lane, const f32x16 (&dk)[DT
                 *reinterpret_cast<f32x4*>(dst) = v;
             }
 }
-// acc = (first ? 0 : acc) + the slot's values
+// acc = (first ? 0 : acc) + one tensor (which: 0 dK, 1 dV) of one wave's share of the slot
 template <int D, int DT>
-VA_DEV void add_partial(const float* slot, int wave, int lane, bool first, f32x16 (&dk)[DT], f32x16 (&dv)[DT]) {
+VA_DEV void add_partial(const float* slot, int which, int wave, int lane, bool first, f32x16 (&acc)[DT]) {
 #pragma unroll
-    for (int which = 0; which < 2; ++which)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+        for (int q = 0; q < 4; ++q) {
+            const float* src = slot + which * (kDkdvKvRows * D) + ((wave * (D / 32) + dt) * 4 + q) * 256 + lane * 4;
+            const f32x4 v = *reinterpret_cast<const f32x4*>(src);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float* src = slot + which * (kDkdvKvRows * D) + ((wave * (D / 32) + dt) * 4 + q) * 256 + lane * 4;
-                const f32x4 v = *reinterpret_cast<const f32x4*>(src);
-                f32x16& a = which ? dv[dt] : dk[dt];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) a[4 * q + e] = first ? v[e] : a[4 * q + e] + v[e];
-            }
+            for (int e = 0; e < 4; ++e) acc[dt][4 * q + e] = first ? v[e] : acc[dt][4 * q + e] + v[e];
+        }
 }
 
 // dK/dV kernel, one work per workgroup: in item order (heaviest first), or, where the list says so
@@ -452,21 +453,23 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     }
 }
 
-// Merge kernel of the split key tiles: one workgroup per (merge record, KV head) adds the pieces of the tile
-// in slot order, every lane the registers it would have held in the dK/dV kernel, and writes dK and dV the
-// way that kernel does.  The order is fixed, so the sums do not depend on scheduling.
+// Merge kernel of the split key tiles: one wave per (merge record, KV head, 32 key rows, dK or dV) adds the
+// pieces of the tile in slot order, every lane the registers it would have held in the dK/dV kernel, and
+// writes the rows the way that kernel does.  The order is fixed, so the sums do not depend on scheduling.
 template <int D, int DR>
-__global__ __launch_bounds__(256) void bwd_dkdv_merge_kernel(AttnParams p) {
+__global__ __launch_bounds__(64) void bwd_dkdv_merge_kernel(AttnParams p) {
     constexpr int DT = (DR + 31) / 32;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m = (int)blockIdx.x / p.Hkv, g = (int)blockIdx.x % p.Hkv;
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // 32 * D * 2 bytes: the wave's staging slice
+    const int lane = threadIdx.x;
+    const int part = (int)blockIdx.x % 8, mg = (int)blockIdx.x / 8;
+    const int which = part & 1, wave = part >> 1;  // the 32-row slice a wave of the dK/dV kernel owns
+    const int m = mg / p.Hkv, g = mg % p.Hkv;
     const WorkItem rec = p.merges[m];
     const int kv_row0 = rec.w[0], kv_rows = dkdv_item_rows(rec.w[1]), first = rec.w[2], pieces = rec.w[3];
-    f32x16 dk[DT], dv[DT];
-    add_partial<D, DT>(partial_slot<D>(p, first, g), wave, lane, true, dk, dv);
-    for (int j = 1; j < pieces; ++j) add_partial<D, DT>(partial_slot<D>(p, first + j, g), wave, lane, false, dk, dv);
-    store_dkdv_rows<D, DR>(p, smem + wave * (32 * D * 2), kv_row0, kv_rows, g, wave, lane, dk, dv);
+    f32x16 acc[DT];
+    add_partial<D, DT>(partial_slot<D>(p, first, g), which, wave, lane, true, acc);
+    for (int j = 1; j < pieces; ++j) add_partial<D, DT>(partial_slot<D>(p, first + j, g), which, wave, lane, false, acc);
+    store_kv_rows<D, DR>(p, smem, which ? p.dv : p.dk, which ? 1.0f : p.scale, kv_row0, kv_rows, g, wave, lane, acc);
 }
 
 // One work per workgroup, in item order (heaviest first).
@@ -496,10 +499,8 @@ hipError_t launch_dkdv_d(const AttnParams& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     e = hipGetLastError();
     if (e != hipSuccess || p.num_merges == 0) return e;
-    constexpr size_t merge_smem = 4 * 32 * D * 2;  // one staging slice per wave
-    const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&bwd_dkdv_merge_kernel<D, DR>), merge_smem);
-    if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((bwd_dkdv_merge_kernel<D, DR>), dim3((unsigned)(p.num_merges * p.Hkv)), dim3(256), merge_smem, stream, p);
+    constexpr size_t merge_smem = 32 * D * 2;  // one staging slice
+    hipLaunchKernelGGL((bwd_dkdv_merge_kernel<D, DR>), dim3((unsigned)(p.num_merges * p.Hkv * 8)), dim3(64), merge_smem, stream, p);
     return hipGetLastError();
 }
 
