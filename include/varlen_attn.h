@@ -79,7 +79,7 @@ typedef struct {
     int32_t num_seqs;     /* n */
     int32_t num_q_heads;  /* Hq */
     int32_t num_kv_heads; /* Hkv, Hq % Hkv == 0 */
-    int32_t head_dim;     /* D in {48, 64, 80, 96, 128, 160, 192, 256}; the FP8 forward takes 128 only */
+    int32_t head_dim;     /* D in {48, 64, 80, 96, 128, 160, 192, 256}; the FP8 forward takes 64, 128 and 256 */
     int32_t max_seqlen;   /* >= every sample length; validation only, never changes results */
     int32_t mask_mode;    /* VA_MASK_* ; VA_MASK_CAUSAL ignores prefix_lens */
 } va_shape;
@@ -341,7 +341,8 @@ int varlen_attn_bwd_static(const void* q, const void* k, const void* v, const vo
  * (scale * q_descale[h] * k_descale[g]) * (Q8 . K8) in float32; the softmax and
  * LSE are float32; the probabilities are requantised to E4M3 (times 256) for
  * the second product; the row sum uses the unquantised probabilities.
- * Output bfloat16 O and float32 LSE as in varlen_attn_fwd.  head_dim 128 only.
+ * Output bfloat16 O and float32 LSE as in varlen_attn_fwd.  head_dim 64, 128 or 256
+ * (VA_EUNSUPPORTED otherwise).
  * (Scaling vocabulary of section 2.2.3; applying FP8 to the attention operands
  * is this library's extension: the paper quantises weights.)
  * Accuracy of the LSE: the matrix unit sums E4M3 products with about 17

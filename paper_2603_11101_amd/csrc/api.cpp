@@ -384,7 +384,8 @@ int fwd_fp8_entry(const char* who, bool blockwise, const void* q8, const void* k
                   const va_shape* shape, float scale, void* out, float* lse, void* stream) {
     int rc = check_shape(shape, cu_seqlens, prefix_lens, who);
     if (rc) return rc;
-    if (shape->head_dim != 128) return fail(VA_EUNSUPPORTED, "%s: head_dim %d, the FP8 forward exists for 128 only", who, shape->head_dim);
+    if (shape->head_dim != 64 && shape->head_dim != 128 && shape->head_dim != 256)
+        return fail(VA_EUNSUPPORTED, "%s: head_dim %d, the FP8 forward exists for 64, 128 and 256", who, shape->head_dim);
     if ((rc = check_scale(scale, who))) return rc;
     if (shape->total_tokens == 0) return VA_OK;
     if (!q8 || !k8 || !v8 || !q_descale || !k_descale || !v_descale || !out || !lse)

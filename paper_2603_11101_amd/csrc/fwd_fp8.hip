@@ -20,6 +20,10 @@
 // of O when the block changes; the row sum takes psum / v_descale per tile,
 // which removes the factor again.
 //
+// Head dimensions 64, 128 and 256 (one, two or four contraction steps of the first product; two, four or
+// eight 32-row blocks of O^T; one workgroup per CU at 256, where the tiles and the output staging take
+// 128 KiB of LDS).
+//
 // Same decomposition as the bf16 forward: one workgroup = 128 stacked
 // (head, token) rows of one KV group, 4 waves x 32 rows, 64 keys per step,
 // S^T = K Q^T then O^T = V^T P^T so a lane owns one query row throughout.
@@ -51,42 +55,89 @@ constexpr float kMaxLag = 0.75f;
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
 
+// "This value is needed here": makes the compiler place its wait for an ordinary load at this point (see
+// settle() in mfma_util.h).  Plain functions, not statements inside the kernel template: an operand whose
+// type depends on a template parameter would have its constraint checked against the host target as well.
+VA_DEV void settle8(const i32x8& f) { asm volatile("" ::"v"(f)); }
+VA_DEV void settle_scalar(float f) { asm volatile("" ::"v"(f)); }
+
 VA_DEV f32x16 mfma_f8(i32x8 a, i32x8 b, f32x16 c) {
     // formats 0 = E4M3 for both operands; block scales 127 = 2^0
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 127, 0, 127);
 }
 
-// LDS tile of 64 rows x 128 bytes, 16-byte chunks, chunk c of row r stored at
-// c ^ swz(r).  Conflict free for (1) 16 lanes reading one chunk of the rows
-// {x, 32 + x : x in 0..7} (+ 16 b), and (2) 32 lanes reading 8 consecutive rows
-// by 32 bytes with the transposing byte read.
-__host__ __device__ constexpr int swz8(int r) { return (((r >> 1) & 3) << 1) | ((r >> 5) & 1); }
-__host__ __device__ constexpr int off8(int r, int c) { return r * 128 + ((c ^ swz8(r)) << 4); }
+// LDS tile of 64 rows x D bytes (D = head dimension, one byte per value), 16-byte chunks, chunk c of row r
+// stored at c ^ swz(r).  Conflict free for (1) 16 lanes reading one chunk of the rows
+// {x, 32 + x : x in 0..7} (+ 16 b), and (2) 32 lanes reading 8 consecutive rows by 32 bytes with the
+// transposing byte read.  A 256-byte line of the 64 banks holds 256 / D rows; the rows that share a line
+// (and, for (2), the two chunks a lane pair reads) must land on different chunk positions:
+//   D =  64: 4 rows per line; rows r, r + 4 (bit 2) and r + 32 (bit 5) share a line position -> bits 1, 0
+//   D = 128: 2 rows per line; bits 1-2 of the row choose among 4 chunk pairs, bit 5 the chunk of the pair
+//   D = 256: one row per line; bits 0-2 of the row choose among 8 chunk pairs, bit 5 the chunk of the pair
+template <int D>
+__host__ __device__ constexpr int swz8(int r) {
+    constexpr int shift = D == 64 ? 2 : D == 128 ? 1 : 0, mask = D == 64 ? 1 : D == 128 ? 3 : 7;
+    return (((r >> shift) & mask) << 1) | ((r >> 5) & 1);
+}
+template <int D>
+__host__ __device__ constexpr int off8(int r, int c) { return r * D + ((c ^ swz8<D>(r)) << 4); }
 
-constexpr int kTileBytes = kFwdKvTile * 128;  // 64 rows of 128 bytes
+template <int D>
+constexpr int kTileBytesOf = kFwdKvTile * D;  // 64 rows of D bytes
 
-// Asynchronous copy of one 64 x 128-byte tile by 4 waves (see AsyncTile in mfma_util.h): two wave
-// instructions per wave, 8 rows each; rows 8 apart share their swizzle, so one per-lane offset serves both.
+// Both access patterns against the 64 banks of 4 bytes: every bank at most once per group of lanes that is
+// served together (16 lanes of a 16-byte read, 32 lanes of an 8-byte transposing read).
+template <int D>
+constexpr bool swz8_conflict_free() {
+    for (int b = 0; b < 2; ++b)
+        for (int quarter = 0; quarter < 4; ++quarter)
+            for (int c = 0; c < D / 16; ++c) {
+                bool used[16] = {};
+                for (int i = 0; i < 16; ++i) {
+                    const int l32 = (quarter & 1) * 16 + i;
+                    const int r = 32 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3) + 16 * b;
+                    const int slot = (off8<D>(r, c) % 256) / 16;
+                    if (used[slot]) return false;
+                    used[slot] = true;
+                }
+            }
+    for (int r0 = 0; r0 < 64; r0 += 8)
+        for (int dt = 0; dt < D / 32; ++dt) {
+            bool used[32] = {};
+            for (int i = 0; i < 32; ++i) {
+                const int r = r0 + (i & 15) / 2, c = 2 * dt + (i >> 4);
+                const int slot = ((off8<D>(r, c) + 8 * (i & 1)) % 256) / 8;
+                if (used[slot]) return false;
+                used[slot] = true;
+            }
+        }
+    return true;
+}
+static_assert(swz8_conflict_free<64>() && swz8_conflict_free<128>() && swz8_conflict_free<256>(),
+              "the tile swizzle leaves a bank conflict");
+
+// Asynchronous copy of one 64 x D-byte tile by 4 waves (see AsyncTile in mfma_util.h): a wave instruction
+// fills 1 KiB of the tile (1024 / D rows); the lane that fills chunk position pc of row r fetches chunk
+// pc ^ swz(r) of that row, so the swizzle costs nothing.
+template <int D>
 struct AsyncTile8 {
-    static constexpr bool self_check() {
-        for (int r = 0; r < 56; ++r)
-            if (swz8(r) != swz8(r + 8) && ((r >> 3) & 1) == 0) return false;
-        return true;
-    }
-    int voff0, first, row_step;
+    static constexpr int CPR = D / 16, RPI = 64 / CPR, INSTR = 64 / RPI, PER_WAVE = INSTR / 4;
+    int voff[PER_WAVE];
+    int first;
     VA_DEV void init(int wave, int lane, int row_bytes) {
-        first = __builtin_amdgcn_readfirstlane(wave * 2);
-        row_step = __builtin_amdgcn_readfirstlane(8 * row_bytes);
-        const int r = wave * 16 + lane / 8, pc = lane % 8;
-        voff0 = r * row_bytes + ((pc ^ swz8(r)) << 4);
+        first = __builtin_amdgcn_readfirstlane(wave * PER_WAVE);
+        const int pc = lane % CPR;
+#pragma unroll
+        for (int j = 0; j < PER_WAVE; ++j) {
+            const int r = (wave * PER_WAVE + j) * RPI + lane / CPR;
+            voff[j] = r * row_bytes + ((pc ^ swz8<D>(r)) << 4);
+        }
     }
     VA_DEV void issue(i32x4 rsrc, unsigned tile_lds, int soffset) const {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) buffer_load_lds_16(tile_lds + (first + j) * 1024, voff0 + j * row_step, rsrc, soffset);
+        for (int j = 0; j < PER_WAVE; ++j) buffer_load_lds_16(tile_lds + (first + j) * 1024, voff[j], rsrc, soffset);
     }
 };
-
-static_assert(AsyncTile8::self_check(), "rows 8 apart must share their swizzle");
 
 // Per-lane LDS offsets of the two fragment patterns in closed form: one lane constant XOR a
 // compile-time constant, plus a compile-time row step.
@@ -98,6 +149,7 @@ static_assert(AsyncTile8::self_check(), "rows 8 apart must share their swizzle")
 // transposing byte reads.  In a group of 16 lanes, lane i receives byte (i % 8) of the 8 bytes addressed
 // by lane 2 e + i / 8 as element e (measured); lane s of the group therefore points at row s / 2,
 // columns 8 (s % 2) .. + 7 of an 8 x 16 block.
+template <int D>
 struct FragAddr8 {
     static __host__ __device__ constexpr int a_row(int lane) {
         const int l32 = lane & 31;
@@ -105,40 +157,41 @@ struct FragAddr8 {
     }
     static __host__ __device__ constexpr int k_base(int lane) {
         const int r = a_row(lane), hf = lane >> 5;
-        return r * 128 + (((2 * hf) ^ swz8(r)) << 4);
+        return r * D + (((2 * hf) ^ swz8<D>(r)) << 4);
     }
     static __host__ __device__ constexpr int k_off(int lane, int b, int t, int e) {
-        return (k_base(lane) ^ ((4 * t + e) << 4)) + b * 16 * 128;
+        return (k_base(lane) ^ ((4 * t + e) << 4)) + b * 16 * D;
     }
     static __host__ __device__ constexpr int v_base(int lane) {
         const int hf = lane >> 5, s16 = lane & 15;
         const int r = 32 * hf + (s16 >> 1);
         const int chunk = (lane >> 4) & 1;  // chunk of the lane's 8 columns inside a 32-column block
-        return r * 128 + ((chunk ^ swz8(r)) << 4) + 8 * (s16 & 1);
+        return r * D + ((chunk ^ swz8<D>(r)) << 4) + 8 * (s16 & 1);
     }
     static __host__ __device__ constexpr int v_off(int lane, int x, int dt) {
-        return (v_base(lane) ^ ((2 * dt) << 4)) + x * 8 * 128;
+        return (v_base(lane) ^ ((2 * dt) << 4)) + x * 8 * D;
     }
     static constexpr bool self_check() {
         for (int lane = 0; lane < 64; ++lane) {
             const int hf = lane >> 5, s16 = lane & 15;
             for (int b = 0; b < 2; ++b)
-                for (int t = 0; t < 2; ++t)
+                for (int t = 0; t < D / 64; ++t)
                     for (int e = 0; e < 2; ++e)
-                        if (k_off(lane, b, t, e) != off8(a_row(lane) + 16 * b, 4 * t + 2 * hf + e)) return false;
+                        if (k_off(lane, b, t, e) != off8<D>(a_row(lane) + 16 * b, 4 * t + 2 * hf + e)) return false;
             for (int x = 0; x < 4; ++x)
-                for (int dt = 0; dt < 4; ++dt) {
+                for (int dt = 0; dt < D / 32; ++dt) {
                     const int col = 32 * dt + 16 * ((lane >> 4) & 1) + 8 * (s16 & 1);
                     const int vr = 32 * hf + 8 * x + (s16 >> 1);
-                    if (v_off(lane, x, dt) != off8(vr, col >> 4) + (col & 8)) return false;
+                    if (v_off(lane, x, dt) != off8<D>(vr, col >> 4) + (col & 8)) return false;
                 }
         }
         return true;
     }
+    static_assert(self_check(), "fragment address closed forms disagree with the tile layout");
     int kb, vb;
     VA_DEV explicit FragAddr8(int lane) : kb(k_base(lane)), vb(v_base(lane)) {}
     VA_DEV i32x8 k_frag(const char* lds, int tile, int b, int t) const {
-        const int at = ((kb + tile) ^ ((4 * t) << 4)) + b * 16 * 128;
+        const int at = ((kb + tile) ^ ((4 * t) << 4)) + b * 16 * D;
         const i32x4 lo = *reinterpret_cast<const i32x4*>(lds + at);
         const i32x4 hi = *reinterpret_cast<const i32x4*>(lds + (at ^ 16));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -149,7 +202,7 @@ struct FragAddr8 {
         i32x8 vf;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            const i32x2 two = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2)(lds_char*)(lds + at + x * 8 * 128));
+            const i32x2 two = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2)(lds_char*)(lds + at + x * 8 * D));
             vf[2 * x] = two[0];
             vf[2 * x + 1] = two[1];
         }
@@ -157,16 +210,14 @@ struct FragAddr8 {
     }
 };
 
-static_assert(FragAddr8::self_check(), "fragment address closed forms disagree with the tile layout");
-
 // Persistent like the bf16 forward: workgroup b runs the works the host assigned to it; the first K/V tile
 // and the Q fragments of the next work are fetched while the last key tile of the current one is processed.
 // WINDOW: the sliding-window mask, as in the bf16 forward (the P word of a work holds the width W; key
 // tiles below the window of the work's first row are not visited, those reaching below the window of its
 // last row carry the mask).
-template <int HPB, bool BLOCK, bool WINDOW>
-__global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
-    constexpr int D = 128;
+template <int D, int HPB, bool BLOCK, bool WINDOW>
+__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_fp8_kernel(AttnParams p) {
+    constexpr int kTileBytes = kTileBytesOf<D>;
     constexpr int BMT = kFwdBlockRows / HPB;
     constexpr int BN = kFwdKvTile;
     constexpr int KSTEPS = D / 64;
@@ -184,9 +235,9 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     const int kv_row_bytes = p.Hkv * D;
     const int tile_step = __builtin_amdgcn_readfirstlane(BN * kv_row_bytes);
     const unsigned smem_lds = lds_addr(smem);
-    AsyncTile8 loader;
+    AsyncTile8<D> loader;
     loader.init(wave, lane, kv_row_bytes);
-    const FragAddr8 fa(lane);
+    const FragAddr8<D> fa(lane);
 
     // first key tile a work visits: 0 unless the window has moved past it
     auto first_tile = [&](const RowWork& w) {
@@ -255,9 +306,12 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     // compiler has no wait of its own to place at the top of a work, where output rows are still leaving.
     auto settle_q = [&] {
 #pragma unroll
-        for (int t = 0; t < KSTEPS; ++t) asm volatile("" ::"v"(qf[t]));
-        asm volatile("" ::"v"(c_row));
-        if constexpr (BLOCK) asm volatile("" ::"v"(kd_next), "v"(vd_next));
+        for (int t = 0; t < KSTEPS; ++t) settle8(qf[t]);
+        settle_scalar(c_row);
+        if constexpr (BLOCK) {
+            settle_scalar(kd_next);
+            settle_scalar(vd_next);
+        }
     };
     settle_q();
 
@@ -420,32 +474,47 @@ __global__ __launch_bounds__(256, 2) void fwd_fp8_kernel(AttnParams p) {
     }
 }
 
-template <int HPB, bool BLOCK>
-hipError_t launch_h(const AttnParams& p, hipStream_t stream) {
-    constexpr size_t smem = 2 * 2 * kTileBytes + 4 * 32 * 128 * 2;
-    if (p.mask_mode == VA_MASK_SLIDING_WINDOW)
-        hipLaunchKernelGGL((fwd_fp8_kernel<HPB, BLOCK, true>), dim3((unsigned)p.num_workgroups), dim3(256), smem, stream, p);
-    else
-        hipLaunchKernelGGL((fwd_fp8_kernel<HPB, BLOCK, false>), dim3((unsigned)p.num_workgroups), dim3(256), smem, stream, p);
+template <int D, int HPB, bool BLOCK, bool WINDOW>
+hipError_t launch_w(const AttnParams& p, hipStream_t stream) {
+    // two stages of (K tile, V tile), then one 32 x D bf16 staging slice per wave
+    constexpr size_t smem = 2 * 2 * kTileBytesOf<D> + 4 * 32 * D * 2;
+    const hipError_t attr = VA_ALLOW_DYNAMIC_LDS((&fwd_fp8_kernel<D, HPB, BLOCK, WINDOW>), smem);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((fwd_fp8_kernel<D, HPB, BLOCK, WINDOW>), dim3((unsigned)p.num_workgroups), dim3(256), smem, stream, p);
     return hipGetLastError();
 }
 
-template <bool BLOCK>
+template <int D, int HPB, bool BLOCK>
+hipError_t launch_h(const AttnParams& p, hipStream_t stream) {
+    if (p.mask_mode == VA_MASK_SLIDING_WINDOW) return launch_w<D, HPB, BLOCK, true>(p, stream);
+    return launch_w<D, HPB, BLOCK, false>(p, stream);
+}
+
+template <int D, bool BLOCK>
 hipError_t launch_b(const AttnParams& p, hipStream_t stream) {
     switch (heads_per_block(p.Hq, p.Hkv)) {
-        case 1: return launch_h<1, BLOCK>(p, stream);
-        case 2: return launch_h<2, BLOCK>(p, stream);
-        case 4: return launch_h<4, BLOCK>(p, stream);
-        default: return launch_h<8, BLOCK>(p, stream);
+        case 1: return launch_h<D, 1, BLOCK>(p, stream);
+        case 2: return launch_h<D, 2, BLOCK>(p, stream);
+        case 4: return launch_h<D, 4, BLOCK>(p, stream);
+        default: return launch_h<D, 8, BLOCK>(p, stream);
     }
+}
+
+template <int D>
+hipError_t launch_d(const AttnParams& p, bool blockwise, hipStream_t stream) {
+    return blockwise ? launch_b<D, true>(p, stream) : launch_b<D, false>(p, stream);
 }
 
 }  // namespace
 
 hipError_t launch_fwd_fp8(const AttnParams& p, bool blockwise, hipStream_t stream) {
-    if (p.D != 128) return hipErrorNotSupported;
     if (p.num_items == 0) return hipSuccess;
-    return blockwise ? launch_b<true>(p, stream) : launch_b<false>(p, stream);
+    switch (p.D) {
+        case 64: return launch_d<64>(p, blockwise, stream);
+        case 128: return launch_d<128>(p, blockwise, stream);
+        case 256: return launch_d<256>(p, blockwise, stream);
+        default: return hipErrorNotSupported;
+    }
 }
 
 }  // namespace va

@@ -105,14 +105,15 @@ OMODE = {va.VA_MASK_CAUSAL: oa.MASK_CAUSAL, va.VA_MASK_PREFIX_LM: oa.MASK_PREFIX
          va.VA_MASK_PREFIX_LM_CAUSAL: oa.MASK_PREFIX_CAUSAL_SUFFIX, va.VA_MASK_THREE_BLOCK: oa.MASK_THREE_BLOCK}
 
 
-@pytest.mark.parametrize("mode,Hq,Hkv", [(va.VA_MASK_CAUSAL, 4, 2), (va.VA_MASK_PREFIX_LM, 8, 1), (va.VA_MASK_CAUSAL, 2, 2),
-                                         (va.VA_MASK_PREFIX_LM_CAUSAL, 4, 1), (va.VA_MASK_THREE_BLOCK, 16, 2)])
-def test_fp8_blockwise_forward_parity(mode, Hq, Hkv):
+@pytest.mark.parametrize("mode,Hq,Hkv,D", [(va.VA_MASK_CAUSAL, 4, 2, 128), (va.VA_MASK_PREFIX_LM, 8, 1, 128), (va.VA_MASK_CAUSAL, 2, 2, 128),
+                                           (va.VA_MASK_PREFIX_LM_CAUSAL, 4, 1, 128), (va.VA_MASK_THREE_BLOCK, 16, 2, 128),
+                                           (va.VA_MASK_CAUSAL, 4, 2, 64), (va.VA_MASK_PREFIX_LM, 8, 1, 256), (va.VA_MASK_CAUSAL, 2, 2, 256),
+                                           (va.VA_MASK_THREE_BLOCK, 4, 1, 64)])
+def test_fp8_blockwise_forward_parity(mode, Hq, Hkv, D):
     # magnitudes of Q, K and V drift by powers of two along the stream (period 90 tokens, so blocks
     # differ and some blocks straddle a change), which is what block scales are for
-    D = 128
     lens = [17, 64, 95, 200, 1, 130, 0, 257, 600]
-    cu, prefix, q, k, v, _ = wl.random_stream(70 + Hq + mode, lens, Hq, Hkv, D, prefix_frac=-1.0)
+    cu, prefix, q, k, v, _ = wl.random_stream(70 + Hq + mode + D, lens, Hq, Hkv, D, prefix_frac=-1.0)
     q, k, v = drifting(1, q, 90, -4, 1), drifting(2, k, 90, -4, 1), drifting(3, v, 90, -5, 5)
     if mode == va.VA_MASK_CAUSAL:
         prefix = None
@@ -121,7 +122,7 @@ def test_fp8_blockwise_forward_parity(mode, Hq, Hkv):
     # sizes that keep |LSE| small: the FP8 products carry a relative error of about 1.4e-5 into the scores,
     # which the absolute LSE bound absorbs only up to |LSE| of a few tens
     scale = 1.0 / np.sqrt(D)
-    print(f"fp8 block-wise forward mode={mode} Hq={Hq} Hkv={Hkv}", flush=True)
+    print(f"fp8 block-wise forward mode={mode} Hq={Hq} Hkv={Hkv} D={D}", flush=True)
     out, lse, (qd, kd, vd) = run_blockwise(cu, prefix, mode, q, k, v, scale)
     ref_out, ref_lse = oa.attn_fwd(qd, kd, vd, cu, prefix, scale=scale, mask_mode=OMODE[mode])
     print(f"  largest |LSE| {np.abs(ref_lse).max():.1f}; out rel-L2 {rel_l2(out, ref_out):.2e} max-abs {max_abs(out, ref_out):.2e} "
