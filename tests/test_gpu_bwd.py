@@ -194,3 +194,39 @@ def test_split_key_tiles_against_the_oracle(mode, Hq, Hkv, n, L):
     again = DeviceRun(cu, prefix, mode, q, k, v, do, scale)
     for name in ("dq", "dk", "dv"):
         assert np.array_equal(getattr(run, name), getattr(again, name)), name
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 2, 128), (8, 1, 256)])
+def test_backward_by_stages_equals_the_whole_backward(Hq, Hkv, D):
+    # varlen_attn_bwd_stages: dQ alone (frozen keys and values), then dK/dV alone reading what the first call
+    # left in the workspace, give the bits of varlen_attn_bwd; outputs of stages not selected stay untouched
+    import torch
+    from gpu_util import DEV, to_dev_bf16
+    lens = [70, 129, 40, 300, 1]
+    cu, _, q, k, v, do = wl.random_stream(80 + D, lens, Hq, Hkv, D)
+    scale = 1.0 / np.sqrt(D)
+    T = int(cu[-1])
+    print(f"backward by stages Hq={Hq} Hkv={Hkv} D={D}", flush=True)
+    ps = va.PackedStream(cu, None, va.VA_MASK_CAUSAL, Hq, Hkv, D, device=DEV)
+    tq, tk, tv, tdo = (to_dev_bf16(x) for x in (q, k, v, do))
+    out, lse = torch.empty_like(tq), torch.empty((Hq, T), dtype=torch.float32, device=DEV)
+    ps.fwd(tq, tk, tv, scale, out, lse)
+    want = [torch.empty_like(t) for t in (tq, tk, tv)]
+    ps.bwd(tq, tk, tv, out, lse, tdo, scale, *want)
+    torch.cuda.synchronize()
+    ps.workspace().fill_(0xFF)                      # nothing of the whole backward's scratch may be relied upon
+    got = [torch.full_like(t, 3.0) for t in (tq, tk, tv)]
+    first = va.VA_BWD_STAGE_DQ | (va.VA_BWD_STAGE_DELTA if va.va_bwd_has_delta_kernel(D) else 0)
+    ps.bwd_stages(tq, tk, tv, out, lse, tdo, scale, *got, first)
+    torch.cuda.synchronize()
+    assert torch.equal(got[0], want[0]) and torch.all(got[1] == 3.0) and torch.all(got[2] == 3.0)
+    got[0].fill_(3.0)
+    ps.bwd_stages(tq, tk, tv, out, lse, tdo, scale, *got, va.VA_BWD_STAGE_DKDV)
+    torch.cuda.synchronize()
+    assert torch.all(got[0] == 3.0) and torch.equal(got[1], want[1]) and torch.equal(got[2], want[2])
+    with pytest.raises(va.VarlenAttnError) as e:
+        ps.bwd_stages(tq, tk, tv, out, lse, tdo, scale, *got, 0)
+    assert e.value.code == va.VA_EINVAL
+    with pytest.raises(va.VarlenAttnError) as e:
+        ps.bwd_stages(tq, tk, tv, out, lse, tdo, scale, *got, 8)
+    assert e.value.code == va.VA_EINVAL

@@ -62,6 +62,59 @@ def test_forward_and_backward_replay_from_a_graph():
             assert torch.equal(got, want), f"replay of input set {i}: {name} differs from the eager run"
 
 
+def test_backward_with_a_split_key_tile_replays_from_a_graph():
+    # 257 equal dK/dV works for the 256 workgroup slots of head_dim 256: one key tile is split, so the captured
+    # backward holds the pieces' float32 partial sums in the workspace and the merge kernel behind the dK/dV kernel
+    Hq, Hkv, D, n, L = 8, 1, 256, 257, 96
+    lens = [L] * n
+    scale = 1.0 / np.sqrt(D)
+    print("graph capture and replay, split key tile", flush=True)
+    sets = []
+    for seed in (51, 52):
+        cu, prefix, q, k, v, do = wl.random_stream(seed, lens, Hq, Hkv, D, prefix_frac=0.6)
+        sets.append([to_dev_bf16(x) for x in (q, k, v, do)])
+    cu, prefix, *_ = wl.random_stream(51, lens, Hq, Hkv, D, prefix_frac=0.6)
+    T = int(cu[-1])
+    ps = va.PackedStream(cu, prefix, va.VA_MASK_PREFIX_LM, Hq, Hkv, D, device=DEV)
+    assert ps.worklist_host[va.VA_PASS_BWD_DKDV][1, 7] >= 1
+    ps.workspace()
+    q, k, v, do = (torch.empty_like(x) for x in sets[0])
+    out, dq = torch.empty_like(q), torch.empty_like(q)
+    dk, dv = torch.empty_like(k), torch.empty_like(v)
+    lse = torch.empty((Hq, T), dtype=torch.float32, device=DEV)
+    outputs = (out, lse, dq, dk, dv)
+
+    def load(i):
+        for dst, src in zip((q, k, v, do), sets[i]):
+            dst.copy_(src)
+        for t in outputs:
+            t.fill_(7.0)
+        ps.workspace().fill_(0x7F)
+
+    def step():
+        ps.fwd(q, k, v, scale, out, lse)
+        ps.bwd(q, k, v, out, lse, do, scale, dq, dk, dv)
+
+    eager = []
+    for i in range(len(sets)):
+        load(i)
+        step()
+        torch.cuda.synchronize()
+        eager.append([t.clone() for t in outputs])
+    graph = torch.cuda.CUDAGraph()
+    load(0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        step()
+    for i in (1, 0, 1, 1):
+        load(i)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, want in zip(("out", "lse", "dq", "dk", "dv"), outputs, eager[i]):
+            assert torch.equal(got, want), f"replay of input set {i}: {name} differs from the eager run"
+
+
 def test_blockwise_fp8_quantise_and_forward_replay_from_a_graph():
     # the block-wise quantiser (one kernel per tensor, block search on the device) and the FP8 forward that
     # reads its per-token-row scales: captured together, replayed on changing inputs, against eager runs
