@@ -195,6 +195,17 @@ int va_build_worklist(const int32_t* cu_seqlens, const int32_t* prefix_lens, int
                       void* host_out, size_t bytes, int32_t* num_items);
 
 /*
+ * The validation the device calls apply to the host copy of a work list, on its
+ * own (this library's own; host only, nothing is launched): VA_OK when the list
+ * is one the kernels of `pass` may follow for this stream (shape, cu_seqlens
+ * and prefix_lens as in the device calls), else the error the device call
+ * would return.  For callers that build or cache lists away from the call that
+ * uses them, and for testing the builder.
+ */
+int va_check_worklist(const void* worklist_host, int32_t pass, const int32_t* cu_seqlens,
+                      const int32_t* prefix_lens, const va_shape* shape);
+
+/*
  * Per-head OCP E4M3 quantisation on the host (per-channel scaling of section
  * 2.2.3 applied along the head axis): descale[h] = amax_h / 448 (1 when the
  * head is all zero), code = round-to-nearest-even e4m3 of x / descale[h],

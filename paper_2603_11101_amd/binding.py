@@ -49,7 +49,7 @@ def _load():
 _lib = _load()
 
 EXPORTS = ["va_last_error", "va_pack_first_fit", "va_bin_layout", "va_tile_shape", "va_worklist_size",
-           "va_build_worklist", "va_quantize_e4m3_per_head", "va_quantize_e4m3_per_head_device",
+           "va_build_worklist", "va_check_worklist", "va_quantize_e4m3_per_head", "va_quantize_e4m3_per_head_device",
            "varlen_attn_bwd_workspace_bytes", "va_bwd_has_delta_kernel",
            "varlen_attn_fwd", "varlen_attn_bwd", "varlen_attn_bwd_stages", "varlen_attn_bwd_static", "varlen_attn_fwd_fp8",
            "va_quantize_e4m3_blockwise", "va_quantize_e4m3_blockwise_device", "varlen_attn_fwd_fp8_blockwise"]
@@ -153,6 +153,14 @@ def va_build_worklist(cu_seqlens, prefix_lens, mask_mode, pass_id, head_dim, num
                                   ctypes.byref(n_items)))
     assert n_items.value == buf[0, 6]
     return buf
+
+
+def va_check_worklist(worklist_host, pass_id, cu_seqlens, prefix_lens, shape):
+    """Raises VarlenAttnError unless the device calls would accept this host copy of a work list."""
+    cu = _i32(cu_seqlens)
+    pl = _prefix(prefix_lens, shape.mask_mode, len(cu) - 1)
+    wl = np.ascontiguousarray(worklist_host, dtype=np.int32)
+    _check(_lib.va_check_worklist(_ptr(wl), ctypes.c_int32(pass_id), _ptr(cu), _ptr(pl), ctypes.byref(shape)))
 
 
 def worklist_items(wl):

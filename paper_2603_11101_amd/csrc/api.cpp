@@ -362,6 +362,18 @@ int varlen_attn_bwd(const void* q, const void* k, const void* v, const void* out
 
 int va_bwd_has_delta_kernel(int32_t head_dim) { return dq_computes_delta(head_dim) ? 0 : 1; }
 
+int va_check_worklist(const void* worklist_host, int32_t pass, const int32_t* cu_seqlens, const int32_t* prefix_lens,
+                      const va_shape* shape) {
+    const char* who = "va_check_worklist";
+    if (pass != VA_PASS_FWD && pass != VA_PASS_BWD_DKDV && pass != VA_PASS_BWD_DQ)
+        return fail(VA_EUNSUPPORTED, "%s: unknown pass %d", who, pass);
+    int rc = check_shape(shape, cu_seqlens, prefix_lens, who);
+    if (rc) return rc;
+    WorklistLayout lay;
+    // the device copy is not looked at by the check: the host copy stands in for it
+    return check_worklist(worklist_host, worklist_host, shape, cu_seqlens, prefix_lens, pass, who, &lay);
+}
+
 int va_quantize_e4m3_per_head_device(const void* x, int32_t T, int32_t H, int32_t D, void* codes, float* descale,
                                      void* stream) {
     const char* who = "va_quantize_e4m3_per_head_device";

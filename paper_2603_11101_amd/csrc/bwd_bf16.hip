@@ -190,7 +190,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     constexpr int AUX = 2 * STAGE_BYTES;  // V tile of the work; output staging at the end of the work
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: say so, it selects pointers and LDS slices
     const int hf = lane >> 5, l32 = lane & 31;
 
     const int G = p.Hq / p.Hkv;
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     // of (sample, head) and the LSE / delta rows are raw buffers: anything past the sample reads as zero.
     struct StageSource {
         i32x4 q, dout, aux;  // aux: LSE rows for wave 0, delta rows for wave 1
-        int step;            // number of the stage issued last
+        int qt, in_group;    // query tile (from qt_first) and head inside the group of the stage issued last
         int head;
     };
     auto head_buffers = [&](const DkdvWork& w, StageSource& src) {
@@ -221,11 +222,14 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
         // Query tiles from the last one down, every head of the group at each tile: the key tiles of one
         // sample, where they run next to each other on one XCD, then read the same Q and dO rows at about the
         // same time, whatever their number of query tiles.  One order for every list, so that the sums do not
-        // depend on how a list was scheduled.  src.step counts the steps.
-        ++src.step;
-        src.head = w.g * G + src.step % G;
+        // depend on how a list was scheduled.
+        if (++src.in_group == G) {  // counters instead of a division by the group size at every step
+            src.in_group = 0;
+            --src.qt;
+        }
+        src.head = w.g * G + src.in_group;
         head_buffers(w, src);
-        const int qt = w.qt_count - 1 - src.step / G;
+        const int qt = src.qt;
         const unsigned st = smem_lds + st_index * STAGE_BYTES;
         const int q0 = (w.qt_first + qt) * BMQ;
         loader.issue(src.q, st, q0 * q_row_bytes);
@@ -265,7 +269,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     const DkdvWork cur = fetch_dkdv_work(p, p.dkdv_by_ids ? p.work_ids[blockIdx.x] : (int)blockIdx.x);
     int stage = 0;
     StageSource src;
-    src.step = -1;
+    src.in_group = G - 1;  // the first stage wraps to head 0 of the last query tile
+    src.qt = cur.qt_count;
     src.head = cur.g * G;
     head_buffers(cur, src);
     int q0_next = issue_next_stage(cur, src, 0);  // first query row of the stage in flight

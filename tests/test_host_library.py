@@ -190,19 +190,16 @@ def test_heavy_key_tiles_are_split_where_the_last_round_would_idle():
     shape = va.make_shape(int(cu[-1]), len(cu) - 1, Hq, Hkv, D, mx, va.VA_MASK_PREFIX_LM)
     need = va.varlen_attn_bwd_workspace_bytes(shape)
     assert need >= 2 * int(cu[-1]) * Hq * 4 + 2 * rows * D * 4 * Hkv * 4
-    # host-side validation of the device call: lists whose pieces leave a gap, overlap, share a slot, or whose
-    # merge record names another tile are refused before anything is launched (so this runs without a GPU)
-    raw = np.zeros(need + 512, dtype=np.uint8)
-    ws = raw[(-raw.ctypes.data) % 256:][:need]
-    buf = np.zeros(1 << 12, dtype=np.uint8)
-    dq_list = va.va_build_worklist(cu, pl, va.VA_MASK_PREFIX_LM, va.VA_PASS_BWD_DQ, D, Hq, Hkv)
+    # the validation of the device calls: the library accepts its own list and refuses lists whose pieces leave
+    # a gap, overlap, share a slot, or whose merge record names another tile
+    va.va_check_worklist(got, va.VA_PASS_BWD_DKDV, cu, pl, shape)
 
     def call(dkdv_list):
-        lst = np.ascontiguousarray(dkdv_list)
-        return va._lib.varlen_attn_bwd(va._ptr(buf), va._ptr(buf), va._ptr(buf), va._ptr(buf), va._ptr(buf), va._ptr(buf),
-                                       va._ptr(cu), va._ptr(pl), va._ptr(lst), va._ptr(lst), va._ptr(dq_list), va._ptr(dq_list),
-                                       ctypes.byref(shape), ctypes.c_float(0.0625), va._ptr(buf), va._ptr(buf), va._ptr(buf),
-                                       va._ptr(ws), ctypes.c_size_t(need), ctypes.c_void_p(0))
+        try:
+            va.va_check_worklist(dkdv_list, va.VA_PASS_BWD_DKDV, cu, pl, shape)
+        except va.VarlenAttnError as e:
+            return e.code
+        return va.VA_OK
 
     pieces = np.nonzero(items[:, 1] >> 8 > 0)[0] + 2            # records of the pieces
     merge = int(got[1, 6]) - int(got[1, 7])                      # record of the first merge record
@@ -253,6 +250,68 @@ def test_in_step_launch_order_keeps_a_sample_on_one_xcd():
     G = w.num_q_heads // w.num_kv_heads
     cost = np.repeat(items[:, 4] * G + 2, w.num_kv_heads)
     assert replay_dispatch(cost[ids], int(got[1, 0])) <= 1.03 * replay_dispatch(cost, int(got[1, 0]))
+
+
+@pytest.mark.parametrize("trial", range(24))
+def test_builder_and_validator_agree_on_random_streams(trial):
+    # random head shapes, masks and length mixes, some with many equal works per workgroup slot so that tiles are
+    # split: every list the builder returns passes the validation of the device calls; put together again, the
+    # dK/dV list is the oracle's; its id array is a permutation; single-word damage anywhere in the items, the
+    # schedule or the merge records is refused or leaves a list that is still safe to follow (it passes again)
+    r = np.random.default_rng(9000 + trial)
+    Hkv = int(r.choice([1, 2, 4, 8]))
+    G = int(r.choice([1, 2, 4, 8]))
+    D = int(r.choice([64, 128, 256]))
+    mode = int(r.choice([va.VA_MASK_CAUSAL, va.VA_MASK_PREFIX_LM, va.VA_MASK_PREFIX_LM_CAUSAL, va.VA_MASK_THREE_BLOCK,
+                         va.VA_MASK_SLIDING_WINDOW]))
+    slots = 512 if D <= 128 else 256
+    kind = trial % 3
+    if kind == 0:       # a few samples of mixed length
+        lens = r.integers(0, 700, size=int(r.integers(1, 12)))
+    elif kind == 1:     # just more equal works than slots: the case the split is for
+        per_sample = Hkv
+        n = slots // per_sample + int(r.integers(1, 4))
+        lens = np.full(n, int(r.choice([64, 100, 128])))
+    else:               # many works per slot
+        lens = r.integers(1, 400, size=int(r.integers(200, 500)))
+    lens = lens.astype(np.int32)
+    cu, _, mx = va.va_bin_layout(lens)
+    if mode == va.VA_MASK_CAUSAL:
+        prefix = None
+    elif mode == va.VA_MASK_THREE_BLOCK:
+        prefix = wl.random_block_ends(trial, lens)
+    elif mode == va.VA_MASK_SLIDING_WINDOW:
+        prefix = r.integers(1, 300, size=len(lens)).astype(np.int32)
+    else:
+        prefix = np.array([int(r.integers(0, L + 1)) for L in lens], dtype=np.int32)
+    if kind == 1 and prefix is not None:
+        prefix[:] = prefix[0]          # equal samples, equal masks
+    Hq = G * Hkv
+    shape = va.make_shape(int(cu[-1]), len(lens), Hq, Hkv, D, mx, mode)
+    for pass_id in (va.VA_PASS_FWD, va.VA_PASS_BWD_DKDV, va.VA_PASS_BWD_DQ):
+        got = va.va_build_worklist(cu, prefix, mode, pass_id, D, Hq, Hkv)
+        va.va_check_worklist(got, pass_id, cu, prefix, shape)
+        _, ids = va.worklist_schedule(got)
+        assert sorted(ids.tolist()) == list(range(int(got[1, 1])))
+        used = got[:int(got[1, 6])]
+        if pass_id == va.VA_PASS_BWD_DKDV and (int(cu[-1]) <= 6000 or kind == 1):
+            rows, cols = va.va_tile_shape(pass_id, D, Hq, Hkv)
+            if kind == 1:    # equal samples: the oracle's (quadratic, brute-force) list of one sample, moved along the stream
+                one = op.build_worklist(cu[:2], None if prefix is None else prefix[:1], pass_id, cols, rows, mode)
+                want = np.concatenate([one + np.array([c, 0, c, 0, 0, 0, 0, 0], dtype=np.int32) for c in cu[:-1]])
+            else:
+                want = op.build_worklist(cu, prefix, pass_id, cols, rows, mode)
+            if kind == 1 and want[:, 4].max() >= 2:      # a tile with one query tile cannot be cut
+                assert got[1, 7] >= 1, "this case is meant to split a tile"
+            assert np.array_equal(sorted_rows(whole_tiles(got)), sorted_rows(want))
+        for _ in range(40):
+            bad = got.copy()
+            rec, word = int(r.integers(0, len(used))), int(r.integers(0, 8))
+            bad[rec, word] += int(r.choice([-3, -1, 1, 2, 64, 1 << 8, 1 << 20]))
+            try:
+                va.va_check_worklist(bad, pass_id, cu, prefix, shape)
+            except va.VarlenAttnError as e:
+                assert e.code in (va.VA_EINVAL, va.VA_EUNSUPPORTED)
 
 
 def test_worklist_counts_on_the_workloads():
