@@ -199,13 +199,20 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
             // independent accumulators so that none waits on the one just issued.
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
+                // A block none of the wave's rows sees (the upper half of a diagonal tile for the rows of its
+                // lower half, a block wholly below the window) has P = 0 and dS = 0: its products are not issued.
+                bool seen = true;
+                if constexpr (need_mask) {
+                    const int jb = j0 + 32 * b;
+                    seen = __builtin_amdgcn_ballot_w64(vis > jb && (!WINDOW || lo < jb + 32)) != 0;
+                }
                 f32x16 s, dp;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     s[r] = 0.0f;
                     dp[r] = 0.0f;
                 }
-                {
+                if (seen) {
                     constexpr int NS = 2 * KSTEPS;  // step i: product i % 2 (0: S from K, 1: dP from V), k-step i / 2
                     auto frag = [&](int i) { return fa.rowmajor(smem, (i % 2) ? v_tile : k_tile, b, i / 2); };
                     bf16x8 ring[PF];
@@ -232,6 +239,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
                         if (has_next) load_rows(nxt);
                     }
                 }
+                if (!seen) continue;
                 // first K^T fragments on their way while the elementwise part runs.
                 // Step i of the last product: keys 32 b + 16 (i / DT) .. + 15, dQ^T block i % DT.
                 bf16x8 kring[PF];
