@@ -87,8 +87,10 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
         const int32_t nrows = pass == VA_PASS_BWD_DKDV ? dkdv_item_rows(it[1]) : it[1];
         const int32_t slot = pass == VA_PASS_BWD_DKDV ? dkdv_item_slot(it[1]) : -1;
         const int32_t P = it[6], P2 = it[pass == VA_PASS_BWD_DKDV ? 5 : 3];
-        const bool ok = nrows > 0 && nrows <= rows && seq0 >= 0 && L > 0 && row0 >= seq0 && row0 + nrows <= seq0 + L &&
-                        seq0 + L <= s->total_tokens && (row0 - seq0) % rows == 0 && it[1] >= 0 && slot < max_slots &&
+        // (sums in 64 bits: the words of a list that was tampered with may be anything)
+        const bool ok = nrows > 0 && nrows <= rows && seq0 >= 0 && L > 0 && row0 >= seq0 &&
+                        (int64_t)row0 + nrows <= (int64_t)seq0 + L && (int64_t)seq0 + L <= s->total_tokens &&
+                        (row0 - seq0) % rows == 0 && it[1] >= 0 && slot < max_slots &&
                         (s->mask_mode == VA_MASK_CAUSAL ? P == -1 : block_ends_valid(P, P2, L, s->mask_mode)) &&
                         (s->mask_mode == VA_MASK_THREE_BLOCK || P2 == -1);
         if (!ok) return fail(VA_EINVAL, "%s: work item %d is out of bounds", who, i);
@@ -107,7 +109,8 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
             int32_t qt_end = (L + cols - 1) / cols;
             if (s->mask_mode == VA_MASK_SLIDING_WINDOW)
                 qt_end = (int32_t)(std::min<int64_t>(L - 1, (int64_t)(row0 - seq0) + nrows - 1 + Pm - 1) / cols) + 1;
-            if (it[3] < 0 || it[4] <= 0 || (slot < 0 ? it[3] + it[4] != qt_end : it[3] + it[4] > qt_end))
+            const int64_t qt_last = (int64_t)it[3] + it[4];
+            if (it[3] < 0 || it[4] <= 0 || (slot < 0 ? qt_last != qt_end : qt_last > qt_end))
                 return fail(VA_EINVAL, "%s: work item %d has a bad query-tile range", who, i);
             if (slot >= 0) {
                 if (piece_row0[slot] >= 0) return fail(VA_EINVAL, "%s: partial slot %d is used by two items", who, slot);
@@ -116,7 +119,7 @@ int check_worklist(const void* dev, const void* host, const va_shape* s, const i
                 piece_row0[slot] = row0;
                 ++num_pieces;
                 // the last piece of a tile must end where the whole tile ends: checked with the merge record below
-                if (it[3] + it[4] == qt_end) piece_count[slot] |= 1 << 30;
+                if (qt_last == qt_end) piece_count[slot] |= 1 << 30;
             }
         } else {
             const int32_t r0 = row0 - seq0;

@@ -477,8 +477,19 @@ def test_device_entry_points_reject_bad_arguments_on_the_host():
     bad_copy[wl_h[1, 4], 1] += 1                       # its copy of its first item differs from the item
     bad_id = wl_h.copy()
     bad_id[wl_h[1, 5], 0] = wl_h[1, 1]                 # a work id past the end
-    for bad in (other, tampered, wrong_pass, bad_table, bad_copy, bad_id, bad_flag):
+    # words near the end of the int32 range: refused by comparisons that cannot wrap around
+    huge_len = wl_h.copy()
+    huge_len[2, 2], huge_len[2, 7] = 2**31 - 5, 2**31 - 1   # first row of the sample, its length
+    huge_row = wl_h.copy()
+    huge_row[2, 0] = 2**31 - 1                               # first row of the item
+    for bad in (other, tampered, wrong_pass, bad_table, bad_copy, bad_id, bad_flag, huge_len, huge_row):
         assert call(va.make_shape(**ok), wl_=np.ascontiguousarray(bad))[0] == va.VA_EINVAL
+    dkdv = va.va_build_worklist(cu, None, va.VA_MASK_CAUSAL, va.VA_PASS_BWD_DKDV, D, Hq, Hkv)
+    huge_range = dkdv.copy()
+    huge_range[2, 3], huge_range[2, 4] = 2**31 - 1, 2**31 - 1   # first query tile and count of the first item
+    with pytest.raises(va.VarlenAttnError) as e:
+        va.va_check_worklist(huge_range, va.VA_PASS_BWD_DKDV, cu, None, va.make_shape(**ok))
+    assert e.value.code == va.VA_EINVAL
     assert va.varlen_attn_bwd_workspace_bytes(va.make_shape(**ok)) >= 100 * Hq * 4
 
 
