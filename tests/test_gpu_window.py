@@ -105,16 +105,15 @@ def test_a_window_as_long_as_the_sample_gives_the_causal_gradient_bits():
 
 
 @pytest.mark.parametrize("blockwise", [False, True])
-@pytest.mark.parametrize("Hq,Hkv", [(4, 2), (8, 1)])
-def test_window_fp8_forward_parity(Hq, Hkv, blockwise):
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 2, 128), (8, 1, 128), (4, 2, 64), (8, 1, 256), (2, 2, 256), (8, 2, 64)])
+def test_window_fp8_forward_parity(Hq, Hkv, D, blockwise):
     import torch
     from oracle import e4m3 as oe
     from gpu_util import DEV, TOL_FP8_REL, from_dev_bf16
-    D = 128
     cu, _, q, k, v, _ = wl.random_stream(46 + Hq, LENS, Hq, Hkv, D)
     T = int(cu[-1])
     scale = 1.0 / np.sqrt(D)
-    print(f"window fp8 forward Hq={Hq} Hkv={Hkv} blockwise={blockwise}", flush=True)
+    print(f"window fp8 forward Hq={Hq} Hkv={Hkv} D={D} blockwise={blockwise}", flush=True)
     ps = va.PackedStream(cu, WINDOWS, MODE, Hq, Hkv, D, device=DEV, passes=(va.VA_PASS_FWD,))
     out = torch.full((T + 2, Hq, D), 768.0, dtype=torch.bfloat16, device=DEV)
     lse = torch.empty((Hq, T), dtype=torch.float32, device=DEV)
