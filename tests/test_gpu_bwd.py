@@ -148,6 +148,29 @@ def test_random_configurations_forward_and_backward(trial):
     assert run.tail_untouched("out")
 
 
+@pytest.mark.parametrize("D", [48, 64, 80, 96, 128, 160, 192, 256])
+@pytest.mark.parametrize("G", [1, 2, 4, 8])
+def test_every_head_dimension_with_every_head_stacking(D, G):
+    # The forward and dQ kernels are instantiated per (head dimension, query heads stacked in a block of rows:
+    # 1, 2, 4 or 8 = the group size here): each of the 32 once, forward and backward, the mask cycling with the case.
+    Hkv = 2 if G <= 2 else 1
+    mode = list(MODES)[(D // 16 + G) % len(MODES)]
+    lens = [70, 0, 129, 33, 200]
+    seed = 7000 + 10 * D + G
+    cu, prefix, q, k, v, do = wl.random_stream(seed, lens, G * Hkv, Hkv, D, prefix_frac=-1.0)
+    if mode == va.VA_MASK_CAUSAL:
+        prefix = None
+    elif mode == va.VA_MASK_THREE_BLOCK:
+        prefix = wl.random_block_ends(seed, lens)
+    scale = 1.0 / np.sqrt(D)
+    print(f"head_dim {D}, {G} heads per KV head ({Hkv} KV heads), mode={mode}", flush=True)
+    run = DeviceRun(cu, prefix, mode, q, k, v, do, scale)
+    ref_out, ref_lse = oa.attn_fwd(q, k, v, cu, prefix, scale=scale, mask_mode=MODES[mode])
+    assert rel_l2(run.out, ref_out) <= TOL_FWD_REL and max_abs(run.lse, ref_lse) <= TOL_LSE_ABS
+    check_bwd(run, oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=MODES[mode]), cu, f"D={D} G={G}")
+    assert run.tail_untouched("out")
+
+
 @pytest.mark.parametrize("mode,Hq,Hkv,D", [(va.VA_MASK_CAUSAL, 4, 2, 128), (va.VA_MASK_PREFIX_LM, 2, 1, 64),
                                            (va.VA_MASK_CAUSAL, 2, 2, 256)])
 def test_peaked_softmax_with_a_rising_row_maximum(mode, Hq, Hkv, D):

@@ -108,7 +108,8 @@ OMODE = {va.VA_MASK_CAUSAL: oa.MASK_CAUSAL, va.VA_MASK_PREFIX_LM: oa.MASK_PREFIX
 @pytest.mark.parametrize("mode,Hq,Hkv,D", [(va.VA_MASK_CAUSAL, 4, 2, 128), (va.VA_MASK_PREFIX_LM, 8, 1, 128), (va.VA_MASK_CAUSAL, 2, 2, 128),
                                            (va.VA_MASK_PREFIX_LM_CAUSAL, 4, 1, 128), (va.VA_MASK_THREE_BLOCK, 16, 2, 128),
                                            (va.VA_MASK_CAUSAL, 4, 2, 64), (va.VA_MASK_PREFIX_LM, 8, 1, 256), (va.VA_MASK_CAUSAL, 2, 2, 256),
-                                           (va.VA_MASK_THREE_BLOCK, 4, 1, 64)])
+                                           (va.VA_MASK_THREE_BLOCK, 4, 1, 64), (va.VA_MASK_CAUSAL, 2, 2, 64), (va.VA_MASK_PREFIX_LM, 8, 1, 64),
+                                           (va.VA_MASK_CAUSAL, 4, 2, 256), (va.VA_MASK_PREFIX_LM_CAUSAL, 4, 1, 256)])
 def test_fp8_blockwise_forward_parity(mode, Hq, Hkv, D):
     # magnitudes of Q, K and V drift by powers of two along the stream (period 90 tokens, so blocks
     # differ and some blocks straddle a change), which is what block scales are for
