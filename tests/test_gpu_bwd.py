@@ -196,18 +196,22 @@ def test_peaked_softmax_with_a_rising_row_maximum(mode, Hq, Hkv, D):
     check_bwd(run, oa.attn_bwd(q, k, v, do, cu, prefix, scale=scale, mask_mode=MODES[mode]), cu, "peaked")
 
 
-@pytest.mark.parametrize("mode,Hq,Hkv,n,L", [(va.VA_MASK_CAUSAL, 4, 4, 65, 64), (va.VA_MASK_PREFIX_LM, 8, 1, 257, 96)])
-def test_split_key_tiles_against_the_oracle(mode, Hq, Hkv, n, L):
-    # One work more than the 256 workgroup slots of head_dim 256 (260 and 257 equal works): the host cuts the
-    # query tiles of the last key tile into pieces, their workgroups write float32 partial sums into the
-    # workspace and the merge kernel adds them.  Every sample against the oracle, and twice for determinism.
-    D = 256
+@pytest.mark.parametrize("mode,Hq,Hkv,n,L,D", [
+    (va.VA_MASK_CAUSAL, 4, 4, 65, 64, 256), (va.VA_MASK_PREFIX_LM, 8, 1, 257, 96, 256),
+    (va.VA_MASK_CAUSAL, 4, 4, 129, 64, 128), (va.VA_MASK_PREFIX_LM, 8, 4, 129, 96, 128), (va.VA_MASK_CAUSAL, 4, 4, 65, 256, 64),
+    (va.VA_MASK_CAUSAL, 4, 4, 129, 96, 80), (va.VA_MASK_PREFIX_LM_CAUSAL, 2, 2, 129, 256, 48), (va.VA_MASK_CAUSAL, 4, 4, 65, 96, 160),
+    (va.VA_MASK_PREFIX_LM, 2, 2, 129, 64, 192), (va.VA_MASK_CAUSAL, 2, 2, 257, 128, 96)])
+def test_split_key_tiles_against_the_oracle(mode, Hq, Hkv, n, L, D):
+    # A few equal works more than the workgroup slots of the head dimension (256 at 256, else 512): the host cuts
+    # the query tiles of the last key tiles into pieces, their workgroups write float32 partial sums into the
+    # workspace and the merge kernel (one instantiation per head dimension) adds them.  Every sample against the
+    # oracle, and twice for determinism.
     lens = [L] * n
     cu, prefix, q, k, v, do = wl.random_stream(300 + n, lens, Hq, Hkv, D, prefix_frac=0.6)
     if mode == va.VA_MASK_CAUSAL:
         prefix = None
     scale = 1.0 / np.sqrt(D)
-    print(f"split key tiles mode={mode} Hq={Hq} Hkv={Hkv} samples={n} L={L}", flush=True)
+    print(f"split key tiles mode={mode} Hq={Hq} Hkv={Hkv} samples={n} L={L} D={D}", flush=True)
     run = DeviceRun(cu, prefix, mode, q, k, v, do, scale)
     dkdv_list = run.ps.worklist_host[va.VA_PASS_BWD_DKDV]
     assert dkdv_list[1, 7] >= 1, "this case is meant to hold a split tile"
