@@ -200,7 +200,8 @@ def test_peaked_softmax_with_a_rising_row_maximum(mode, Hq, Hkv, D):
     (va.VA_MASK_CAUSAL, 4, 4, 65, 64, 256), (va.VA_MASK_PREFIX_LM, 8, 1, 257, 96, 256),
     (va.VA_MASK_CAUSAL, 4, 4, 129, 64, 128), (va.VA_MASK_PREFIX_LM, 8, 4, 129, 96, 128), (va.VA_MASK_CAUSAL, 4, 4, 65, 256, 64),
     (va.VA_MASK_CAUSAL, 4, 4, 129, 96, 80), (va.VA_MASK_PREFIX_LM_CAUSAL, 2, 2, 129, 256, 48), (va.VA_MASK_CAUSAL, 4, 4, 65, 96, 160),
-    (va.VA_MASK_PREFIX_LM, 2, 2, 129, 64, 192), (va.VA_MASK_CAUSAL, 2, 2, 257, 128, 96)])
+    (va.VA_MASK_PREFIX_LM, 2, 2, 129, 64, 192), (va.VA_MASK_CAUSAL, 2, 2, 257, 128, 96),
+    (va.VA_MASK_THREE_BLOCK, 4, 4, 65, 96, 256), (va.VA_MASK_THREE_BLOCK, 4, 2, 257, 96, 128)])
 def test_split_key_tiles_against_the_oracle(mode, Hq, Hkv, n, L, D):
     # A few equal works more than the workgroup slots of the head dimension (256 at 256, else 512): the host cuts
     # the query tiles of the last key tiles into pieces, their workgroups write float32 partial sums into the
@@ -210,6 +211,8 @@ def test_split_key_tiles_against_the_oracle(mode, Hq, Hkv, n, L, D):
     cu, prefix, q, k, v, do = wl.random_stream(300 + n, lens, Hq, Hkv, D, prefix_frac=0.6)
     if mode == va.VA_MASK_CAUSAL:
         prefix = None
+    elif mode == va.VA_MASK_THREE_BLOCK:
+        prefix = wl.random_block_ends(300 + n, lens)
     scale = 1.0 / np.sqrt(D)
     print(f"split key tiles mode={mode} Hq={Hq} Hkv={Hkv} samples={n} L={L} D={D}", flush=True)
     run = DeviceRun(cu, prefix, mode, q, k, v, do, scale)

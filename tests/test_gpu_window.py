@@ -94,6 +94,21 @@ def test_window_backward_parity(Hq, Hkv, D):
     assert np.abs(run.dq[s4]).max() <= 1e-6 and np.abs(run.dk[s4]).max() <= 1e-6
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,n,L", [(4, 4, 128, 129, 96), (4, 4, 256, 65, 96), (2, 2, 64, 129, 256)])
+def test_window_backward_with_split_key_tiles(Hq, Hkv, D, n, L):
+    # a few equal works more than the workgroup slots, widths drawn per sample: key tiles cut into pieces over
+    # query ranges that end where the window of the tile's last key ends
+    lens = [L] * n
+    widths = np.random.default_rng(9 + D).integers(1, L + 1, size=n).astype(np.int32)
+    cu, _, q, k, v, do = wl.random_stream(47 + D, lens, Hq, Hkv, D)
+    scale = 1.0 / np.sqrt(D)
+    print(f"window backward with split key tiles Hq={Hq} Hkv={Hkv} D={D} samples={n} L={L}", flush=True)
+    run = DeviceRun(cu, widths, MODE, q, k, v, do, scale)
+    assert run.ps.worklist_host[va.VA_PASS_BWD_DKDV][1, 7] >= 1, "this case is meant to hold a split tile"
+    ref = oa.attn_bwd(q, k, v, do, cu, widths, scale=scale, mask_mode=oa.MASK_SLIDING_WINDOW)
+    check_bwd(run, ref, cu, f"window split {Hq}/{Hkv}x{D}")
+
+
 def test_a_window_as_long_as_the_sample_gives_the_causal_gradient_bits():
     Hq, Hkv, D = 4, 2, 128
     lens = [100, 33, 180]
