@@ -191,30 +191,56 @@ class Case:
         evs[3].synchronize()
         return float(np.median([evs[b].elapsed_time(evs[b + 1]) / iters for b in range(3)]))
 
+    def time_in_step(self, iters):
+        """{kernel: average milliseconds per launch} inside whole steps: `iters` steps of forward + backward in the
+        library's own kernel order, buffer sets rotating, an event on the launch stream between every two kernels
+        (the backward goes through varlen_attn_bwd_stages one kernel at a time, which launches what
+        varlen_attn_bwd launches).  These are the durations a kernel trace of the step shows."""
+        torch, va = self.torch, self.va
+        order = ([("bwd_dq", va.VA_BWD_STAGE_DQ), ("bwd_dkdv", va.VA_BWD_STAGE_DKDV)] if self.fused else
+                 [("bwd_delta", va.VA_BWD_STAGE_DELTA), ("bwd_dkdv", va.VA_BWD_STAGE_DKDV), ("bwd_dq", va.VA_BWD_STAGE_DQ)])
+        names = ["fwd_bf16"] + [n for n, _ in order]
+        for i in range(4):
+            self.step(i)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(iters)]
+        for i in range(iters):
+            evs[i][0].record()
+            self.fwd(i)
+            evs[i][1].record()
+            for j, (_, stage) in enumerate(order):
+                self.bwd(i, stage)
+                evs[i][j + 2].record()
+        evs[-1][-1].synchronize()
+        return {n: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(iters)])) for j, n in enumerate(names)}
+
     def kernels(self, iters):
-        """{kernel: {ms, flops, bytes}}: algorithmic work per launch.  Forward 2 products; dK/dV kernel 4 (scores,
-        dP, dV, dK); dQ kernel 1 (dQ; its recomputation of the scores and dP is overhead and is not counted).
-        Bytes: every input read once, every output written once."""
+        """{kernel: {ms, ms_train, flops, bytes}}: duration inside the step (time_in_step) and in a train of
+        back-to-back launches of the one kernel, and the algorithmic work per launch.  Forward 2 products; dK/dV
+        kernel 4 (scores, dP, dV, dK); dQ kernel 1 (dQ; its recomputation of the scores and dP is overhead and is
+        not counted).  Bytes: every input read once, every output written once."""
         va = self.va
         T, Hq, Hkv, D, pairs = self.T, self.Hq, self.Hkv, self.D, self.pairs
         self.step(0)  # the workspace holds delta and the rescaled LSE of every set the dK/dV train reads
         for i in range(1, len(self.sets)):
             self.step(i)
         self.time_train(self.fwd, iters)  # the first train of one kernel after the mixed loop runs slow: not taken
-        k = {"fwd_bf16": {"ms": self.time_train(self.fwd, iters), "flops": self.flops_fwd,
+        k = {"fwd_bf16": {"ms_train": self.time_train(self.fwd, iters), "flops": self.flops_fwd,
                           "bytes": 2.0 * T * D * (2 * Hq + 2 * Hkv) + 4.0 * T * Hq}}
-        k["bwd_dq"] = {"ms": self.time_train(lambda i: self.bwd(i, va.VA_BWD_STAGE_DQ), iters),
+        k["bwd_dq"] = {"ms_train": self.time_train(lambda i: self.bwd(i, va.VA_BWD_STAGE_DQ), iters),
                        "flops": 2.0 * D * Hq * pairs,
                        "bytes": (2.0 * T * D * (4 * Hq + 2 * Hkv) + 12.0 * T * Hq if self.fused
                                  else 2.0 * T * D * (3 * Hq + 2 * Hkv) + 8.0 * T * Hq)}
         # one workspace serves all buffer sets; they hold the same values, so the delta and rescaled LSE the dQ
         # train left there are those of every set
-        k["bwd_dkdv"] = {"ms": self.time_train(lambda i: self.bwd(i, va.VA_BWD_STAGE_DKDV), iters),
+        k["bwd_dkdv"] = {"ms_train": self.time_train(lambda i: self.bwd(i, va.VA_BWD_STAGE_DKDV), iters),
                          "flops": 8.0 * D * Hq * pairs,
                          "bytes": 2.0 * T * D * (2 * Hq + 4 * Hkv) + 8.0 * T * Hq}
         if not self.fused:
-            k["bwd_delta"] = {"ms": self.time_train(lambda i: self.bwd(i, va.VA_BWD_STAGE_DELTA), iters),
+            k["bwd_delta"] = {"ms_train": self.time_train(lambda i: self.bwd(i, va.VA_BWD_STAGE_DELTA), iters),
                               "flops": 2.0 * T * Hq * D, "bytes": 4.0 * T * D * Hq + 12.0 * T * Hq}
+        in_step = self.time_in_step(iters)
+        for n in k:
+            k[n]["ms"] = in_step[n]
         return k
 
 
@@ -270,7 +296,8 @@ def measure(case, steps, warmup, iters, full=True):
         r["ms_per_step_graph"] = gms
         r["value_graph"] = flops / (gms * 1e-3) / 1e12
     k = case.kernels(iters)
-    r["kernels_ms"] = {n: k[n]["ms"] for n in k}
+    r["kernels_ms"] = {n: k[n]["ms"] for n in k}               # inside the step: what the roofline is priced with
+    r["kernels_ms_train"] = {n: k[n]["ms_train"] for n in k}   # back-to-back launches of the one kernel
     r["kernels_tflops"] = {n: k[n]["flops"] / (k[n]["ms"] * 1e-3) / 1e12 for n in k}
     r["kernels_gbps"] = {n: k[n]["bytes"] / (k[n]["ms"] * 1e-3) / 1e9 for n in k}
     r["roofline"] = roofline_of(k, case.name)
@@ -605,7 +632,7 @@ def main():
                    "pairs_per_head": head["pairs_per_head"], "buffer_sets": NUM_BUFFER_SETS,
                    "clock_ramp_ms": CLOCK_RAMP_MS},
         **{n: head[n] for n in ("tokens_per_s", "mfma_util_useful", "ms_per_step_warm", "value_warm",
-                                "ms_per_step_graph", "value_graph", "host_plan_ms", "host_call_us", "host_call_us_c_abi", "kernels_ms",
+                                "ms_per_step_graph", "value_graph", "host_plan_ms", "host_call_us", "host_call_us_c_abi", "kernels_ms", "kernels_ms_train",
                                 "kernels_tflops", "kernels_gbps", "step_floor_us", "step_frac_of_floor")},
         "roofline": head["roofline"],
         "source_digest": source_digest(),

@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Condense rocprofv3 output of `bench.py --profile-leg` runs into the short summaries kept under profiles/.
 
-    python bench_profile.py stats <results.db>
+    python bench_profile.py stats <results.db> [--last <steps>]
     python bench_profile.py hbm   <fetch_dir> <write_dir> [<out.json>]
     python bench_profile.py pmc   <pmc_dir> [<pmc_dir> ...] [--json <out.json>]
 
@@ -45,16 +45,25 @@ def short_name(name):
     return None
 
 
-def stats(db):
+def stats(db, last=0):
+    """Per kernel: calls, average / min / max duration and share of the total; with `last` > 0 also the average
+    over the last `last` launches of the kernel (the timed steps of the profiled program, which come after its
+    clock ramp and warm-up steps: the figure to hold against the program's own milliseconds per step)."""
     con = sqlite3.connect(db)
     rows = con.execute("select name, count(*), avg(end-start), min(end-start), max(end-start), sum(end-start) "
                        "from kernels group by name order by sum(end-start) desc").fetchall()
     total = sum(r[5] for r in rows)
-    print(f"{'kernel':60s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'total_ms':>9s} {'pct':>6s}")
+    tail = f" {'last' + str(last) + '_avg_us':>14s}" if last else ""
+    print(f"{'kernel':60s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'total_ms':>9s} {'pct':>6s}{tail}")
     for name, calls, avg, mn, mx, sm in rows:
+        extra = ""
+        if last:
+            d = [r[0] for r in con.execute("select end-start from kernels where name = ? order by start desc limit ?",
+                                           (name, last))]
+            extra = f" {sum(d) / len(d) / 1e3:14.2f}"
         name = re.sub(r"va::\(anonymous namespace\)::|\(va::AttnParams\)|void ", "", name)
         print(f"{name[:60]:60s} {calls:6d} {avg / 1e3:9.2f} {mn / 1e3:9.2f} {mx / 1e3:9.2f} {sm / 1e6:9.3f} "
-              f"{100 * sm / total:6.1f}")
+              f"{100 * sm / total:6.1f}{extra}")
 
 
 def counter_rows(directory):
@@ -138,7 +147,7 @@ def pmc(dirs, out=None):
 
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "stats":
-        stats(sys.argv[2])
+        stats(sys.argv[2], int(sys.argv[4]) if len(sys.argv) >= 5 and sys.argv[3] == "--last" else 0)
     elif len(sys.argv) >= 4 and sys.argv[1] == "hbm":
         hbm(sys.argv[2], sys.argv[3], sys.argv[4] if len(sys.argv) > 4 else None)
     elif len(sys.argv) >= 3 and sys.argv[1] == "pmc":
