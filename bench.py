@@ -363,6 +363,31 @@ def fp8_forward(case, iters):
     return r
 
 
+def gemm_reference(torch, dev, n=8192, seconds=1.0):
+    """What the vendor's dense bf16 GEMM (hipBLASLt through torch.matmul, n^3, standard normal operands) reaches on
+    this box right now: context for the published 2.5 PFLOP/s that the rooflines are priced with.  Not part of the
+    path; nothing of the library is used here."""
+    a = torch.randn((n, n), device=dev).to(torch.bfloat16)
+    b = torch.randn((n, n), device=dev).to(torch.bfloat16)
+    c = torch.empty((n, n), dtype=torch.bfloat16, device=dev)
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < 0.3 * seconds:      # clocks up, library warmed
+        for _ in range(8):
+            torch.matmul(a, b, out=c)
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    iters = 200
+    e0.record()
+    for _ in range(iters):
+        torch.matmul(a, b, out=c)
+    e1.record()
+    e1.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    tf = 2.0 * n ** 3 / (ms * 1e-3) / 1e12
+    return {"what": f"torch.matmul (hipBLASLt) bf16 {n}x{n}x{n}, standard normal operands", "ms": ms, "tflops": tf,
+            "frac_of_peak": tf / PEAK_BF16_TFLOPS}
+
+
 def tiny_latency(va, wl, torch, reps=200):
     """Configuration 1 is a latency case: microseconds per forward + backward call pair, eager and as a graph
     replay, and the host microseconds the two calls take to return; the oracle on one thread beside it."""
@@ -666,6 +691,8 @@ def main():
         torch.cuda.empty_cache()
     if configs:
         result["configs"] = configs
+    if not args.no_bins:    # the full default run only
+        result["gemm_reference"] = gemm_reference(torch, dev)
     print(json.dumps(result))
 
 
