@@ -388,6 +388,30 @@ def gemm_reference(torch, dev, n=8192, seconds=1.0):
             "frac_of_peak": tf / PEAK_BF16_TFLOPS}
 
 
+def gemm_reference_fp8(torch, dev, n=8192):
+    """The same for E4M3 operands (torch._scaled_mm, unit scales, bf16 result): context for the 5 PFLOP/s the FP8
+    forward is priced with.  None where this PyTorch build has no such routine."""
+    try:
+        a = torch.randn((n, n), device=dev).to(torch.float8_e4m3fn)
+        b = torch.randn((n, n), device=dev).to(torch.float8_e4m3fn)
+        one = torch.ones((), device=dev)
+        run = lambda: torch._scaled_mm(a, b.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16)
+        for _ in range(30):
+            run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(200):
+            run()
+        e1.record()
+        e1.synchronize()
+    except Exception as exc:  # noqa: BLE001 - a reference figure only
+        return {"what": "torch._scaled_mm not available", "error": repr(exc)[:200]}
+    ms = e0.elapsed_time(e1) / 200
+    tf = 2.0 * n ** 3 / (ms * 1e-3) / 1e12
+    return {"what": f"torch._scaled_mm (hipBLASLt) e4m3 {n}x{n}x{n}, standard normal operands, bf16 result", "ms": ms,
+            "tflops": tf, "frac_of_peak": tf / PEAK_FP8_TFLOPS}
+
+
 def tiny_latency(va, wl, torch, reps=200):
     """Configuration 1 is a latency case: microseconds per forward + backward call pair, eager and as a graph
     replay, and the host microseconds the two calls take to return; the oracle on one thread beside it."""
@@ -693,6 +717,7 @@ def main():
         result["configs"] = configs
     if not args.no_bins:    # the full default run only
         result["gemm_reference"] = gemm_reference(torch, dev)
+        result["gemm_reference_fp8"] = gemm_reference_fp8(torch, dev)
         if result["roofline"]["unit"] == "TFLOP/s":   # the dominant kernel against what a plain GEMM gets here
             result["roofline"]["achieved_over_gemm_reference"] = result["roofline"]["achieved"] / result["gemm_reference"]["tflops"]
     print(json.dumps(result))
