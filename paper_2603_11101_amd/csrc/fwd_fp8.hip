@@ -190,15 +190,19 @@ struct FragAddr8 {
     static_assert(self_check(), "fragment address closed forms disagree with the tile layout");
     int kb, vb;
     VA_DEV explicit FragAddr8(int lane) : kb(k_base(lane)), vb(v_base(lane)) {}
+    // `tile` is a multiple of the tile size and the lane constants lie below it, so the compile-time chunk bits
+    // can be XOR-ed into the lane constant first: those values do not change from tile to tile, and what is left
+    // per tile is one addition each.
     VA_DEV i32x8 k_frag(const char* lds, int tile, int b, int t) const {
-        const int at = ((kb + tile) ^ ((4 * t) << 4)) + b * 16 * D;
-        const i32x4 lo = *reinterpret_cast<const i32x4*>(lds + at);
-        const i32x4 hi = *reinterpret_cast<const i32x4*>(lds + (at ^ 16));
+        const int lo_at = (kb ^ ((4 * t) << 4)) + tile + b * 16 * D;
+        const int hi_at = (kb ^ ((4 * t + 1) << 4)) + tile + b * 16 * D;
+        const i32x4 lo = *reinterpret_cast<const i32x4*>(lds + lo_at);
+        const i32x4 hi = *reinterpret_cast<const i32x4*>(lds + hi_at);
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
     VA_DEV i32x8 v_frag(const char* lds, int tile, int dt) const {
         typedef __attribute__((address_space(3))) i32x2* lds_i32x2;
-        const int at = (vb + tile) ^ ((2 * dt) << 4);
+        const int at = (vb ^ ((2 * dt) << 4)) + tile;
         i32x8 vf;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
@@ -427,7 +431,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_fp8_kernel(AttnPara
 #pragma unroll
             for (int w = 0; w < 8; ++w) {
                 const int b = w >> 2, r = (w & 3) * 4;
-                int word = __builtin_amdgcn_cvt_pk_fp8_f32(s[b][r], s[b][r + 1], 0, false);
+                // The low half first; the half it leaves alone is overwritten next, so whatever the destination
+                // register holds serves as the old value: the empty statement declares it defined, at no cost (a zero,
+                // or a copy of a live value, would have to be moved there first: one more instruction per word).
+                int word;
+                asm volatile("" : "=v"(word));
+                word = __builtin_amdgcn_cvt_pk_fp8_f32(s[b][r], s[b][r + 1], word, false);
                 word = __builtin_amdgcn_cvt_pk_fp8_f32(s[b][r + 2], s[b][r + 3], word, true);
                 pf[w] = word;
             }
