@@ -188,6 +188,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
     constexpr int TILE_BYTES = BMQ * D * 2;
     constexpr int STAGE_BYTES = 2 * TILE_BYTES + 2 * 64 * (int)sizeof(float);  // Q, dO, LSE2[64], delta[64]
     constexpr int AUX = 2 * STAGE_BYTES;  // V tile of the work; output staging at the end of the work
+    static_assert(TILE_BYTES % FragAddr<D>::kTileAlign == 0 && STAGE_BYTES % FragAddr<D>::kTileAlign == 0,
+                  "fragment addresses take tile offsets in multiples of the tile alignment");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;

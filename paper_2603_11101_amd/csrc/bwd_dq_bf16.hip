@@ -37,6 +37,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
     constexpr int KSTEPS = DR / 16;
     constexpr int DT = (DR + 31) / 32;
     constexpr int TILE_BYTES = BN * D * 2;
+    static_assert(TILE_BYTES % FragAddr<D>::kTileAlign == 0 && (32 * D * 2) % FragAddr<D>::kTileAlign == 0,
+                  "fragment addresses take tile and slice offsets in multiples of the tile alignment");
     constexpr int PF = D == 128 ? 2 : kPrefetch;  // fragment reads in flight; D = 128 has no registers to spare
     extern __shared__ __attribute__((aligned(16))) char smem[];  // two stages, each a K tile then a V tile
 

@@ -56,6 +56,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void fwd_bf16_kernel(AttnPar
     constexpr int NQ = D / 16;             // row fragments a block of rows is fetched as (the first KSTEPS are used)
     using Rows = RowBlock<D, DR>;
     constexpr int TILE_BYTES = BN * D * 2;
+    static_assert(TILE_BYTES % FragAddr<D>::kTileAlign == 0 && (32 * D * 2) % FragAddr<D>::kTileAlign == 0,
+                  "fragment addresses take tile and slice offsets in multiples of the tile alignment");
     extern __shared__ __attribute__((aligned(16))) char smem[];  // two stages, each a K tile then a V tile
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

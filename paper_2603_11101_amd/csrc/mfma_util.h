@@ -166,17 +166,22 @@ struct FragAddr {
 
     VA_DEV explicit FragAddr(int lane) : rm(rm_base(lane)), tr(tr_base(lane, 0)) {}
 
-    // `lds` is the base of dynamic shared memory, `tile` the byte offset of the tile inside it
+    // `lds` is the base of dynamic shared memory, `tile` the byte offset of the tile inside it: a multiple of
+    // kTileAlign.  The compile-time chunk bits (below kTileAlign) are XOR-ed into the lane constant, not into
+    // lane constant + tile: those values do not change from tile to tile, so the compiler keeps them in
+    // registers and a tile costs one addition per fragment address instead of an addition and an XOR.
+    static constexpr int kTileAlign = 512;
+    static_assert((15 << 5) < kTileAlign && ((7 << 6) ^ 32) < kTileAlign, "chunk bits must stay below the tile alignment");
     VA_DEV bf16x8 rowmajor(const char* lds, int tile, int b, int t) const {
-        return *reinterpret_cast<const bf16x8*>(lds + (((rm + tile) ^ (t << 5)) + b * 32 * (D * 2)));
+        return *reinterpret_cast<const bf16x8*>(lds + (((rm ^ (t << 5)) + tile) + b * 32 * (D * 2)));
     }
     VA_DEV bf16x8 transposed(const char* lds, int tile, int x, int dt) const {
         typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
         typedef short s16x8 __attribute__((ext_vector_type(8)));
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4)(lds_char*)(lds + (((tr + tile) ^ (dt << 6)) + x * 16 * (D * 2))));
+            (lds_s16x4)(lds_char*)(lds + (((tr ^ (dt << 6)) + tile) + x * 16 * (D * 2))));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4)(lds_char*)(lds + (((tr + tile) ^ ((dt << 6) ^ 32)) + 8 * (D * 2) + x * 16 * (D * 2))));
+            (lds_s16x4)(lds_char*)(lds + (((tr ^ ((dt << 6) ^ 32)) + tile) + 8 * (D * 2) + x * 16 * (D * 2))));
         return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
 };
