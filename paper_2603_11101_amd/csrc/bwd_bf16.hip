@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
         const size_t row = row0 + i;
         if (row < rows && c == 0) {
             const size_t t = row / Hq, h = row % Hq;
-            delta[h * T + t] = acc;
+            delta[h * T + t] = -acc;  // stored negated: the dK/dV kernel starts its dP sums from it
             lse2[h * T + t] = lse[h * T + t] * kLog2e;  // the other kernels work with base-2 exponentials
         }
     }
@@ -326,11 +326,17 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
 
                 // S = Q K^T and dP = dO V^T: rows = query rows (registers), columns = key rows (lanes).
                 // MFMAs alternate between the two accumulators so that none waits on the one just issued.
+                // The dP sums start from -delta of their rows (the workspace holds delta negated; registers
+                // 4 r4 .. 4 r4 + 3 of the accumulator are four consecutive rows, one 16-byte read), so that
+                // dP - delta comes out of the matrix unit and dS costs one multiplication per element.
                 f32x16 s, dp;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    s[r] = 0.0f;
-                    dp[r] = 0.0f;
+                for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_s + 32 * qb + 8 * r4 + 4 * hf);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dp[4 * r4 + e] = d4[e];
                 }
                 {
                     constexpr int NS = 2 * KSTEPS;  // step i: product i % 2 (0: S, 1: dP), k-step i / 2
@@ -351,6 +357,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                         if (prod(i)) dp = mfma32(a, bv, dp);
                         else s = mfma32(a, kf[kstep(i)], s);
                     }
+                    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);  // the four reads of -delta above
 #pragma unroll
                     for (int i = 0; i < PF; ++i) {
                         if (V_IN_LDS && (i % 2)) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
@@ -382,13 +389,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dkdv_kernel(AttnPar
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int rb = 32 * qb + 8 * r4 + 4 * hf;  // tile row of registers 4 r4 .. 4 r4 + 3
                     const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + rb);
-                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_s + rb);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int r = 4 * r4 + e;
                         const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -l4[e]));
                         s[r] = pv;
-                        dp[r] = pv * (dp[r] - d4[e]);
+                        dp[r] = pv * dp[r];  // dp holds dP - delta
                     }
                 }
                 if (need_mask) {

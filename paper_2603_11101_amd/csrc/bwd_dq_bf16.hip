@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
         lse2 = __builtin_bit_cast(
             float, __builtin_amdgcn_raw_buffer_load_b32(Rows::rows((FUSE ? p.lse : p.lse2) + first, bytes), off, 0, 0));
         if constexpr (!FUSE)
-            delta = __builtin_bit_cast(
+            delta = -__builtin_bit_cast(  // stored negated
                 float, __builtin_amdgcn_raw_buffer_load_b32(Rows::rows(p.delta + first, bytes), off, 0, 0));
     };
     // FUSE: the O rows of the block, requested where the registers of the tile loop are free
@@ -134,7 +134,8 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void bwd_dq_kernel(AttnParam
             const size_t first = (size_t)w.h0 * p.T + w.q_row0;
             const unsigned bytes = (unsigned)((HPB - 1) * p.T + w.q_rows) * 4u;
             const int off = (tok < w.q_rows && l < 32) ? ((rr / BMT) * p.T + tok) * 4 : 0x7ffffff0;
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, delta), Rows::rows(p.delta + first, bytes), off, 0, 0);
+            // the workspace holds delta negated (the dK/dV kernel starts its dP sums from it)
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, -delta), Rows::rows(p.delta + first, bytes), off, 0, 0);
             __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, lse2), Rows::rows(p.lse2 + first, bytes), off, 0, 0);
         }
     };

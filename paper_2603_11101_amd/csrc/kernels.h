@@ -19,7 +19,7 @@ struct AttnParams {
     void* dq;             // [T, Hq, D]
     void* dk;             // [T, Hkv, D]
     void* dv;             // [T, Hkv, D]
-    float* delta;         // [Hq, T]  rowsum(dO * O)
+    float* delta;         // [Hq, T]  -rowsum(dO * O): negated, the dK/dV kernel starts its dP sums from it
     float* lse2;          // [Hq, T]  LSE * log2(e), written by the delta kernel
     const float* q_descale;  // fp8 only
     const float* k_descale;

@@ -89,9 +89,11 @@ def test_window_backward_parity(Hq, Hkv, D):
     run = DeviceRun(cu, WINDOWS, MODE, q, k, v, do, scale)
     ref = oa.attn_bwd(q, k, v, do, cu, WINDOWS, scale=scale, mask_mode=oa.MASK_SLIDING_WINDOW)
     check_bwd(run, ref, cu, f"window {Hq}/{Hkv}x{D}")
-    # a window of one key: p = 1, so dS = dP - delta vanishes up to the rounding of two float32 sums
+    # a window of one key: p = 1, so dS = dP - delta vanishes up to the float32 rounding of the two sums, whose
+    # size is |dO . v| (up to about 40 at head_dim 256: half a unit in the last place is 2e-6, a few of them
+    # accumulate over the k-steps), times scale * |q| (about 0.2): 5e-6 bounds it at every head dimension
     s4 = slice(cu[4], cu[5])
-    assert np.abs(run.dq[s4]).max() <= 1e-6 and np.abs(run.dk[s4]).max() <= 1e-6
+    assert np.abs(run.dq[s4]).max() <= 5e-6 and np.abs(run.dk[s4]).max() <= 5e-6
 
 
 @pytest.mark.parametrize("Hq,Hkv,D,n,L", [(4, 4, 128, 129, 96), (4, 4, 256, 65, 96), (2, 2, 64, 129, 256)])
