@@ -296,7 +296,7 @@ int va_bwd_has_delta_kernel(int32_t head_dim);
 /*
  * The backward restricted to some of its kernels (this library's own; the
  * paper names no such call).  `stages` is a non-empty combination of
- *   VA_BWD_STAGE_DELTA  delta = rowsum(dO * O) and LSE * log2(e) into the workspace
+ *   VA_BWD_STAGE_DELTA  delta = rowsum(dO * O) (kept negated) and LSE * log2(e) into the workspace
  *   VA_BWD_STAGE_DKDV   dK and dV; reads both arrays from the workspace
  *   VA_BWD_STAGE_DQ     dQ; at head_dim <= 128 its kernel also writes both arrays
  *                       (VA_BWD_STAGE_DELTA is then implied and costs nothing extra)
