@@ -584,28 +584,75 @@ def sweep(va, torch, quick):
     """The paper's varlen-against-fixlen sweep with this library: the same kernels once on the packed stream
     of the true lengths and once on a stream in which every sample is padded to the maximum length (what a
     fixed-length batch computes), causal, 16 / 8 heads, head_dim 128, forward + backward.  Lengths are seeded:
-    B samples, uniform around (1 - padding rate) * S, clipped to [16, S], one sample forced to S."""
+    B samples, uniform around (1 - padding rate) * S, clipped to [16, S], one sample forced to S.  Prints the
+    table and, under it, the statements of the paper's section 3.2.1 checked against the rows."""
     HQ, D = SWEEP_HQ, SWEEP_D
     batches = (8, 32) if quick else (8, 16, 32)
     seqs = (1024, 8192) if quick else (1024, 2048, 4096, 8192, 16384, 32768)
     rates = (0.03, 0.5, 0.9) if quick else (0.03, 0.25, 0.5, 0.75, 0.9)
     rng = np.random.default_rng(7)
+    print("# Packed variable-length attention against the padded fixed-length layout (forward + backward, causal,\n"
+          f"# {HQ} query / {SWEEP_HKV} KV heads, head_dim {D}) on one MI355X: the sweep of the paper's section 3.2.1 (batch, sequence\n"
+          "# length, padding rate) with this library's kernels.  Command:\n"
+          f"#   python3 bench.py --sweep{' --quick' if quick else ''}\n"
+          "# 'target' is the padding rate the lengths were drawn for, 'padding' the rate of the drawn batch (one sample\n"
+          "# always has the full length); 'saved' = 1 - packed/padded time; packed_TF and padded_TF count the useful pairs\n"
+          "# only; fixlen_TF credits the padded batch with every pair it computes (14 * D * Hq * B * S (S + 1) / 2 over the\n"
+          "# padded time): the figure a fixed-length benchmark reports.")
     print(f"{'batch':>5s} {'seq':>6s} {'target':>7s} {'padding':>8s} {'packed_ms':>10s} {'padded_ms':>10s} "
-          f"{'saved':>7s} {'packed_TF':>10s} {'padded_TF':>10s}")
+          f"{'saved':>7s} {'packed_TF':>10s} {'padded_TF':>10s} {'fixlen_TF':>10s}")
+    rows = []
     for b in batches:
         for s in seqs:
             padded = np.full(b, s, dtype=np.int64)
             steps = max(2, min(10, int(1e9 / (b * s * s))))
             t_padded = sweep_time(va, torch, padded, steps)
+            fixlen = 14.0 * D * HQ * b * (s * (s + 1) // 2) / t_padded / 1e9
             for r in rates:
                 lens = sweep_lengths(b, s, r, rng)
                 pad = 1.0 - lens.sum() / float(b * s)
                 t_packed = sweep_time(va, torch, lens, steps)
                 flops = 14.0 * D * HQ * float((lens * (lens + 1) // 2).sum())
                 # the padded batch is credited with the useful pairs only
+                rows.append({"b": b, "s": s, "r": r, "pad": pad, "packed": t_packed, "padded": t_padded,
+                             "saved": 1.0 - t_packed / t_padded, "tf": flops / t_packed / 1e9, "fixlen": fixlen})
                 print(f"{b:5d} {s:6d} {r:7.2f} {pad:8.3f} {t_packed:10.3f} {t_padded:10.3f} "
-                      f"{1.0 - t_packed / t_padded:7.1%} {flops / t_packed / 1e9:10.0f} {flops / t_padded / 1e9:10.0f}",
-                      flush=True)
+                      f"{1.0 - t_packed / t_padded:7.1%} {flops / t_packed / 1e9:10.0f} {flops / t_padded / 1e9:10.0f} "
+                      f"{fixlen:10.0f}", flush=True)
+    sweep_statements(rows, batches, seqs, rates)
+
+
+def sweep_statements(rows, batches, seqs, rates):
+    """The four statements of the paper's section 3.2.1 (its hardware, its kernels) held against the rows."""
+    pick = lambda **kw: [x for x in rows if all(x[k] == v for k, v in kw.items())]
+    span = lambda xs, key, f="{:.1%}": f.format(min(x[key] for x in xs)) + " ... " + f.format(max(x[key] for x in xs))
+    lo_r, hi_r = min(rates), max(rates)
+    print("#\n# The paper's statements (section 3.2.1; other hardware, other kernels), checked against the table:")
+    print(f"# 1. 'varlen latency is consistently lower than fixlen': packed_ms < padded_ms in all {len(rows)} rows: "
+          f"{all(x['packed'] < x['padded'] for x in rows)}.")
+    print(f"#    'savings rise from 2.28 % at 3 % padding to 89.73 % at 90 %': here {span(pick(r=lo_r), 'saved')} at "
+          f"{lo_r:.0%} and {span(pick(r=hi_r), 'saved')} at {hi_r:.0%} (drawn padding at that target: "
+          f"{span(pick(r=hi_r), 'pad', '{:.0%}')}; one sample is full length);")
+    print("#    savings exceed the padding rate because causal cost grows with the square of the length.")
+    if 2048 in seqs:
+        peak = {b: max(x["tf"] for x in pick(b=b, s=2048)) for b in batches}
+        b0, b1 = min(batches), max(batches)
+        at = pick(b=b1, s=2048)
+        print(f"# 2. 'at 2048 tokens the peak TFLOPS grows 1.2x from batch {b0} to {b1}, and varlen stays below fixlen': peak "
+              f"packed_TF {peak[b0]:.0f} -> {peak[b1]:.0f} ({peak[b1] / peak[b0]:.2f}x); at batch {b1} packed_TF by padding "
+              f"target {' / '.join(format(x['tf'], '.0f') for x in at)} against fixlen_TF {at[0]['fixlen']:.0f}.")
+    top = pick(s=max(seqs))
+    ratio = [x["tf"] / x["fixlen"] for x in top]
+    print(f"#    'at {max(seqs)} tokens varlen is on par with or above fixlen': packed_TF / fixlen_TF is {min(ratio):.2f} ... "
+          f"{max(ratio):.2f} in the {len(top)} rows of that length.")
+    if 16 in batches:
+        long_rows = [x for x in pick(b=16) if x["s"] > 8192 and x["r"] >= 0.25]
+        if long_rows:
+            print(f"# 3. 'batch 16, sequences above 8k: savings of 25-90 %': here {span(long_rows, 'saved')} for padding "
+                  f"targets of 25 % and more.")
+    bmid = 16 if 16 in batches else max(batches)
+    best = ", ".join(f"{s}: {max(x['tf'] for x in pick(b=bmid, s=s)):.0f}" for s in seqs)
+    print(f"# 4. 'TFLOPS rises quickly from 1k to 8k and is flat beyond': best packed_TF at batch {bmid} by length: {best}.")
 
 
 def main():
