@@ -93,3 +93,40 @@ def test_forward_packing_invariance_and_no_leak_on_gpu():
     poisoned = DeviceRun(cu, None, va.VA_MASK_CAUSAL, q2, k2, v2, do, scale, backward=False)
     keep = np.r_[0:cu[1], cu[2]:cu[3]]
     assert np.array_equal(poisoned.out[keep], full.out[keep]) and np.array_equal(poisoned.lse[:, keep], full.lse[:, keep])
+
+
+@pytest.mark.parametrize("mode,Hq,Hkv,D", [(va.VA_MASK_CAUSAL, 4, 2, 128), (va.VA_MASK_PREFIX_LM, 8, 1, 256),
+                                           (va.VA_MASK_PREFIX_LM_CAUSAL, 2, 2, 64), (va.VA_MASK_SLIDING_WINDOW, 4, 1, 128)])
+def test_zero_queries_give_the_mean_of_the_visible_values(mode, Hq, Hkv, D):
+    # Q = 0: every score is 0, the softmax is uniform over the keys a row sees, so O is the plain mean of their V
+    # rows and LSE = ln(their number) -- closed forms written here from the mask definition, no oracle involved.
+    # The gradient of K is then exactly zero (dS is multiplied by Q = 0).
+    lens = [1, 70, 129, 300]
+    cu, prefix, q, k, v, do = wl.random_stream(31 + D, lens, Hq, Hkv, D, prefix_frac=0.4)
+    q[:] = 0.0
+    if mode == va.VA_MASK_CAUSAL:
+        prefix = None
+    elif mode == va.VA_MASK_SLIDING_WINDOW:
+        prefix = np.array([1, 16, 200, 65], dtype=np.int32)
+    print(f"zero queries mode={mode} Hq={Hq} Hkv={Hkv} D={D}", flush=True)
+    run = DeviceRun(cu, prefix, mode, q, k, v, do, 0.3)
+    G = Hq // Hkv
+    for s, L in enumerate(lens):
+        c = int(cu[s])
+        for i in range(L):
+            if mode == va.VA_MASK_CAUSAL:
+                lo, hi = 0, i + 1
+            elif mode == va.VA_MASK_PREFIX_LM:
+                lo, hi = 0, (int(prefix[s]) if i < prefix[s] else L)
+            elif mode == va.VA_MASK_PREFIX_LM_CAUSAL:
+                lo, hi = 0, (int(prefix[s]) if i < prefix[s] else i + 1)
+            else:
+                lo, hi = max(0, i + 1 - int(prefix[s])), i + 1
+            want = v[c + lo:c + hi].astype(np.float64).mean(axis=0)          # [Hkv, D]
+            got = run.out[c + i].reshape(Hkv, G, D)
+            # bf16 P (1/n rounded) and bf16 output rounding: 2^-8 relative to the largest value averaged
+            tol = 2.0 ** -7 * np.abs(v[c + lo:c + hi]).max() + 1e-6
+            assert np.abs(got - want[:, None, :]).max() <= tol, (s, i)
+            assert np.abs(run.lse[:, c + i] - np.log(hi - lo)).max() <= 1e-5, (s, i)
+    assert np.all(run.dk == 0.0)
+    assert run.tail_untouched("out", "dq", "dk", "dv")
